@@ -1,0 +1,450 @@
+/*
+ * CPU oracle for one pre-norm decoder layer (prefill and single-token decode).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference that the
+ * GPU library is compared against.  It shares no code, header, table or
+ * helper with the HIP path and must never be called from the product path.
+ *
+ * The paper treats the inference engine as a black box whose prefill
+ * throughput and TPOT-versus-batch curve are measured (sections "Acquire
+ * prefill throughput under TTFT constraints" and "Acquire decode throughput
+ * under TPOT constraints"); it defines no layer.  The layer evaluated here is
+ * therefore the textbook Llama-style block at the benchmark's shapes:
+ *
+ *     y   = rmsnorm(x, g_attn)
+ *     q,k,v = y Wq^T, y Wk^T, y Wv^T          (no bias)
+ *     q,k = rope(q,k, position inside own sequence)     (rotate-half pairing)
+ *     o   = causal grouped-query attention, scale 1/sqrt(head_dim)
+ *     h   = x + o Wo^T
+ *     y2  = rmsnorm(h, g_ffn)
+ *     out = h + (silu(y2 Wg^T) * (y2 Wu^T)) Wd^T        (dense)
+ *     out = h + sum_{e in top-k} w_e FFN_e(y2)           (mixture of experts)
+ *
+ * Tensors are stored as fp32; every dot product, mean square, softmax sum and
+ * rotation angle is accumulated / evaluated in double, so results do not
+ * depend on summation order at the tolerances used by the tests.
+ *
+ * Every function is pinned by tests/test_oracle_layer.py against an
+ * independent float64 composition of library primitives, brute-force
+ * attention, the decode == prefill-of-extended-sequence identity and
+ * textbook invariants.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+typedef struct {
+    int32_t d_model, n_q_heads, n_kv_heads, head_dim, d_ff;
+    int32_t n_experts; /* 0 = dense FFN */
+    int32_t top_k;
+    double rms_eps, rope_base;
+} orc_config;
+
+typedef struct {
+    const float *g_attn;   /* [d] */
+    const float *w_q;      /* [Hq*hd, d] */
+    const float *w_k;      /* [Hkv*hd, d] */
+    const float *w_v;      /* [Hkv*hd, d] */
+    const float *w_o;      /* [d, Hq*hd] */
+    const float *g_ffn;    /* [d] */
+    const float *w_gate;   /* [F, d]  (MoE: [E, F, d]) */
+    const float *w_up;     /* [F, d]  (MoE: [E, F, d]) */
+    const float *w_down;   /* [d, F]  (MoE: [E, d, F]) */
+    const float *w_router; /* [E, d] or NULL */
+} orc_weights;
+
+/* y[i] = x[i] / sqrt(mean_j x[j]^2 + eps) * g[i]   (one row) */
+void orc_rmsnorm_row(const float *x, const float *g, int d, double eps, float *y)
+{
+    double ss = 0.0;
+    for (int j = 0; j < d; ++j) ss += (double)x[j] * (double)x[j];
+    double inv = 1.0 / sqrt(ss / (double)d + eps);
+    for (int j = 0; j < d; ++j) y[j] = (float)((double)x[j] * inv * (double)g[j]);
+}
+
+void orc_rmsnorm(const float *x, const float *g, int T, int d, double eps, float *y)
+{
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < T; ++t) orc_rmsnorm_row(x + (size_t)t * d, g, d, eps, y + (size_t)t * d);
+}
+
+/* y[o] = sum_i x[i] W[o][i]   (one row; W is [n_out, n_in] row-major) */
+void orc_linear_row(const float *x, const float *W, int n_in, int n_out, float *y)
+{
+    for (int o = 0; o < n_out; ++o) {
+        const float *w = W + (size_t)o * n_in;
+        double acc = 0.0;
+#pragma omp simd reduction(+ : acc)
+        for (int i = 0; i < n_in; ++i) acc += (double)x[i] * (double)w[i];
+        y[o] = (float)acc;
+    }
+}
+
+void orc_linear(const float *x, const float *W, int T, int n_in, int n_out, float *y)
+{
+#pragma omp parallel for schedule(static)
+    for (int t = 0; t < T; ++t)
+        orc_linear_row(x + (size_t)t * n_in, W, n_in, n_out, y + (size_t)t * n_out);
+}
+
+/*
+ * Rotary embedding of one token's heads x[H][hd] at absolute position pos.
+ * Rotate-half pairing: channel i (< hd/2) is paired with channel i + hd/2,
+ * angle = pos * base^(-2i/hd).
+ */
+void orc_rope_row(float *x, int H, int hd, int pos, double base)
+{
+    int half = hd / 2;
+    for (int h = 0; h < H; ++h) {
+        float *v = x + (size_t)h * hd;
+        for (int i = 0; i < half; ++i) {
+            double theta = pow(base, -2.0 * (double)i / (double)hd);
+            double ang = (double)pos * theta;
+            double c = cos(ang), s = sin(ang);
+            double a = v[i], b = v[i + half];
+            v[i] = (float)(a * c - b * s);
+            v[i + half] = (float)(b * c + a * s);
+        }
+    }
+}
+
+/*
+ * One query token attending over n_keys keys (softmax with max subtraction).
+ * q is [Hq][hd]; key s / kv-head g lives at K + s*stride_s + g*stride_h.
+ * Query head h reads kv-head h / (Hq/Hkv).  o is [Hq][hd].
+ */
+void orc_attend_row(const float *q, const float *K, const float *V, size_t stride_s,
+                    size_t stride_h, int n_keys, int Hq, int Hkv, int hd, float *o)
+{
+    int group = Hq / Hkv;
+    double scale = 1.0 / sqrt((double)hd);
+    double *p = (double *)malloc(sizeof(double) * (size_t)n_keys);
+    for (int h = 0; h < Hq; ++h) {
+        int g = h / group;
+        const float *qh = q + (size_t)h * hd;
+        double mx = -INFINITY;
+        for (int s = 0; s < n_keys; ++s) {
+            const float *ks = K + (size_t)s * stride_s + (size_t)g * stride_h;
+            double acc = 0.0;
+            for (int i = 0; i < hd; ++i) acc += (double)qh[i] * (double)ks[i];
+            p[s] = acc * scale;
+            if (p[s] > mx) mx = p[s];
+        }
+        double denom = 0.0;
+        for (int s = 0; s < n_keys; ++s) {
+            p[s] = exp(p[s] - mx);
+            denom += p[s];
+        }
+        for (int i = 0; i < hd; ++i) {
+            double acc = 0.0;
+            for (int s = 0; s < n_keys; ++s)
+                acc += p[s] * (double)V[(size_t)s * stride_s + (size_t)g * stride_h + i];
+            o[(size_t)h * hd + i] = (float)(acc / denom);
+        }
+    }
+    free(p);
+}
+
+static double silu(double z) { return z / (1.0 + exp(-z)); }
+
+/* out[d] += scale * Wd (silu(Wg y) * (Wu y)) for one token and one FFN. */
+static void ffn_row_accumulate(const float *y, const float *Wg, const float *Wu, const float *Wd,
+                               int d, int F, double scale, double *out_acc, float *act)
+{
+    for (int f = 0; f < F; ++f) {
+        const float *wg = Wg + (size_t)f * d, *wu = Wu + (size_t)f * d;
+        double a = 0.0, b = 0.0;
+#pragma omp simd reduction(+ : a, b)
+        for (int i = 0; i < d; ++i) {
+            a += (double)y[i] * (double)wg[i];
+            b += (double)y[i] * (double)wu[i];
+        }
+        act[f] = (float)(silu(a) * b);
+    }
+    for (int o = 0; o < d; ++o) {
+        const float *wd = Wd + (size_t)o * F;
+        double acc = 0.0;
+#pragma omp simd reduction(+ : acc)
+        for (int f = 0; f < F; ++f) acc += (double)act[f] * (double)wd[f];
+        out_acc[o] += scale * acc;
+    }
+}
+
+/*
+ * Router for one token: p = softmax(logits over all E experts); pick the top_k
+ * largest p (ties: lower expert index first); weights renormalised to sum 1.
+ */
+void orc_route_row(const float *logits, int E, int top_k, int32_t *idx, double *wgt)
+{
+    double mx = -INFINITY, denom = 0.0;
+    double *p = (double *)malloc(sizeof(double) * (size_t)E);
+    for (int e = 0; e < E; ++e)
+        if ((double)logits[e] > mx) mx = (double)logits[e];
+    for (int e = 0; e < E; ++e) {
+        p[e] = exp((double)logits[e] - mx);
+        denom += p[e];
+    }
+    for (int e = 0; e < E; ++e) p[e] /= denom;
+    double sum = 0.0;
+    for (int k = 0; k < top_k; ++k) {
+        int best = -1;
+        for (int e = 0; e < E; ++e) {
+            int taken = 0;
+            for (int j = 0; j < k; ++j)
+                if (idx[j] == e) taken = 1;
+            if (taken) continue;
+            if (best < 0 || p[e] > p[best]) best = e; /* strict '>' keeps the lower index on ties */
+        }
+        idx[k] = best;
+        wgt[k] = p[best];
+        sum += p[best];
+    }
+    for (int k = 0; k < top_k; ++k) wgt[k] /= sum;
+    free(p);
+}
+
+/* Second half of the layer for one token: out = h + FFN(rmsnorm(h)). */
+static void ffn_block_row(const orc_config *c, const orc_weights *w, const float *h,
+                          const float *router_logits_row, float *out, int32_t *expert_idx_out)
+{
+    int d = c->d_model, F = c->d_ff;
+    float *y2 = (float *)malloc(sizeof(float) * (size_t)d);
+    float *act = (float *)malloc(sizeof(float) * (size_t)F);
+    double *acc = (double *)calloc((size_t)d, sizeof(double));
+    orc_rmsnorm_row(h, w->g_ffn, d, c->rms_eps, y2);
+    if (c->n_experts <= 0) {
+        ffn_row_accumulate(y2, w->w_gate, w->w_up, w->w_down, d, F, 1.0, acc, act);
+    } else {
+        int E = c->n_experts, K = c->top_k;
+        float *logits = (float *)malloc(sizeof(float) * (size_t)E);
+        int32_t *idx = (int32_t *)malloc(sizeof(int32_t) * (size_t)K);
+        double *wgt = (double *)malloc(sizeof(double) * (size_t)K);
+        if (router_logits_row) {
+            memcpy(logits, router_logits_row, sizeof(float) * (size_t)E);
+        } else {
+            orc_linear_row(y2, w->w_router, d, E, logits);
+        }
+        orc_route_row(logits, E, K, idx, wgt);
+        for (int k = 0; k < K; ++k) {
+            size_t e = (size_t)idx[k];
+            ffn_row_accumulate(y2, w->w_gate + e * (size_t)F * d, w->w_up + e * (size_t)F * d,
+                               w->w_down + e * (size_t)d * F, d, F, wgt[k], acc, act);
+            if (expert_idx_out) expert_idx_out[k] = idx[k];
+        }
+        free(logits);
+        free(idx);
+        free(wgt);
+    }
+    for (int o = 0; o < d; ++o) out[o] = (float)((double)h[o] + acc[o]);
+    free(y2);
+    free(act);
+    free(acc);
+}
+
+/*
+ * Prefill of a packed batch of sequences.
+ *
+ *   x            [T, d] hidden-state rows; sequence s owns rows cu_seqlens[s] .. cu_seqlens[s+1]-1
+ *   router_logits [T, E] or NULL (then w_router is used when the layer is MoE)
+ *   rows / n_rows  if rows != NULL only those token rows are produced: out is
+ *                [n_rows, d] in the order of rows[].  Keys and values are still
+ *                computed for every earlier token of the same sequence, so the
+ *                sampled rows equal the rows of a full evaluation.
+ *   slots        NULL, or n_seqs cache slots: rotated k and v of sequence s are
+ *                stored in k_cache/v_cache [n_slots][Hkv][max_len][hd] and
+ *                lens[slot] = length.  (Requires rows == NULL.)
+ *   expert_idx   NULL or [n_out_rows, top_k] chosen experts (MoE)
+ * Returns 0, or -1 on an invalid argument.
+ */
+int orc_prefill(const orc_config *c, const orc_weights *w, const float *x, int T, int n_seqs,
+                const int32_t *cu_seqlens, const float *router_logits, const int32_t *rows,
+                int n_rows, const int32_t *slots, float *k_cache, float *v_cache, int32_t *lens,
+                int max_len, float *out, int32_t *expert_idx)
+{
+    int d = c->d_model, Hq = c->n_q_heads, Hkv = c->n_kv_heads, hd = c->head_dim;
+    if (Hkv <= 0 || Hq % Hkv != 0 || hd % 2 != 0) return -1;
+    if (cu_seqlens[0] != 0 || cu_seqlens[n_seqs] != T) return -1;
+    if (slots && rows) return -1;
+    size_t dq = (size_t)Hq * hd, dkv = (size_t)Hkv * hd;
+
+    int32_t *seq_of = (int32_t *)malloc(sizeof(int32_t) * (size_t)(T > 0 ? T : 1));
+    char *need_out = (char *)calloc((size_t)(T > 0 ? T : 1), 1);
+    char *need_kv = (char *)calloc((size_t)(T > 0 ? T : 1), 1);
+    int32_t *out_slot = (int32_t *)malloc(sizeof(int32_t) * (size_t)(T > 0 ? T : 1));
+    for (int s = 0; s < n_seqs; ++s) {
+        if (cu_seqlens[s + 1] < cu_seqlens[s]) return -1;
+        for (int t = cu_seqlens[s]; t < cu_seqlens[s + 1]; ++t) seq_of[t] = s;
+    }
+    if (rows) {
+        for (int r = 0; r < n_rows; ++r) {
+            if (rows[r] < 0 || rows[r] >= T) return -1;
+            need_out[rows[r]] = 1;
+        }
+    } else {
+        for (int t = 0; t < T; ++t) need_out[t] = 1;
+    }
+    /* a token's k,v are needed if it or any later token of its sequence is produced */
+    for (int s = 0; s < n_seqs; ++s) {
+        int later = 0;
+        for (int t = cu_seqlens[s + 1] - 1; t >= cu_seqlens[s]; --t) {
+            if (need_out[t]) later = 1;
+            need_kv[t] = (char)later;
+        }
+    }
+
+    float *kbuf = (float *)calloc((size_t)(T > 0 ? T : 1) * dkv, sizeof(float));
+    float *vbuf = (float *)calloc((size_t)(T > 0 ? T : 1) * dkv, sizeof(float));
+
+    /* pass 1: normalise, project and rotate keys / values */
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int t = 0; t < T; ++t) {
+        if (!need_kv[t]) continue;
+        float *y = (float *)malloc(sizeof(float) * (size_t)d);
+        orc_rmsnorm_row(x + (size_t)t * d, w->g_attn, d, c->rms_eps, y);
+        orc_linear_row(y, w->w_k, d, (int)dkv, kbuf + (size_t)t * dkv);
+        orc_linear_row(y, w->w_v, d, (int)dkv, vbuf + (size_t)t * dkv);
+        orc_rope_row(kbuf + (size_t)t * dkv, Hkv, hd, t - cu_seqlens[seq_of[t]], c->rope_base);
+        free(y);
+    }
+    if (slots) {
+        for (int s = 0; s < n_seqs; ++s) {
+            int L = cu_seqlens[s + 1] - cu_seqlens[s];
+            if (L > max_len) return -1;
+            size_t base = (size_t)slots[s] * Hkv * (size_t)max_len * hd;
+            for (int p = 0; p < L; ++p)
+                for (int g = 0; g < Hkv; ++g) {
+                    size_t dst = base + ((size_t)g * max_len + p) * hd;
+                    size_t src = (size_t)(cu_seqlens[s] + p) * dkv + (size_t)g * hd;
+                    memcpy(k_cache + dst, kbuf + src, sizeof(float) * (size_t)hd);
+                    memcpy(v_cache + dst, vbuf + src, sizeof(float) * (size_t)hd);
+                }
+            lens[slots[s]] = L;
+        }
+    }
+    if (rows) {
+        for (int r = 0; r < n_rows; ++r) out_slot[rows[r]] = r;
+    } else {
+        for (int t = 0; t < T; ++t) out_slot[t] = t;
+    }
+
+    /* pass 2: queries, attention, output projection, FFN for produced rows */
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int t = 0; t < T; ++t) {
+        if (!need_out[t]) continue;
+        int s0 = cu_seqlens[seq_of[t]];
+        float *y = (float *)malloc(sizeof(float) * (size_t)d);
+        float *q = (float *)malloc(sizeof(float) * dq);
+        float *o = (float *)malloc(sizeof(float) * dq);
+        float *h = (float *)malloc(sizeof(float) * (size_t)d);
+        orc_rmsnorm_row(x + (size_t)t * d, w->g_attn, d, c->rms_eps, y);
+        orc_linear_row(y, w->w_q, d, (int)dq, q);
+        orc_rope_row(q, Hq, hd, t - s0, c->rope_base);
+        orc_attend_row(q, kbuf + (size_t)s0 * dkv, vbuf + (size_t)s0 * dkv, dkv, (size_t)hd,
+                       t - s0 + 1, Hq, Hkv, hd, o);
+        orc_linear_row(o, w->w_o, (int)dq, d, h);
+        for (int i = 0; i < d; ++i) h[i] = (float)((double)x[(size_t)t * d + i] + (double)h[i]);
+        size_t r = (size_t)out_slot[t];
+        ffn_block_row(c, w, h, router_logits ? router_logits + (size_t)t * c->n_experts : NULL,
+                      out + r * d, expert_idx ? expert_idx + r * (size_t)c->top_k : NULL);
+        free(y);
+        free(q);
+        free(o);
+        free(h);
+    }
+    free(seq_of);
+    free(need_out);
+    free(need_kv);
+    free(out_slot);
+    free(kbuf);
+    free(vbuf);
+    return 0;
+}
+
+/*
+ * One decode step for B sequences.  Row b is the newest token of the sequence
+ * held in cache slot slots[b]; its position is p = lens[slot].  Its rotated key
+ * and its value are appended at p first, then it attends over positions 0..p
+ * (itself included), and lens[slot] becomes p + 1.
+ * Caches are [n_slots][Hkv][max_len][hd] fp32.  Returns 0, -1 bad argument,
+ * -2 cache capacity exceeded (nothing is modified in that case).
+ */
+int orc_decode_step(const orc_config *c, const orc_weights *w, const float *x, int B,
+                    const int32_t *slots, float *k_cache, float *v_cache, int32_t *lens,
+                    int max_len, const float *router_logits, float *out, int32_t *expert_idx)
+{
+    int d = c->d_model, Hq = c->n_q_heads, Hkv = c->n_kv_heads, hd = c->head_dim;
+    if (Hkv <= 0 || Hq % Hkv != 0 || hd % 2 != 0) return -1;
+    size_t dq = (size_t)Hq * hd, dkv = (size_t)Hkv * hd;
+    for (int b = 0; b < B; ++b)
+        if (lens[slots[b]] + 1 > max_len) return -2;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        int slot = slots[b], p = lens[slot];
+        float *y = (float *)malloc(sizeof(float) * (size_t)d);
+        float *q = (float *)malloc(sizeof(float) * dq);
+        float *k = (float *)malloc(sizeof(float) * dkv);
+        float *v = (float *)malloc(sizeof(float) * dkv);
+        float *o = (float *)malloc(sizeof(float) * dq);
+        float *h = (float *)malloc(sizeof(float) * (size_t)d);
+        orc_rmsnorm_row(x + (size_t)b * d, w->g_attn, d, c->rms_eps, y);
+        orc_linear_row(y, w->w_q, d, (int)dq, q);
+        orc_linear_row(y, w->w_k, d, (int)dkv, k);
+        orc_linear_row(y, w->w_v, d, (int)dkv, v);
+        orc_rope_row(q, Hq, hd, p, c->rope_base);
+        orc_rope_row(k, Hkv, hd, p, c->rope_base);
+        size_t base = (size_t)slot * Hkv * (size_t)max_len * hd;
+        for (int g = 0; g < Hkv; ++g) {
+            memcpy(k_cache + base + ((size_t)g * max_len + p) * hd, k + (size_t)g * hd,
+                   sizeof(float) * (size_t)hd);
+            memcpy(v_cache + base + ((size_t)g * max_len + p) * hd, v + (size_t)g * hd,
+                   sizeof(float) * (size_t)hd);
+        }
+        orc_attend_row(q, k_cache + base, v_cache + base, (size_t)hd, (size_t)max_len * hd, p + 1,
+                       Hq, Hkv, hd, o);
+        orc_linear_row(o, w->w_o, (int)dq, d, h);
+        for (int i = 0; i < d; ++i) h[i] = (float)((double)x[(size_t)b * d + i] + (double)h[i]);
+        ffn_block_row(c, w, h, router_logits ? router_logits + (size_t)b * c->n_experts : NULL,
+                      out + (size_t)b * d, expert_idx ? expert_idx + (size_t)b * c->top_k : NULL);
+        free(y);
+        free(q);
+        free(k);
+        free(v);
+        free(o);
+        free(h);
+    }
+    for (int b = 0; b < B; ++b) lens[slots[b]] += 1;
+    return 0;
+}
+
+/* Stand-alone pieces exposed so that tests can pin each one separately. */
+void orc_rope(float *x, int T, int H, int hd, const int32_t *pos, double base)
+{
+    for (int t = 0; t < T; ++t) orc_rope_row(x + (size_t)t * H * hd, H, hd, pos[t], base);
+}
+
+/* Causal attention over one packed batch; q [T,Hq,hd], k,v [T,Hkv,hd], o [T,Hq,hd]. */
+void orc_attention(const float *q, const float *k, const float *v, int n_seqs,
+                   const int32_t *cu_seqlens, int Hq, int Hkv, int hd, float *o)
+{
+    size_t dq = (size_t)Hq * hd, dkv = (size_t)Hkv * hd;
+    for (int s = 0; s < n_seqs; ++s) {
+        int s0 = cu_seqlens[s], s1 = cu_seqlens[s + 1];
+#pragma omp parallel for schedule(dynamic, 1)
+        for (int t = s0; t < s1; ++t)
+            orc_attend_row(q + (size_t)t * dq, k + (size_t)s0 * dkv, v + (size_t)s0 * dkv, dkv,
+                           (size_t)hd, t - s0 + 1, Hq, Hkv, hd, o + (size_t)t * dq);
+    }
+}
+
+/* out = h + FFN(rmsnorm(h)) for T rows (dense or MoE). */
+void orc_ffn_block(const orc_config *c, const orc_weights *w, const float *h, int T,
+                   const float *router_logits, float *out, int32_t *expert_idx)
+{
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int t = 0; t < T; ++t)
+        ffn_block_row(c, w, h + (size_t)t * c->d_model,
+                      router_logits ? router_logits + (size_t)t * c->n_experts : NULL,
+                      out + (size_t)t * c->d_model,
+                      expert_idx ? expert_idx + (size_t)t * c->top_k : NULL);
+}

@@ -1,0 +1,316 @@
+"""Pins of the C layer oracle against things other than itself: an independent float64 composition
+of PyTorch CPU library primitives, brute-force attention, decode == prefill of the extended
+sequence, and textbook invariants.  CPU only."""
+import numpy as np
+import pytest
+import torch
+
+import pd_inputs as I
+from oracle import layer as O
+
+
+# ---- independent float64 composition of library routines ----------------------------------------
+
+def torch_layer(cfg, w, x, cu, router_logits=None):
+    f64 = torch.float64
+    W = {k: torch.from_numpy(np.asarray(v)).to(f64) for k, v in w.items()}
+    x = torch.from_numpy(x).to(f64)
+    d, hq, hkv, hd = cfg["d_model"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"]
+
+    def norm(a, g):
+        return torch.nn.functional.rms_norm(a, (d,), g, cfg["rms_eps"])
+
+    def rot(a, pos):            # a [L, H, hd]
+        half = hd // 2
+        inv = cfg["rope_base"] ** (-torch.arange(0, half, dtype=f64) * 2.0 / hd)
+        ang = pos.to(f64)[:, None] * inv[None, :]
+        c, s = torch.cos(ang)[:, None, :], torch.sin(ang)[:, None, :]
+        a1, a2 = a[..., :half], a[..., half:]
+        return torch.cat([a1 * c - a2 * s, a2 * c + a1 * s], dim=-1)
+
+    y = norm(x, W["g_attn"])
+    q = (y @ W["w_q"].T).view(-1, hq, hd)
+    k = (y @ W["w_k"].T).view(-1, hkv, hd)
+    v = (y @ W["w_v"].T).view(-1, hkv, hd)
+    o = torch.zeros_like(q)
+    for s in range(len(cu) - 1):
+        a, b = int(cu[s]), int(cu[s + 1])
+        if b == a:
+            continue
+        pos = torch.arange(b - a)
+        qs = rot(q[a:b], pos).transpose(0, 1)[None]
+        ks = rot(k[a:b], pos).transpose(0, 1)[None].repeat_interleave(hq // hkv, dim=1)
+        vs = v[a:b].transpose(0, 1)[None].repeat_interleave(hq // hkv, dim=1)
+        os_ = torch.nn.functional.scaled_dot_product_attention(qs, ks, vs, is_causal=True)
+        o[a:b] = os_[0].transpose(0, 1)
+    h = x + o.reshape(-1, hq * hd) @ W["w_o"].T
+    y2 = norm(h, W["g_ffn"])
+
+    def ffn(z, wg, wu, wd):
+        return (torch.nn.functional.silu(z @ wg.T) * (z @ wu.T)) @ wd.T
+
+    if cfg.get("n_experts", 0) == 0:
+        out = h + ffn(y2, W["w_gate"], W["w_up"], W["w_down"])
+    else:
+        r = torch.from_numpy(router_logits).to(f64) if router_logits is not None else y2 @ W["w_router"].T
+        p = torch.softmax(r, dim=-1)
+        tv, ti = torch.topk(p, cfg["top_k"], dim=-1)
+        tv = tv / tv.sum(-1, keepdim=True)
+        out = h.clone()
+        for t in range(x.shape[0]):
+            for j in range(cfg["top_k"]):
+                e = int(ti[t, j])
+                out[t] += tv[t, j] * ffn(y2[t:t + 1], W["w_gate"][e], W["w_up"][e], W["w_down"][e])[0]
+    return out.numpy()
+
+
+def relmax(a, b):
+    return float(np.max(np.abs(np.asarray(a, np.float64) - np.asarray(b, np.float64))) / np.max(np.abs(b)))
+
+
+CASES = [
+    dict(),                                              # GQA 4/2
+    dict(n_q_heads=4, n_kv_heads=4),                     # MHA
+    dict(n_q_heads=8, n_kv_heads=1, head_dim=16),        # MQA
+    dict(d_model=96, n_q_heads=6, n_kv_heads=3, head_dim=8, d_ff=80),
+]
+
+
+@pytest.mark.parametrize("over", CASES)
+def test_prefill_matches_float64_library_composition(over):
+    cfg = I.small_config(**over)
+    w = I.layer_weights(cfg, std=0.08)
+    cu = np.array([0, 17, 17, 40, 41], np.int32)        # ragged, one empty, one single-token sequence
+    x = I.hidden(int(cu[-1]), cfg["d_model"], seed=5)
+    got = O.prefill(O.Layer(cfg, w), x, cu)
+    ref = torch_layer(cfg, w, x, cu)
+    assert relmax(got, ref) < 2e-6          # only the fp32 rounding of stored intermediates differs
+
+
+def test_moe_matches_float64_library_composition():
+    cfg = I.small_config(n_experts=4, top_k=2, d_ff=64)
+    w = I.layer_weights(cfg, std=0.08, with_router=True)
+    cu = np.array([0, 9, 24], np.int32)
+    x = I.hidden(24, cfg["d_model"], seed=6)
+    r = I.router_logits(24, 4, seed=8)
+    L = O.Layer(cfg, w)
+    assert relmax(O.prefill(L, x, cu, router_logits=r), torch_layer(cfg, w, x, cu, r)) < 2e-6
+    # router computed from w_router when no logits are handed in
+    assert relmax(O.prefill(L, x, cu), torch_layer(cfg, w, x, cu, None)) < 2e-6
+
+
+# ---- brute force ----------------------------------------------------------------------------------
+
+def test_attention_brute_force_tiny():
+    rng = np.random.default_rng(0)
+    T, hq, hkv, hd = 13, 4, 2, 8
+    q = rng.standard_normal((T, hq, hd)).astype(np.float32)
+    k = rng.standard_normal((T, hkv, hd)).astype(np.float32)
+    v = rng.standard_normal((T, hkv, hd)).astype(np.float32)
+    cu = np.array([0, 5, 13], np.int32)
+    got = O.attention(q, k, v, cu)
+    ref = np.zeros((T, hq, hd))
+    for s in range(2):
+        a, b = cu[s], cu[s + 1]
+        for h in range(hq):
+            S = q[a:b, h].astype(np.float64) @ k[a:b, h // 2].astype(np.float64).T / np.sqrt(hd)
+            S = np.where(np.tril(np.ones_like(S)) > 0, S, -np.inf)
+            P = np.exp(S - S.max(1, keepdims=True))
+            P /= P.sum(1, keepdims=True)
+            ref[a:b, h] = P @ v[a:b, h // 2].astype(np.float64)
+    assert np.max(np.abs(got - ref)) < 1e-6
+
+
+# ---- decode == prefill of the extended sequence ---------------------------------------------------
+
+@pytest.mark.parametrize("over", [dict(), dict(n_q_heads=4, n_kv_heads=4), dict(n_experts=4, top_k=2, d_ff=64)])
+def test_decode_equals_prefill_of_extended_sequence(over):
+    cfg = I.small_config(**over)
+    w = I.layer_weights(cfg, std=0.08, with_router=True)
+    L = O.Layer(cfg, w)
+    lens = [1, 6, 19]
+    S_max = 24
+    xs = [I.hidden(S_max, cfg["d_model"], seed=20 + i) for i in range(3)]
+    cache = O.KVCache(L, n_slots=4, max_len=S_max)
+    slots = [2, 0, 3]
+    x0 = np.concatenate([xs[i][:lens[i]] for i in range(3)])
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    O.prefill(L, x0, cu, cache=cache, slots=slots)
+    assert list(cache.lens[[2, 0, 3]]) == lens
+    for step in range(3):                                   # three successive decode steps
+        cur = [n + step for n in lens]
+        xb = np.stack([xs[i][cur[i]] for i in range(3)])
+        got = O.decode_step(L, xb, slots, cache)
+        for i in range(3):
+            full = O.prefill(L, xs[i][:cur[i] + 1], np.array([0, cur[i] + 1], np.int32))
+            assert relmax(got[i], full[-1]) < 1e-6
+        assert list(cache.lens[[2, 0, 3]]) == [n + 1 for n in cur]
+
+
+def test_decode_capacity_error_leaves_state():
+    cfg = I.small_config()
+    L = O.Layer(cfg, I.layer_weights(cfg))
+    cache = O.KVCache(L, 2, 4)
+    O.prefill(L, I.hidden(4, cfg["d_model"], 1), np.array([0, 4], np.int32), cache=cache, slots=[1])
+    before = cache.k.copy()
+    with pytest.raises(OverflowError):
+        O.decode_step(L, I.hidden(1, cfg["d_model"], 2), [1], cache)
+    assert cache.lens[1] == 4 and np.array_equal(before, cache.k)
+
+
+# ---- invariants -------------------------------------------------------------------------------------
+
+def test_rmsnorm_unit_rms_and_gain():
+    x = I.hidden(9, 64, 3) * 5
+    y = O.rmsnorm(x, np.ones(64, np.float32), 1e-6)
+    assert np.allclose(np.sqrt((y.astype(np.float64) ** 2).mean(1)), 1.0, atol=1e-6)
+    g = np.linspace(0.5, 2, 64).astype(np.float32)
+    assert np.allclose(O.rmsnorm(x, g, 1e-6), y * g, rtol=2e-7, atol=0)
+    # eps sits inside the square root: a zero row stays zero and tiny rows scale by 1/sqrt(eps)
+    z = np.full((1, 64), 1e-6, np.float32)
+    assert np.allclose(O.rmsnorm(z, np.ones(64, np.float32), 1e-2), z / np.sqrt(1e-12 + 1e-2), rtol=1e-6)
+
+
+def test_rope_properties():
+    rng = np.random.default_rng(1)
+    hd = 16
+    q = rng.standard_normal((1, 1, hd)).astype(np.float32)
+    k = rng.standard_normal((1, 1, hd)).astype(np.float32)
+    assert np.array_equal(O.rope(q, [0]), q)                      # position 0 is the identity
+    r = O.rope(q, [37])
+    half = hd // 2
+    n0 = q[0, 0, :half] ** 2 + q[0, 0, half:] ** 2
+    n1 = r[0, 0, :half] ** 2 + r[0, 0, half:] ** 2
+    assert np.allclose(n0, n1, rtol=1e-6)                         # each (i, i+hd/2) pair keeps its norm
+    dots = [float((O.rope(q, [m]).astype(np.float64) * O.rope(k, [n]).astype(np.float64)).sum())
+            for m, n in [(5, 2), (40, 37), (103, 100)]]
+    assert np.allclose(dots, dots[0], atol=1e-5)                  # depends on m - n only
+    # closed form for the first pair (theta_0 = 1) and the last pair (theta = base^(-(hd-2)/hd))
+    p = 3
+    th = 10000.0 ** (-(hd - 2) / hd)
+    a, b = float(q[0, 0, 0]), float(q[0, 0, half])
+    r3 = O.rope(q, [p])
+    assert r3[0, 0, 0] == pytest.approx(a * np.cos(p) - b * np.sin(p), rel=1e-6)
+    assert r3[0, 0, half] == pytest.approx(b * np.cos(p) + a * np.sin(p), rel=1e-6)
+    a, b = float(q[0, 0, half - 1]), float(q[0, 0, hd - 1])
+    assert r3[0, 0, half - 1] == pytest.approx(a * np.cos(p * th) - b * np.sin(p * th), rel=1e-6)
+
+
+def test_attention_single_key_and_uniform():
+    rng = np.random.default_rng(2)
+    q = rng.standard_normal((3, 2, 8)).astype(np.float32)
+    k = rng.standard_normal((3, 2, 8)).astype(np.float32)
+    v = rng.standard_normal((3, 2, 8)).astype(np.float32)
+    o = O.attention(q, k, v, np.array([0, 3], np.int32))
+    assert np.allclose(o[0], v[0], atol=1e-7)                     # first token sees only itself
+    o = O.attention(q * 0, k, v, np.array([0, 3], np.int32))       # zero query -> uniform average
+    assert np.allclose(o[2], v.mean(0), atol=1e-6)
+
+
+def test_causality_and_batch_independence():
+    cfg = I.small_config()
+    L = O.Layer(cfg, I.layer_weights(cfg, std=0.08))
+    x = I.hidden(30, cfg["d_model"], 9)
+    cu = np.array([0, 12, 30], np.int32)
+    base = O.prefill(L, x, cu)
+    x2 = x.copy()
+    x2[8:12] += 1.0                                               # perturb the tail of sequence 0
+    pert = O.prefill(L, x2, cu)
+    assert np.array_equal(base[:8], pert[:8])                     # earlier rows bit-identical
+    assert np.array_equal(base[12:], pert[12:])                   # other sequence untouched
+    assert not np.array_equal(base[8:12], pert[8:12])
+    alone = O.prefill(L, x[12:], np.array([0, 18], np.int32))
+    assert np.array_equal(alone, base[12:])                       # packed == alone
+
+
+def test_gqa_equals_mha_with_duplicated_kv_heads():
+    cfg = I.small_config(n_q_heads=4, n_kv_heads=2)
+    w = I.layer_weights(cfg, std=0.08)
+    hd, d = cfg["head_dim"], cfg["d_model"]
+    w2 = dict(w)
+    w2["w_k"] = np.repeat(w["w_k"].reshape(2, hd, d), 2, axis=0).reshape(4 * hd, d)
+    w2["w_v"] = np.repeat(w["w_v"].reshape(2, hd, d), 2, axis=0).reshape(4 * hd, d)
+    cfg2 = dict(cfg, n_kv_heads=4)
+    x = I.hidden(21, d, 4)
+    cu = np.array([0, 21], np.int32)
+    assert np.array_equal(O.prefill(O.Layer(cfg, w), x, cu), O.prefill(O.Layer(cfg2, w2), x, cu))
+
+
+def test_moe_special_cases_reduce_to_dense():
+    cfg = I.small_config(d_ff=64)
+    w = I.layer_weights(cfg, std=0.08)
+    x = I.hidden(10, cfg["d_model"], 12)
+    cu = np.array([0, 10], np.int32)
+    dense = O.prefill(O.Layer(cfg, w), x, cu)
+    # identical experts: the renormalised weights sum to 1
+    cfgm = dict(cfg, n_experts=4, top_k=2)
+    wm = dict(w)
+    for n in ("w_gate", "w_up", "w_down"):
+        wm[n] = np.repeat(w[n][None], 4, axis=0)
+    moe = O.prefill(O.Layer(cfgm, wm), x, cu, router_logits=I.router_logits(10, 4, 1))
+    assert relmax(moe, dense) < 1e-6
+    # one expert, top-1
+    cfg1 = dict(cfg, n_experts=1, top_k=1)
+    w1 = dict(w)
+    for n in ("w_gate", "w_up", "w_down"):
+        w1[n] = w[n][None]
+    one = O.prefill(O.Layer(cfg1, w1), x, cu, router_logits=np.zeros((10, 1), np.float32))
+    assert relmax(one, dense) < 1e-7
+
+
+def test_router_top2_weights_and_tie_break():
+    r = np.array([[0.0, 1.0, 3.0, 2.0], [1.0, 1.0, 1.0, 1.0], [2.0, 5.0, 5.0, 0.0]], np.float32)
+    idx, wgt = O.route(r, 2)
+    assert idx.tolist() == [[2, 3], [0, 1], [1, 2]]               # ties -> lower index first
+    assert np.allclose(wgt.sum(1), 1.0)
+    # renormalised softmax over all experts == softmax over the two chosen logits
+    assert wgt[0, 0] == pytest.approx(np.exp(3) / (np.exp(3) + np.exp(2)), rel=1e-12)
+    assert np.allclose(wgt[1], 0.5)
+
+
+def test_ffn_zero_branches_and_silu_closed_form():
+    # W_up = 0, W_down = 0 or W_gate = 0 (silu(0) = 0) each make the FFN add nothing: out == h.
+    cfg = I.small_config(d_ff=32)
+    w = I.layer_weights(cfg, std=0.08)
+    h = I.hidden(5, cfg["d_model"], 2)
+    for name in ("w_gate", "w_up", "w_down"):
+        wz = dict(w)
+        wz[name] = np.zeros_like(w[name])
+        assert np.array_equal(O.ffn_block(O.Layer(cfg, wz), h), h)
+    # silu closed form at one point: an FFN with F=1 and known scalars
+    cfg1 = dict(cfg, d_model=2, n_q_heads=1, n_kv_heads=1, head_dim=2, d_ff=1)
+    w1 = {"g_attn": np.ones(2, np.float32), "g_ffn": np.ones(2, np.float32),
+          "w_q": np.zeros((2, 2), np.float32), "w_k": np.zeros((2, 2), np.float32),
+          "w_v": np.zeros((2, 2), np.float32), "w_o": np.zeros((2, 2), np.float32),
+          "w_gate": np.array([[1.0, 0.0]], np.float32), "w_up": np.array([[0.0, 1.0]], np.float32),
+          "w_down": np.array([[1.0], [0.0]], np.float32)}
+    hh = np.array([[3.0, 4.0]], np.float32)                        # rms = sqrt(12.5)
+    y = hh.astype(np.float64) / np.sqrt(12.5 + 1e-6)
+    z = y[0, 0]
+    expect0 = 3.0 + (z / (1 + np.exp(-z))) * y[0, 1]
+    out = O.ffn_block(O.Layer(cfg1, w1), hh)
+    assert out[0, 0] == pytest.approx(expect0, rel=1e-6) and out[0, 1] == 4.0
+
+
+def test_row_sampled_prefill_equals_full_rows():
+    cfg = I.small_config()
+    L = O.Layer(cfg, I.layer_weights(cfg, std=0.08))
+    cu = np.array([0, 14, 33], np.int32)
+    x = I.hidden(33, cfg["d_model"], 14)
+    full = O.prefill(L, x, cu)
+    rows = [32, 0, 13, 20]
+    assert np.array_equal(O.prefill(L, x, cu, rows=rows), full[rows])
+
+
+def test_linear_is_x_times_w_transposed():
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((3, 7)).astype(np.float32)
+    W = rng.standard_normal((5, 7)).astype(np.float32)
+    assert np.allclose(O.linear(x, W), x.astype(np.float64) @ W.astype(np.float64).T, rtol=1e-6, atol=1e-6)
+
+
+def test_input_module_bf16_rounding_is_rne():
+    a = np.array([1.0, 1.00390625, 1.01171875, -3.1415927, 65504.0, 1e-8], np.float32)
+    ref = torch.from_numpy(a).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(I.round_to_bf16(a), ref)
+    assert np.array_equal(I.bf16_bits_to_f32(I.f32_to_bf16_bits(a)), ref)
