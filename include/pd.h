@@ -1,0 +1,224 @@
+/*
+ * pd.h - C ABI of the prefill/decode layer-forward library and of the P/D allocation model.
+ *
+ * The paper sizes a prefill/decode-disaggregated deployment from two measured curves of one
+ * serving instance (maximum prefill throughput at a given input length; TPOT versus decode batch)
+ * and closed forms (Eqs. (5)-(7), (13)).  This library provides the measured side on one GPU -
+ * one decoder layer's forward pass, for prefill and for a batched single-token decode step over a
+ * KV cache - and the closed forms themselves.
+ *
+ * Conventions
+ *   - Plain C, no exceptions cross the boundary; every call returns a pd_status.
+ *   - "device" pointers are HIP device memory on the current device; "host" pointers are ordinary
+ *     host memory.  The caller owns every tensor it passes and keeps it alive until the stream has
+ *     executed the call's work.  The library owns only its opaque handles (and the repacked copies
+ *     of the weights they hold).  *_destroy(NULL) is a no-op.
+ *   - pd_prefill / pd_decode_step only enqueue work on the given stream (a hipStream_t passed as
+ *     void*, NULL = default stream) and do not synchronise; small host arrays (cu_seqlens, slots)
+ *     are consumed during the call.  A layer's scratch workspace is shared by all calls on that
+ *     layer: calls on one layer must be ordered on one stream.  The workspace grows on demand
+ *     (device allocation, which may synchronise); pd_layer_reserve sizes it ahead of time.
+ *   - Tensors are row-major; "hidden" rows are hidden-state vectors, not token ids.  Element type
+ *     is the layer's dtype (fp32 or bf16) unless stated otherwise.
+ *   - On error nothing is enqueued, no output is written and no state changes; pd_last_error()
+ *     returns a thread-local description of the last failure.
+ *   - Throughputs are tokens per second, times are seconds, lengths are (mean) token counts.
+ */
+#ifndef PD_H
+#define PD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PD_OK = 0,
+    PD_ERR_INVALID_ARG = 1,
+    PD_ERR_SHAPE = 2,
+    PD_ERR_DTYPE = 3,
+    PD_ERR_OOM = 4,
+    PD_ERR_DEVICE = 5,
+    PD_ERR_KV_CAPACITY = 6,
+    PD_ERR_TTFT_INFEASIBLE = 7,
+    PD_ERR_TPOT_INFEASIBLE = 8
+} pd_status;
+
+typedef enum { PD_F32 = 0, PD_BF16 = 1 } pd_dtype;
+
+/*
+ * One pre-norm decoder layer (the unit whose forward time the method benchmarks; the paper's
+ * Introduction characterises prefill as compute-bound and decode as memory-bandwidth-bound):
+ *   y = rmsnorm(x, g_attn); q,k,v = y Wq^T, y Wk^T, y Wv^T; rotary embedding of q,k (rotate-half
+ *   pairing, angle = position * rope_base^(-2i/head_dim)); causal grouped-query attention with
+ *   scale 1/sqrt(head_dim) (query head h reads kv head h / (n_q_heads/n_kv_heads));
+ *   h = x + o Wo^T; y2 = rmsnorm(h, g_ffn); out = h + (silu(y2 Wg^T) * (y2 Wu^T)) Wd^T,
+ *   or, when n_experts > 0, out = h + sum over the top_k experts of w_e FFN_e(y2) with
+ *   p = softmax(router logits over all experts), ties to the lower index, w = p_top / sum p_top.
+ * rmsnorm(x, g)_i = x_i / sqrt(mean_j x_j^2 + rms_eps) * g_i.
+ */
+typedef struct {
+    int32_t d_model, n_q_heads, n_kv_heads, head_dim, d_ff;
+    int32_t n_experts; /* 0 = dense FFN */
+    int32_t top_k;     /* used when n_experts > 0 */
+    float rms_eps, rope_base;
+    int32_t dtype;     /* pd_dtype */
+} pd_layer_config;
+
+/* Device pointers, each [out_features, in_features] row-major in the layer's dtype. */
+typedef struct {
+    const void *g_attn;   /* [d] */
+    const void *w_q;      /* [n_q_heads*head_dim, d] */
+    const void *w_k;      /* [n_kv_heads*head_dim, d] */
+    const void *w_v;      /* [n_kv_heads*head_dim, d] */
+    const void *w_o;      /* [d, n_q_heads*head_dim] */
+    const void *g_ffn;    /* [d] */
+    const void *w_gate;   /* [F, d]   (MoE: [E, F, d]) */
+    const void *w_up;     /* [F, d]   (MoE: [E, F, d]) */
+    const void *w_down;   /* [d, F]   (MoE: [E, d, F]) */
+    const void *w_router; /* [E, d] or NULL (then router logits must be passed per call) */
+} pd_layer_weights;
+
+typedef struct pd_layer pd_layer;       /* opaque */
+typedef struct pd_kv_cache pd_kv_cache; /* opaque */
+
+/*
+ * Creates a layer on the current device.  The weights are copied (and repacked) into memory the
+ * layer owns; the caller's buffers may be released once the call returns (the call synchronises).
+ * Errors: PD_ERR_INVALID_ARG (NULL), PD_ERR_SHAPE (non-positive sizes, odd head_dim, n_q_heads not
+ * a multiple of n_kv_heads, top_k > n_experts, n_experts > 64, head_dim > 256), PD_ERR_DTYPE,
+ * PD_ERR_OOM, PD_ERR_DEVICE.
+ */
+pd_status pd_layer_create(const pd_layer_config *cfg, const pd_layer_weights *w, pd_layer **out);
+void pd_layer_destroy(pd_layer *layer);
+
+/* Pre-sizes the layer's workspace for calls of up to max_tokens rows (prefill T or decode B). */
+pd_status pd_layer_reserve(pd_layer *layer, int32_t max_tokens);
+
+/*
+ * A KV cache of max_seqs slots, each holding up to max_len positions of rotated keys and values
+ * for every kv head, in the layer's dtype.  The memory layout is private to the library.
+ */
+pd_status pd_kv_cache_create(const pd_layer *layer, int32_t max_seqs, int32_t max_len,
+                             pd_kv_cache **out);
+void pd_kv_cache_destroy(pd_kv_cache *cache);
+
+/*
+ * Benchmark fill: copies len positions of (already rotated) keys and values, each a device tensor
+ * [n_kv_heads, len, head_dim], into a slot and sets its length.  Enqueued on `stream`.
+ * Errors: PD_ERR_INVALID_ARG (bad slot, NULL), PD_ERR_KV_CAPACITY (len > max_len).
+ */
+pd_status pd_kv_cache_set(pd_kv_cache *cache, int32_t slot, int32_t len, const void *k,
+                          const void *v, void *stream);
+/* Sets a slot's length without touching its contents (0 <= len <= max_len); used to rewind a
+ * cache between timed repetitions of the same decode step.  Enqueued on `stream`. */
+pd_status pd_kv_cache_set_len(pd_kv_cache *cache, int32_t slot, int32_t len, void *stream);
+/* Reads a slot's length (host-side mirror; no device access). */
+pd_status pd_kv_cache_len(const pd_kv_cache *cache, int32_t slot, int32_t *len);
+/* Debug/test read-back of one slot's first len positions into device tensors [n_kv_heads, len, head_dim]. */
+pd_status pd_kv_cache_get(const pd_kv_cache *cache, int32_t slot, int32_t len, void *k, void *v,
+                          void *stream);
+
+/*
+ * Prefill: the layer forward over a packed batch of n_seqs sequences (T = cu_seqlens[n_seqs]
+ * rows; sequence s owns rows cu_seqlens[s] .. cu_seqlens[s+1]-1 and its positions start at 0).
+ * This is the operation whose saturated throughput is the paper's maximum prefill throughput
+ * (section "Acquire prefill throughput under TTFT constraints").
+ */
+typedef struct {
+    const void *hidden;          /* device [T, d] */
+    int32_t n_seqs;              /* 1 .. 4096 */
+    const int32_t *cu_seqlens;   /* host [n_seqs + 1], non-decreasing, cu_seqlens[0] = 0 */
+    const int32_t *slots;        /* host [n_seqs] distinct cache slots, or NULL = keep no KV */
+    const void *router_logits;   /* device fp32 [T, n_experts], or NULL (MoE: use w_router) */
+} pd_tokens;
+
+/*
+ * Writes out_hidden (device [T, d]).  With a cache and slots, stores each sequence's rotated keys
+ * and values into its slot and sets the slot's length to the sequence length.
+ * Errors: PD_ERR_INVALID_ARG, PD_ERR_SHAPE (bad cu_seqlens), PD_ERR_KV_CAPACITY (a sequence longer
+ * than max_len), PD_ERR_OOM / PD_ERR_DEVICE (workspace growth, launch failure).
+ */
+pd_status pd_prefill(pd_layer *layer, const pd_tokens *tokens, pd_kv_cache *cache /* nullable */,
+                     void *out_hidden, void *stream);
+
+/*
+ * One decode step (section "Acquire decode throughput under TPOT constraints": TPOT is measured as
+ * a function of the decode batch).  Row b is the newest token of the sequence in slots[b], at
+ * position p = len(slot).  Its rotated key and its value are appended at p, the row attends over
+ * positions 0..p, and the slot's length becomes p + 1.
+ */
+typedef struct {
+    const void *hidden;          /* device [B, d] */
+    int32_t batch;               /* B, 1 .. 4096 */
+    const int32_t *slots;        /* host [B], distinct */
+    const void *router_logits;   /* device fp32 [B, n_experts], or NULL */
+} pd_batch;
+
+/* Errors as pd_prefill; PD_ERR_KV_CAPACITY if any listed slot is full (checked before anything is
+ * enqueued). */
+pd_status pd_decode_step(pd_layer *layer, const pd_batch *batch, pd_kv_cache *cache,
+                         void *out_hidden, void *stream);
+
+/* MoE only: device-to-device copy of the experts chosen by the last call on this layer, int32
+ * [rows, top_k], into `expert_idx` (device).  Enqueued on `stream`. */
+pd_status pd_last_expert_choice(const pd_layer *layer, int32_t rows, void *expert_idx, void *stream);
+
+/*
+ * Allocation model (host only; needs no GPU).
+ *   T_s        = ttft_slo - t_overhead                                         Eq. (12)
+ *   TP_prefill = prefill_max_tps - l_in / T_s                                  Eq. (13)
+ *   b*         = largest measured batch with TPOT <= tpot_slo (duplicates of a batch keep their
+ *                smallest TPOT), TP_decode = b* / TPOT(b*)
+ *   N_prefill  = (tp_total l_in)  / ((l_in + l_out) TP_prefill)                Eq. (5)
+ *   N_decode   = (tp_total l_out) / ((l_in + l_out) TP_decode)                 Eq. (6)
+ *   R          = (l_in TP_decode) / (l_out TP_prefill)                         Eq. (7)
+ * evaluated in IEEE double in exactly this order and parenthesisation.
+ * Integer counts: rounding 0 = max(1, floor(N + 0.5)) (reproduces the paper's worked example),
+ * rounding 1 = max(1, ceil(N)).
+ */
+typedef struct {
+    double prefill_max_tps;       /* measured maximum prefill tokens/s of one instance at this l_in */
+    int32_t n_decode;             /* points on the measured TPOT-versus-batch curve */
+    const int32_t *decode_batch;  /* host [n_decode], > 0, any order */
+    const double *decode_tpot_s;  /* host [n_decode], > 0 */
+    double t_overhead_s;          /* Eq. (8) overhead term, >= 0 */
+    int32_t rounding;             /* 0 nearest (half up), 1 ceiling */
+} pd_measured_curves;
+
+typedef struct {
+    double tp_prefill_eff, tp_decode_eff;
+    int32_t decode_batch;
+    double decode_tpot_s;
+    double n_prefill_real, n_decode_real, ratio_pd;
+    int32_t n_prefill, n_decode;
+    int32_t curve_non_monotone;   /* 1 if TPOT does not increase with batch somewhere (warning only) */
+} pd_allocation;
+
+/*
+ * Errors: PD_ERR_INVALID_ARG (NULL, non-finite or non-positive input, empty or malformed curve),
+ * PD_ERR_TTFT_INFEASIBLE (T_s <= 0 or Eq. (13) <= 0), PD_ERR_TPOT_INFEASIBLE (no point meets the
+ * target).  *out is untouched on error.
+ */
+pd_status pd_allocate(double tp_total_tps, double l_in, double l_out, double ttft_slo_s,
+                      double tpot_slo_s, const pd_measured_curves *curves, pd_allocation *out);
+
+/*
+ * Queue check helpers (host only).  pd_fifo_replay serves n requests in arrival order on one
+ * server in virtual time, D_i = max(A_i, D_{i-1}) + S_i, and writes each request's sojourn time
+ * D_i - A_i (the queueing + computation part of TTFT, Eq. (8)).  pd_mm1_sojourn is Eq. (12),
+ * 1 / (mu - lambda) with mu = prefill_max_tps / l_in (Eq. (9)); PD_ERR_TTFT_INFEASIBLE when
+ * lambda >= mu.
+ */
+pd_status pd_fifo_replay(int32_t n, const double *arrival_s, const double *service_s,
+                         double *sojourn_s);
+pd_status pd_mm1_sojourn(double prefill_max_tps, double l_in, double lambda_rps, double *t_s);
+
+const char *pd_status_string(pd_status s);
+const char *pd_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PD_H */

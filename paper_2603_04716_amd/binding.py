@@ -1,0 +1,212 @@
+"""ctypes binding of include/pd.h: same entry-point names, argument marshalling only.
+
+Device tensors are torch tensors (used purely as owners of device memory); their raw pointers and
+the current torch stream are handed to the library.  Every step of the path runs inside
+libpd_mi355x.so; if that library is missing the import fails.
+"""
+import ctypes as C
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libpd_mi355x.so")
+
+PD_OK = 0
+PD_ERR_INVALID_ARG, PD_ERR_SHAPE, PD_ERR_DTYPE, PD_ERR_OOM, PD_ERR_DEVICE = 1, 2, 3, 4, 5
+PD_ERR_KV_CAPACITY, PD_ERR_TTFT_INFEASIBLE, PD_ERR_TPOT_INFEASIBLE = 6, 7, 8
+PD_F32, PD_BF16 = 0, 1
+
+EXPORTS = [
+    "pd_layer_create", "pd_layer_destroy", "pd_layer_reserve", "pd_kv_cache_create",
+    "pd_kv_cache_destroy", "pd_kv_cache_set", "pd_kv_cache_set_len", "pd_kv_cache_len",
+    "pd_kv_cache_get", "pd_prefill", "pd_decode_step", "pd_last_expert_choice", "pd_allocate",
+    "pd_fifo_replay", "pd_mm1_sojourn", "pd_status_string", "pd_last_error",
+]
+
+
+class PdError(RuntimeError):
+    def __init__(self, status, msg):
+        super().__init__(f"pd status {status}: {msg}")
+        self.status = status
+
+
+class pd_layer_config(C.Structure):
+    _fields_ = [("d_model", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("d_ff", C.c_int32), ("n_experts", C.c_int32),
+                ("top_k", C.c_int32), ("rms_eps", C.c_float), ("rope_base", C.c_float),
+                ("dtype", C.c_int32)]
+
+
+_WNAMES = ["g_attn", "w_q", "w_k", "w_v", "w_o", "g_ffn", "w_gate", "w_up", "w_down", "w_router"]
+
+
+class pd_layer_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _WNAMES]
+
+
+class pd_tokens(C.Structure):
+    _fields_ = [("hidden", C.c_void_p), ("n_seqs", C.c_int32), ("cu_seqlens", C.POINTER(C.c_int32)),
+                ("slots", C.POINTER(C.c_int32)), ("router_logits", C.c_void_p)]
+
+
+class pd_batch(C.Structure):
+    _fields_ = [("hidden", C.c_void_p), ("batch", C.c_int32), ("slots", C.POINTER(C.c_int32)),
+                ("router_logits", C.c_void_p)]
+
+
+class pd_measured_curves(C.Structure):
+    _fields_ = [("prefill_max_tps", C.c_double), ("n_decode", C.c_int32),
+                ("decode_batch", C.POINTER(C.c_int32)), ("decode_tpot_s", C.POINTER(C.c_double)),
+                ("t_overhead_s", C.c_double), ("rounding", C.c_int32)]
+
+
+class pd_allocation(C.Structure):
+    _fields_ = [("tp_prefill_eff", C.c_double), ("tp_decode_eff", C.c_double),
+                ("decode_batch", C.c_int32), ("decode_tpot_s", C.c_double),
+                ("n_prefill_real", C.c_double), ("n_decode_real", C.c_double),
+                ("ratio_pd", C.c_double), ("n_prefill", C.c_int32), ("n_decode", C.c_int32),
+                ("curve_non_monotone", C.c_int32)]
+
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2603_04716_amd.build` "
+                      "(there is no fallback path)")
+lib = C.CDLL(LIB_PATH)
+for _n in EXPORTS:
+    getattr(lib, _n)          # raises AttributeError if the library lacks a declared symbol
+lib.pd_status_string.restype = C.c_char_p
+lib.pd_last_error.restype = C.c_char_p
+lib.pd_layer_destroy.restype = None
+lib.pd_kv_cache_destroy.restype = None
+lib.pd_layer_destroy.argtypes = [C.c_void_p]
+lib.pd_kv_cache_destroy.argtypes = [C.c_void_p]
+lib.pd_allocate.argtypes = [C.c_double] * 5 + [C.POINTER(pd_measured_curves), C.POINTER(pd_allocation)]
+lib.pd_mm1_sojourn.argtypes = [C.c_double] * 3 + [C.POINTER(C.c_double)]
+
+
+def _check(status):
+    if status != PD_OK:
+        raise PdError(status, lib.pd_last_error().decode())
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _i32_array(values):
+    values = [int(v) for v in values]
+    return (C.c_int32 * max(len(values), 1))(*values)
+
+
+def make_config(cfg: dict) -> pd_layer_config:
+    return pd_layer_config(cfg["d_model"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"],
+                           cfg["d_ff"], cfg.get("n_experts", 0), cfg.get("top_k", 0),
+                           float(cfg.get("rms_eps", 1e-6)), float(cfg.get("rope_base", 10000.0)),
+                           PD_BF16 if cfg.get("dtype", "f32") == "bf16" else PD_F32)
+
+
+# ---- device entry points ---------------------------------------------------------------------------
+
+def pd_layer_create(cfg: dict, weights: dict):
+    """weights: name -> contiguous device torch tensor in the layer's dtype."""
+    w = pd_layer_weights()
+    for n in _WNAMES:
+        t = weights.get(n)
+        setattr(w, n, None if t is None else t.data_ptr())
+    h = C.c_void_p()
+    c = make_config(cfg)
+    _check(lib.pd_layer_create(C.byref(c), C.byref(w), C.byref(h)))
+    return h
+
+
+def pd_layer_destroy(layer):
+    lib.pd_layer_destroy(layer)
+
+
+def pd_layer_reserve(layer, max_tokens):
+    _check(lib.pd_layer_reserve(layer, C.c_int32(max_tokens)))
+
+
+def pd_kv_cache_create(layer, max_seqs, max_len):
+    h = C.c_void_p()
+    _check(lib.pd_kv_cache_create(layer, C.c_int32(max_seqs), C.c_int32(max_len), C.byref(h)))
+    return h
+
+
+def pd_kv_cache_destroy(cache):
+    lib.pd_kv_cache_destroy(cache)
+
+
+def pd_kv_cache_set(cache, slot, k, v):
+    """k, v: device tensors [Hkv, len, hd]."""
+    _check(lib.pd_kv_cache_set(cache, C.c_int32(slot), C.c_int32(k.shape[1]), _ptr(k), _ptr(v), _stream()))
+
+
+def pd_kv_cache_set_len(cache, slot, length):
+    _check(lib.pd_kv_cache_set_len(cache, C.c_int32(slot), C.c_int32(length), _stream()))
+
+
+def pd_kv_cache_len(cache, slot):
+    n = C.c_int32()
+    _check(lib.pd_kv_cache_len(cache, C.c_int32(slot), C.byref(n)))
+    return n.value
+
+
+def pd_kv_cache_get(cache, slot, k, v):
+    _check(lib.pd_kv_cache_get(cache, C.c_int32(slot), C.c_int32(k.shape[1]), _ptr(k), _ptr(v), _stream()))
+
+
+def pd_prefill(layer, hidden, cu_seqlens, out, cache=None, slots=None, router_logits=None):
+    cu = _i32_array(cu_seqlens)
+    sl = None if slots is None else _i32_array(slots)
+    tk = pd_tokens(None if hidden is None else hidden.data_ptr(), len(cu_seqlens) - 1, cu,
+                   sl if sl is not None else C.POINTER(C.c_int32)(),
+                   None if router_logits is None else router_logits.data_ptr())
+    _check(lib.pd_prefill(layer, C.byref(tk), cache, _ptr(out), _stream()))
+    return out
+
+
+def pd_decode_step(layer, hidden, slots, cache, out, router_logits=None):
+    sl = _i32_array(slots)
+    bt = pd_batch(hidden.data_ptr(), len(slots), sl,
+                  None if router_logits is None else router_logits.data_ptr())
+    _check(lib.pd_decode_step(layer, C.byref(bt), cache, _ptr(out), _stream()))
+    return out
+
+
+def pd_last_expert_choice(layer, rows, expert_idx):
+    _check(lib.pd_last_expert_choice(layer, C.c_int32(rows), _ptr(expert_idx), _stream()))
+    return expert_idx
+
+
+# ---- host entry points -----------------------------------------------------------------------------
+
+def pd_allocate(tp_total_tps, l_in, l_out, ttft_slo_s, tpot_slo_s, prefill_max_tps, decode_batch,
+                decode_tpot_s, t_overhead_s=0.0, rounding=0):
+    n = len(decode_batch)
+    b = _i32_array(decode_batch)
+    t = (C.c_double * max(n, 1))(*[float(x) for x in decode_tpot_s])
+    cv = pd_measured_curves(float(prefill_max_tps), n, b, t, float(t_overhead_s), int(rounding))
+    out = pd_allocation()
+    _check(lib.pd_allocate(float(tp_total_tps), float(l_in), float(l_out), float(ttft_slo_s),
+                           float(tpot_slo_s), C.byref(cv), C.byref(out)))
+    return {f[0]: getattr(out, f[0]) for f in pd_allocation._fields_}
+
+
+def pd_fifo_replay(arrival_s, service_s):
+    n = len(arrival_s)
+    a = (C.c_double * max(n, 1))(*[float(x) for x in arrival_s])
+    s = (C.c_double * max(n, 1))(*[float(x) for x in service_s])
+    o = (C.c_double * max(n, 1))()
+    _check(lib.pd_fifo_replay(C.c_int32(n), a, s, o))
+    return [o[i] for i in range(n)]
+
+
+def pd_mm1_sojourn(prefill_max_tps, l_in, lambda_rps):
+    t = C.c_double()
+    _check(lib.pd_mm1_sojourn(float(prefill_max_tps), float(l_in), float(lambda_rps), C.byref(t)))
+    return t.value

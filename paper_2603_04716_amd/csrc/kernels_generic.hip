@@ -1,0 +1,498 @@
+// Shape-generic kernels (fp32 or bf16 storage, fp32 arithmetic): RMSNorm, a tiled FMA GEMM with
+// fused epilogues, rotary embedding + KV-cache write, wave-per-row attention, and the small
+// metadata kernels.  These carry the fp32 parity configuration and any bf16 shape the MFMA
+// kernels do not cover.
+#include "pd_internal.h"
+
+namespace pd {
+
+// ---------------------------------------------------------------------------------------------
+// RMSNorm: y = x * rsqrt(mean(x^2) + eps) * g.  One 256-thread block per row.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const T *__restrict__ x,
+                                                      const T *__restrict__ g, T *__restrict__ y,
+                                                      int d, float eps)
+{
+    __shared__ float red[4];
+    const T *xr = x + (size_t)blockIdx.x * d;
+    T *yr = y + (size_t)blockIdx.x * d;
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < d; i += 256) {
+        float v = Elem<T>::ld(xr + i);
+        ss += v * v;
+    }
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    float tot = red[0] + red[1] + red[2] + red[3];
+    float inv = rsqrtf(tot / (float)d + eps);
+    for (int i = threadIdx.x; i < d; i += 256)
+        Elem<T>::st(yr + i, Elem<T>::ld(xr + i) * inv * Elem<T>::ld(g + i));
+}
+
+// bf16 rows with d % 8 == 0: 16-byte loads and stores.
+__global__ __launch_bounds__(256) void rmsnorm_bf16_vec_kernel(const uint4 *__restrict__ x,
+                                                               const uint4 *__restrict__ g,
+                                                               uint4 *__restrict__ y, int d8,
+                                                               float d_inv, float eps)
+{
+    __shared__ float red[4];
+    const uint4 *xr = x + (size_t)blockIdx.x * d8;
+    uint4 *yr = y + (size_t)blockIdx.x * d8;
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < d8; i += 256) {
+        uint4 v = xr[i];
+        uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float a = bfbits2f(w[j] & 0xffffu), b = bfbits2f(w[j] >> 16);
+            ss += a * a + b * b;
+        }
+    }
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    float inv = rsqrtf((red[0] + red[1] + red[2] + red[3]) * d_inv + eps);
+    for (int i = threadIdx.x; i < d8; i += 256) {
+        uint4 v = xr[i], gg = g[i];
+        uint32_t w[4] = {v.x, v.y, v.z, v.w}, gw[4] = {gg.x, gg.y, gg.z, gg.w}, o[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float a = bfbits2f(w[j] & 0xffffu) * inv * bfbits2f(gw[j] & 0xffffu);
+            float b = bfbits2f(w[j] >> 16) * inv * bfbits2f(gw[j] >> 16);
+            o[j] = pack2bf(a, b);
+        }
+        yr[i] = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+}
+
+hipError_t launch_rmsnorm(int dtype, const void *x, const void *g, void *y, int T, int d, float eps,
+                          hipStream_t s)
+{
+    if (T <= 0) return hipSuccess;
+    if (dtype == PD_F32) {
+        rmsnorm_kernel<float><<<T, 256, 0, s>>>((const float *)x, (const float *)g, (float *)y, d, eps);
+    } else if (d % 8 == 0) {
+        rmsnorm_bf16_vec_kernel<<<T, 256, 0, s>>>((const uint4 *)x, (const uint4 *)g, (uint4 *)y,
+                                                  d / 8, 1.0f / (float)d, eps);
+    } else {
+        rmsnorm_kernel<bf16_t><<<T, 256, 0, s>>>((const bf16_t *)x, (const bf16_t *)g, (bf16_t *)y, d, eps);
+    }
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Generic GEMM: 64x64 tile, K step 16, 256 threads, 4x4 outputs per thread, fp32 accumulate.
+// ---------------------------------------------------------------------------------------------
+constexpr int GT = 64, GK = 16;
+
+__device__ __forceinline__ float silu_f(float z) { return z / (1.0f + expf(-z)); }
+
+template <typename T, int EPI>
+__global__ __launch_bounds__(256) void gemm_generic_kernel(GemmArgs a)
+{
+    __shared__ float As[GK][GT + 1];
+    __shared__ float Bs[GK][GT + 1];
+    __shared__ float B1s[EPI == EPI_SWIGLU ? GK : 1][GT + 1];
+
+    // locate this block's group and row range
+    int row0, row_end, group = 0;
+    {
+        int vt = blockIdx.y;
+        if (a.group_offsets) {
+            int acc = 0;
+            row0 = -1;
+            row_end = 0;
+            for (int g = 0; g < a.n_groups; ++g) {
+                int lo = a.group_offsets[g], hi = a.group_offsets[g + 1];
+                int nt = (hi - lo + GT - 1) / GT;
+                if (vt < acc + nt) {
+                    group = g;
+                    row0 = lo + (vt - acc) * GT;
+                    row_end = hi;
+                    break;
+                }
+                acc += nt;
+            }
+            if (row0 < 0) return;
+        } else {
+            row0 = vt * GT;
+            row_end = a.M;
+            if (row0 >= a.M) return;
+        }
+    }
+    const int col0 = blockIdx.x * GT;
+    const T *A = (const T *)a.A;
+    const T *B = (const T *)a.B + (size_t)group * a.b_group_stride;
+    const T *B1 = EPI == EPI_SWIGLU ? (a.interleaved ? B : (const T *)a.B1 + (size_t)group * a.b_group_stride) : nullptr;
+
+    const int tid = threadIdx.x;
+    const int tx = tid & 15, ty = tid >> 4;
+    float acc[4][4] = {}, acc1[4][4] = {};
+
+    // loader mapping: 64 rows x 16 k = 1024 elements, 4 per thread
+    const int lr = tid >> 2;          // 0..63 row in tile
+    const int lk = (tid & 3) * 4;     // 0,4,8,12
+    int arow = row0 + lr;
+    const bool arow_ok = arow < row_end;
+    size_t a_off = 0;
+    if (arow_ok) a_off = (size_t)(a.a_gather ? a.a_gather[arow] : arow) * a.lda;
+    const int bcol = col0 + lr;
+    const bool bcol_ok = bcol < a.N;
+    size_t b_off = 0, b1_off = 0;
+    if (bcol_ok) {
+        if (EPI == EPI_SWIGLU && a.interleaved) {
+            int pr = (bcol >> 5) * 64 + (bcol & 31);
+            b_off = (size_t)pr * a.ldb;
+            b1_off = (size_t)(pr + 32) * a.ldb;
+        } else {
+            b_off = (size_t)bcol * a.ldb;
+            b1_off = b_off;
+        }
+    }
+
+    for (int k0 = 0; k0 < a.K; k0 += GK) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int k = k0 + lk + j;
+            bool kok = k < a.K;
+            As[lk + j][lr] = (arow_ok && kok) ? Elem<T>::ld(A + a_off + k) : 0.f;
+            Bs[lk + j][lr] = (bcol_ok && kok) ? Elem<T>::ld(B + b_off + k) : 0.f;
+            if (EPI == EPI_SWIGLU) B1s[lk + j][lr] = (bcol_ok && kok) ? Elem<T>::ld(B1 + b1_off + k) : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < GK; ++k) {
+            float av[4], bv[4], b1v[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                av[i] = As[k][ty * 4 + i];
+                bv[i] = Bs[k][tx * 4 + i];
+                if (EPI == EPI_SWIGLU) b1v[i] = B1s[k][tx * 4 + i];
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    acc[i][j] = fmaf(av[i], bv[j], acc[i][j]);
+                    if (EPI == EPI_SWIGLU) acc1[i][j] = fmaf(av[i], b1v[j], acc1[i][j]);
+                }
+        }
+        __syncthreads();
+    }
+
+    T *C = (T *)a.C;
+    const T *R = (const T *)a.R;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int r = row0 + ty * 4 + i;
+        if (r >= row_end) continue;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            int c = col0 + tx * 4 + j;
+            if (c >= a.N) continue;
+            float v = acc[i][j];
+            if (EPI == EPI_RESIDUAL) v += Elem<T>::ld(R + (size_t)r * a.ldr + c);
+            if (EPI == EPI_SWIGLU) v = silu_f(v) * acc1[i][j];
+            Elem<T>::st(C + (size_t)r * a.ldc + c, v);
+        }
+    }
+}
+
+template <typename T>
+static hipError_t launch_gemm_generic_t(const GemmArgs &a, hipStream_t s)
+{
+    if (a.M <= 0 || a.N <= 0) return hipSuccess;
+    int mt = (a.M + GT - 1) / GT + (a.group_offsets ? a.n_groups : 0);
+    dim3 grid((a.N + GT - 1) / GT, mt);
+    switch (a.epilogue) {
+    case EPI_NONE: gemm_generic_kernel<T, EPI_NONE><<<grid, 256, 0, s>>>(a); break;
+    case EPI_RESIDUAL: gemm_generic_kernel<T, EPI_RESIDUAL><<<grid, 256, 0, s>>>(a); break;
+    default: gemm_generic_kernel<T, EPI_SWIGLU><<<grid, 256, 0, s>>>(a); break;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_generic(int dtype, const GemmArgs &a, hipStream_t s)
+{
+    return dtype == PD_F32 ? launch_gemm_generic_t<float>(a, s) : launch_gemm_generic_t<bf16_t>(a, s);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Metadata kernels.
+// ---------------------------------------------------------------------------------------------
+__global__ void write_ints_kernel(int32_t *dst, IntChunk c, int n)
+{
+    int i = threadIdx.x;
+    if (i < n) dst[i] = c.v[i];
+}
+
+hipError_t launch_write_ints(int32_t *dst, const int32_t *host_src, int n, hipStream_t s)
+{
+    for (int off = 0; off < n; off += 256) {
+        IntChunk c;
+        int m = n - off < 256 ? n - off : 256;
+        for (int i = 0; i < m; ++i) c.v[i] = host_src[off + i];
+        write_ints_kernel<<<1, 256, 0, s>>>(dst + off, c, m);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+__global__ void token_meta_kernel(const int32_t *__restrict__ cu, const int32_t *__restrict__ slots,
+                                  int n_seqs, int T, int32_t *__restrict__ tok_seq,
+                                  int32_t *__restrict__ tok_pos, int32_t *__restrict__ tok_slot)
+{
+    int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= T) return;
+    int lo = 0, hi = n_seqs;  // largest s with cu[s] <= t
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (cu[mid] <= t) lo = mid; else hi = mid;
+    }
+    tok_seq[t] = lo;
+    tok_pos[t] = t - cu[lo];
+    if (slots) tok_slot[t] = slots[lo];
+}
+
+hipError_t launch_token_meta(const int32_t *d_cu, const int32_t *d_slots, int n_seqs, int T,
+                             int32_t *tok_seq, int32_t *tok_pos, int32_t *tok_slot, hipStream_t s)
+{
+    if (T <= 0) return hipSuccess;
+    token_meta_kernel<<<(T + 255) / 256, 256, 0, s>>>(d_cu, d_slots, n_seqs, T, tok_seq, tok_pos,
+                                                      tok_slot);
+    return hipGetLastError();
+}
+
+__global__ void decode_meta_kernel(const int32_t *__restrict__ slots, int B, int32_t *len,
+                                   int32_t *pos)
+{
+    int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    int s = slots[b];
+    int p = len[s];
+    pos[b] = p;
+    len[s] = p + 1;  // slots are distinct
+}
+
+hipError_t launch_decode_meta(const int32_t *d_slots, int B, int32_t *d_len, int32_t *d_pos,
+                              hipStream_t s)
+{
+    decode_meta_kernel<<<(B + 255) / 256, 256, 0, s>>>(d_slots, B, d_len, d_pos);
+    return hipGetLastError();
+}
+
+__global__ void prefill_set_len_kernel(const int32_t *__restrict__ slots,
+                                       const int32_t *__restrict__ cu, int n, int32_t *len)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) len[slots[i]] = cu[i + 1] - cu[i];
+}
+
+hipError_t launch_prefill_set_len(const int32_t *d_slots, const int32_t *d_cu, int n_seqs,
+                                  int32_t *d_len, hipStream_t s)
+{
+    prefill_set_len_kernel<<<(n_seqs + 255) / 256, 256, 0, s>>>(d_slots, d_cu, n_seqs, d_len);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Rotary embedding (rotate-half pairing) of q and k in place + write of k, v into the cache.
+// One block per token row.  The angle pos * inv_freq[i] and its sine / cosine are evaluated in
+// double so that the fp32 configuration stays inside its 1e-5 budget at any position.
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void rope_kv_kernel(RopeArgs a)
+{
+    __shared__ float cs[128], sn[128];
+    const int t = blockIdx.x;
+    const int half = a.hd >> 1;
+    const int pos = a.tok_pos[t];
+    for (int i = threadIdx.x; i < half; i += 256) {
+        double ang = (double)pos * a.inv_freq[i];
+        double sv, cv;
+        sincos(ang, &sv, &cv);
+        cs[i] = (float)cv;
+        sn[i] = (float)sv;
+    }
+    __syncthreads();
+    T *row = (T *)a.qkv + (size_t)t * a.ld;
+    const int slot = a.tok_slot ? a.tok_slot[t] : -1;
+    const int n_rot = (a.Hq + a.Hkv) * half;
+    for (int idx = threadIdx.x; idx < n_rot; idx += 256) {
+        int h = idx / half, i = idx - h * half;
+        T *v = row + (size_t)h * a.hd;
+        float x0 = Elem<T>::ld(v + i), x1 = Elem<T>::ld(v + i + half);
+        float y0 = x0 * cs[i] - x1 * sn[i];
+        float y1 = x1 * cs[i] + x0 * sn[i];
+        Elem<T>::st(v + i, y0);
+        Elem<T>::st(v + i + half, y1);
+        if (slot >= 0 && h >= a.Hq) {
+            int g = h - a.Hq;
+            T *kc = (T *)a.k_cache + (((size_t)slot * a.Hkv + g) * a.max_len + pos) * a.hd;
+            Elem<T>::st(kc + i, y0);
+            Elem<T>::st(kc + i + half, y1);
+        }
+    }
+    if (slot >= 0) {
+        const T *vsrc = row + (size_t)(a.Hq + a.Hkv) * a.hd;
+        for (int idx = threadIdx.x; idx < a.Hkv * a.hd; idx += 256) {
+            int g = idx / a.hd, i = idx - g * a.hd;
+            T *vc = (T *)a.v_cache + (((size_t)slot * a.Hkv + g) * a.max_len + pos) * a.hd;
+            vc[i] = vsrc[idx];
+        }
+    }
+}
+
+hipError_t launch_rope_kv(int dtype, const RopeArgs &a, hipStream_t s)
+{
+    if (a.T <= 0) return hipSuccess;
+    if (dtype == PD_F32) rope_kv_kernel<float><<<a.T, 256, 0, s>>>(a);
+    else rope_kv_kernel<bf16_t><<<a.T, 256, 0, s>>>(a);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Generic attention: one wavefront per (row, query head).  Lanes split the keys of a 64-key
+// chunk for the scores and split head_dim for the weighted sum of values; online softmax across
+// chunks.  head_dim <= 256.
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void attn_generic_kernel(AttnArgs a)
+{
+    __shared__ float qs[4][256];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const long long item = (long long)blockIdx.x * 4 + wave;
+    const long long n_items = (long long)a.T * a.Hq;
+    const bool active = item < n_items;
+    const int t = active ? (int)(item / a.Hq) : 0;
+    const int h = active ? (int)(item - (long long)t * a.Hq) : 0;
+    const int g = h / (a.Hq / a.Hkv);
+    const int hd = a.hd;
+    const T *q = (const T *)a.qkv + (size_t)t * a.ld + (size_t)h * hd;
+    for (int i = lane; i < hd; i += 64) qs[wave][i] = active ? Elem<T>::ld(q + i) * a.scale : 0.f;
+    __syncthreads();
+    if (!active) return;
+
+    const int pos = a.tok_pos[t];
+    const int n_keys = pos + 1;
+    const T *Kb, *Vb;
+    size_t stride;
+    if (a.decode) {
+        size_t base = (((size_t)a.tok_slot[t] * a.Hkv + g) * a.max_len) * hd;
+        Kb = (const T *)a.k_cache + base;
+        Vb = (const T *)a.v_cache + base;
+        stride = (size_t)hd;
+    } else {
+        const T *first = (const T *)a.qkv + (size_t)(t - pos) * a.ld;
+        Kb = first + (size_t)(a.Hq + g) * hd;
+        Vb = first + (size_t)(a.Hq + a.Hkv + g) * hd;
+        stride = (size_t)a.ld;
+    }
+
+    float m = -INFINITY, l = 0.f;
+    float o[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int c0 = 0; c0 < n_keys; c0 += 64) {
+        int s = c0 + lane;
+        float sc = -INFINITY;
+        if (s < n_keys) {
+            const T *kr = Kb + (size_t)s * stride;
+            float acc = 0.f;
+            for (int i = 0; i < hd; ++i) acc = fmaf(qs[wave][i], Elem<T>::ld(kr + i), acc);
+            sc = acc;
+        }
+        float m_new = fmaxf(m, wave_max(sc));
+        float p = (s < n_keys) ? expf(sc - m_new) : 0.f;
+        float corr = expf(m - m_new);   // m = -inf on the first chunk -> 0
+        l = l * corr + wave_sum(p);
+        m = m_new;
+        int cnt = n_keys - c0 < 64 ? n_keys - c0 : 64;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] *= corr;
+        for (int j = 0; j < cnt; ++j) {
+            float pj = __shfl(p, j, 64);
+            const T *vr = Vb + (size_t)(c0 + j) * stride;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                int i = lane + 64 * e;
+                if (i < hd) o[e] = fmaf(pj, Elem<T>::ld(vr + i), o[e]);
+            }
+        }
+    }
+    T *orow = (T *)a.o + (size_t)t * a.Hq * hd + (size_t)h * hd;
+    float inv = 1.0f / l;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        int i = lane + 64 * e;
+        if (i < hd) Elem<T>::st(orow + i, o[e] * inv);
+    }
+}
+
+hipError_t launch_attn_generic(int dtype, const AttnArgs &a, hipStream_t s)
+{
+    long long items = (long long)a.T * a.Hq;
+    if (items <= 0) return hipSuccess;
+    unsigned grid = (unsigned)((items + 3) / 4);
+    if (dtype == PD_F32) attn_generic_kernel<float><<<grid, 256, 0, s>>>(a);
+    else attn_generic_kernel<bf16_t><<<grid, 256, 0, s>>>(a);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Cache fill / read-back: [Hkv, len, hd] tensor <-> one slot of the cache.
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void kv_copy_kernel(T *ck, T *cv, T *k, T *v, int slot, int Hkv, int len, int hd,
+                               int max_len, int to_cache)
+{
+    size_t n = (size_t)Hkv * len * hd;
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n;
+         idx += (size_t)gridDim.x * blockDim.x) {
+        int i = (int)(idx % hd);
+        size_t r = idx / hd;
+        int p = (int)(r % len);
+        int g = (int)(r / len);
+        size_t c = (((size_t)slot * Hkv + g) * max_len + p) * hd + i;
+        if (to_cache) {
+            ck[c] = k[idx];
+            cv[c] = v[idx];
+        } else {
+            k[idx] = ck[c];
+            v[idx] = cv[c];
+        }
+    }
+}
+
+hipError_t launch_kv_copy(int dtype, void *cache_k, void *cache_v, const void *k, const void *v,
+                          int slot, int Hkv, int len, int hd, int max_len, int to_cache,
+                          hipStream_t s)
+{
+    size_t n = (size_t)Hkv * len * hd;
+    if (n == 0) return hipSuccess;
+    unsigned grid = (unsigned)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
+    if (dtype == PD_F32)
+        kv_copy_kernel<float><<<grid, 256, 0, s>>>((float *)cache_k, (float *)cache_v, (float *)k,
+                                                   (float *)v, slot, Hkv, len, hd, max_len, to_cache);
+    else
+        kv_copy_kernel<uint16_t><<<grid, 256, 0, s>>>((uint16_t *)cache_k, (uint16_t *)cache_v,
+                                                      (uint16_t *)k, (uint16_t *)v, slot, Hkv, len,
+                                                      hd, max_len, to_cache);
+    return hipGetLastError();
+}
+
+}  // namespace pd

@@ -1,0 +1,165 @@
+// Mixture-of-experts routing: router logits, softmax + top-k selection, a stable counting sort of
+// the (token, expert) pairs by expert, and the weighted combine of the expert outputs.
+#include "pd_internal.h"
+
+namespace pd {
+
+// logits[t][e] = sum_i y[t][i] * Wr[e][i], fp32 output.  One wavefront per token.
+template <typename T>
+__global__ __launch_bounds__(256) void router_logits_kernel(const T *__restrict__ y,
+                                                            const T *__restrict__ wr,
+                                                            float *__restrict__ logits, int Tn, int d,
+                                                            int E)
+{
+    int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+    int lane = threadIdx.x & 63;
+    if (t >= Tn) return;
+    const T *yr = y + (size_t)t * d;
+    for (int e = 0; e < E; ++e) {
+        const T *w = wr + (size_t)e * d;
+        float acc = 0.f;
+        for (int i = lane; i < d; i += 64) acc = fmaf(Elem<T>::ld(yr + i), Elem<T>::ld(w + i), acc);
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+        if (lane == 0) logits[(size_t)t * E + e] = acc;
+    }
+}
+
+hipError_t launch_router_logits(int dtype, const void *y, const void *w_router, float *logits,
+                                int T, int d, int E, hipStream_t s)
+{
+    if (T <= 0) return hipSuccess;
+    if (dtype == PD_F32)
+        router_logits_kernel<float><<<(T + 3) / 4, 256, 0, s>>>((const float *)y, (const float *)w_router, logits, T, d, E);
+    else
+        router_logits_kernel<bf16_t><<<(T + 3) / 4, 256, 0, s>>>((const bf16_t *)y, (const bf16_t *)w_router, logits, T, d, E);
+    return hipGetLastError();
+}
+
+// p = softmax(logits) over all experts; the top_k largest p (ties: lower index); weights
+// renormalised to sum 1.  The selection compares probabilities in double.
+__global__ void moe_topk_kernel(MoeRouteArgs a)
+{
+    int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= a.T) return;
+    const float *r = a.logits + (size_t)t * a.E;
+    double mx = -INFINITY;
+    for (int e = 0; e < a.E; ++e) mx = fmax(mx, (double)r[e]);
+    double denom = 0.0;
+    for (int e = 0; e < a.E; ++e) denom += exp((double)r[e] - mx);
+    unsigned long long taken = 0ull;
+    double sum = 0.0;
+    double pk[8];
+    int ik[8];
+    for (int k = 0; k < a.top_k; ++k) {
+        int best = -1;
+        double pbest = -1.0;
+        for (int e = 0; e < a.E; ++e) {
+            if ((taken >> e) & 1ull) continue;
+            double p = exp((double)r[e] - mx) / denom;
+            if (best < 0 || p > pbest) {
+                best = e;
+                pbest = p;
+            }
+        }
+        taken |= 1ull << best;
+        pk[k] = pbest;
+        ik[k] = best;
+        sum += pbest;
+    }
+    for (int k = 0; k < a.top_k; ++k) {
+        a.expert_idx[(size_t)t * a.top_k + k] = ik[k];
+        a.expert_w[(size_t)t * a.top_k + k] = (float)(pk[k] / sum);
+    }
+}
+
+// Stable counting sort of the T*top_k pairs by expert, one 1024-thread block.  Pair index is
+// t*top_k + k; within an expert the pairs keep that order.
+__global__ __launch_bounds__(1024) void moe_sort_kernel(MoeRouteArgs a)
+{
+    __shared__ int wave_tot[16];
+    __shared__ int base_s;
+    const int P = a.T * a.top_k;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int per = (P + 1023) / 1024;
+    const int lo = tid * per, hi = min(P, lo + per);
+    if (tid == 0) {
+        base_s = 0;
+        a.offsets[0] = 0;
+    }
+    __syncthreads();
+    for (int e = 0; e < a.E; ++e) {
+        int cnt = 0;
+        for (int i = lo; i < hi; ++i) cnt += (a.expert_idx[i] == e);
+        // inclusive scan inside the wave
+        int inc = cnt;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            int v = __shfl_up(inc, off, 64);
+            if (lane >= off) inc += v;
+        }
+        if (lane == 63) wave_tot[wave] = inc;
+        __syncthreads();
+        int wbase = 0, total = 0;
+        for (int w = 0; w < 16; ++w) {
+            if (w < wave) wbase += wave_tot[w];
+            total += wave_tot[w];
+        }
+        int pos = base_s + wbase + inc - cnt;
+        for (int i = lo; i < hi; ++i)
+            if (a.expert_idx[i] == e) {
+                a.sorted_token[pos] = i / a.top_k;
+                a.pair_pos[i] = pos;
+                ++pos;
+            }
+        __syncthreads();
+        if (tid == 0) {
+            base_s += total;
+            a.offsets[e + 1] = base_s;
+        }
+        __syncthreads();
+    }
+}
+
+hipError_t launch_moe_route(const MoeRouteArgs &a, hipStream_t s)
+{
+    if (a.T <= 0) return hipSuccess;
+    moe_topk_kernel<<<(a.T + 255) / 256, 256, 0, s>>>(a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    moe_sort_kernel<<<1, 1024, 0, s>>>(a);
+    return hipGetLastError();
+}
+
+// out[t] = h[t] + sum_k w[t,k] * expert_out[pair_pos[t,k]]
+template <typename T>
+__global__ __launch_bounds__(256) void moe_combine_kernel(const T *__restrict__ h,
+                                                          const T *__restrict__ eo,
+                                                          const int32_t *__restrict__ pair_pos,
+                                                          const float *__restrict__ w,
+                                                          T *__restrict__ out, int d, int top_k)
+{
+    const int t = blockIdx.x;
+    for (int i = threadIdx.x; i < d; i += 256) {
+        float acc = 0.f;
+        for (int k = 0; k < top_k; ++k) {
+            int p = pair_pos[(size_t)t * top_k + k];
+            acc = fmaf(w[(size_t)t * top_k + k], Elem<T>::ld(eo + (size_t)p * d + i), acc);
+        }
+        Elem<T>::st(out + (size_t)t * d + i, Elem<T>::ld(h + (size_t)t * d + i) + acc);
+    }
+}
+
+hipError_t launch_moe_combine(int dtype, const void *h, const void *expert_out,
+                              const int32_t *pair_pos, const float *expert_w, void *out, int T,
+                              int d, int top_k, hipStream_t s)
+{
+    if (T <= 0) return hipSuccess;
+    if (dtype == PD_F32)
+        moe_combine_kernel<float><<<T, 256, 0, s>>>((const float *)h, (const float *)expert_out, pair_pos, expert_w, (float *)out, d, top_k);
+    else
+        moe_combine_kernel<bf16_t><<<T, 256, 0, s>>>((const bf16_t *)h, (const bf16_t *)expert_out, pair_pos, expert_w, (bf16_t *)out, d, top_k);
+    return hipGetLastError();
+}
+
+}  // namespace pd

@@ -1,0 +1,579 @@
+// C-ABI entry points that touch the device: layer and KV-cache handles, pd_prefill and
+// pd_decode_step.  Each call validates on the host, then enqueues the layer's kernels on the
+// caller's stream in the order of the layer definition in pd.h.
+#include <math.h>
+#include <string.h>
+
+#include <vector>
+
+#include "pd_internal.h"
+
+using namespace pd;
+
+struct pd_layer {
+    pd_layer_config cfg;
+    int device;
+    size_t esz;
+    int Nq, Nkv, Nqkv;
+    bool use_mfma;       // bf16 layer whose shapes fit the MFMA kernels
+    bool interleaved;    // gate/up rows stored as alternating 32-row blocks
+    void *g_attn, *g_ffn, *w_qkv, *w_o, *w_gate, *w_up, *w_down, *w_router;
+    double *inv_freq;
+    int32_t *d_cu, *d_slots;  // [4097] each
+    // workspace, sized for ws_tokens rows
+    int ws_tokens;
+    char *ws;
+    void *y, *qkv, *o, *h, *act, *eo;
+    int32_t *tok_seq, *tok_pos, *tok_slot, *eidx, *sorted_token, *pair_pos, *offsets;
+    float *logits, *ew;
+    int last_rows;
+};
+
+struct pd_kv_cache {
+    int dtype, Hkv, hd, max_seqs, max_len;
+    void *k, *v;
+    int32_t *d_len;
+    std::vector<int32_t> h_len;
+};
+
+static const int kMaxSeqs = 4096;
+
+#define HIP_TRY(expr, status)                                                        \
+    do {                                                                             \
+        hipError_t e__ = (expr);                                                     \
+        if (e__ != hipSuccess) {                                                     \
+            set_error("%s failed: %s", #expr, hipGetErrorString(e__));               \
+            return (e__ == hipErrorOutOfMemory) ? PD_ERR_OOM : (status);             \
+        }                                                                            \
+    } while (0)
+
+static size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+// dst row (j/32)*64 + j%32 (+32 for `up`) <- src row j; rows are row_bytes long (multiple of 16)
+__global__ void interleave_rows_kernel(uint4 *dst, const uint4 *gate, const uint4 *up, int F,
+                                       int row_vec)
+{
+    size_t n = (size_t)F * row_vec;
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n;
+         idx += (size_t)gridDim.x * blockDim.x) {
+        int j = (int)(idx / row_vec);
+        int c = (int)(idx % row_vec);
+        size_t pr = (size_t)(j >> 5) * 64 + (j & 31);
+        dst[pr * row_vec + c] = gate[idx];
+        dst[(pr + 32) * row_vec + c] = up[idx];
+    }
+}
+
+static void free_layer(pd_layer *L)
+{
+    if (!L) return;
+    void *ptrs[] = {L->g_attn, L->g_ffn, L->w_qkv, L->w_o, L->w_gate, L->w_up, L->w_down,
+                    L->w_router, L->inv_freq, L->d_cu, L->d_slots, L->ws};
+    for (void *p : ptrs)
+        if (p) (void)hipFree(p);
+    delete L;
+}
+
+extern "C" pd_status pd_layer_create(const pd_layer_config *cfg, const pd_layer_weights *w,
+                                     pd_layer **out)
+{
+    if (!cfg || !w || !out) {
+        set_error("pd_layer_create: NULL argument");
+        return PD_ERR_INVALID_ARG;
+    }
+    if (cfg->dtype != PD_F32 && cfg->dtype != PD_BF16) {
+        set_error("pd_layer_create: dtype %d is neither fp32 nor bf16", cfg->dtype);
+        return PD_ERR_DTYPE;
+    }
+    const int d = cfg->d_model, Hq = cfg->n_q_heads, Hkv = cfg->n_kv_heads, hd = cfg->head_dim,
+              F = cfg->d_ff, E = cfg->n_experts;
+    if (d <= 0 || Hq <= 0 || Hkv <= 0 || hd <= 0 || F <= 0 || E < 0 || (hd & 1) || hd > 256 ||
+        Hq % Hkv != 0 || E > 64 || (E > 0 && (cfg->top_k <= 0 || cfg->top_k > E || cfg->top_k > 8)) ||
+        !(cfg->rms_eps >= 0.f) || !(cfg->rope_base > 0.f)) {
+        set_error("pd_layer_create: unsupported shape (d=%d Hq=%d Hkv=%d hd=%d F=%d E=%d top_k=%d)", d,
+                  Hq, Hkv, hd, F, E, cfg->top_k);
+        return PD_ERR_SHAPE;
+    }
+    if (!w->g_attn || !w->w_q || !w->w_k || !w->w_v || !w->w_o || !w->g_ffn || !w->w_gate ||
+        !w->w_up || !w->w_down) {
+        set_error("pd_layer_create: a weight pointer is NULL");
+        return PD_ERR_INVALID_ARG;
+    }
+    pd_layer *L = new pd_layer();
+    memset((void *)L, 0, sizeof(*L));
+    L->cfg = *cfg;
+    L->esz = cfg->dtype == PD_F32 ? 4 : 2;
+    L->Nq = Hq * hd;
+    L->Nkv = Hkv * hd;
+    L->Nqkv = L->Nq + 2 * L->Nkv;
+    L->use_mfma = cfg->dtype == PD_BF16 && d % 64 == 0 && F % 64 == 0 && L->Nq % 64 == 0 &&
+                  L->Nkv % 64 == 0;
+    L->interleaved = L->use_mfma;
+    const size_t esz = L->esz;
+    const int G = E > 0 ? E : 1;
+    pd_status st = PD_OK;
+    auto fail = [&](pd_status s) {
+        free_layer(L);
+        return s;
+    };
+#define CREATE_TRY(expr)                                                               \
+    do {                                                                               \
+        hipError_t e__ = (expr);                                                       \
+        if (e__ != hipSuccess) {                                                       \
+            set_error("pd_layer_create: %s failed: %s", #expr, hipGetErrorString(e__)); \
+            return fail(e__ == hipErrorOutOfMemory ? PD_ERR_OOM : PD_ERR_DEVICE);      \
+        }                                                                              \
+    } while (0)
+    CREATE_TRY(hipGetDevice(&L->device));
+    CREATE_TRY(hipMalloc(&L->g_attn, d * esz));
+    CREATE_TRY(hipMalloc(&L->g_ffn, d * esz));
+    CREATE_TRY(hipMalloc(&L->w_qkv, (size_t)L->Nqkv * d * esz));
+    CREATE_TRY(hipMalloc(&L->w_o, (size_t)d * L->Nq * esz));
+    CREATE_TRY(hipMalloc(&L->w_down, (size_t)G * d * F * esz));
+    CREATE_TRY(hipMalloc(&L->inv_freq, sizeof(double) * (hd / 2)));
+    CREATE_TRY(hipMalloc(&L->d_cu, sizeof(int32_t) * (kMaxSeqs + 1)));
+    CREATE_TRY(hipMalloc(&L->d_slots, sizeof(int32_t) * (kMaxSeqs + 1)));
+    CREATE_TRY(hipMemcpy(L->g_attn, w->g_attn, d * esz, hipMemcpyDeviceToDevice));
+    CREATE_TRY(hipMemcpy(L->g_ffn, w->g_ffn, d * esz, hipMemcpyDeviceToDevice));
+    CREATE_TRY(hipMemcpy(L->w_qkv, w->w_q, (size_t)L->Nq * d * esz, hipMemcpyDeviceToDevice));
+    CREATE_TRY(hipMemcpy((char *)L->w_qkv + (size_t)L->Nq * d * esz, w->w_k,
+                         (size_t)L->Nkv * d * esz, hipMemcpyDeviceToDevice));
+    CREATE_TRY(hipMemcpy((char *)L->w_qkv + (size_t)(L->Nq + L->Nkv) * d * esz, w->w_v,
+                         (size_t)L->Nkv * d * esz, hipMemcpyDeviceToDevice));
+    CREATE_TRY(hipMemcpy(L->w_o, w->w_o, (size_t)d * L->Nq * esz, hipMemcpyDeviceToDevice));
+    CREATE_TRY(hipMemcpy(L->w_down, w->w_down, (size_t)G * d * F * esz, hipMemcpyDeviceToDevice));
+    if (L->interleaved) {
+        CREATE_TRY(hipMalloc(&L->w_gate, (size_t)G * 2 * F * d * esz));
+        const int row_vec = (int)(d * esz / 16);
+        for (int g = 0; g < G; ++g) {
+            interleave_rows_kernel<<<1024, 256>>>(
+                (uint4 *)((char *)L->w_gate + (size_t)g * 2 * F * d * esz),
+                (const uint4 *)((const char *)w->w_gate + (size_t)g * F * d * esz),
+                (const uint4 *)((const char *)w->w_up + (size_t)g * F * d * esz), F, row_vec);
+            CREATE_TRY(hipGetLastError());
+        }
+    } else {
+        CREATE_TRY(hipMalloc(&L->w_gate, (size_t)G * F * d * esz));
+        CREATE_TRY(hipMalloc(&L->w_up, (size_t)G * F * d * esz));
+        CREATE_TRY(hipMemcpy(L->w_gate, w->w_gate, (size_t)G * F * d * esz, hipMemcpyDeviceToDevice));
+        CREATE_TRY(hipMemcpy(L->w_up, w->w_up, (size_t)G * F * d * esz, hipMemcpyDeviceToDevice));
+    }
+    if (E > 0 && w->w_router) {
+        CREATE_TRY(hipMalloc(&L->w_router, (size_t)E * d * esz));
+        CREATE_TRY(hipMemcpy(L->w_router, w->w_router, (size_t)E * d * esz, hipMemcpyDeviceToDevice));
+    }
+    {
+        std::vector<double> f(hd / 2);
+        for (int i = 0; i < hd / 2; ++i)
+            f[i] = pow((double)cfg->rope_base, -2.0 * (double)i / (double)hd);
+        CREATE_TRY(hipMemcpy(L->inv_freq, f.data(), sizeof(double) * f.size(), hipMemcpyHostToDevice));
+    }
+    CREATE_TRY(hipDeviceSynchronize());
+#undef CREATE_TRY
+    (void)st;
+    *out = L;
+    return PD_OK;
+}
+
+extern "C" void pd_layer_destroy(pd_layer *layer)
+{
+    if (!layer) return;
+    (void)hipDeviceSynchronize();
+    free_layer(layer);
+}
+
+extern "C" pd_status pd_layer_reserve(pd_layer *L, int32_t max_tokens)
+{
+    if (!L || max_tokens < 0) {
+        set_error("pd_layer_reserve: bad argument");
+        return PD_ERR_INVALID_ARG;
+    }
+    if (max_tokens <= L->ws_tokens) return PD_OK;
+    const size_t T = (size_t)max_tokens, esz = L->esz;
+    const int d = L->cfg.d_model, F = L->cfg.d_ff, E = L->cfg.n_experts;
+    const size_t K = E > 0 ? (size_t)L->cfg.top_k : 1;
+    size_t off = 0;
+    auto carve = [&](size_t bytes) {
+        size_t o = off;
+        off += align256(bytes);
+        return o;
+    };
+    size_t o_y = carve(T * d * esz), o_qkv = carve(T * L->Nqkv * esz), o_o = carve(T * L->Nq * esz),
+           o_h = carve(T * d * esz), o_act = carve(T * K * F * esz),
+           o_eo = carve(E > 0 ? T * K * d * esz : 0), o_seq = carve(T * 4), o_pos = carve(T * 4),
+           o_slot = carve(T * 4), o_eidx = carve(T * K * 4), o_sorted = carve(T * K * 4),
+           o_pp = carve(T * K * 4), o_off = carve(65 * 4 + 4), o_log = carve(T * (E > 0 ? E : 1) * 4),
+           o_ew = carve(T * K * 4);
+    HIP_TRY(hipDeviceSynchronize(), PD_ERR_DEVICE);
+    char *nw = nullptr;
+    hipError_t e = hipMalloc((void **)&nw, off);
+    if (e != hipSuccess) {
+        set_error("pd_layer_reserve: cannot allocate %zu bytes of workspace: %s", off, hipGetErrorString(e));
+        return PD_ERR_OOM;
+    }
+    if (L->ws) (void)hipFree(L->ws);
+    L->ws = nw;
+    L->ws_tokens = max_tokens;
+    L->y = nw + o_y;
+    L->qkv = nw + o_qkv;
+    L->o = nw + o_o;
+    L->h = nw + o_h;
+    L->act = nw + o_act;
+    L->eo = nw + o_eo;
+    L->tok_seq = (int32_t *)(nw + o_seq);
+    L->tok_pos = (int32_t *)(nw + o_pos);
+    L->tok_slot = (int32_t *)(nw + o_slot);
+    L->eidx = (int32_t *)(nw + o_eidx);
+    L->sorted_token = (int32_t *)(nw + o_sorted);
+    L->pair_pos = (int32_t *)(nw + o_pp);
+    L->offsets = (int32_t *)(nw + o_off);
+    L->logits = (float *)(nw + o_log);
+    L->ew = (float *)(nw + o_ew);
+    return PD_OK;
+}
+
+// ---- KV cache ------------------------------------------------------------------------------------
+
+extern "C" pd_status pd_kv_cache_create(const pd_layer *L, int32_t max_seqs, int32_t max_len,
+                                        pd_kv_cache **out)
+{
+    if (!L || !out || max_seqs <= 0 || max_len <= 0) {
+        set_error("pd_kv_cache_create: bad argument");
+        return PD_ERR_INVALID_ARG;
+    }
+    pd_kv_cache *c = new pd_kv_cache();
+    c->dtype = L->cfg.dtype;
+    c->Hkv = L->cfg.n_kv_heads;
+    c->hd = L->cfg.head_dim;
+    c->max_seqs = max_seqs;
+    c->max_len = max_len;
+    c->k = c->v = nullptr;
+    c->d_len = nullptr;
+    size_t bytes = (size_t)max_seqs * c->Hkv * max_len * c->hd * L->esz;
+    hipError_t e = hipMalloc(&c->k, bytes);
+    if (e == hipSuccess) e = hipMalloc(&c->v, bytes);
+    if (e == hipSuccess) e = hipMalloc((void **)&c->d_len, sizeof(int32_t) * max_seqs);
+    if (e == hipSuccess) e = hipMemset(c->d_len, 0, sizeof(int32_t) * max_seqs);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        set_error("pd_kv_cache_create: %s (2 x %zu bytes)", hipGetErrorString(e), bytes);
+        if (c->k) (void)hipFree(c->k);
+        if (c->v) (void)hipFree(c->v);
+        if (c->d_len) (void)hipFree(c->d_len);
+        delete c;
+        return e == hipErrorOutOfMemory ? PD_ERR_OOM : PD_ERR_DEVICE;
+    }
+    c->h_len.assign((size_t)max_seqs, 0);
+    *out = c;
+    return PD_OK;
+}
+
+extern "C" void pd_kv_cache_destroy(pd_kv_cache *c)
+{
+    if (!c) return;
+    (void)hipDeviceSynchronize();
+    (void)hipFree(c->k);
+    (void)hipFree(c->v);
+    (void)hipFree(c->d_len);
+    delete c;
+}
+
+extern "C" pd_status pd_kv_cache_set_len(pd_kv_cache *c, int32_t slot, int32_t len, void *stream)
+{
+    if (!c || slot < 0 || slot >= c->max_seqs || len < 0) {
+        set_error("pd_kv_cache_set_len: bad argument");
+        return PD_ERR_INVALID_ARG;
+    }
+    if (len > c->max_len) {
+        set_error("pd_kv_cache_set_len: len %d > max_len %d", len, c->max_len);
+        return PD_ERR_KV_CAPACITY;
+    }
+    HIP_TRY(launch_write_ints(c->d_len + slot, &len, 1, (hipStream_t)stream), PD_ERR_DEVICE);
+    c->h_len[(size_t)slot] = len;
+    return PD_OK;
+}
+
+extern "C" pd_status pd_kv_cache_set(pd_kv_cache *c, int32_t slot, int32_t len, const void *k,
+                                     const void *v, void *stream)
+{
+    if (!c || slot < 0 || slot >= c->max_seqs || len < 0 || (len > 0 && (!k || !v))) {
+        set_error("pd_kv_cache_set: bad argument");
+        return PD_ERR_INVALID_ARG;
+    }
+    if (len > c->max_len) {
+        set_error("pd_kv_cache_set: len %d > max_len %d", len, c->max_len);
+        return PD_ERR_KV_CAPACITY;
+    }
+    HIP_TRY(launch_kv_copy(c->dtype, c->k, c->v, k, v, slot, c->Hkv, len, c->hd, c->max_len, 1,
+                           (hipStream_t)stream),
+            PD_ERR_DEVICE);
+    return pd_kv_cache_set_len(c, slot, len, stream);
+}
+
+extern "C" pd_status pd_kv_cache_get(const pd_kv_cache *c, int32_t slot, int32_t len, void *k,
+                                     void *v, void *stream)
+{
+    if (!c || slot < 0 || slot >= c->max_seqs || len < 0 || len > c->max_len || (len > 0 && (!k || !v))) {
+        set_error("pd_kv_cache_get: bad argument");
+        return PD_ERR_INVALID_ARG;
+    }
+    HIP_TRY(launch_kv_copy(c->dtype, c->k, c->v, k, v, slot, c->Hkv, len, c->hd, c->max_len, 0,
+                           (hipStream_t)stream),
+            PD_ERR_DEVICE);
+    return PD_OK;
+}
+
+extern "C" pd_status pd_kv_cache_len(const pd_kv_cache *c, int32_t slot, int32_t *len)
+{
+    if (!c || !len || slot < 0 || slot >= c->max_seqs) {
+        set_error("pd_kv_cache_len: bad argument");
+        return PD_ERR_INVALID_ARG;
+    }
+    *len = c->h_len[(size_t)slot];
+    return PD_OK;
+}
+
+// ---- layer forward -------------------------------------------------------------------------------
+
+static hipError_t run_gemm(const pd_layer *L, const GemmArgs &g, hipStream_t s)
+{
+    if (L->use_mfma && gemm_mfma_supported(g)) return launch_gemm_mfma(g, s);
+    return launch_gemm_generic(L->cfg.dtype, g, s);
+}
+
+static bool cache_matches(const pd_layer *L, const pd_kv_cache *c)
+{
+    return c->dtype == L->cfg.dtype && c->Hkv == L->cfg.n_kv_heads && c->hd == L->cfg.head_dim;
+}
+
+// Everything after the attention output: O projection + residual, RMSNorm, FFN or MoE.
+static pd_status run_tail(pd_layer *L, const void *x, int T, const void *router_logits, void *out,
+                          hipStream_t s)
+{
+    const pd_layer_config &c = L->cfg;
+    const int d = c.d_model, F = c.d_ff, E = c.n_experts;
+    GemmArgs g;
+    memset(&g, 0, sizeof(g));
+    // h = x + o Wo^T
+    g.A = L->o; g.lda = L->Nq; g.B = L->w_o; g.ldb = L->Nq; g.C = L->h; g.ldc = d; g.R = x; g.ldr = d;
+    g.M = T; g.N = d; g.K = L->Nq; g.epilogue = EPI_RESIDUAL; g.n_groups = 1;
+    HIP_TRY(run_gemm(L, g, s), PD_ERR_DEVICE);
+    HIP_TRY(launch_rmsnorm(c.dtype, L->h, L->g_ffn, L->y, T, d, c.rms_eps, s), PD_ERR_DEVICE);
+    if (E == 0) {
+        memset(&g, 0, sizeof(g));
+        g.A = L->y; g.lda = d; g.B = L->w_gate; g.B1 = L->w_up; g.ldb = d; g.C = L->act; g.ldc = F;
+        g.M = T; g.N = F; g.K = d; g.epilogue = EPI_SWIGLU; g.interleaved = L->interleaved; g.n_groups = 1;
+        HIP_TRY(run_gemm(L, g, s), PD_ERR_DEVICE);
+        memset(&g, 0, sizeof(g));
+        g.A = L->act; g.lda = F; g.B = L->w_down; g.ldb = F; g.C = out; g.ldc = d; g.R = L->h; g.ldr = d;
+        g.M = T; g.N = d; g.K = F; g.epilogue = EPI_RESIDUAL; g.n_groups = 1;
+        HIP_TRY(run_gemm(L, g, s), PD_ERR_DEVICE);
+        return PD_OK;
+    }
+    const float *logits = (const float *)router_logits;
+    if (!logits) {
+        HIP_TRY(launch_router_logits(c.dtype, L->y, L->w_router, L->logits, T, d, E, s), PD_ERR_DEVICE);
+        logits = L->logits;
+    }
+    MoeRouteArgs r;
+    r.logits = logits; r.T = T; r.E = E; r.top_k = c.top_k; r.expert_idx = L->eidx; r.expert_w = L->ew;
+    r.sorted_token = L->sorted_token; r.pair_pos = L->pair_pos; r.offsets = L->offsets;
+    HIP_TRY(launch_moe_route(r, s), PD_ERR_DEVICE);
+    const int P = T * c.top_k;
+    memset(&g, 0, sizeof(g));
+    g.A = L->y; g.lda = d; g.a_gather = L->sorted_token; g.B = L->w_gate; g.B1 = L->w_up; g.ldb = d;
+    g.b_group_stride = (int64_t)(L->interleaved ? 2 : 1) * F * d; g.group_offsets = L->offsets; g.n_groups = E;
+    g.C = L->act; g.ldc = F; g.M = P; g.N = F; g.K = d; g.epilogue = EPI_SWIGLU; g.interleaved = L->interleaved;
+    HIP_TRY(run_gemm(L, g, s), PD_ERR_DEVICE);
+    memset(&g, 0, sizeof(g));
+    g.A = L->act; g.lda = F; g.B = L->w_down; g.ldb = F; g.b_group_stride = (int64_t)d * F;
+    g.group_offsets = L->offsets; g.n_groups = E; g.C = L->eo; g.ldc = d; g.M = P; g.N = d; g.K = F;
+    g.epilogue = EPI_NONE;
+    HIP_TRY(run_gemm(L, g, s), PD_ERR_DEVICE);
+    HIP_TRY(launch_moe_combine(c.dtype, L->h, L->eo, L->pair_pos, L->ew, out, T, d, c.top_k, s),
+            PD_ERR_DEVICE);
+    return PD_OK;
+}
+
+extern "C" pd_status pd_prefill(pd_layer *L, const pd_tokens *tk, pd_kv_cache *cache, void *out,
+                                void *stream)
+{
+    if (!L || !tk || !tk->cu_seqlens) {
+        set_error("pd_prefill: NULL argument");
+        return PD_ERR_INVALID_ARG;
+    }
+    const int n = tk->n_seqs;
+    if (n < 1 || n > kMaxSeqs) {
+        set_error("pd_prefill: n_seqs %d outside 1..%d", n, kMaxSeqs);
+        return PD_ERR_INVALID_ARG;
+    }
+    if (tk->cu_seqlens[0] != 0) {
+        set_error("pd_prefill: cu_seqlens[0] must be 0");
+        return PD_ERR_SHAPE;
+    }
+    int max_L = 0;
+    for (int s = 0; s < n; ++s) {
+        int Ls = tk->cu_seqlens[s + 1] - tk->cu_seqlens[s];
+        if (Ls < 0) {
+            set_error("pd_prefill: cu_seqlens decreases at %d", s);
+            return PD_ERR_SHAPE;
+        }
+        if (Ls > max_L) max_L = Ls;
+    }
+    const int T = tk->cu_seqlens[n];
+    const bool keep = cache && tk->slots;
+    if (keep) {
+        if (!cache_matches(L, cache)) {
+            set_error("pd_prefill: cache was created for a different layer shape");
+            return PD_ERR_INVALID_ARG;
+        }
+        std::vector<char> seen((size_t)cache->max_seqs, 0);
+        for (int s = 0; s < n; ++s) {
+            int sl = tk->slots[s];
+            if (sl < 0 || sl >= cache->max_seqs || seen[(size_t)sl]) {
+                set_error("pd_prefill: slot %d (sequence %d) out of range or repeated", sl, s);
+                return PD_ERR_INVALID_ARG;
+            }
+            seen[(size_t)sl] = 1;
+        }
+        if (max_L > cache->max_len) {
+            set_error("pd_prefill: a sequence of %d tokens exceeds the cache's max_len %d", max_L, cache->max_len);
+            return PD_ERR_KV_CAPACITY;
+        }
+    }
+    if (T == 0) {
+        if (keep)
+            for (int s = 0; s < n; ++s) {
+                pd_status st = pd_kv_cache_set_len(cache, tk->slots[s], 0, stream);
+                if (st != PD_OK) return st;
+            }
+        return PD_OK;
+    }
+    if (!tk->hidden || !out) {
+        set_error("pd_prefill: NULL hidden or output");
+        return PD_ERR_INVALID_ARG;
+    }
+    const pd_layer_config &c = L->cfg;
+    if (c.n_experts > 0 && !tk->router_logits && !L->w_router) {
+        set_error("pd_prefill: MoE layer needs router_logits or w_router");
+        return PD_ERR_INVALID_ARG;
+    }
+    pd_status st = pd_layer_reserve(L, T);
+    if (st != PD_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+
+    HIP_TRY(launch_write_ints(L->d_cu, tk->cu_seqlens, n + 1, s), PD_ERR_DEVICE);
+    if (keep) HIP_TRY(launch_write_ints(L->d_slots, tk->slots, n, s), PD_ERR_DEVICE);
+    HIP_TRY(launch_token_meta(L->d_cu, keep ? L->d_slots : nullptr, n, T, L->tok_seq, L->tok_pos,
+                              L->tok_slot, s),
+            PD_ERR_DEVICE);
+    HIP_TRY(launch_rmsnorm(c.dtype, tk->hidden, L->g_attn, L->y, T, c.d_model, c.rms_eps, s), PD_ERR_DEVICE);
+    GemmArgs g;
+    memset(&g, 0, sizeof(g));
+    g.A = L->y; g.lda = c.d_model; g.B = L->w_qkv; g.ldb = c.d_model; g.C = L->qkv; g.ldc = L->Nqkv;
+    g.M = T; g.N = L->Nqkv; g.K = c.d_model; g.epilogue = EPI_NONE; g.n_groups = 1;
+    HIP_TRY(run_gemm(L, g, s), PD_ERR_DEVICE);
+    RopeArgs r;
+    r.qkv = L->qkv; r.ld = L->Nqkv; r.T = T; r.Hq = c.n_q_heads; r.Hkv = c.n_kv_heads; r.hd = c.head_dim;
+    r.tok_pos = L->tok_pos; r.tok_slot = keep ? L->tok_slot : nullptr;
+    r.k_cache = keep ? cache->k : nullptr; r.v_cache = keep ? cache->v : nullptr;
+    r.max_len = keep ? cache->max_len : 0; r.inv_freq = L->inv_freq;
+    HIP_TRY(launch_rope_kv(c.dtype, r, s), PD_ERR_DEVICE);
+    AttnArgs a;
+    memset(&a, 0, sizeof(a));
+    a.qkv = L->qkv; a.ld = L->Nqkv; a.o = L->o; a.T = T; a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads;
+    a.hd = c.head_dim; a.scale = (float)(1.0 / sqrt((double)c.head_dim)); a.tok_pos = L->tok_pos;
+    a.decode = 0; a.d_cu = L->d_cu; a.n_seqs = n; a.max_seq_len = max_L;
+    if (L->use_mfma && attn_prefill_mfma_supported(a)) HIP_TRY(launch_attn_prefill_mfma(a, s), PD_ERR_DEVICE);
+    else HIP_TRY(launch_attn_generic(c.dtype, a, s), PD_ERR_DEVICE);
+    st = run_tail(L, tk->hidden, T, tk->router_logits, out, s);
+    if (st != PD_OK) return st;
+    if (keep) {
+        HIP_TRY(launch_prefill_set_len(L->d_slots, L->d_cu, n, cache->d_len, s), PD_ERR_DEVICE);
+        for (int q = 0; q < n; ++q)
+            cache->h_len[(size_t)tk->slots[q]] = tk->cu_seqlens[q + 1] - tk->cu_seqlens[q];
+    }
+    L->last_rows = T;
+    return PD_OK;
+}
+
+extern "C" pd_status pd_decode_step(pd_layer *L, const pd_batch *bt, pd_kv_cache *cache, void *out,
+                                    void *stream)
+{
+    if (!L || !bt || !cache || !bt->slots || !bt->hidden || !out) {
+        set_error("pd_decode_step: NULL argument");
+        return PD_ERR_INVALID_ARG;
+    }
+    const int B = bt->batch;
+    if (B < 1 || B > kMaxSeqs) {
+        set_error("pd_decode_step: batch %d outside 1..%d", B, kMaxSeqs);
+        return PD_ERR_INVALID_ARG;
+    }
+    if (!cache_matches(L, cache)) {
+        set_error("pd_decode_step: cache was created for a different layer shape");
+        return PD_ERR_INVALID_ARG;
+    }
+    const pd_layer_config &c = L->cfg;
+    if (c.n_experts > 0 && !bt->router_logits && !L->w_router) {
+        set_error("pd_decode_step: MoE layer needs router_logits or w_router");
+        return PD_ERR_INVALID_ARG;
+    }
+    {
+        std::vector<char> seen((size_t)cache->max_seqs, 0);
+        for (int b = 0; b < B; ++b) {
+            int sl = bt->slots[b];
+            if (sl < 0 || sl >= cache->max_seqs || seen[(size_t)sl]) {
+                set_error("pd_decode_step: slot %d (row %d) out of range or repeated", sl, b);
+                return PD_ERR_INVALID_ARG;
+            }
+            seen[(size_t)sl] = 1;
+        }
+        for (int b = 0; b < B; ++b)
+            if (cache->h_len[(size_t)bt->slots[b]] + 1 > cache->max_len) {
+                set_error("pd_decode_step: slot %d is full (%d positions)", bt->slots[b], cache->max_len);
+                return PD_ERR_KV_CAPACITY;
+            }
+    }
+    pd_status st = pd_layer_reserve(L, B);
+    if (st != PD_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+
+    HIP_TRY(launch_write_ints(L->d_slots, bt->slots, B, s), PD_ERR_DEVICE);
+    HIP_TRY(launch_decode_meta(L->d_slots, B, cache->d_len, L->tok_pos, s), PD_ERR_DEVICE);
+    HIP_TRY(launch_rmsnorm(c.dtype, bt->hidden, L->g_attn, L->y, B, c.d_model, c.rms_eps, s), PD_ERR_DEVICE);
+    GemmArgs g;
+    memset(&g, 0, sizeof(g));
+    g.A = L->y; g.lda = c.d_model; g.B = L->w_qkv; g.ldb = c.d_model; g.C = L->qkv; g.ldc = L->Nqkv;
+    g.M = B; g.N = L->Nqkv; g.K = c.d_model; g.epilogue = EPI_NONE; g.n_groups = 1;
+    HIP_TRY(run_gemm(L, g, s), PD_ERR_DEVICE);
+    RopeArgs r;
+    r.qkv = L->qkv; r.ld = L->Nqkv; r.T = B; r.Hq = c.n_q_heads; r.Hkv = c.n_kv_heads; r.hd = c.head_dim;
+    r.tok_pos = L->tok_pos; r.tok_slot = L->d_slots; r.k_cache = cache->k; r.v_cache = cache->v;
+    r.max_len = cache->max_len; r.inv_freq = L->inv_freq;
+    HIP_TRY(launch_rope_kv(c.dtype, r, s), PD_ERR_DEVICE);
+    AttnArgs a;
+    memset(&a, 0, sizeof(a));
+    a.qkv = L->qkv; a.ld = L->Nqkv; a.o = L->o; a.T = B; a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads;
+    a.hd = c.head_dim; a.scale = (float)(1.0 / sqrt((double)c.head_dim)); a.tok_pos = L->tok_pos;
+    a.tok_slot = L->d_slots; a.k_cache = cache->k; a.v_cache = cache->v; a.max_len = cache->max_len;
+    a.decode = 1;
+    HIP_TRY(launch_attn_generic(c.dtype, a, s), PD_ERR_DEVICE);
+    st = run_tail(L, bt->hidden, B, bt->router_logits, out, s);
+    if (st != PD_OK) return st;
+    for (int b = 0; b < B; ++b) cache->h_len[(size_t)bt->slots[b]] += 1;
+    L->last_rows = B;
+    return PD_OK;
+}
+
+extern "C" pd_status pd_last_expert_choice(const pd_layer *L, int32_t rows, void *expert_idx,
+                                           void *stream)
+{
+    if (!L || !expert_idx || L->cfg.n_experts <= 0 || rows < 0 || rows > L->last_rows) {
+        set_error("pd_last_expert_choice: bad argument");
+        return PD_ERR_INVALID_ARG;
+    }
+    HIP_TRY(hipMemcpyAsync(expert_idx, L->eidx, sizeof(int32_t) * (size_t)rows * L->cfg.top_k,
+                           hipMemcpyDeviceToDevice, (hipStream_t)stream),
+            PD_ERR_DEVICE);
+    return PD_OK;
+}

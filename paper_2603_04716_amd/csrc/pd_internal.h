@@ -1,0 +1,146 @@
+// Internal declarations shared by the library's translation units (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "pd.h"
+
+namespace pd {
+
+// bf16 storage element (raw bits); conversions are round-to-nearest-even.
+struct bf16_t {
+    uint16_t x;
+};
+
+__device__ __forceinline__ float bf2f(bf16_t v) { return __uint_as_float(((uint32_t)v.x) << 16); }
+__device__ __forceinline__ float bfbits2f(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
+__device__ __forceinline__ bf16_t f2bf(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    bf16_t r;
+    if ((u & 0x7fffffffu) > 0x7f800000u) {  // NaN stays NaN
+        r.x = (uint16_t)((u >> 16) | 0x40u);
+        return r;
+    }
+    u += 0x7fffu + ((u >> 16) & 1u);
+    r.x = (uint16_t)(u >> 16);
+    return r;
+}
+__device__ __forceinline__ uint32_t pack2bf(float lo, float hi)
+{
+    return (uint32_t)f2bf(lo).x | ((uint32_t)f2bf(hi).x << 16);
+}
+
+template <typename T>
+struct Elem;
+template <>
+struct Elem<float> {
+    static __device__ __forceinline__ float ld(const float *p) { return *p; }
+    static __device__ __forceinline__ void st(float *p, float v) { *p = v; }
+};
+template <>
+struct Elem<bf16_t> {
+    static __device__ __forceinline__ float ld(const bf16_t *p) { return bf2f(*p); }
+    static __device__ __forceinline__ void st(bf16_t *p, float v) { *p = f2bf(v); }
+};
+
+constexpr int kMetaChunk = 255;  // ints carried by value per meta-kernel launch (+1 for cu_seqlens)
+struct IntChunk {
+    int32_t v[256];
+};
+
+enum Epilogue { EPI_NONE = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2 };
+
+// C[M,N] = epilogue(A[M,K] * B[N,K]^T).  All matrices row-major with leading dimensions in
+// elements.  a_gather (optional): logical row i of A is physical row a_gather[i].  Groups
+// (optional): rows [group_offsets[g], group_offsets[g+1]) multiply B + g*b_group_stride.
+struct GemmArgs {
+    const void *A;
+    const void *B;        // EPI_SWIGLU: gate rows (or the interleaved gate/up pack)
+    const void *B1;       // EPI_SWIGLU with plain layout: up rows; else unused
+    void *C;
+    const void *R;        // EPI_RESIDUAL: residual [M,N]
+    const int32_t *a_gather;
+    const int32_t *group_offsets;  // device [n_groups+1] or nullptr
+    int64_t b_group_stride;        // elements
+    int32_t n_groups;
+    int32_t M, N, K;               // N = output columns (for SWIGLU: F)
+    int32_t lda, ldb, ldc, ldr;
+    int32_t epilogue;
+    int32_t interleaved;           // EPI_SWIGLU: B holds 32-row blocks gate,up,gate,up...
+};
+
+// ---- launchers (each returns hipGetLastError() after the launch) ------------------------------
+hipError_t launch_rmsnorm(int dtype, const void *x, const void *g, void *y, int T, int d, float eps,
+                          hipStream_t s);
+hipError_t launch_gemm_generic(int dtype, const GemmArgs &a, hipStream_t s);
+bool gemm_mfma_supported(const GemmArgs &a);
+hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t s);   // bf16 only
+// per token row: its sequence, its position inside it and (if d_slots) its cache slot
+hipError_t launch_token_meta(const int32_t *d_cu, const int32_t *d_slots, int n_seqs, int T,
+                             int32_t *tok_seq, int32_t *tok_pos, int32_t *tok_slot, hipStream_t s);
+hipError_t launch_write_ints(int32_t *dst, const int32_t *host_src, int n, hipStream_t s);
+// decode meta: for b in [0,B): pos[b] = len[slot[b]]; len[slot[b]] += 1
+hipError_t launch_decode_meta(const int32_t *d_slots, int B, int32_t *d_len, int32_t *d_pos,
+                              hipStream_t s);
+// prefill: len[slot[s]] = cu[s+1]-cu[s]
+hipError_t launch_prefill_set_len(const int32_t *d_slots, const int32_t *d_cu, int n_seqs,
+                                  int32_t *d_len, hipStream_t s);
+
+struct RopeArgs {
+    void *qkv;               // [T, (Hq+2Hkv)*hd]; q and k rotated in place
+    int32_t ld;              // row stride of qkv (elements)
+    int32_t T, Hq, Hkv, hd;
+    const int32_t *tok_pos;  // [T] position of each row inside its sequence
+    const int32_t *tok_slot; // [T] cache slot of each row, or nullptr = no cache write
+    void *k_cache, *v_cache; // [slots][Hkv][max_len][hd]
+    int32_t max_len;
+    const double *inv_freq;  // [hd/2] rope_base^(-2i/hd)
+};
+hipError_t launch_rope_kv(int dtype, const RopeArgs &a, hipStream_t s);
+
+struct AttnArgs {
+    const void *qkv;         // rotated q (and, for prefill, k and v) rows
+    int32_t ld;
+    void *o;                 // [T, Hq*hd]
+    int32_t T, Hq, Hkv, hd;
+    float scale;
+    // prefill: keys of row t are rows (t - tok_pos[t]) .. t of qkv
+    const int32_t *tok_pos;
+    // decode: keys of row b are cache positions 0 .. tok_pos[b] of slot tok_slot[b]
+    const int32_t *tok_slot;
+    const void *k_cache, *v_cache;
+    int32_t max_len;
+    int32_t decode;
+    // prefill tiling helpers
+    const int32_t *d_cu;     // [n_seqs+1]
+    int32_t n_seqs, max_seq_len;
+};
+hipError_t launch_attn_generic(int dtype, const AttnArgs &a, hipStream_t s);
+bool attn_prefill_mfma_supported(const AttnArgs &a);
+hipError_t launch_attn_prefill_mfma(const AttnArgs &a, hipStream_t s);  // bf16, hd = 128
+
+hipError_t launch_kv_copy(int dtype, void *cache_k, void *cache_v, const void *k, const void *v,
+                          int slot, int Hkv, int len, int hd, int max_len, int to_cache,
+                          hipStream_t s);
+
+// ---- MoE -----------------------------------------------------------------------------------------
+struct MoeRouteArgs {
+    const float *logits;   // [T, E]
+    int32_t T, E, top_k;
+    int32_t *expert_idx;   // [T, top_k]
+    float *expert_w;       // [T, top_k]
+    int32_t *sorted_token; // [T*top_k] token of each (token, expert) pair, ordered by expert
+    int32_t *pair_pos;     // [T, top_k] position of each pair in the sorted order
+    int32_t *offsets;      // [E+1]
+};
+hipError_t launch_moe_route(const MoeRouteArgs &a, hipStream_t s);
+hipError_t launch_router_logits(int dtype, const void *y, const void *w_router, float *logits,
+                                int T, int d, int E, hipStream_t s);
+hipError_t launch_moe_combine(int dtype, const void *h, const void *expert_out,
+                              const int32_t *pair_pos, const float *expert_w, void *out, int T,
+                              int d, int top_k, hipStream_t s);
+
+void set_error(const char *fmt, ...);
+
+}  // namespace pd

@@ -1,0 +1,193 @@
+"""GPU parity: the HIP layer forward (through the C ABI) against the CPU oracle, element by
+element, on the same seeded inputs.  Bound: max |gpu - ref| / max |ref| <= 1e-5 (fp32 layers),
+<= 2e-2 (bf16 layers)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2603_04716_amd as pd
+import pd_inputs as I
+from oracle import layer as O
+from gpu_util import GpuLayer, TOL, relmax, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def both(cfg, std=0.02, with_router=False, seed=None):
+    w = I.layer_weights(cfg, seed=seed, std=std, with_router=with_router)
+    return O.Layer(cfg, w), GpuLayer(cfg, w)
+
+
+def test_tiny_config_two_layers_prefill_and_decode():
+    cfg = I.CONFIGS["tiny"]
+    layers = [both(cfg, seed=cfg["seed"] + i) for i in range(2)]
+    tol = TOL["f32"]
+    # prefill: 4 sequences of 128 rows through both layers
+    x = I.hidden(512, cfg["d_model"], seed=100)
+    cu = I.uniform_cu_seqlens(4, 128)
+    ref, got = x, x
+    for ol, gl in layers:
+        ref = O.prefill(ol, ref, cu)
+        got = gl.prefill(got, cu)
+        assert relmax(got, ref) <= tol
+    # decode: batch 8, each sequence over a 128-token cache produced by its own prefill
+    xp = I.hidden(8 * 128, cfg["d_model"], seed=101)
+    cu8 = I.uniform_cu_seqlens(8, 128)
+    slots = list(range(8))
+    ocaches = [O.KVCache(ol, 8, 130) for ol, _ in layers]
+    gcaches = [gl.cache(8, 130) for _, gl in layers]
+    ref, got = xp, xp
+    for (ol, gl), oc, gc in zip(layers, ocaches, gcaches):
+        ref = O.prefill(ol, ref, cu8, cache=oc, slots=slots)
+        got = gl.prefill(got, cu8, cache=gc, slots=slots)
+        assert relmax(got, ref) <= tol
+    for step in range(2):
+        xn = I.hidden(8, cfg["d_model"], seed=102 + step)
+        ref, got = xn, xn
+        for (ol, gl), oc, gc in zip(layers, ocaches, gcaches):
+            ref = O.decode_step(ol, ref, slots, oc)
+            got = gl.decode(got, slots, gc)
+            assert relmax(got, ref) <= tol
+            assert pd.pd_kv_cache_len(gc, 3) == 129 + step
+    for _, gl in layers:
+        gl.close()
+
+
+SMALL = [
+    dict(),
+    dict(n_q_heads=4, n_kv_heads=4),
+    dict(n_q_heads=8, n_kv_heads=1, head_dim=16),
+    dict(d_model=96, n_q_heads=6, n_kv_heads=3, head_dim=8, d_ff=80),
+    dict(d_model=200, n_q_heads=2, n_kv_heads=1, head_dim=130, d_ff=72),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("over", SMALL)
+def test_small_ragged_prefill_then_decode(over, dtype):
+    cfg = I.small_config(dtype=dtype, **over)
+    ol, gl = both(cfg, std=0.08)
+    tol = TOL[dtype]
+    cu = np.array([0, 70, 70, 199, 200, 333], np.int32)     # ragged, one empty, one single-token
+    x = I.hidden(int(cu[-1]), cfg["d_model"], seed=5, dtype=dtype)
+    slots = [4, 0, 2, 5, 1]
+    oc, gc = O.KVCache(ol, 6, 140), gl.cache(6, 140)
+    ref = O.prefill(ol, x, cu, cache=oc, slots=slots)
+    got = gl.prefill(x, cu, cache=gc, slots=slots)
+    assert relmax(got, ref) <= tol
+    assert [pd.pd_kv_cache_len(gc, s) for s in slots] == [70, 0, 129, 1, 133]
+    # without a cache the output is the same
+    assert np.array_equal(gl.prefill(x, cu), got)
+    for step in range(3):
+        xn = I.hidden(5, cfg["d_model"], seed=50 + step, dtype=dtype)
+        ref = O.decode_step(ol, xn, slots, oc)
+        got = gl.decode(xn, slots, gc)
+        assert relmax(got, ref) <= tol
+    # cache contents: rotated keys and values of slot 2
+    Hkv, hd = cfg["n_kv_heads"], cfg["head_dim"]
+    n = 129 + 3
+    k = torch.empty((Hkv, n, hd), dtype=torch.bfloat16 if dtype == "bf16" else torch.float32, device="cuda")
+    v = torch.empty_like(k)
+    pd.pd_kv_cache_get(gc, 2, k, v)
+    torch.cuda.synchronize()
+    assert relmax(to_np(k), oc.k[2, :, :n]) <= tol
+    assert relmax(to_np(v), oc.v[2, :, :n]) <= tol
+    gl.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_moe_small(dtype):
+    cfg = I.small_config(dtype=dtype, n_experts=8, top_k=2, d_ff=96)
+    ol, gl = both(cfg, std=0.08, with_router=True)
+    tol = TOL[dtype]
+    cu = np.array([0, 37, 150], np.int32)
+    x = I.hidden(150, cfg["d_model"], seed=6, dtype=dtype)
+    r = I.router_logits(150, 8, seed=9)
+    r[3] = 0.25                                  # all-equal logits: ties resolve to experts 0, 1
+    r[4, 5] = r[4, 2] = 3.0                      # two-way tie at the top
+    ref, eref = O.prefill(ol, x, cu, router_logits=r, return_experts=True)
+    got = gl.prefill(x, cu, router_logits=r)
+    assert np.array_equal(gl.experts(150), eref)            # integer decisions: bit-exact
+    assert relmax(got, ref) <= tol
+    if dtype == "f32":
+        # router computed on the device from w_router (fp32 logits decide the experts; a bf16
+        # layer could legitimately flip a near-tie, so only the fp32 layer is compared here)
+        ref, eref = O.prefill(ol, x, cu, return_experts=True)
+        got = gl.prefill(x, cu)
+        assert np.array_equal(gl.experts(150), eref)
+        assert relmax(got, ref) <= tol
+    oc, gc = O.KVCache(ol, 2, 160), gl.cache(2, 160)
+    O.prefill(ol, x, cu, router_logits=r, cache=oc, slots=[0, 1])
+    gl.prefill(x, cu, cache=gc, slots=[0, 1], router_logits=r)
+    xn = I.hidden(2, cfg["d_model"], seed=77, dtype=dtype)
+    rn = I.router_logits(2, 8, seed=78)
+    ref, eref = O.decode_step(ol, xn, [0, 1], oc, router_logits=rn, return_experts=True)
+    got = gl.decode(xn, [0, 1], gc, router_logits=rn)
+    assert np.array_equal(gl.experts(2), eref)
+    assert relmax(got, ref) <= tol
+    gl.close()
+
+
+def test_kv_cache_set_get_and_errors():
+    cfg = I.small_config()
+    ol, gl = both(cfg)
+    gc = gl.cache(3, 16)
+    k, v = I.kv_fill(cfg["n_kv_heads"], 10, cfg["head_dim"], seed=3, dtype="f32")
+    kd, vd = to_dev(k, "f32"), to_dev(v, "f32")
+    pd.pd_kv_cache_set(gc, 1, kd, vd)
+    assert pd.pd_kv_cache_len(gc, 1) == 10
+    k2, v2 = torch.empty_like(kd), torch.empty_like(vd)
+    pd.pd_kv_cache_get(gc, 1, k2, v2)
+    torch.cuda.synchronize()
+    assert torch.equal(k2, kd) and torch.equal(v2, vd)
+    # decode over a filled cache equals the oracle over the same contents
+    oc = O.KVCache(ol, 3, 16)
+    oc.set(1, k, v)
+    xn = I.hidden(1, cfg["d_model"], seed=4)
+    assert relmax(gl.decode(xn, [1], gc), O.decode_step(ol, xn, [1], oc)) <= TOL["f32"]
+    # errors: full slot, repeated slot, slot out of range, too-long sequence; state unchanged
+    pd.pd_kv_cache_set_len(gc, 2, 16)
+    x2 = to_dev(I.hidden(2, cfg["d_model"], seed=5), "f32")
+    out = torch.zeros_like(x2)
+    for slots, status in [([1, 2], pd.PD_ERR_KV_CAPACITY), ([1, 1], pd.PD_ERR_INVALID_ARG), ([1, 3], pd.PD_ERR_INVALID_ARG)]:
+        with pytest.raises(pd.PdError) as e:
+            pd.pd_decode_step(gl.h, x2, slots, gc, out)
+        assert e.value.status == status
+    torch.cuda.synchronize()
+    assert pd.pd_kv_cache_len(gc, 1) == 11 and float(out.abs().sum()) == 0.0
+    xl = to_dev(I.hidden(17, cfg["d_model"], seed=6), "f32")
+    with pytest.raises(pd.PdError) as e:
+        pd.pd_prefill(gl.h, xl, [0, 17], torch.empty_like(xl), gc, [0])
+    assert e.value.status == pd.PD_ERR_KV_CAPACITY
+    with pytest.raises(pd.PdError) as e:
+        pd.pd_prefill(gl.h, xl, [0, 9, 8, 17], torch.empty_like(xl))
+    assert e.value.status == pd.PD_ERR_SHAPE
+    # empty batch is a no-op
+    pd.pd_prefill(gl.h, None, [0, 0], None)
+    gl.close()
+
+
+def test_layer_create_rejects_bad_shapes():
+    cfg = I.small_config()
+    w = {k: to_dev(v, "f32") for k, v in I.layer_weights(cfg).items()}
+    for over, status in [(dict(head_dim=31), pd.PD_ERR_SHAPE), (dict(n_q_heads=3), pd.PD_ERR_SHAPE),
+                         (dict(n_experts=4, top_k=5), pd.PD_ERR_SHAPE)]:
+        with pytest.raises(pd.PdError) as e:
+            pd.pd_layer_create(dict(cfg, **over), w)
+        assert e.value.status == status
+    w2 = dict(w)
+    w2["w_o"] = None
+    with pytest.raises(pd.PdError) as e:
+        pd.pd_layer_create(cfg, w2)
+    assert e.value.status == pd.PD_ERR_INVALID_ARG
+
+
+def test_deterministic_across_runs():
+    cfg = I.small_config(dtype="bf16")
+    ol, gl = both(cfg, std=0.08)
+    x = I.hidden(300, cfg["d_model"], seed=1, dtype="bf16")
+    cu = np.array([0, 100, 300], np.int32)
+    a = gl.prefill(x, cu)
+    for _ in range(3):
+        assert np.array_equal(gl.prefill(x, cu), a)
+    gl.close()
