@@ -1,5 +1,287 @@
+// bf16 GEMM on the CDNA4 matrix cores:  C[M,N] = epilogue(A[M,K] * B[N,K]^T), fp32 accumulation.
+//
+// Both operands are K-contiguous, which is exactly the per-lane operand layout of
+// v_mfma_f32_32x32x16_bf16 (each lane supplies 8 consecutive k of one row / column), so tiles go
+// global -> LDS with the direct-to-LDS 16-byte loads of gfx950 (no staging registers, no LDS
+// write instructions) and LDS -> registers with 16-byte reads, with no transposition anywhere.
+// A direct load puts lane i's 16 bytes at LDS offset base + 16*i, so the XOR swizzle that keeps
+// the fragment reads free of bank conflicts is applied on the global side: the lane that owns LDS
+// slot (row, s) fetches chunk s ^ ((row >> 1) & 7) of that row.  LDS is double buffered: the loads
+// of tile k+1 are in flight while the matrix cores work on tile k; one barrier per tile.
+//
+// Epilogues: plain store, residual add, and SwiGLU.  For SwiGLU the weight is packed at layer
+// creation as alternating 32-row blocks (gate rows j..j+31, then up rows j..j+31); an MFMA output
+// block pair then holds gate and up of the same (row, column) in the same lane and register, and
+// silu(gate)*up is formed without any data exchange.
+//
+// Optional row gather on A and per-group B matrices serve the mixture-of-experts grouped GEMM.
 #include "pd_internal.h"
+
 namespace pd {
-bool gemm_mfma_supported(const GemmArgs &) { return false; }
-hipError_t launch_gemm_mfma(const GemmArgs &, hipStream_t) { return hipErrorNotSupported; }
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int BK = 64;  // k per tile: 8 chunks of 16 bytes per row
+
+__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
+
+__device__ __forceinline__ float silu_fast(float z) { return z / (1.0f + __expf(-z)); }
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
+__global__ __launch_bounds__(64 * WAVES_M *WAVES_N) void gemm_mfma_kernel(GemmArgs a, int tiles_m,
+                                                                          int tiles_n)
+{
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;   // wave tile
+    constexpr int MB = WM / 32, NB = WN / 32;             // 32x32 blocks per wave
+    static_assert(EPI != EPI_SWIGLU || NB % 2 == 0, "SwiGLU pairs two column blocks");
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
+
+    // ---- tile id: contiguous ranges of tiles per XCD, 8-row bands inside ------------------------
+    const int n_tiles = tiles_m * tiles_n;
+    int pid = blockIdx.x;
+    {
+        const int per = n_tiles / 8, rem = n_tiles % 8;
+        if (per > 0) {
+            // blocks are dealt to the 8 XCDs round-robin; give each XCD one contiguous range
+            int xcd = pid % 8, j = pid / 8;
+            if (j < per) pid = xcd * per + j;
+            else pid = 8 * per + (pid - 8 * per);   // leftover tiles keep their order
+            (void)rem;
+        }
+    }
+    int tm, tn;
+    {
+        constexpr int GM = 8;
+        int band = pid / (GM * tiles_n);
+        int first = band * GM;
+        int rows = tiles_m - first < GM ? tiles_m - first : GM;
+        int in = pid - band * GM * tiles_n;
+        tm = first + in % rows;
+        tn = in / rows;
+    }
+
+    // ---- rows of this tile (virtual m-tiles map to groups for the grouped GEMM) -----------------
+    int row0, row_end, group = 0;
+    if (a.group_offsets) {
+        int acc = 0;
+        row0 = -1;
+        row_end = 0;
+        for (int g = 0; g < a.n_groups; ++g) {
+            int lo = a.group_offsets[g], hi = a.group_offsets[g + 1];
+            int nt = (hi - lo + BM - 1) / BM;
+            if (tm < acc + nt) {
+                group = g;
+                row0 = lo + (tm - acc) * BM;
+                row_end = hi;
+                break;
+            }
+            acc += nt;
+        }
+        if (row0 < 0) return;
+    } else {
+        row0 = tm * BM;
+        row_end = a.M;
+    }
+    const int col0 = tn * BN;
+    const int n_cols = (EPI == EPI_SWIGLU) ? 2 * a.N : a.N;   // rows of (packed) B
+    const __bf16 *A = (const __bf16 *)a.A;
+    const __bf16 *B = (const __bf16 *)a.B + (size_t)group * a.b_group_stride;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+
+    // ---- loader: wave instruction i covers 8 rows x 128 bytes = 1 KB of LDS; lane l owns slot
+    //      (row = 8*blk + l/8, s = l%8) and fetches chunk s ^ swizzle(row) of that row ------------------
+    constexpr int NW = WAVES_M * WAVES_N;
+    constexpr int A_LD = BM / 8 / NW, B_LD = BN / 8 / NW;   // load instructions per wave
+    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "loader mapping");
+    uint32_t a_off[A_LD], b_off[B_LD];
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i) {
+        int r = (i * NW + wave) * 8 + (lane >> 3);
+        int c = swz(r, lane & 7);
+        int gr = row0 + r;
+        if (gr >= row_end) gr = row_end - 1;          // clamp: loaded but never stored
+        if (a.a_gather) gr = a.a_gather[gr];
+        a_off[i] = (uint32_t)gr * (uint32_t)(a.lda * 2) + c * 16;
+    }
+#pragma unroll
+    for (int i = 0; i < B_LD; ++i) {
+        int r = (i * NW + wave) * 8 + (lane >> 3);
+        int c = swz(r, lane & 7);
+        int gc = col0 + r;
+        if (gc >= n_cols) gc = n_cols - 1;
+        b_off[i] = (uint32_t)gc * (uint32_t)(a.ldb * 2) + c * 16;
+    }
+    typedef const void __attribute__((address_space(1))) *gptr_t;
+    typedef void __attribute__((address_space(3))) *lptr_t;
+    auto issue_loads = [&](int kt, unsigned char *st) {
+        const char *ab = (const char *)A + (size_t)kt * (BK * 2);
+        const char *bb = (const char *)B + (size_t)kt * (BK * 2);
+#pragma unroll
+        for (int i = 0; i < A_LD; ++i)
+            __builtin_amdgcn_global_load_lds((gptr_t)(ab + a_off[i]),
+                                             (lptr_t)(st + (i * NW + wave) * 1024), 16, 0, 0);
+#pragma unroll
+        for (int i = 0; i < B_LD; ++i)
+            __builtin_amdgcn_global_load_lds((gptr_t)(bb + b_off[i]),
+                                             (lptr_t)(st + A_BYTES + (i * NW + wave) * 1024), 16, 0, 0);
+    };
+
+    f32x16 acc[MB][NB];
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const int nk = a.K / BK;
+    issue_loads(0, smem);
+    __syncthreads();
+
+    // fragment addresses inside a stage: row and the two chunk parities of this lane
+    const int frow = lane & 31, fhalf = lane >> 5;
+    // Fragment reads of k-step kk+1 are issued between the MFMAs of k-step kk (register double
+    // buffer); sched_group_barrier pins that interleaving so that LDS latency hides behind the
+    // matrix pipe.
+    auto load_frags = [&](const unsigned char *st, int kk, bf16x8 (&fa)[MB], bf16x8 (&fb)[NB]) {
+        const int c = kk * 2 + fhalf;
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+            int r = wm * WM + i * 32 + frow;
+            fa[i] = *(const bf16x8 *)(st + r * 128 + swz(r, c) * 16);
+        }
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            int r = wn * WN + j * 32 + frow;
+            fb[j] = *(const bf16x8 *)(st + A_BYTES + r * 128 + swz(r, c) * 16);
+        }
+    };
+    auto mma = [&](bf16x8 (&fa)[MB], bf16x8 (&fb)[NB]) {
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+#pragma unroll
+            for (int j = 0; j < NB; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    };
+    auto compute = [&](const unsigned char *st) {
+        bf16x8 fa0[MB], fb0[NB], fa1[MB], fb1[NB];
+        load_frags(st, 0, fa0, fb0);
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; kk += 2) {
+            load_frags(st, kk + 1, fa1, fb1);
+            mma(fa0, fb0);
+#pragma unroll
+            for (int q = 0; q < MB + NB; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, MB * NB - (MB + NB), 0);
+            if (kk + 2 < BK / 16) load_frags(st, kk + 2, fa0, fb0);
+            mma(fa1, fb1);
+            if (kk + 2 < BK / 16) {
+#pragma unroll
+                for (int q = 0; q < MB + NB; ++q) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, MB * NB - (MB + NB), 0);
+            }
+        }
+    };
+    for (int kt = 0; kt + 1 < nk; ++kt) {
+        issue_loads(kt + 1, smem + ((kt + 1) & 1) * STAGE);
+        __builtin_amdgcn_sched_barrier(0);     // keep the loads ahead of the compute phase
+        compute(smem + (kt & 1) * STAGE);
+        __syncthreads();                       // waits for the loads, then for all waves
+    }
+    compute(smem + ((nk - 1) & 1) * STAGE);
+
+    // ---- epilogue: lane holds column (lane % 32) of each block; register r is row
+    //      8*(r/4) + 4*(lane/32) + r%4 ----------------------------------------------------------------
+    uint16_t *C = (uint16_t *)a.C;
+    const uint16_t *R = (const uint16_t *)a.R;
+#pragma unroll
+    for (int i = 0; i < MB; ++i) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int m = row0 + wm * WM + i * 32 + 8 * (r >> 2) + 4 * fhalf + (r & 3);
+            if (m >= row_end) continue;
+            if (EPI == EPI_SWIGLU) {
+#pragma unroll
+                for (int j = 0; j < NB; j += 2) {
+                    const int np = col0 + wn * WN + j * 32;       // packed column of the gate block
+                    const int f = (np >> 6) * 32 + frow;
+                    if (f < a.N) {
+                        float v = silu_fast(acc[i][j][r]) * acc[i][j + 1][r];
+                        C[(size_t)m * a.ldc + f] = f2bf(v).x;
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < NB; ++j) {
+                    const int n = col0 + wn * WN + j * 32 + frow;
+                    if (n < a.N) {
+                        float v = acc[i][j][r];
+                        if (EPI == EPI_RESIDUAL) v += bfbits2f(R[(size_t)m * a.ldr + n]);
+                        C[(size_t)m * a.ldc + n] = f2bf(v).x;
+                    }
+                }
+            }
+        }
+    }
+}
+
+bool gemm_mfma_supported(const GemmArgs &a)
+{
+    if (a.K % BK != 0 || a.K <= 0 || a.M <= 0) return false;
+    if (a.lda % 8 != 0 || a.ldb % 8 != 0) return false;
+    // 32-bit byte offsets inside A and inside one group of B
+    const int64_t brows = a.epilogue == EPI_SWIGLU ? 2 * (int64_t)a.N : a.N;
+    if ((int64_t)a.ldb * 2 * brows >= (1ll << 32)) return false;
+    if (!a.a_gather && (int64_t)a.lda * 2 * a.M >= (1ll << 32)) return false;
+    if (a.a_gather && (int64_t)a.lda * 2 * a.M >= (1ll << 31)) return false;
+    if (a.epilogue == EPI_SWIGLU) return a.interleaved && a.N % 32 == 0;
+    return true;
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N>
+static hipError_t launch_cfg(const GemmArgs &a, hipStream_t s)
+{
+    const int n_cols = a.epilogue == EPI_SWIGLU ? 2 * a.N : a.N;
+    const int tiles_n = (n_cols + BN - 1) / BN;
+    const int tiles_m = (a.M + BM - 1) / BM + (a.group_offsets ? a.n_groups : 0);
+    const size_t smem = 2 * (size_t)(BM + BN) * BK * 2;
+    const dim3 grid((unsigned)(tiles_m * tiles_n));
+    const dim3 block(64 * WAVES_M * WAVES_N);
+#define LAUNCH(EPI)                                                                              \
+    do {                                                                                         \
+        auto kern = gemm_mfma_kernel<BM, BN, WAVES_M, WAVES_N, EPI>;                             \
+        static bool attr_set = false;                                                            \
+        if (!attr_set) {                                                                         \
+            hipError_t e = hipFuncSetAttribute((const void *)kern,                               \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); \
+            if (e != hipSuccess) return e;                                                       \
+            attr_set = true;                                                                     \
+        }                                                                                        \
+        kern<<<grid, block, smem, s>>>(a, tiles_m, tiles_n);                                     \
+    } while (0)
+    switch (a.epilogue) {
+    case EPI_NONE: LAUNCH(EPI_NONE); break;
+    case EPI_RESIDUAL: LAUNCH(EPI_RESIDUAL); break;
+    default: LAUNCH(EPI_SWIGLU); break;
+    }
+#undef LAUNCH
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t s)
+{
+    if (a.M > 128) return launch_cfg<256, 256, 2, 4>(a, s);   // 8 waves: two per SIMD hide each other's stalls
+    return launch_cfg<128, 128, 2, 2>(a, s);
+}
+
 }  // namespace pd
