@@ -19,7 +19,9 @@ struct pd_layer {
     bool interleaved;    // gate/up rows stored as alternating 32-row blocks
     void *g_attn, *g_ffn, *w_qkv, *w_o, *w_gate, *w_up, *w_down, *w_router;
     double *inv_freq;
-    int32_t *d_cu, *d_slots;  // [4097] each
+    int32_t *d_cu, *d_slots, *d_pad_cu;  // [4097] each
+    void *vt;                 // transposed-V scratch for the MFMA attention, vt_cap bytes
+    size_t vt_cap;
     // workspace, sized for ws_tokens rows
     int ws_tokens;
     char *ws;
@@ -68,7 +70,7 @@ static void free_layer(pd_layer *L)
 {
     if (!L) return;
     void *ptrs[] = {L->g_attn, L->g_ffn, L->w_qkv, L->w_o, L->w_gate, L->w_up, L->w_down,
-                    L->w_router, L->inv_freq, L->d_cu, L->d_slots, L->ws};
+                    L->w_router, L->inv_freq, L->d_cu, L->d_slots, L->d_pad_cu, L->vt, L->ws};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     delete L;
@@ -133,6 +135,7 @@ extern "C" pd_status pd_layer_create(const pd_layer_config *cfg, const pd_layer_
     CREATE_TRY(hipMalloc(&L->inv_freq, sizeof(double) * (hd / 2)));
     CREATE_TRY(hipMalloc(&L->d_cu, sizeof(int32_t) * (kMaxSeqs + 1)));
     CREATE_TRY(hipMalloc(&L->d_slots, sizeof(int32_t) * (kMaxSeqs + 1)));
+    CREATE_TRY(hipMalloc(&L->d_pad_cu, sizeof(int32_t) * (kMaxSeqs + 1)));
     CREATE_TRY(hipMemcpy(L->g_attn, w->g_attn, d * esz, hipMemcpyDeviceToDevice));
     CREATE_TRY(hipMemcpy(L->g_ffn, w->g_ffn, d * esz, hipMemcpyDeviceToDevice));
     CREATE_TRY(hipMemcpy(L->w_qkv, w->w_q, (size_t)L->Nq * d * esz, hipMemcpyDeviceToDevice));
@@ -484,8 +487,31 @@ extern "C" pd_status pd_prefill(pd_layer *L, const pd_tokens *tk, pd_kv_cache *c
     a.qkv = L->qkv; a.ld = L->Nqkv; a.o = L->o; a.T = T; a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads;
     a.hd = c.head_dim; a.scale = (float)(1.0 / sqrt((double)c.head_dim)); a.tok_pos = L->tok_pos;
     a.decode = 0; a.d_cu = L->d_cu; a.n_seqs = n; a.max_seq_len = max_L;
-    if (L->use_mfma && attn_prefill_mfma_supported(a)) HIP_TRY(launch_attn_prefill_mfma(a, s), PD_ERR_DEVICE);
-    else HIP_TRY(launch_attn_generic(c.dtype, a, s), PD_ERR_DEVICE);
+    if (L->use_mfma && attn_prefill_mfma_supported(a)) {
+        // padded sequence starts (multiples of 64) for the transposed-V scratch
+        std::vector<int32_t> pad((size_t)n + 1);
+        pad[0] = 0;
+        for (int q = 0; q < n; ++q)
+            pad[(size_t)q + 1] = pad[(size_t)q] + (tk->cu_seqlens[q + 1] - tk->cu_seqlens[q] + 63) / 64 * 64;
+        const int vt_ld = pad[(size_t)n];
+        const size_t need = (size_t)c.n_kv_heads * c.head_dim * vt_ld * 2;
+        if (need > L->vt_cap) {
+            HIP_TRY(hipDeviceSynchronize(), PD_ERR_DEVICE);
+            if (L->vt) (void)hipFree(L->vt);
+            L->vt = nullptr;
+            L->vt_cap = 0;
+            hipError_t e = hipMalloc(&L->vt, need);
+            if (e != hipSuccess) {
+                set_error("pd_prefill: cannot allocate %zu bytes of attention scratch", need);
+                return PD_ERR_OOM;
+            }
+            L->vt_cap = need;
+        }
+        HIP_TRY(launch_write_ints(L->d_pad_cu, pad.data(), n + 1, s), PD_ERR_DEVICE);
+        HIP_TRY(launch_attn_prefill_mfma(a, (uint16_t *)L->vt, vt_ld, L->d_pad_cu, s), PD_ERR_DEVICE);
+    } else {
+        HIP_TRY(launch_attn_generic(c.dtype, a, s), PD_ERR_DEVICE);
+    }
     st = run_tail(L, tk->hidden, T, tk->router_logits, out, s);
     if (st != PD_OK) return st;
     if (keep) {

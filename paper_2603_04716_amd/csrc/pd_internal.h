@@ -118,7 +118,10 @@ struct AttnArgs {
 };
 hipError_t launch_attn_generic(int dtype, const AttnArgs &a, hipStream_t s);
 bool attn_prefill_mfma_supported(const AttnArgs &a);
-hipError_t launch_attn_prefill_mfma(const AttnArgs &a, hipStream_t s);  // bf16, hd = 128
+// bf16, hd = 128.  vt: scratch for V transposed, [Hkv][128][vt_ld] with vt_ld = padded token count
+// (each sequence start rounded up to a multiple of 64); pad_cu: device [n_seqs+1] padded starts.
+hipError_t launch_attn_prefill_mfma(const AttnArgs &a, uint16_t *vt, int vt_ld, const int32_t *pad_cu,
+                                    hipStream_t s);
 
 hipError_t launch_kv_copy(int dtype, void *cache_k, void *cache_v, const void *k, const void *v,
                           int slot, int Hkv, int len, int hd, int max_len, int to_cache,

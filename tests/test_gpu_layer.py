@@ -59,6 +59,7 @@ SMALL = [
     dict(n_q_heads=8, n_kv_heads=1, head_dim=16),
     dict(d_model=96, n_q_heads=6, n_kv_heads=3, head_dim=8, d_ff=80),
     dict(d_model=200, n_q_heads=2, n_kv_heads=1, head_dim=130, d_ff=72),
+    dict(d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=128, d_ff=512),     # MFMA-eligible in bf16
 ]
 
 
@@ -125,6 +126,29 @@ def test_moe_small(dtype):
     got = gl.decode(xn, [0, 1], gc, router_logits=rn)
     assert np.array_equal(gl.experts(2), eref)
     assert relmax(got, ref) <= tol
+    gl.close()
+
+
+@pytest.mark.parametrize("hq,hkv", [(4, 1), (2, 2)])
+def test_bf16_matrix_core_path_long_ragged(hq, hkv):
+    """head_dim 128 in bf16 runs the MFMA GEMM and MFMA attention kernels: several query blocks and
+    key tiles per sequence, ragged tails, a one-token and an empty sequence."""
+    cfg = I.small_config(dtype="bf16", d_model=256, n_q_heads=hq, n_kv_heads=hkv, head_dim=128, d_ff=512)
+    ol, gl = both(cfg, std=0.05)
+    cu = np.array([0, 600, 601, 601, 858, 1243, 1307], np.int32)
+    x = I.hidden(int(cu[-1]), cfg["d_model"], seed=21, dtype="bf16")
+    slots = [0, 1, 2, 3, 4, 5]
+    oc, gc = O.KVCache(ol, 6, 640), gl.cache(6, 640)
+    ref = O.prefill(ol, x, cu, cache=oc, slots=slots)
+    got = gl.prefill(x, cu, cache=gc, slots=slots)
+    assert relmax(got, ref) <= TOL["bf16"]
+    # per-sequence check as well, so that a short sequence cannot hide behind a large global max
+    for s in range(6):
+        a, b = cu[s], cu[s + 1]
+        if b > a:
+            assert relmax(got[a:b], ref[a:b]) <= TOL["bf16"]
+    xn = I.hidden(6, cfg["d_model"], seed=22, dtype="bf16")
+    assert relmax(gl.decode(xn, slots, gc), O.decode_step(ol, xn, slots, oc)) <= TOL["bf16"]
     gl.close()
 
 
