@@ -1,0 +1,210 @@
+#!/usr/bin/env python3
+"""Benchmark of the P/D hot path on one MI355X.
+
+One "step" is one pass of the whole path on the Llama-8B-shaped bf16 layer: a prefill of 8192
+tokens (4 sequences of 2048), one decode step at every batch of the sweep 1..256 over a
+2048-token KV cache, and the allocation model on the curves just measured (per-layer times
+scaled by 32 layers).  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0     # dense bf16 matrix peak of MI355X
+HBM_PEAK_GBPS = 8000.0
+N_LAYERS = 32
+L_IN, N_SEQ = 2048, 4              # prefill workload: 4 x 2048 = 8192 tokens
+KV_LEN = 2048
+BATCHES = [1, 2, 4, 8, 16, 32, 64, 128, 256]
+TTFT_SLO, TPOT_SLO, L_OUT = 2.0, 0.020, 512.0
+
+
+def cpu_baseline(cfg, weights):
+    """The oracle, as it stands, timed on a bounded sample: prefill of one 192-token sequence
+    through the full 8B-shaped layer on the host cores."""
+    import numpy as np
+    import pd_inputs as I
+    from oracle import layer as O
+    n = 192
+    x = I.hidden(n, cfg["d_model"], seed=99, dtype="bf16")
+    L = O.Layer(cfg, weights)
+    t0 = time.perf_counter()
+    O.prefill(L, x, np.array([0, n], np.int32))
+    dt = time.perf_counter() - t0
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    cores = min(cores, os.cpu_count() or cores)
+    return {"value": n / (dt * N_LAYERS), "unit": "prefill tokens/s (32-layer model)", "cores": cores,
+            "kind": "oracle", "sample": f"prefill of 1x{n} tokens through the full 8B-shaped layer, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the path uses no second device and no collectives; "
+              "run it with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import pd_inputs as I
+    import paper_2603_04716_amd as pd
+    from paper_2603_04716_amd import harness as H
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    cfg = I.CONFIGS["llama8b"]
+    weights = I.layer_weights(cfg)
+    layer = H.Layer(cfg, weights)
+    T = L_IN * N_SEQ
+    x = H._dev(I.hidden(T, cfg["d_model"], seed=10, dtype="bf16"), "bf16")
+    out = torch.empty_like(x)
+    cu = [L_IN * i for i in range(N_SEQ + 1)]
+    pd.pd_layer_reserve(layer.h, T)
+
+    # decode state: every slot holds the same seeded N(0,1) keys / values
+    bmax = max(BATCHES)
+    cache = layer.new_cache(bmax, KV_LEN + 8)
+    k, v = I.kv_fill(cfg["n_kv_heads"], KV_LEN, cfg["head_dim"], seed=11, dtype="bf16")
+    kd, vd = H._dev(k, "bf16"), H._dev(v, "bf16")
+    layer.fill_cache(cache, [KV_LEN] * bmax, kd, vd)
+    xdec = H._dev(I.hidden(bmax, cfg["d_model"], seed=12, dtype="bf16"), "bf16")
+    runs = {B: layer.make_decode_step(cache, xdec[:B].contiguous(), [KV_LEN] * B, use_graph=not args.no_graph)
+            for B in BATCHES}
+    torch.cuda.synchronize()
+
+    prof = {}            # step name -> list of ms (prefill call)
+    dec_prof = {}        # (B, name) -> list of ms (un-graphed profiled decode step, outside the timed region)
+
+    def one_step(record):
+        pd.pd_profile_enable(layer.h, True)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        pd.pd_prefill(layer.h, x, cu, out)
+        e1.record()
+        e1.synchronize()
+        entries = pd.pd_profile_read(layer.h)
+        pd.pd_profile_enable(layer.h, False)
+        t_pre = e0.elapsed_time(e1)
+        t_dec = {B: runs[B]() for B in BATCHES}
+        # allocation model on the curves just measured (instance = 32 layers of this layer)
+        tp_hat = T / (N_LAYERS * t_pre * 1e-3)
+        tpot = [N_LAYERS * t_dec[B] * 1e-3 for B in BATCHES]
+        alloc = pd.pd_allocate(5e6 / 60.0, float(L_IN), L_OUT, TTFT_SLO, TPOT_SLO, tp_hat, BATCHES, tpot)
+        if record:
+            for name, ms in entries:
+                prof.setdefault(name, []).append(ms)
+        return t_pre, t_dec, alloc
+
+    for _ in range(args.warmup):
+        one_step(False)
+    torch.cuda.synchronize()
+    t_pre_all, t_dec_all, alloc = [], {B: [] for B in BATCHES}, None
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        t_pre, t_dec, alloc = one_step(True)
+        t_pre_all.append(t_pre)
+        for B in BATCHES:
+            t_dec_all[B].append(t_dec[B])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    # per-kernel durations of a decode step (events between kernels; not part of the timed region)
+    slots_all = list(range(bmax))
+    pd.pd_profile_enable(layer.h, True)
+    for B in (BATCHES[0], BATCHES[-1]):
+        for _ in range(3):
+            pd.pd_kv_cache_set_lens(cache, slots_all[:B], [KV_LEN] * B)
+            pd.pd_decode_step(layer.h, xdec[:B].contiguous(), slots_all[:B], cache, runs[B].out)
+            for name, ms in pd.pd_profile_read(layer.h):
+                dec_prof.setdefault((B, name), []).append(ms)
+    pd.pd_profile_enable(layer.h, False)
+
+    med = H.median
+    t_pre = med(t_pre_all)
+    t_dec = {B: med(t_dec_all[B]) for B in BATCHES}
+    prefill_tps_layer = T / (t_pre * 1e-3)
+    prefill_tps = prefill_tps_layer / N_LAYERS
+    fl = H.prefill_flops(cfg, [L_IN] * N_SEQ)
+    curve = []
+    for B in BATCHES:
+        by = H.decode_bytes(cfg, [KV_LEN] * B)
+        curve.append({"batch": B, "ms_per_layer": round(t_dec[B], 4), "tpot_ms": round(N_LAYERS * t_dec[B], 3),
+                      "tok_s": round(B / (N_LAYERS * t_dec[B] * 1e-3), 1),
+                      "hbm_gbps": round(by / (t_dec[B] * 1e-3) / 1e9, 1),
+                      "hbm_frac": round(by / (t_dec[B] * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)})
+    b_star = alloc["decode_batch"]
+    star = next(c for c in curve if c["batch"] == b_star)
+
+    # dominant kernel of the step: the fused gate/up + SwiGLU GEMM of the prefill pass
+    d, f = cfg["d_model"], cfg["d_ff"]
+    gu_ms = med(prof["gate_up_swiglu"])
+    gu_flops = 2.0 * T * (2 * f) * d
+    kernels = {}
+    gemm_flops = {"qkv_proj": 2.0 * T * (cfg["n_q_heads"] + 2 * cfg["n_kv_heads"]) * cfg["head_dim"] * d,
+                  "o_proj_residual": 2.0 * T * d * cfg["n_q_heads"] * cfg["head_dim"],
+                  "gate_up_swiglu": gu_flops, "down_residual": 2.0 * T * d * f,
+                  "prefill_attention": N_SEQ * 2.0 * cfg["n_q_heads"] * cfg["head_dim"] * L_IN * (L_IN + 1)}
+    for name, ms in prof.items():
+        e = {"ms": round(med(ms), 4)}
+        if name in gemm_flops:
+            e["tflops"] = round(gemm_flops[name] / (med(ms) * 1e-3) / 1e12, 1)
+            e["mfma_frac"] = round(e["tflops"] / MFMA_BF16_PEAK_TFLOPS, 4)
+        kernels["prefill." + name] = e
+    kv_bytes = lambda B: 2.0 * cfg["n_kv_heads"] * cfg["head_dim"] * 2 * (KV_LEN + 1) * B
+    attn_p, ffn_p = H.layer_params(cfg)
+    w_bytes = {"qkv_proj": 2.0 * d * (cfg["n_q_heads"] + 2 * cfg["n_kv_heads"]) * cfg["head_dim"],
+               "o_proj_residual": 2.0 * d * cfg["n_q_heads"] * cfg["head_dim"],
+               "gate_up_swiglu": 4.0 * d * f, "down_residual": 2.0 * d * f}
+    for (B, name), ms in dec_prof.items():
+        e = {"ms": round(med(ms), 4)}
+        by = kv_bytes(B) if name == "decode_attention" else w_bytes.get(name)
+        if by:
+            e["gbps"] = round(by / (med(ms) * 1e-3) / 1e9, 1)
+            e["hbm_frac"] = round(e["gbps"] / HBM_PEAK_GBPS, 4)
+        kernels[f"decode_b{B}." + name] = e
+
+    line = {
+        "metric": "prefill tok/s & decode tok/s at max TPOT-feasible batch; % MFMA/HBM roofline",
+        "value": round(prefill_tps, 1),
+        "unit": "prefill tokens/s (32-layer model, one GPU)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(wall / args.steps * 1e3, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "llama8b-shaped layer, bf16: prefill 4x2048 tokens; decode batch 1..256 at KV 2048; "
+                               "per-layer time x32", "n_layers_scaling": N_LAYERS, "l_in": L_IN, "kv_len": KV_LEN,
+                   "ttft_slo_s": TTFT_SLO, "tpot_slo_s": TPOT_SLO, "l_out": L_OUT, "decode_graph": not args.no_graph},
+        "prefill": {"ms_per_layer": round(t_pre, 4), "tok_s_per_layer": round(prefill_tps_layer, 1),
+                    "tok_s_model": round(prefill_tps, 1), "tflops": round(fl / (t_pre * 1e-3) / 1e12, 1),
+                    "mfma_frac": round(fl / (t_pre * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)},
+        "decode": {"max_feasible_batch": b_star, "tpot_ms": star["tpot_ms"], "tok_s": star["tok_s"],
+                   "hbm_gbps": star["hbm_gbps"], "hbm_frac": star["hbm_frac"], "curve": curve},
+        "allocation": {k2: alloc[k2] for k2 in ("n_prefill", "n_decode", "ratio_pd", "tp_prefill_eff", "tp_decode_eff")},
+        "roofline": {"bound": "mfma", "kernel": "gemm_mfma_kernel (gate/up + SwiGLU, M=8192 N=28672 K=4096)",
+                     "achieved": round(gu_flops / (gu_ms * 1e-3) / 1e12, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(gu_flops / (gu_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                     "traffic": None, "avg_launch_ms": round(gu_ms, 4)},
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(cfg, weights)
+    layer.close()
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

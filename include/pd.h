@@ -114,6 +114,9 @@ pd_status pd_kv_cache_set(pd_kv_cache *cache, int32_t slot, int32_t len, const v
 /* Sets a slot's length without touching its contents (0 <= len <= max_len); used to rewind a
  * cache between timed repetitions of the same decode step.  Enqueued on `stream`. */
 pd_status pd_kv_cache_set_len(pd_kv_cache *cache, int32_t slot, int32_t len, void *stream);
+/* The same for n (slot, len) pairs at once (host arrays). */
+pd_status pd_kv_cache_set_lens(pd_kv_cache *cache, int32_t n, const int32_t *slots,
+                               const int32_t *lens, void *stream);
 /* Reads a slot's length (host-side mirror; no device access). */
 pd_status pd_kv_cache_len(const pd_kv_cache *cache, int32_t slot, int32_t *len);
 /* Debug/test read-back of one slot's first len positions into device tensors [n_kv_heads, len, head_dim]. */
@@ -164,6 +167,17 @@ pd_status pd_decode_step(pd_layer *layer, const pd_batch *batch, pd_kv_cache *ca
 /* MoE only: device-to-device copy of the experts chosen by the last call on this layer, int32
  * [rows, top_k], into `expert_idx` (device).  Enqueued on `stream`. */
 pd_status pd_last_expert_choice(const pd_layer *layer, int32_t rows, void *expert_idx, void *stream);
+
+/*
+ * Optional per-kernel timing, for roofline accounting of the individual steps of the layer.
+ * While enabled, pd_prefill / pd_decode_step bracket every step they enqueue with events on the
+ * caller's stream.  pd_profile_read waits for the last call's events and returns up to
+ * max_entries (name, milliseconds) pairs in launch order; names are static strings owned by the
+ * library ("qkv_proj", "gate_up_swiglu", "decode_attention", ...).
+ */
+pd_status pd_profile_enable(pd_layer *layer, int32_t on);
+pd_status pd_profile_read(pd_layer *layer, int32_t max_entries, const char **names, float *ms,
+                          int32_t *n);
 
 /*
  * Allocation model (host only; needs no GPU).

@@ -18,7 +18,7 @@ PD_F32, PD_BF16 = 0, 1
 EXPORTS = [
     "pd_layer_create", "pd_layer_destroy", "pd_layer_reserve", "pd_kv_cache_create",
     "pd_kv_cache_destroy", "pd_kv_cache_set", "pd_kv_cache_set_len", "pd_kv_cache_len",
-    "pd_kv_cache_get", "pd_prefill", "pd_decode_step", "pd_last_expert_choice", "pd_allocate",
+    "pd_kv_cache_set_lens", "pd_kv_cache_get", "pd_profile_enable", "pd_profile_read", "pd_prefill", "pd_decode_step", "pd_last_expert_choice", "pd_allocate",
     "pd_fifo_replay", "pd_mm1_sojourn", "pd_status_string", "pd_last_error",
 ]
 
@@ -148,6 +148,23 @@ def pd_kv_cache_set(cache, slot, k, v):
 
 def pd_kv_cache_set_len(cache, slot, length):
     _check(lib.pd_kv_cache_set_len(cache, C.c_int32(slot), C.c_int32(length), _stream()))
+
+
+def pd_kv_cache_set_lens(cache, slots, lens):
+    _check(lib.pd_kv_cache_set_lens(cache, C.c_int32(len(slots)), _i32_array(slots), _i32_array(lens), _stream()))
+
+
+def pd_profile_enable(layer, on=True):
+    _check(lib.pd_profile_enable(layer, C.c_int32(1 if on else 0)))
+
+
+def pd_profile_read(layer, max_entries=64):
+    """[(step name, milliseconds)] of the last pd_prefill / pd_decode_step on this layer."""
+    names = (C.c_char_p * max_entries)()
+    ms = (C.c_float * max_entries)()
+    n = C.c_int32()
+    _check(lib.pd_profile_read(layer, C.c_int32(max_entries), names, ms, C.byref(n)))
+    return [(names[i].decode(), float(ms[i])) for i in range(n.value)]
 
 
 def pd_kv_cache_len(cache, slot):

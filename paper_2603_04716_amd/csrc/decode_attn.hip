@@ -1,0 +1,227 @@
+// Decode attention (one query token per sequence) over the blocked bf16 KV cache, head_dim 128.
+//
+// The step is bound by streaming the cache from HBM once, so the kernel is organised around the
+// loads: one wavefront is an independent worker that owns a chunk of consecutive keys of one
+// (sequence, kv head) and serves all query heads of that GQA group at once, so every cache byte
+// is fetched exactly once.  Thanks to the blocked layout each 16-byte-per-lane load instruction
+// reads 1 KB of contiguous memory straight into MFMA operand registers: no LDS, no barriers.
+// The score and value contractions run on v_mfma_f32_16x16x32_bf16 with the (up to 16) query
+// heads of the group as the N dimension; that wastes matrix-core columns, which are free here.
+//
+//   S^T[key, q] = K[key, :] . Q[q, :]       A = keys (16 per block), B = the group's query rows
+//   O^T[d, q]   = V^T[d, key] . P^T[key, q] A = transposed value block, B = exp'd scores taken
+//                                           from the S^T accumulators in place
+//
+// Workers write un-normalised partial outputs with their running max and sum; a small merge
+// kernel combines the chunks of each (sequence, head).  Chunks have a fixed key count, so ragged
+// batches balance by construction.
+#include "pd_internal.h"
+
+namespace pd {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float dexp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// One block: pos / len update and the prefix sum of chunks per sequence (B <= 4096).
+__global__ __launch_bounds__(1024) void decode_meta_chunks_kernel(const int32_t *__restrict__ slots,
+                                                                  int B, int32_t *len, int32_t *pos,
+                                                                  int32_t *chunk_cu, int chunk_keys)
+{
+    __shared__ int wave_tot[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int cnt[4], sum = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int b = tid * 4 + i;
+        cnt[i] = 0;
+        if (b < B) {
+            int s = slots[b];
+            int p = len[s];
+            pos[b] = p;
+            len[s] = p + 1;
+            cnt[i] = (p + 1 + chunk_keys - 1) / chunk_keys;
+        }
+        sum += cnt[i];
+    }
+    int inc = sum;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        int v = __shfl_up(inc, off, 64);
+        if (lane >= off) inc += v;
+    }
+    if (lane == 63) wave_tot[wave] = inc;
+    __syncthreads();
+    int base = 0;
+    for (int w = 0; w < wave; ++w) base += wave_tot[w];
+    int run = base + inc - sum;
+    if (tid == 0) chunk_cu[0] = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int b = tid * 4 + i;
+        run += cnt[i];
+        if (b < B) chunk_cu[b + 1] = run;
+    }
+}
+
+hipError_t launch_decode_meta_chunks(const int32_t *d_slots, int B, int32_t *d_len, int32_t *d_pos,
+                                     int32_t *chunk_cu, int chunk_keys, hipStream_t s)
+{
+    decode_meta_chunks_kernel<<<1, 1024, 0, s>>>(d_slots, B, d_len, d_pos, chunk_cu, chunk_keys);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a, int n_workers)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int w = blockIdx.x * 4 + wave;
+    if (w >= n_workers) return;
+    const int g = w % a.Hkv, cid = w / a.Hkv;
+    int lo = 0, hi = a.B;   // largest b with chunk_cu[b] <= cid (every sequence has >= 1 chunk)
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (a.chunk_cu[mid] <= cid) lo = mid; else hi = mid;
+    }
+    const int b = lo;
+    const int n_keys = a.pos[b] + 1;
+    const int key0 = (cid - a.chunk_cu[b]) * a.chunk_keys;
+    const int key1 = min(n_keys, key0 + a.chunk_keys);
+    const int group = a.Hq / a.Hkv;
+    const int qi = lane & 15, kg = lane >> 4;
+
+    // query rows of the group as B operand: lane (n = qi, kg) holds channels 32s + 8kg .. +7
+    bf16x8 qf[4];
+    {
+        const uint16_t *qp = (const uint16_t *)a.qkv + (size_t)b * a.ld + (size_t)(g * group + qi) * 128 + kg * 8;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            u32x4 z = {0u, 0u, 0u, 0u};
+            if (qi < group) z = *(const u32x4 *)(qp + 32 * s);
+            qf[s] = __builtin_bit_cast(bf16x8, z);
+        }
+    }
+    const size_t plane = ((size_t)a.slots[b] * a.Hkv + g) * (size_t)a.max_len_pad * 128;
+    const uint16_t *Kp = (const uint16_t *)a.k_cache + plane + qi * 32 + kg * 8;
+    const uint16_t *Vp = (const uint16_t *)a.v_cache + plane + qi * 32 + kg * 8;
+
+    f32x4 oacc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) oacc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run = -INFINITY, l_run = 0.f;
+    const float sl2e = a.scale * 1.4426950408889634f;
+
+    for (int k = key0; k < key1; k += 64) {
+        bf16x8 kf[4][4], vf[2][8];
+        const uint16_t *kb_ptr = Kp + (size_t)(k >> 4) * 2048;
+        const uint16_t *vb_ptr = Vp + (size_t)(k >> 5) * 4096;
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+            for (int s = 0; s < 4; ++s) kf[kb][s] = *(const bf16x8 *)(kb_ptr + kb * 2048 + s * 512);
+#pragma unroll
+        for (int vb = 0; vb < 2; ++vb)
+#pragma unroll
+            for (int db = 0; db < 8; ++db) vf[vb][db] = *(const bf16x8 *)(vb_ptr + vb * 4096 + db * 512);
+
+        // scores: lane (qi, kg), block kb, register j  <->  key k + 16*kb + 4*kg + j
+        f32x4 sacc[4];
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb) {
+            sacc[kb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+                sacc[kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kb][s], qf[s], sacc[kb], 0, 0, 0);
+        }
+        const bool tail = k + 64 > key1;
+        float mx = -INFINITY;
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float sv = sacc[kb][j] * sl2e;
+                if (tail && k + 16 * kb + 4 * kg + j >= key1) sv = -INFINITY;
+                sacc[kb][j] = sv;
+                mx = fmaxf(mx, sv);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run, mx);      // finite: key k < key1 is always unmasked
+        const float alpha = dexp2(m_run - m_new);
+        m_run = m_new;
+        float psum = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float p = dexp2(sacc[kb][j] - m_new);
+                sacc[kb][j] = p;
+                psum += p;
+            }
+        l_run = l_run * alpha + psum;
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) oacc[i][j] *= alpha;
+        // exp'd scores as B operand of the value contraction: k-index 8kg+i  <->  key 16*(i/4)+4kg+i%4
+        bf16x8 pf[2];
+#pragma unroll
+        for (int vb = 0; vb < 2; ++vb) {
+            u32x4 pk = {pack2bf(sacc[2 * vb][0], sacc[2 * vb][1]), pack2bf(sacc[2 * vb][2], sacc[2 * vb][3]),
+                        pack2bf(sacc[2 * vb + 1][0], sacc[2 * vb + 1][1]),
+                        pack2bf(sacc[2 * vb + 1][2], sacc[2 * vb + 1][3])};
+            pf[vb] = __builtin_bit_cast(bf16x8, pk);
+        }
+#pragma unroll
+        for (int db = 0; db < 8; ++db)
+#pragma unroll
+            for (int vb = 0; vb < 2; ++vb)
+                oacc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[vb][db], pf[vb], oacc[db], 0, 0, 0);
+    }
+
+    float l_tot = l_run + __shfl_xor(l_run, 16, 64);
+    l_tot += __shfl_xor(l_tot, 32, 64);
+    if (qi < group) {
+        const int head = g * group + qi;
+        float *po = a.part_o + ((size_t)cid * a.Hq + head) * 128;
+#pragma unroll
+        for (int db = 0; db < 8; ++db)
+            *(f32x4 *)(po + 16 * db + 4 * kg) = oacc[db];   // rows 16*db + 4*kg + j of O^T
+        if (kg == 0) {
+            float *pm = a.part_ml + ((size_t)cid * a.Hq + head) * 2;
+            pm[0] = m_run;
+            pm[1] = l_tot;
+        }
+    }
+}
+
+// o[b, head, :] = sum_c 2^(m_c - M) o_c / sum_c 2^(m_c - M) l_c over the chunks of sequence b.
+__global__ __launch_bounds__(128) void decode_attn_merge_kernel(DecodeAttnArgs a)
+{
+    const int b = blockIdx.x, head = blockIdx.y, d = threadIdx.x;
+    const int c0 = a.chunk_cu[b], c1 = a.chunk_cu[b + 1];
+    float M = -INFINITY;
+    for (int c = c0; c < c1; ++c) M = fmaxf(M, a.part_ml[((size_t)c * a.Hq + head) * 2]);
+    float L = 0.f, acc = 0.f;
+    for (int c = c0; c < c1; ++c) {
+        const float *pm = a.part_ml + ((size_t)c * a.Hq + head) * 2;
+        float wgt = dexp2(pm[0] - M);
+        L += wgt * pm[1];
+        acc += wgt * a.part_o[((size_t)c * a.Hq + head) * 128 + d];
+    }
+    ((uint16_t *)a.o)[((size_t)b * a.Hq + head) * 128 + d] = f2bf(acc / L).x;
+}
+
+hipError_t launch_decode_attn_mfma(const DecodeAttnArgs &a, hipStream_t s)
+{
+    const int n_workers = a.total_chunks * a.Hkv;
+    if (n_workers <= 0) return hipSuccess;
+    decode_attn_kernel<<<(n_workers + 3) / 4, 256, 0, s>>>(a, n_workers);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    decode_attn_merge_kernel<<<dim3(a.B, a.Hq), 128, 0, s>>>(a);
+    return hipGetLastError();
+}
+
+}  // namespace pd

@@ -1,0 +1,138 @@
+// Skinny bf16 GEMM for decode batches of up to 16 rows:  C[M<=16, N] = epilogue(A[M,K] * B[N,K]^T).
+//
+// The step is bound by streaming the weight matrix B from HBM exactly once, so the weights are
+// the MFMA A operand and go straight from global memory into operand registers (16 weight rows x
+// 64 bytes per load instruction, eight k-steps in flight per wave); the (tiny, L2-resident)
+// activations are the B operand with the batch as the N dimension of v_mfma_f32_16x16x32_bf16,
+// padded with zero columns.  A workgroup owns 16 weight rows (one output column block); its four
+// waves split K and combine through LDS in a fixed order, so results are deterministic.
+// Epilogues as in the tiled GEMM; for SwiGLU the workgroup takes the gate block and the matching
+// up block of the interleaved weight pack.
+#include "pd_internal.h"
+
+namespace pd {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int GV_WAVES = 4;
+constexpr int GV_UNROLL = 8;
+
+template <int EPI>
+__global__ __launch_bounds__(64 * GV_WAVES) void gemv_mfma_kernel(GemmArgs a)
+{
+    constexpr int RB = EPI == EPI_SWIGLU ? 2 : 1;
+    __shared__ f32x4 red[GV_WAVES][RB][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r = lane & 15, kg = lane >> 4;
+    const int blk = blockIdx.x;
+    // first weight row of each row block
+    int row0[RB];
+    if (EPI == EPI_SWIGLU) {
+        row0[0] = (blk >> 1) * 64 + (blk & 1) * 16;   // gate rows of output columns 16*blk .. +15
+        row0[RB - 1] = row0[0] + 32;                  // matching up rows
+    } else {
+        row0[0] = blk * 16;
+    }
+    const int ksteps = a.K / 32;                      // k-steps of 32, split evenly over the waves
+    const int per = (ksteps + GV_WAVES - 1) / GV_WAVES;
+    const int s_begin = wave * per, s_end = min(ksteps, s_begin + per);
+
+    const uint16_t *W = (const uint16_t *)a.B;
+    const uint16_t *wp[RB];
+#pragma unroll
+    for (int i = 0; i < RB; ++i) wp[i] = W + (size_t)(row0[i] + r) * a.ldb + kg * 8;
+    const bool xrow = r < a.M;
+    const uint16_t *xp = (const uint16_t *)a.A + (size_t)(xrow ? r : 0) * a.lda + kg * 8;
+
+    f32x4 acc[RB];
+#pragma unroll
+    for (int i = 0; i < RB; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    int s = s_begin;
+    for (; s + GV_UNROLL <= s_end; s += GV_UNROLL) {
+        bf16x8 wf[RB][GV_UNROLL], xf[GV_UNROLL];
+#pragma unroll
+        for (int u = 0; u < GV_UNROLL; ++u) {
+#pragma unroll
+            for (int i = 0; i < RB; ++i) wf[i][u] = *(const bf16x8 *)(wp[i] + (size_t)(s + u) * 32);
+            u32x4 z = {0u, 0u, 0u, 0u};
+            if (xrow) z = *(const u32x4 *)(xp + (size_t)(s + u) * 32);
+            xf[u] = __builtin_bit_cast(bf16x8, z);
+        }
+#pragma unroll
+        for (int u = 0; u < GV_UNROLL; ++u)
+#pragma unroll
+            for (int i = 0; i < RB; ++i)
+                acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[i][u], xf[u], acc[i], 0, 0, 0);
+    }
+    for (; s < s_end; ++s) {
+        u32x4 z = {0u, 0u, 0u, 0u};
+        if (xrow) z = *(const u32x4 *)(xp + (size_t)s * 32);
+        bf16x8 xf = __builtin_bit_cast(bf16x8, z);
+#pragma unroll
+        for (int i = 0; i < RB; ++i) {
+            bf16x8 wf = *(const bf16x8 *)(wp[i] + (size_t)s * 32);
+            acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xf, acc[i], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < RB; ++i) red[wave][i][lane] = acc[i];
+    __syncthreads();
+    if (wave != 0) return;
+    f32x4 tot[RB];
+#pragma unroll
+    for (int i = 0; i < RB; ++i) {
+        tot[i] = red[0][i][lane];
+#pragma unroll
+        for (int w = 1; w < GV_WAVES; ++w) tot[i] += red[w][i][lane];
+    }
+    // lane (batch row b = r, kg): register j is weight row 4*kg + j of the block
+    if (!xrow) return;
+    uint16_t *C = (uint16_t *)a.C + (size_t)r * a.ldc;
+    const int col = blk * 16 + 4 * kg;                // first of 4 consecutive output columns
+    float v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        if (EPI == EPI_SWIGLU) {
+            float gte = tot[0][j];
+            v[j] = gte / (1.0f + __expf(-gte)) * tot[RB - 1][j];
+        } else {
+            v[j] = tot[0][j];
+        }
+    }
+    if (EPI == EPI_RESIDUAL) {
+        uint2 rr = *(const uint2 *)((const uint16_t *)a.R + (size_t)r * a.ldr + col);
+        v[0] += bfbits2f(rr.x & 0xffffu);
+        v[1] += bfbits2f(rr.x >> 16);
+        v[2] += bfbits2f(rr.y & 0xffffu);
+        v[3] += bfbits2f(rr.y >> 16);
+    }
+    uint2 o;
+    o.x = pack2bf(v[0], v[1]);
+    o.y = pack2bf(v[2], v[3]);
+    *(uint2 *)(C + col) = o;
+}
+
+bool gemv_mfma_supported(const GemmArgs &a)
+{
+    if (a.M < 1 || a.M > 16 || a.a_gather || a.group_offsets) return false;
+    if (a.K % 32 != 0 || a.N % 16 != 0 || a.lda % 8 != 0 || a.ldb % 8 != 0) return false;
+    if (a.ldc % 4 != 0 || (a.epilogue == EPI_RESIDUAL && a.ldr % 4 != 0)) return false;
+    if (a.epilogue == EPI_SWIGLU && (!a.interleaved || a.N % 32 != 0)) return false;
+    return true;
+}
+
+hipError_t launch_gemv_mfma(const GemmArgs &a, hipStream_t s)
+{
+    const dim3 grid(a.N / 16), block(64 * GV_WAVES);
+    switch (a.epilogue) {
+    case EPI_NONE: gemv_mfma_kernel<EPI_NONE><<<grid, block, 0, s>>>(a); break;
+    case EPI_RESIDUAL: gemv_mfma_kernel<EPI_RESIDUAL><<<grid, block, 0, s>>>(a); break;
+    default: gemv_mfma_kernel<EPI_SWIGLU><<<grid, block, 0, s>>>(a); break;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace pd

@@ -254,6 +254,29 @@ hipError_t launch_write_ints(int32_t *dst, const int32_t *host_src, int n, hipSt
     return hipSuccess;
 }
 
+__global__ void scatter_ints_kernel(int32_t *dst, IntChunk c, int n)
+{
+    int i = threadIdx.x;
+    if (i < n) dst[c.v[i]] = c.v[128 + i];
+}
+
+hipError_t launch_scatter_ints(int32_t *dst, const int32_t *host_idx, const int32_t *host_val, int n,
+                               hipStream_t s)
+{
+    for (int off = 0; off < n; off += 128) {
+        IntChunk c;
+        int m = n - off < 128 ? n - off : 128;
+        for (int i = 0; i < m; ++i) {
+            c.v[i] = host_idx[off + i];
+            c.v[128 + i] = host_val[off + i];
+        }
+        scatter_ints_kernel<<<1, 128, 0, s>>>(dst, c, m);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
 __global__ void token_meta_kernel(const int32_t *__restrict__ cu, const int32_t *__restrict__ slots,
                                   int n_seqs, int T, int32_t *__restrict__ tok_seq,
                                   int32_t *__restrict__ tok_pos, int32_t *__restrict__ tok_slot)
@@ -344,17 +367,23 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(RopeArgs a)
         Elem<T>::st(v + i + half, y1);
         if (slot >= 0 && h >= a.Hq) {
             int g = h - a.Hq;
-            T *kc = (T *)a.k_cache + (((size_t)slot * a.Hkv + g) * a.max_len + pos) * a.hd;
-            Elem<T>::st(kc + i, y0);
-            Elem<T>::st(kc + i + half, y1);
+            T *plane = (T *)a.k_cache + ((size_t)slot * a.Hkv + g) * a.max_len * a.hd;
+            if (a.blocked) {
+                Elem<T>::st(plane + kblk_off(pos, i), y0);
+                Elem<T>::st(plane + kblk_off(pos, i + half), y1);
+            } else {
+                Elem<T>::st(plane + (size_t)pos * a.hd + i, y0);
+                Elem<T>::st(plane + (size_t)pos * a.hd + i + half, y1);
+            }
         }
     }
     if (slot >= 0) {
         const T *vsrc = row + (size_t)(a.Hq + a.Hkv) * a.hd;
         for (int idx = threadIdx.x; idx < a.Hkv * a.hd; idx += 256) {
             int g = idx / a.hd, i = idx - g * a.hd;
-            T *vc = (T *)a.v_cache + (((size_t)slot * a.Hkv + g) * a.max_len + pos) * a.hd;
-            vc[i] = vsrc[idx];
+            T *plane = (T *)a.v_cache + ((size_t)slot * a.Hkv + g) * a.max_len * a.hd;
+            if (a.blocked) plane[vblk_off(pos, i)] = vsrc[idx];
+            else plane[(size_t)pos * a.hd + i] = vsrc[idx];
         }
     }
 }
@@ -458,7 +487,7 @@ hipError_t launch_attn_generic(int dtype, const AttnArgs &a, hipStream_t s)
 // ---------------------------------------------------------------------------------------------
 template <typename T>
 __global__ void kv_copy_kernel(T *ck, T *cv, T *k, T *v, int slot, int Hkv, int len, int hd,
-                               int max_len, int to_cache)
+                               int max_len, int blocked, int to_cache)
 {
     size_t n = (size_t)Hkv * len * hd;
     for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n;
@@ -467,19 +496,21 @@ __global__ void kv_copy_kernel(T *ck, T *cv, T *k, T *v, int slot, int Hkv, int 
         size_t r = idx / hd;
         int p = (int)(r % len);
         int g = (int)(r / len);
-        size_t c = (((size_t)slot * Hkv + g) * max_len + p) * hd + i;
+        size_t plane = ((size_t)slot * Hkv + g) * max_len * hd;
+        size_t c = plane + (blocked ? kblk_off(p, i) : (size_t)p * hd + i);
+        size_t cvo = plane + (blocked ? vblk_off(p, i) : (size_t)p * hd + i);
         if (to_cache) {
             ck[c] = k[idx];
-            cv[c] = v[idx];
+            cv[cvo] = v[idx];
         } else {
             k[idx] = ck[c];
-            v[idx] = cv[c];
+            v[idx] = cv[cvo];
         }
     }
 }
 
 hipError_t launch_kv_copy(int dtype, void *cache_k, void *cache_v, const void *k, const void *v,
-                          int slot, int Hkv, int len, int hd, int max_len, int to_cache,
+                          int slot, int Hkv, int len, int hd, int max_len, int blocked, int to_cache,
                           hipStream_t s)
 {
     size_t n = (size_t)Hkv * len * hd;
@@ -487,11 +518,11 @@ hipError_t launch_kv_copy(int dtype, void *cache_k, void *cache_v, const void *k
     unsigned grid = (unsigned)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
     if (dtype == PD_F32)
         kv_copy_kernel<float><<<grid, 256, 0, s>>>((float *)cache_k, (float *)cache_v, (float *)k,
-                                                   (float *)v, slot, Hkv, len, hd, max_len, to_cache);
+                                                   (float *)v, slot, Hkv, len, hd, max_len, blocked, to_cache);
     else
         kv_copy_kernel<uint16_t><<<grid, 256, 0, s>>>((uint16_t *)cache_k, (uint16_t *)cache_v,
                                                       (uint16_t *)k, (uint16_t *)v, slot, Hkv, len,
-                                                      hd, max_len, to_cache);
+                                                      hd, max_len, blocked, to_cache);
     return hipGetLastError();
 }
 

@@ -22,17 +22,24 @@ struct pd_layer {
     int32_t *d_cu, *d_slots, *d_pad_cu;  // [4097] each
     void *vt;                 // transposed-V scratch for the MFMA attention, vt_cap bytes
     size_t vt_cap;
+    float *dec_part;          // partial outputs of the decode attention chunks (inside ws)
     // workspace, sized for ws_tokens rows
     int ws_tokens;
     char *ws;
     void *y, *qkv, *o, *h, *act, *eo;
-    int32_t *tok_seq, *tok_pos, *tok_slot, *eidx, *sorted_token, *pair_pos, *offsets;
+    int32_t *tok_seq, *tok_pos, *tok_slot, *eidx, *sorted_token, *pair_pos, *offsets, *chunk_cu;
     float *logits, *ew;
     int last_rows;
+    // optional per-kernel timing of the last call
+    bool prof_on;
+    std::vector<hipEvent_t> prof_ev;          // pairs (start, stop)
+    std::vector<const char *> prof_names;     // one per recorded pair
 };
 
 struct pd_kv_cache {
     int dtype, Hkv, hd, max_seqs, max_len;
+    int blocked;       // bf16 / head_dim 128: blocked layout for the matrix-core decode attention
+    int plane_len;     // positions per (slot, kv head) plane: max_len, or padded to 64 when blocked
     void *k, *v;
     int32_t *d_len;
     std::vector<int32_t> h_len;
@@ -47,6 +54,30 @@ static const int kMaxSeqs = 4096;
             set_error("%s failed: %s", #expr, hipGetErrorString(e__));               \
             return (e__ == hipErrorOutOfMemory) ? PD_ERR_OOM : (status);             \
         }                                                                            \
+    } while (0)
+
+static void prof_begin(pd_layer *L, const char *name, hipStream_t s)
+{
+    if (!L->prof_on) return;
+    const size_t i = L->prof_names.size();
+    while (L->prof_ev.size() < 2 * (i + 1)) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) return;
+        L->prof_ev.push_back(e);
+    }
+    L->prof_names.push_back(name);
+    (void)hipEventRecord(L->prof_ev[2 * i], s);
+}
+static void prof_end(pd_layer *L, hipStream_t s)
+{
+    if (!L->prof_on || L->prof_names.empty()) return;
+    (void)hipEventRecord(L->prof_ev[2 * L->prof_names.size() - 1], s);
+}
+#define STEP(name, expr)                 \
+    do {                                 \
+        prof_begin(L, name, s);          \
+        HIP_TRY(expr, PD_ERR_DEVICE);    \
+        prof_end(L, s);                  \
     } while (0)
 
 static size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
@@ -73,6 +104,7 @@ static void free_layer(pd_layer *L)
                     L->w_router, L->inv_freq, L->d_cu, L->d_slots, L->d_pad_cu, L->vt, L->ws};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
+    for (hipEvent_t e : L->prof_ev) (void)hipEventDestroy(e);
     delete L;
 }
 
@@ -101,8 +133,7 @@ extern "C" pd_status pd_layer_create(const pd_layer_config *cfg, const pd_layer_
         set_error("pd_layer_create: a weight pointer is NULL");
         return PD_ERR_INVALID_ARG;
     }
-    pd_layer *L = new pd_layer();
-    memset((void *)L, 0, sizeof(*L));
+    pd_layer *L = new pd_layer();   // value-initialised: every pointer and counter starts at zero
     L->cfg = *cfg;
     L->esz = cfg->dtype == PD_F32 ? 4 : 2;
     L->Nq = Hq * hd;
@@ -185,6 +216,14 @@ extern "C" void pd_layer_destroy(pd_layer *layer)
     free_layer(layer);
 }
 
+// Decode attention splits the keys of a step into at most 8192 / n_kv_heads fixed-size chunks plus
+// one ragged tail per sequence; the workspace holds partial outputs for that many chunks, so a
+// decode step never allocates.
+static size_t decode_chunk_bound(const pd_layer *L, int batch)
+{
+    return (size_t)(8192 / L->cfg.n_kv_heads + 1) + (size_t)batch;
+}
+
 extern "C" pd_status pd_layer_reserve(pd_layer *L, int32_t max_tokens)
 {
     if (!L || max_tokens < 0) {
@@ -206,7 +245,8 @@ extern "C" pd_status pd_layer_reserve(pd_layer *L, int32_t max_tokens)
            o_eo = carve(E > 0 ? T * K * d * esz : 0), o_seq = carve(T * 4), o_pos = carve(T * 4),
            o_slot = carve(T * 4), o_eidx = carve(T * K * 4), o_sorted = carve(T * K * 4),
            o_pp = carve(T * K * 4), o_off = carve(65 * 4 + 4), o_log = carve(T * (E > 0 ? E : 1) * 4),
-           o_ew = carve(T * K * 4);
+           o_ew = carve(T * K * 4), o_ccu = carve((T + 1) * 4),
+           o_part = carve(decode_chunk_bound(L, max_tokens) * L->cfg.n_q_heads * 130 * sizeof(float));
     HIP_TRY(hipDeviceSynchronize(), PD_ERR_DEVICE);
     char *nw = nullptr;
     hipError_t e = hipMalloc((void **)&nw, off);
@@ -232,6 +272,8 @@ extern "C" pd_status pd_layer_reserve(pd_layer *L, int32_t max_tokens)
     L->offsets = (int32_t *)(nw + o_off);
     L->logits = (float *)(nw + o_log);
     L->ew = (float *)(nw + o_ew);
+    L->chunk_cu = (int32_t *)(nw + o_ccu);
+    L->dec_part = (float *)(nw + o_part);
     return PD_OK;
 }
 
@@ -250,11 +292,16 @@ extern "C" pd_status pd_kv_cache_create(const pd_layer *L, int32_t max_seqs, int
     c->hd = L->cfg.head_dim;
     c->max_seqs = max_seqs;
     c->max_len = max_len;
+    c->blocked = (L->cfg.dtype == PD_BF16 && c->hd == 128 && L->cfg.n_q_heads / c->Hkv <= 16) ? 1 : 0;
+    c->plane_len = c->blocked ? (max_len + 63) / 64 * 64 : max_len;
     c->k = c->v = nullptr;
     c->d_len = nullptr;
-    size_t bytes = (size_t)max_seqs * c->Hkv * max_len * c->hd * L->esz;
+    size_t bytes = (size_t)max_seqs * c->Hkv * c->plane_len * c->hd * L->esz;
     hipError_t e = hipMalloc(&c->k, bytes);
     if (e == hipSuccess) e = hipMalloc(&c->v, bytes);
+    // zero fill: positions past a slot's length are multiplied by zero weights and must be finite
+    if (e == hipSuccess) e = hipMemset(c->k, 0, bytes);
+    if (e == hipSuccess) e = hipMemset(c->v, 0, bytes);
     if (e == hipSuccess) e = hipMalloc((void **)&c->d_len, sizeof(int32_t) * max_seqs);
     if (e == hipSuccess) e = hipMemset(c->d_len, 0, sizeof(int32_t) * max_seqs);
     if (e == hipSuccess) e = hipDeviceSynchronize();
@@ -307,8 +354,8 @@ extern "C" pd_status pd_kv_cache_set(pd_kv_cache *c, int32_t slot, int32_t len, 
         set_error("pd_kv_cache_set: len %d > max_len %d", len, c->max_len);
         return PD_ERR_KV_CAPACITY;
     }
-    HIP_TRY(launch_kv_copy(c->dtype, c->k, c->v, k, v, slot, c->Hkv, len, c->hd, c->max_len, 1,
-                           (hipStream_t)stream),
+    HIP_TRY(launch_kv_copy(c->dtype, c->k, c->v, k, v, slot, c->Hkv, len, c->hd, c->plane_len,
+                           c->blocked, 1, (hipStream_t)stream),
             PD_ERR_DEVICE);
     return pd_kv_cache_set_len(c, slot, len, stream);
 }
@@ -320,8 +367,8 @@ extern "C" pd_status pd_kv_cache_get(const pd_kv_cache *c, int32_t slot, int32_t
         set_error("pd_kv_cache_get: bad argument");
         return PD_ERR_INVALID_ARG;
     }
-    HIP_TRY(launch_kv_copy(c->dtype, c->k, c->v, k, v, slot, c->Hkv, len, c->hd, c->max_len, 0,
-                           (hipStream_t)stream),
+    HIP_TRY(launch_kv_copy(c->dtype, c->k, c->v, k, v, slot, c->Hkv, len, c->hd, c->plane_len,
+                           c->blocked, 0, (hipStream_t)stream),
             PD_ERR_DEVICE);
     return PD_OK;
 }
@@ -340,6 +387,7 @@ extern "C" pd_status pd_kv_cache_len(const pd_kv_cache *c, int32_t slot, int32_t
 
 static hipError_t run_gemm(const pd_layer *L, const GemmArgs &g, hipStream_t s)
 {
+    if (L->use_mfma && gemv_mfma_supported(g)) return launch_gemv_mfma(g, s);
     if (L->use_mfma && gemm_mfma_supported(g)) return launch_gemm_mfma(g, s);
     return launch_gemm_generic(L->cfg.dtype, g, s);
 }
@@ -360,41 +408,40 @@ static pd_status run_tail(pd_layer *L, const void *x, int T, const void *router_
     // h = x + o Wo^T
     g.A = L->o; g.lda = L->Nq; g.B = L->w_o; g.ldb = L->Nq; g.C = L->h; g.ldc = d; g.R = x; g.ldr = d;
     g.M = T; g.N = d; g.K = L->Nq; g.epilogue = EPI_RESIDUAL; g.n_groups = 1;
-    HIP_TRY(run_gemm(L, g, s), PD_ERR_DEVICE);
-    HIP_TRY(launch_rmsnorm(c.dtype, L->h, L->g_ffn, L->y, T, d, c.rms_eps, s), PD_ERR_DEVICE);
+    STEP("o_proj_residual", run_gemm(L, g, s));
+    STEP("rmsnorm_ffn", launch_rmsnorm(c.dtype, L->h, L->g_ffn, L->y, T, d, c.rms_eps, s));
     if (E == 0) {
         memset(&g, 0, sizeof(g));
         g.A = L->y; g.lda = d; g.B = L->w_gate; g.B1 = L->w_up; g.ldb = d; g.C = L->act; g.ldc = F;
         g.M = T; g.N = F; g.K = d; g.epilogue = EPI_SWIGLU; g.interleaved = L->interleaved; g.n_groups = 1;
-        HIP_TRY(run_gemm(L, g, s), PD_ERR_DEVICE);
+        STEP("gate_up_swiglu", run_gemm(L, g, s));
         memset(&g, 0, sizeof(g));
         g.A = L->act; g.lda = F; g.B = L->w_down; g.ldb = F; g.C = out; g.ldc = d; g.R = L->h; g.ldr = d;
         g.M = T; g.N = d; g.K = F; g.epilogue = EPI_RESIDUAL; g.n_groups = 1;
-        HIP_TRY(run_gemm(L, g, s), PD_ERR_DEVICE);
+        STEP("down_residual", run_gemm(L, g, s));
         return PD_OK;
     }
     const float *logits = (const float *)router_logits;
     if (!logits) {
-        HIP_TRY(launch_router_logits(c.dtype, L->y, L->w_router, L->logits, T, d, E, s), PD_ERR_DEVICE);
+        STEP("router_logits", launch_router_logits(c.dtype, L->y, L->w_router, L->logits, T, d, E, s));
         logits = L->logits;
     }
     MoeRouteArgs r;
     r.logits = logits; r.T = T; r.E = E; r.top_k = c.top_k; r.expert_idx = L->eidx; r.expert_w = L->ew;
     r.sorted_token = L->sorted_token; r.pair_pos = L->pair_pos; r.offsets = L->offsets;
-    HIP_TRY(launch_moe_route(r, s), PD_ERR_DEVICE);
+    STEP("moe_route_sort", launch_moe_route(r, s));
     const int P = T * c.top_k;
     memset(&g, 0, sizeof(g));
     g.A = L->y; g.lda = d; g.a_gather = L->sorted_token; g.B = L->w_gate; g.B1 = L->w_up; g.ldb = d;
     g.b_group_stride = (int64_t)(L->interleaved ? 2 : 1) * F * d; g.group_offsets = L->offsets; g.n_groups = E;
     g.C = L->act; g.ldc = F; g.M = P; g.N = F; g.K = d; g.epilogue = EPI_SWIGLU; g.interleaved = L->interleaved;
-    HIP_TRY(run_gemm(L, g, s), PD_ERR_DEVICE);
+    STEP("moe_gate_up_swiglu", run_gemm(L, g, s));
     memset(&g, 0, sizeof(g));
     g.A = L->act; g.lda = F; g.B = L->w_down; g.ldb = F; g.b_group_stride = (int64_t)d * F;
     g.group_offsets = L->offsets; g.n_groups = E; g.C = L->eo; g.ldc = d; g.M = P; g.N = d; g.K = F;
     g.epilogue = EPI_NONE;
-    HIP_TRY(run_gemm(L, g, s), PD_ERR_DEVICE);
-    HIP_TRY(launch_moe_combine(c.dtype, L->h, L->eo, L->pair_pos, L->ew, out, T, d, c.top_k, s),
-            PD_ERR_DEVICE);
+    STEP("moe_down", run_gemm(L, g, s));
+    STEP("moe_combine", launch_moe_combine(c.dtype, L->h, L->eo, L->pair_pos, L->ew, out, T, d, c.top_k, s));
     return PD_OK;
 }
 
@@ -464,24 +511,25 @@ extern "C" pd_status pd_prefill(pd_layer *L, const pd_tokens *tk, pd_kv_cache *c
     pd_status st = pd_layer_reserve(L, T);
     if (st != PD_OK) return st;
     hipStream_t s = (hipStream_t)stream;
+    L->prof_names.clear();
 
     HIP_TRY(launch_write_ints(L->d_cu, tk->cu_seqlens, n + 1, s), PD_ERR_DEVICE);
     if (keep) HIP_TRY(launch_write_ints(L->d_slots, tk->slots, n, s), PD_ERR_DEVICE);
     HIP_TRY(launch_token_meta(L->d_cu, keep ? L->d_slots : nullptr, n, T, L->tok_seq, L->tok_pos,
                               L->tok_slot, s),
             PD_ERR_DEVICE);
-    HIP_TRY(launch_rmsnorm(c.dtype, tk->hidden, L->g_attn, L->y, T, c.d_model, c.rms_eps, s), PD_ERR_DEVICE);
+    STEP("rmsnorm_attn", launch_rmsnorm(c.dtype, tk->hidden, L->g_attn, L->y, T, c.d_model, c.rms_eps, s));
     GemmArgs g;
     memset(&g, 0, sizeof(g));
     g.A = L->y; g.lda = c.d_model; g.B = L->w_qkv; g.ldb = c.d_model; g.C = L->qkv; g.ldc = L->Nqkv;
     g.M = T; g.N = L->Nqkv; g.K = c.d_model; g.epilogue = EPI_NONE; g.n_groups = 1;
-    HIP_TRY(run_gemm(L, g, s), PD_ERR_DEVICE);
+    STEP("qkv_proj", run_gemm(L, g, s));
     RopeArgs r;
     r.qkv = L->qkv; r.ld = L->Nqkv; r.T = T; r.Hq = c.n_q_heads; r.Hkv = c.n_kv_heads; r.hd = c.head_dim;
     r.tok_pos = L->tok_pos; r.tok_slot = keep ? L->tok_slot : nullptr;
     r.k_cache = keep ? cache->k : nullptr; r.v_cache = keep ? cache->v : nullptr;
-    r.max_len = keep ? cache->max_len : 0; r.inv_freq = L->inv_freq;
-    HIP_TRY(launch_rope_kv(c.dtype, r, s), PD_ERR_DEVICE);
+    r.max_len = keep ? cache->plane_len : 0; r.blocked = keep ? cache->blocked : 0; r.inv_freq = L->inv_freq;
+    STEP("rope_kv_write", launch_rope_kv(c.dtype, r, s));
     AttnArgs a;
     memset(&a, 0, sizeof(a));
     a.qkv = L->qkv; a.ld = L->Nqkv; a.o = L->o; a.T = T; a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads;
@@ -508,9 +556,9 @@ extern "C" pd_status pd_prefill(pd_layer *L, const pd_tokens *tk, pd_kv_cache *c
             L->vt_cap = need;
         }
         HIP_TRY(launch_write_ints(L->d_pad_cu, pad.data(), n + 1, s), PD_ERR_DEVICE);
-        HIP_TRY(launch_attn_prefill_mfma(a, (uint16_t *)L->vt, vt_ld, L->d_pad_cu, s), PD_ERR_DEVICE);
+        STEP("prefill_attention", launch_attn_prefill_mfma(a, (uint16_t *)L->vt, vt_ld, L->d_pad_cu, s));
     } else {
-        HIP_TRY(launch_attn_generic(c.dtype, a, s), PD_ERR_DEVICE);
+        STEP("prefill_attention", launch_attn_generic(c.dtype, a, s));
     }
     st = run_tail(L, tk->hidden, T, tk->router_logits, out, s);
     if (st != PD_OK) return st;
@@ -563,27 +611,58 @@ extern "C" pd_status pd_decode_step(pd_layer *L, const pd_batch *bt, pd_kv_cache
     pd_status st = pd_layer_reserve(L, B);
     if (st != PD_OK) return st;
     hipStream_t s = (hipStream_t)stream;
+    L->prof_names.clear();
 
+    // decode attention work split: fixed-size key chunks, about 8192 wavefront-sized workers
+    const bool mfma_dec = cache->blocked != 0;
+    int chunk_keys = 64, total_chunks = 0;
+    if (mfma_dec) {
+        long long total_keys = 0;
+        for (int b = 0; b < B; ++b) total_keys += cache->h_len[(size_t)bt->slots[b]] + 1;
+        long long ck = (total_keys * c.n_kv_heads / 8192 + 63) / 64 * 64;
+        chunk_keys = (int)(ck < 64 ? 64 : ck);
+        for (int b = 0; b < B; ++b)
+            total_chunks += (cache->h_len[(size_t)bt->slots[b]] + 1 + chunk_keys - 1) / chunk_keys;
+        if ((size_t)total_chunks > decode_chunk_bound(L, B)) {
+            set_error("pd_decode_step: internal chunk bound exceeded (%d chunks)", total_chunks);
+            return PD_ERR_DEVICE;
+        }
+    }
     HIP_TRY(launch_write_ints(L->d_slots, bt->slots, B, s), PD_ERR_DEVICE);
-    HIP_TRY(launch_decode_meta(L->d_slots, B, cache->d_len, L->tok_pos, s), PD_ERR_DEVICE);
-    HIP_TRY(launch_rmsnorm(c.dtype, bt->hidden, L->g_attn, L->y, B, c.d_model, c.rms_eps, s), PD_ERR_DEVICE);
+    if (mfma_dec)
+        HIP_TRY(launch_decode_meta_chunks(L->d_slots, B, cache->d_len, L->tok_pos, L->chunk_cu, chunk_keys, s),
+                PD_ERR_DEVICE);
+    else
+        HIP_TRY(launch_decode_meta(L->d_slots, B, cache->d_len, L->tok_pos, s), PD_ERR_DEVICE);
+    STEP("rmsnorm_attn", launch_rmsnorm(c.dtype, bt->hidden, L->g_attn, L->y, B, c.d_model, c.rms_eps, s));
     GemmArgs g;
     memset(&g, 0, sizeof(g));
     g.A = L->y; g.lda = c.d_model; g.B = L->w_qkv; g.ldb = c.d_model; g.C = L->qkv; g.ldc = L->Nqkv;
     g.M = B; g.N = L->Nqkv; g.K = c.d_model; g.epilogue = EPI_NONE; g.n_groups = 1;
-    HIP_TRY(run_gemm(L, g, s), PD_ERR_DEVICE);
+    STEP("qkv_proj", run_gemm(L, g, s));
     RopeArgs r;
     r.qkv = L->qkv; r.ld = L->Nqkv; r.T = B; r.Hq = c.n_q_heads; r.Hkv = c.n_kv_heads; r.hd = c.head_dim;
     r.tok_pos = L->tok_pos; r.tok_slot = L->d_slots; r.k_cache = cache->k; r.v_cache = cache->v;
-    r.max_len = cache->max_len; r.inv_freq = L->inv_freq;
-    HIP_TRY(launch_rope_kv(c.dtype, r, s), PD_ERR_DEVICE);
-    AttnArgs a;
-    memset(&a, 0, sizeof(a));
-    a.qkv = L->qkv; a.ld = L->Nqkv; a.o = L->o; a.T = B; a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads;
-    a.hd = c.head_dim; a.scale = (float)(1.0 / sqrt((double)c.head_dim)); a.tok_pos = L->tok_pos;
-    a.tok_slot = L->d_slots; a.k_cache = cache->k; a.v_cache = cache->v; a.max_len = cache->max_len;
-    a.decode = 1;
-    HIP_TRY(launch_attn_generic(c.dtype, a, s), PD_ERR_DEVICE);
+    r.max_len = cache->plane_len; r.blocked = cache->blocked; r.inv_freq = L->inv_freq;
+    STEP("rope_kv_append", launch_rope_kv(c.dtype, r, s));
+    if (mfma_dec) {
+        DecodeAttnArgs da;
+        da.qkv = L->qkv; da.ld = L->Nqkv; da.o = L->o; da.B = B; da.Hq = c.n_q_heads; da.Hkv = c.n_kv_heads;
+        da.scale = (float)(1.0 / sqrt((double)c.head_dim)); da.slots = L->d_slots; da.pos = L->tok_pos;
+        da.chunk_cu = L->chunk_cu; da.chunk_keys = chunk_keys; da.total_chunks = total_chunks;
+        da.k_cache = cache->k; da.v_cache = cache->v; da.max_len_pad = cache->plane_len;
+        da.part_o = L->dec_part;
+        da.part_ml = L->dec_part + (size_t)total_chunks * c.n_q_heads * 128;
+        STEP("decode_attention", launch_decode_attn_mfma(da, s));
+    } else {
+        AttnArgs a;
+        memset(&a, 0, sizeof(a));
+        a.qkv = L->qkv; a.ld = L->Nqkv; a.o = L->o; a.T = B; a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads;
+        a.hd = c.head_dim; a.scale = (float)(1.0 / sqrt((double)c.head_dim)); a.tok_pos = L->tok_pos;
+        a.tok_slot = L->d_slots; a.k_cache = cache->k; a.v_cache = cache->v; a.max_len = cache->max_len;
+        a.decode = 1;
+        STEP("decode_attention", launch_attn_generic(c.dtype, a, s));
+    }
     st = run_tail(L, bt->hidden, B, bt->router_logits, out, s);
     if (st != PD_OK) return st;
     for (int b = 0; b < B; ++b) cache->h_len[(size_t)bt->slots[b]] += 1;
@@ -601,5 +680,59 @@ extern "C" pd_status pd_last_expert_choice(const pd_layer *L, int32_t rows, void
     HIP_TRY(hipMemcpyAsync(expert_idx, L->eidx, sizeof(int32_t) * (size_t)rows * L->cfg.top_k,
                            hipMemcpyDeviceToDevice, (hipStream_t)stream),
             PD_ERR_DEVICE);
+    return PD_OK;
+}
+
+extern "C" pd_status pd_profile_enable(pd_layer *L, int32_t on)
+{
+    if (!L) {
+        set_error("pd_profile_enable: NULL layer");
+        return PD_ERR_INVALID_ARG;
+    }
+    L->prof_on = on != 0;
+    L->prof_names.clear();
+    return PD_OK;
+}
+
+extern "C" pd_status pd_profile_read(pd_layer *L, int32_t max_entries, const char **names, float *ms,
+                                     int32_t *n)
+{
+    if (!L || !n || max_entries < 0 || (max_entries > 0 && (!names || !ms))) {
+        set_error("pd_profile_read: bad argument");
+        return PD_ERR_INVALID_ARG;
+    }
+    const int cnt = (int)L->prof_names.size();
+    int outn = 0;
+    for (int i = 0; i < cnt && outn < max_entries; ++i) {
+        HIP_TRY(hipEventSynchronize(L->prof_ev[2 * i + 1]), PD_ERR_DEVICE);
+        float t = 0.f;
+        HIP_TRY(hipEventElapsedTime(&t, L->prof_ev[2 * i], L->prof_ev[2 * i + 1]), PD_ERR_DEVICE);
+        names[outn] = L->prof_names[(size_t)i];
+        ms[outn] = t;
+        ++outn;
+    }
+    *n = outn;
+    return PD_OK;
+}
+
+extern "C" pd_status pd_kv_cache_set_lens(pd_kv_cache *c, int32_t n, const int32_t *slots,
+                                          const int32_t *lens, void *stream)
+{
+    if (!c || n < 0 || (n > 0 && (!slots || !lens))) {
+        set_error("pd_kv_cache_set_lens: bad argument");
+        return PD_ERR_INVALID_ARG;
+    }
+    for (int i = 0; i < n; ++i) {
+        if (slots[i] < 0 || slots[i] >= c->max_seqs || lens[i] < 0) {
+            set_error("pd_kv_cache_set_lens: entry %d out of range", i);
+            return PD_ERR_INVALID_ARG;
+        }
+        if (lens[i] > c->max_len) {
+            set_error("pd_kv_cache_set_lens: len %d > max_len %d", lens[i], c->max_len);
+            return PD_ERR_KV_CAPACITY;
+        }
+    }
+    HIP_TRY(launch_scatter_ints(c->d_len, slots, lens, n, (hipStream_t)stream), PD_ERR_DEVICE);
+    for (int i = 0; i < n; ++i) c->h_len[(size_t)slots[i]] = lens[i];
     return PD_OK;
 }

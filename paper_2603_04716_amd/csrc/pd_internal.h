@@ -44,6 +44,24 @@ struct Elem<bf16_t> {
     static __device__ __forceinline__ void st(bf16_t *p, float v) { *p = f2bf(v); }
 };
 
+// Blocked bf16 / head_dim-128 cache layout used by the matrix-core decode attention.  Offsets are
+// in elements inside one (slot, kv head) plane of max_len_pad * 128 elements (max_len_pad is a
+// multiple of 64).
+//   keys:   blocks of 16 positions; inside a block [channel/32][position%16][channel%32], so the
+//           16 rows x 64 bytes that one MFMA A-operand load touches are 1 KB contiguous.
+//   values: blocks of 32 positions stored transposed, [channel][sigma(position%32)], where
+//           sigma(16a + 4q + j) = 8q + 4a + j is the key order in which the exp'd scores leave the
+//           S^T accumulators; again every operand load is 1 KB contiguous.
+__host__ __device__ __forceinline__ size_t kblk_off(int pos, int c)
+{
+    return (size_t)(pos >> 4) * 2048 + (size_t)(c >> 5) * 512 + (pos & 15) * 32 + (c & 31);
+}
+__host__ __device__ __forceinline__ size_t vblk_off(int pos, int d)
+{
+    const int pp = pos & 31;
+    return (size_t)(pos >> 5) * 4096 + (size_t)d * 32 + 8 * ((pp >> 2) & 3) + 4 * (pp >> 4) + (pp & 3);
+}
+
 constexpr int kMetaChunk = 255;  // ints carried by value per meta-kernel launch (+1 for cu_seqlens)
 struct IntChunk {
     int32_t v[256];
@@ -76,10 +94,15 @@ hipError_t launch_rmsnorm(int dtype, const void *x, const void *g, void *y, int 
 hipError_t launch_gemm_generic(int dtype, const GemmArgs &a, hipStream_t s);
 bool gemm_mfma_supported(const GemmArgs &a);
 hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t s);   // bf16 only
+bool gemv_mfma_supported(const GemmArgs &a);                      // bf16, M <= 16
+hipError_t launch_gemv_mfma(const GemmArgs &a, hipStream_t s);
 // per token row: its sequence, its position inside it and (if d_slots) its cache slot
 hipError_t launch_token_meta(const int32_t *d_cu, const int32_t *d_slots, int n_seqs, int T,
                              int32_t *tok_seq, int32_t *tok_pos, int32_t *tok_slot, hipStream_t s);
 hipError_t launch_write_ints(int32_t *dst, const int32_t *host_src, int n, hipStream_t s);
+// dst[idx[i]] = val[i] for i < n (host arrays, carried by value in the kernel arguments)
+hipError_t launch_scatter_ints(int32_t *dst, const int32_t *host_idx, const int32_t *host_val, int n,
+                               hipStream_t s);
 // decode meta: for b in [0,B): pos[b] = len[slot[b]]; len[slot[b]] += 1
 hipError_t launch_decode_meta(const int32_t *d_slots, int B, int32_t *d_len, int32_t *d_pos,
                               hipStream_t s);
@@ -93,8 +116,9 @@ struct RopeArgs {
     int32_t T, Hq, Hkv, hd;
     const int32_t *tok_pos;  // [T] position of each row inside its sequence
     const int32_t *tok_slot; // [T] cache slot of each row, or nullptr = no cache write
-    void *k_cache, *v_cache; // [slots][Hkv][max_len][hd]
-    int32_t max_len;
+    void *k_cache, *v_cache; // [slots][Hkv][max_len][hd], or the blocked layout above
+    int32_t max_len;         // plane length in positions (padded length for the blocked layout)
+    int32_t blocked;
     const double *inv_freq;  // [hd/2] rope_base^(-2i/hd)
 };
 hipError_t launch_rope_kv(int dtype, const RopeArgs &a, hipStream_t s);
@@ -124,8 +148,30 @@ hipError_t launch_attn_prefill_mfma(const AttnArgs &a, uint16_t *vt, int vt_ld, 
                                     hipStream_t s);
 
 hipError_t launch_kv_copy(int dtype, void *cache_k, void *cache_v, const void *k, const void *v,
-                          int slot, int Hkv, int len, int hd, int max_len, int to_cache,
+                          int slot, int Hkv, int len, int hd, int max_len, int blocked, int to_cache,
                           hipStream_t s);
+
+// ---- matrix-core decode attention over the blocked cache (bf16, head_dim 128, group <= 16) ---------
+struct DecodeAttnArgs {
+    const void *qkv;           // [B, ld] rotated q rows
+    int32_t ld;
+    void *o;                   // [B, Hq*128] bf16
+    int32_t B, Hq, Hkv;
+    float scale;
+    const int32_t *slots;      // [B]
+    const int32_t *pos;        // [B] position of the new token = keys - 1
+    const int32_t *chunk_cu;   // [B+1] prefix sum of key chunks per sequence
+    int32_t chunk_keys;        // keys per chunk (multiple of 64)
+    int32_t total_chunks;
+    const void *k_cache, *v_cache;
+    int32_t max_len_pad;
+    float *part_o;             // [total_chunks][Hq][128]
+    float *part_ml;            // [total_chunks][Hq][2]
+};
+hipError_t launch_decode_attn_mfma(const DecodeAttnArgs &a, hipStream_t s);
+// pos[b] = len[slot[b]]; len[slot[b]] += 1; chunk_cu = prefix sum of ceil((pos+1)/chunk_keys)
+hipError_t launch_decode_meta_chunks(const int32_t *d_slots, int B, int32_t *d_len, int32_t *d_pos,
+                                     int32_t *chunk_cu, int chunk_keys, hipStream_t s);
 
 // ---- MoE -----------------------------------------------------------------------------------------
 struct MoeRouteArgs {

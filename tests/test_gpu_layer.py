@@ -147,8 +147,14 @@ def test_bf16_matrix_core_path_long_ragged(hq, hkv):
         a, b = cu[s], cu[s + 1]
         if b > a:
             assert relmax(got[a:b], ref[a:b]) <= TOL["bf16"]
-    xn = I.hidden(6, cfg["d_model"], seed=22, dtype="bf16")
-    assert relmax(gl.decode(xn, slots, gc), O.decode_step(ol, xn, slots, oc)) <= TOL["bf16"]
+    # 36 decode steps: appended tokens cross the 16-, 32- and 64-position block boundaries of the cache
+    for step in range(36):
+        xn = I.hidden(6, cfg["d_model"], seed=220 + step, dtype="bf16")
+        ref = O.decode_step(ol, xn, slots, oc)
+        got = gl.decode(xn, slots, gc)
+        assert relmax(got, ref) <= TOL["bf16"], step
+        for i in range(6):
+            assert relmax(got[i], ref[i]) <= 2 * TOL["bf16"], (step, i)
     gl.close()
 
 
