@@ -27,21 +27,21 @@ TTFT_SLO, TPOT_SLO, L_OUT = 2.0, 0.020, 512.0
 
 
 def cpu_baseline(cfg, weights):
-    """The oracle, as it stands, timed on a bounded sample: prefill of one 192-token sequence
-    through the full 8B-shaped layer on the host cores."""
+    """The oracle, as it stands, timed on a bounded sample: prefill of 2 x 1024 tokens through the
+    full 8B-shaped layer on the host cores."""
     import numpy as np
     import pd_inputs as I
     from oracle import layer as O
-    n = 192
+    n = 2048
     x = I.hidden(n, cfg["d_model"], seed=99, dtype="bf16")
     L = O.Layer(cfg, weights)
     t0 = time.perf_counter()
-    O.prefill(L, x, np.array([0, n], np.int32))
+    O.prefill(L, x, np.array([0, n // 2, n], np.int32))
     dt = time.perf_counter() - t0
     cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
     cores = min(cores, os.cpu_count() or cores)
     return {"value": n / (dt * N_LAYERS), "unit": "prefill tokens/s (32-layer model)", "cores": cores,
-            "kind": "oracle", "sample": f"prefill of 1x{n} tokens through the full 8B-shaped layer, {dt:.1f} s"}
+            "kind": "oracle", "sample": f"prefill of 2x{n // 2} tokens through the full 8B-shaped layer, {dt:.1f} s"}
 
 
 def main():

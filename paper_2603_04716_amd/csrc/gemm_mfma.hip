@@ -15,6 +15,11 @@
 // silu(gate)*up is formed without any data exchange.
 //
 // Optional row gather on A and per-group B matrices serve the mixture-of-experts grouped GEMM.
+//
+// Decode-sized problems (M <= 256) have too few output tiles to occupy 256 CUs while the weights
+// stream from HBM, so K is split over gridDim.y: each split writes an fp32 partial tile and a
+// second small kernel adds the splits in a fixed order and applies the epilogue (deterministic,
+// no atomics).
 #include "pd_internal.h"
 
 namespace pd {
@@ -30,7 +35,7 @@ __device__ __forceinline__ float silu_fast(float z) { return z / (1.0f + __expf(
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
 __global__ __launch_bounds__(64 * WAVES_M *WAVES_N) void gemm_mfma_kernel(GemmArgs a, int tiles_m,
-                                                                          int tiles_n)
+                                                                          int tiles_n, int kt_per_split)
 {
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;   // wave tile
     constexpr int MB = WM / 32, NB = WN / 32;             // 32x32 blocks per wave
@@ -85,7 +90,8 @@ __global__ __launch_bounds__(64 * WAVES_M *WAVES_N) void gemm_mfma_kernel(GemmAr
         row_end = a.M;
     }
     const int col0 = tn * BN;
-    const int n_cols = (EPI == EPI_SWIGLU) ? 2 * a.N : a.N;   // rows of (packed) B
+    // rows of (packed) B; a split-K launch of a SwiGLU GEMM works on the packed columns
+    const int n_cols = (EPI == EPI_SWIGLU || (EPI == EPI_PARTIAL && a.epilogue == EPI_SWIGLU)) ? 2 * a.N : a.N;
     const __bf16 *A = (const __bf16 *)a.A;
     const __bf16 *B = (const __bf16 *)a.B + (size_t)group * a.b_group_stride;
 
@@ -138,8 +144,9 @@ __global__ __launch_bounds__(64 * WAVES_M *WAVES_N) void gemm_mfma_kernel(GemmAr
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    const int nk = a.K / BK;
-    issue_loads(0, smem);
+    const int kt0 = blockIdx.y * kt_per_split;
+    const int kt1 = min(a.K / BK, kt0 + kt_per_split);
+    issue_loads(kt0, smem);
     __syncthreads();
 
     // fragment addresses inside a stage: row and the two chunk parities of this lane
@@ -192,16 +199,32 @@ __global__ __launch_bounds__(64 * WAVES_M *WAVES_N) void gemm_mfma_kernel(GemmAr
             }
         }
     };
-    for (int kt = 0; kt + 1 < nk; ++kt) {
-        issue_loads(kt + 1, smem + ((kt + 1) & 1) * STAGE);
+    for (int kt = kt0; kt + 1 < kt1; ++kt) {
+        issue_loads(kt + 1, smem + ((kt + 1 - kt0) & 1) * STAGE);
         __builtin_amdgcn_sched_barrier(0);     // keep the loads ahead of the compute phase
-        compute(smem + (kt & 1) * STAGE);
+        compute(smem + ((kt - kt0) & 1) * STAGE);
         __syncthreads();                       // waits for the loads, then for all waves
     }
-    compute(smem + ((nk - 1) & 1) * STAGE);
+    compute(smem + ((kt1 - 1 - kt0) & 1) * STAGE);
 
     // ---- epilogue: lane holds column (lane % 32) of each block; register r is row
     //      8*(r/4) + 4*(lane/32) + r%4 ----------------------------------------------------------------
+    if (EPI == EPI_PARTIAL) {
+        float *P = a.splitk_ws + (size_t)blockIdx.y * a.M * n_cols;
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = row0 + wm * WM + i * 32 + 8 * (r >> 2) + 4 * fhalf + (r & 3);
+                if (m >= row_end) continue;
+#pragma unroll
+                for (int j = 0; j < NB; ++j) {
+                    const int n = col0 + wn * WN + j * 32 + frow;
+                    if (n < n_cols) P[(size_t)m * n_cols + n] = acc[i][j][r];
+                }
+            }
+        return;
+    }
     uint16_t *C = (uint16_t *)a.C;
     const uint16_t *R = (const uint16_t *)a.R;
 #pragma unroll
@@ -235,6 +258,46 @@ __global__ __launch_bounds__(64 * WAVES_M *WAVES_N) void gemm_mfma_kernel(GemmAr
     }
 }
 
+// out = epilogue(sum over splits of the fp32 partials); 4 consecutive output columns per thread.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmArgs a, int splits)
+{
+    const int n4 = a.N / 4;
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (size_t)a.M * n4) return;
+    const int m = (int)(idx / n4), n = (int)(idx % n4) * 4;
+    const int n_cols = a.epilogue == EPI_SWIGLU ? 2 * a.N : a.N;
+    const size_t plane = (size_t)a.M * n_cols;
+    float v[4];
+    if (a.epilogue == EPI_SWIGLU) {
+        const int pc = (n >> 5) * 64 + (n & 31);     // packed gate column; up is 32 further
+        float4 g = make_float4(0.f, 0.f, 0.f, 0.f), u = g;
+        for (int z = 0; z < splits; ++z) {
+            const float *p = a.splitk_ws + z * plane + (size_t)m * n_cols + pc;
+            float4 gz = *(const float4 *)p, uz = *(const float4 *)(p + 32);
+            g.x += gz.x; g.y += gz.y; g.z += gz.z; g.w += gz.w;
+            u.x += uz.x; u.y += uz.y; u.z += uz.z; u.w += uz.w;
+        }
+        v[0] = silu_fast(g.x) * u.x; v[1] = silu_fast(g.y) * u.y;
+        v[2] = silu_fast(g.z) * u.z; v[3] = silu_fast(g.w) * u.w;
+    } else {
+        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int z = 0; z < splits; ++z) {
+            float4 tz = *(const float4 *)(a.splitk_ws + z * plane + (size_t)m * n_cols + n);
+            t.x += tz.x; t.y += tz.y; t.z += tz.z; t.w += tz.w;
+        }
+        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+        if (a.epilogue == EPI_RESIDUAL) {
+            uint2 rr = *(const uint2 *)((const uint16_t *)a.R + (size_t)m * a.ldr + n);
+            v[0] += bfbits2f(rr.x & 0xffffu); v[1] += bfbits2f(rr.x >> 16);
+            v[2] += bfbits2f(rr.y & 0xffffu); v[3] += bfbits2f(rr.y >> 16);
+        }
+    }
+    uint2 o;
+    o.x = pack2bf(v[0], v[1]);
+    o.y = pack2bf(v[2], v[3]);
+    *(uint2 *)((uint16_t *)a.C + (size_t)m * a.ldc + n) = o;
+}
+
 bool gemm_mfma_supported(const GemmArgs &a)
 {
     if (a.K % BK != 0 || a.K <= 0 || a.M <= 0) return false;
@@ -249,13 +312,16 @@ bool gemm_mfma_supported(const GemmArgs &a)
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N>
-static hipError_t launch_cfg(const GemmArgs &a, hipStream_t s)
+static hipError_t launch_cfg(const GemmArgs &a, hipStream_t s, int splits = 1)
 {
     const int n_cols = a.epilogue == EPI_SWIGLU ? 2 * a.N : a.N;
     const int tiles_n = (n_cols + BN - 1) / BN;
     const int tiles_m = (a.M + BM - 1) / BM + (a.group_offsets ? a.n_groups : 0);
     const size_t smem = 2 * (size_t)(BM + BN) * BK * 2;
-    const dim3 grid((unsigned)(tiles_m * tiles_n));
+    const int nk = a.K / BK;
+    const int kt_per = (nk + splits - 1) / splits;
+    splits = (nk + kt_per - 1) / kt_per;               // no empty split
+    const dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)splits);
     const dim3 block(64 * WAVES_M * WAVES_N);
 #define LAUNCH(EPI)                                                                              \
     do {                                                                                         \
@@ -267,8 +333,16 @@ static hipError_t launch_cfg(const GemmArgs &a, hipStream_t s)
             if (e != hipSuccess) return e;                                                       \
             attr_set = true;                                                                     \
         }                                                                                        \
-        kern<<<grid, block, smem, s>>>(a, tiles_m, tiles_n);                                     \
+        kern<<<grid, block, smem, s>>>(a, tiles_m, tiles_n, kt_per);                             \
     } while (0)
+    if (splits > 1) {
+        LAUNCH(EPI_PARTIAL);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        const size_t n_out = (size_t)a.M * (a.N / 4);
+        splitk_reduce_kernel<<<(unsigned)((n_out + 255) / 256), 256, 0, s>>>(a, splits);
+        return hipGetLastError();
+    }
     switch (a.epilogue) {
     case EPI_NONE: LAUNCH(EPI_NONE); break;
     case EPI_RESIDUAL: LAUNCH(EPI_RESIDUAL); break;
@@ -278,10 +352,28 @@ static hipError_t launch_cfg(const GemmArgs &a, hipStream_t s)
     return hipGetLastError();
 }
 
+// Split count for decode-sized problems: enough workgroups to keep every CU streaming weights,
+// at least 4 k-tiles per split, and the partials must fit the scratch buffer.
+static int choose_splits(const GemmArgs &a, int BM, int BN)
+{
+    if (!a.splitk_ws || a.group_offsets || a.a_gather || a.N % 4 != 0 || a.ldc % 4 != 0 ||
+        (a.epilogue == EPI_RESIDUAL && a.ldr % 4 != 0))
+        return 1;
+    const int n_cols = a.epilogue == EPI_SWIGLU ? 2 * a.N : a.N;
+    const int tiles = ((a.M + BM - 1) / BM) * ((n_cols + BN - 1) / BN);
+    const int nk = a.K / BK;
+    int splits = (640 + tiles - 1) / tiles;
+    if (splits > nk / 4) splits = nk / 4;
+    while (splits > 1 && (size_t)splits * a.M * n_cols > a.splitk_ws_elems) --splits;
+    return splits < 1 ? 1 : splits;
+}
+
 hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t s)
 {
-    if (a.M > 128) return launch_cfg<256, 256, 2, 4>(a, s);   // 8 waves: two per SIMD hide each other's stalls
-    return launch_cfg<128, 128, 2, 2>(a, s);
+    if (a.M > 256) return launch_cfg<256, 256, 2, 4>(a, s);   // 8 waves: two per SIMD hide each other's stalls
+    if (a.M > 128) return launch_cfg<256, 128, 4, 2>(a, s, choose_splits(a, 256, 128));
+    if (a.M > 64) return launch_cfg<128, 128, 2, 2>(a, s, choose_splits(a, 128, 128));
+    return launch_cfg<64, 128, 2, 2>(a, s, choose_splits(a, 64, 128));
 }
 
 }  // namespace pd

@@ -23,6 +23,8 @@ struct pd_layer {
     void *vt;                 // transposed-V scratch for the MFMA attention, vt_cap bytes
     size_t vt_cap;
     float *dec_part;          // partial outputs of the decode attention chunks (inside ws)
+    float *splitk;            // split-K partials of the decode-sized GEMMs (inside ws)
+    size_t splitk_elems;
     // workspace, sized for ws_tokens rows
     int ws_tokens;
     char *ws;
@@ -247,6 +249,12 @@ extern "C" pd_status pd_layer_reserve(pd_layer *L, int32_t max_tokens)
            o_pp = carve(T * K * 4), o_off = carve(65 * 4 + 4), o_log = carve(T * (E > 0 ? E : 1) * 4),
            o_ew = carve(T * K * 4), o_ccu = carve((T + 1) * 4),
            o_part = carve(decode_chunk_bound(L, max_tokens) * L->cfg.n_q_heads * 130 * sizeof(float));
+    // split-K scratch: splits * columns never exceeds 640 tiles * 128 columns + one row of tiles
+    size_t maxn = (size_t)L->Nqkv;
+    if ((size_t)2 * F > maxn) maxn = (size_t)2 * F;
+    if ((size_t)d > maxn) maxn = (size_t)d;
+    const size_t sk_elems = L->use_mfma ? (size_t)256 * (640 * 128 + 2 * maxn) : 0;
+    size_t o_sk = carve(sk_elems * sizeof(float));
     HIP_TRY(hipDeviceSynchronize(), PD_ERR_DEVICE);
     char *nw = nullptr;
     hipError_t e = hipMalloc((void **)&nw, off);
@@ -274,6 +282,8 @@ extern "C" pd_status pd_layer_reserve(pd_layer *L, int32_t max_tokens)
     L->ew = (float *)(nw + o_ew);
     L->chunk_cu = (int32_t *)(nw + o_ccu);
     L->dec_part = (float *)(nw + o_part);
+    L->splitk = sk_elems ? (float *)(nw + o_sk) : nullptr;
+    L->splitk_elems = sk_elems;
     return PD_OK;
 }
 
@@ -385,8 +395,10 @@ extern "C" pd_status pd_kv_cache_len(const pd_kv_cache *c, int32_t slot, int32_t
 
 // ---- layer forward -------------------------------------------------------------------------------
 
-static hipError_t run_gemm(const pd_layer *L, const GemmArgs &g, hipStream_t s)
+static hipError_t run_gemm(const pd_layer *L, GemmArgs g, hipStream_t s)
 {
+    g.splitk_ws = L->splitk;
+    g.splitk_ws_elems = L->splitk_elems;
     if (L->use_mfma && gemv_mfma_supported(g)) return launch_gemv_mfma(g, s);
     if (L->use_mfma && gemm_mfma_supported(g)) return launch_gemm_mfma(g, s);
     return launch_gemm_generic(L->cfg.dtype, g, s);

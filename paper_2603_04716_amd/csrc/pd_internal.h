@@ -67,7 +67,7 @@ struct IntChunk {
     int32_t v[256];
 };
 
-enum Epilogue { EPI_NONE = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2 };
+enum Epilogue { EPI_NONE = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2, EPI_PARTIAL = 3 /* internal: fp32 split-K partials */ };
 
 // C[M,N] = epilogue(A[M,K] * B[N,K]^T).  All matrices row-major with leading dimensions in
 // elements.  a_gather (optional): logical row i of A is physical row a_gather[i].  Groups
@@ -86,6 +86,8 @@ struct GemmArgs {
     int32_t lda, ldb, ldc, ldr;
     int32_t epilogue;
     int32_t interleaved;           // EPI_SWIGLU: B holds 32-row blocks gate,up,gate,up...
+    float *splitk_ws;              // optional scratch for split-K partials (decode-sized M)
+    size_t splitk_ws_elems;
 };
 
 // ---- launchers (each returns hipGetLastError() after the launch) ------------------------------

@@ -158,6 +158,33 @@ def test_bf16_matrix_core_path_long_ragged(hq, hkv):
     gl.close()
 
 
+@pytest.mark.parametrize("B", [1, 3, 16, 17, 64, 65, 130, 256])
+def test_bf16_decode_batch_sizes_ragged_cache(B):
+    """Every decode GEMM variant (<=16 rows, <=64, <=128, <=256 with split-K) and the chunked decode
+    attention, over caches of ragged length filled through pd_kv_cache_set."""
+    cfg = I.small_config(dtype="bf16", d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=128, d_ff=512)
+    ol, gl = both(cfg, std=0.05)
+    rng = np.random.default_rng(B)
+    lens = rng.integers(0, 300, B)
+    lens[0] = 299
+    cap = 320
+    oc, gc = O.KVCache(ol, B, cap), gl.cache(B, cap)
+    for i, n in enumerate(lens):
+        k, v = I.kv_fill(2, int(n), 128, seed=1000 + i, dtype="bf16")
+        oc.set(i, k, v)
+        if n > 0:
+            pd.pd_kv_cache_set(gc, i, to_dev(k, "bf16"), to_dev(v, "bf16"))
+    slots = list(range(B))
+    for step in range(2):
+        xn = I.hidden(B, cfg["d_model"], seed=31 + step, dtype="bf16")
+        ref = O.decode_step(ol, xn, slots, oc)
+        got = gl.decode(xn, slots, gc)
+        assert relmax(got, ref) <= TOL["bf16"]
+        worst = max(relmax(got[i], ref[i]) for i in range(B))
+        assert worst <= 2 * TOL["bf16"]
+    gl.close()
+
+
 def test_kv_cache_set_get_and_errors():
     cfg = I.small_config()
     ol, gl = both(cfg)
