@@ -1,0 +1,192 @@
+"""Measurement runs that feed (and check) the allocation model, on one GPU.
+
+    python -m paper_2603_04716_amd.experiments prefill      # max prefill throughput vs L_in
+    python -m paper_2603_04716_amd.experiments longctx      # decode TPOT curves at KV 4096..16384, uniform + ragged,
+                                                            # largest batch meeting TPOT 20/50/100 ms
+    python -m paper_2603_04716_amd.experiments queue        # Poisson arrivals served FIFO by the GPU prefill,
+                                                            # mean TTFT vs the M/M/1 prediction of Eq. (12)
+    python -m paper_2603_04716_amd.experiments moe          # 8-expert top-2 layer: prefill + decode sweep
+
+Each run prints one JSON document.  Inputs are the seeded synthetic draws of pd_inputs.
+"""
+import json
+import os
+import sys
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import pd_inputs as I  # noqa: E402
+from . import binding as pd  # noqa: E402
+from . import harness as H  # noqa: E402
+
+N_LAYERS = 32
+HBM_PEAK, MFMA_PEAK = 8e12, 2.5e15
+
+
+def _layer(name):
+    cfg = I.CONFIGS[name]
+    return cfg, H.Layer(cfg, I.layer_weights(cfg))
+
+
+def run_prefill(name="llama8b"):
+    cfg, layer = _layer(name)
+    T = 8192
+    x = H._dev(I.hidden(T, cfg["d_model"], seed=10, dtype="bf16"), "bf16")
+    rl = torch.from_numpy(I.router_logits(T, cfg["n_experts"], seed=13)).cuda() if cfg["n_experts"] else None
+    pts = []
+    for l_in in (1024, 2048, 4096):
+        cu = I.uniform_cu_seqlens(T // l_in, l_in)
+        ms = layer.time_prefill(x, cu, iters=10, warmup=3, router_logits=rl)
+        fl = H.prefill_flops(cfg, [l_in] * (T // l_in))
+        pts.append({"l_in": l_in, "ms_per_layer": round(ms, 4), "tok_s_model": round(T / (N_LAYERS * ms * 1e-3), 1),
+                    "tflops": round(fl / (ms * 1e-3) / 1e12, 1), "mfma_frac": round(fl / (ms * 1e-3) / MFMA_PEAK, 4)})
+    layer.close()
+    return {"experiment": "max prefill throughput vs input length", "layer": name, "tokens": T, "points": pts}
+
+
+def run_longctx():
+    cfg, layer = _layer("llama8b")
+    hkv, hd, d = cfg["n_kv_heads"], cfg["head_dim"], cfg["d_model"]
+    bmax = 128
+    out = {"experiment": "long-context decode: TPOT vs batch, uniform and ragged KV", "cases": []}
+    xall = H._dev(I.hidden(bmax, d, seed=12, dtype="bf16"), "bf16")
+    for S in (4096, 8192, 16384):
+        cache = layer.new_cache(bmax, S + 8)
+        k, v = I.kv_fill(hkv, S, hd, seed=11, dtype="bf16")
+        kd, vd = H._dev(k, "bf16"), H._dev(v, "bf16")
+        for mode in ("uniform", "ragged"):
+            lens_all = np.full(bmax, S, np.int32) if mode == "uniform" else I.ragged_kv_lengths(bmax, S, seed=S)
+            layer.fill_cache(cache, lens_all, kd, vd)
+            cache_pts = {}
+
+            def tpot(B):
+                if B not in cache_pts:
+                    run = layer.make_decode_step(cache, xall[:B].contiguous(), lens_all[:B])
+                    ms = H.median([run() for _ in range(7)])
+                    cache_pts[B] = ms
+                return N_LAYERS * cache_pts[B] * 1e-3
+
+            curve = []
+            for B in (1, 2, 4, 8, 16, 32, 64, 128):
+                t = tpot(B)
+                by = H.decode_bytes(cfg, lens_all[:B])
+                curve.append({"batch": B, "tpot_ms": round(t * 1e3, 3), "tok_s": round(B / t, 1),
+                              "hbm_frac": round(by / (t / N_LAYERS) / HBM_PEAK, 4)})
+            targets = []
+            for slo in (0.020, 0.050, 0.100):
+                b, t, _ = H.largest_feasible_batch(tpot, slo, bmax)
+                e = {"tpot_slo_ms": slo * 1e3, "max_batch": b}
+                if b:
+                    by = H.decode_bytes(cfg, lens_all[:b])
+                    e.update(tpot_ms=round(t * 1e3, 3), tok_s=round(b / t, 1),
+                             hbm_gbps=round(by / (t / N_LAYERS) / 1e9, 1),
+                             hbm_frac=round(by / (t / N_LAYERS) / HBM_PEAK, 4), capped=(b == bmax))
+                targets.append(e)
+            out["cases"].append({"kv_capacity": S, "lengths": mode, "mean_kv": float(np.mean(lens_all)),
+                                 "curve": curve, "targets": targets})
+        layer.free_cache(cache)
+        del kd, vd
+    layer.close()
+    return out
+
+
+def run_queue(n_req=2000):
+    cfg, layer = _layer("llama8b")
+    d = cfg["d_model"]
+    lens = I.request_lengths(n_req, seed=3)
+    xbuf = H._dev(I.hidden(int(lens.max()), d, seed=14, dtype="bf16"), "bf16")   # timing is value-independent
+    out_buf = torch.empty_like(xbuf)
+    pd.pd_layer_reserve(layer.h, int(lens.max()))
+    # service time of every request = measured GPU time of its own prefill (x 32 layers)
+    uniq = np.unique(lens)
+    svc_ms = {}
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for L in uniq:
+        L = int(L)
+        reps = 3
+        pd.pd_prefill(layer.h, xbuf[:L], [0, L], out_buf[:L])
+        e0.record()
+        for _ in range(reps):
+            pd.pd_prefill(layer.h, xbuf[:L], [0, L], out_buf[:L])
+        e1.record()
+        e1.synchronize()
+        svc_ms[L] = e0.elapsed_time(e1) / reps
+    service = np.array([N_LAYERS * svc_ms[int(L)] * 1e-3 for L in lens])
+    # saturated pass: back-to-back service of the same 2000 requests
+    tp_hat = float(lens.sum() / service.sum())
+    mean_l = float(lens.mean())
+    mu = tp_hat / mean_l                                 # Eq. (9) on the drawn lengths = 1 / mean service
+    res = {"experiment": "FIFO prefill queue vs M/M/1", "requests": n_req, "mean_l_in": mean_l,
+           "tp_prefill_max_tok_s": round(tp_hat, 1), "mu_req_s": round(mu, 4), "rates": []}
+    for f in (0.3, 0.5, 0.7, 0.9):
+        lam = f * mu
+        arr = I.poisson_arrivals(n_req, lam, seed=int(f * 100))
+        soj = pd.pd_fifo_replay(arr, service)
+        pred = pd.pd_mm1_sojourn(tp_hat, mean_l, lam)
+        rho = lam * service.mean()
+        pk = service.mean() + lam * float(np.mean(service ** 2)) / (2 * (1 - rho))
+        res["rates"].append({"load": f, "lambda_req_s": round(lam, 4), "mean_ttft_s": round(float(np.mean(soj)), 5),
+                             "mm1_pred_s": round(pred, 5), "ratio_measured_over_mm1": round(float(np.mean(soj)) / pred, 4),
+                             "mg1_pk_s": round(pk, 5)})
+    layer.close()
+    return res
+
+
+def run_moe():
+    cfg, layer = _layer("moe")
+    d, E = cfg["d_model"], cfg["n_experts"]
+    res = run_prefill_on(layer, cfg)
+    S, bmax = 4096, 256
+    cache = layer.new_cache(bmax, S + 8)
+    k, v = I.kv_fill(cfg["n_kv_heads"], S, cfg["head_dim"], seed=11, dtype="bf16")
+    layer.fill_cache(cache, [S] * bmax, H._dev(k, "bf16"), H._dev(v, "bf16"))
+    xall = H._dev(I.hidden(bmax, d, seed=12, dtype="bf16"), "bf16")
+    rl_np = I.router_logits(bmax, E, seed=15)
+    rl = torch.from_numpy(rl_np).cuda()
+    curve = []
+    for B in (1, 2, 4, 8, 16, 32, 64, 128, 256):
+        run = layer.make_decode_step(cache, xall[:B].contiguous(), [S] * B, router_logits=rl[:B].contiguous())
+        ms = H.median([run() for _ in range(7)])
+        top2 = np.argsort(-rl_np[:B], 1, kind="stable")[:, :2]
+        touched = len(np.unique(top2))
+        by = H.decode_bytes(cfg, [S] * B, experts_touched=touched)
+        curve.append({"batch": B, "experts_touched": touched, "ms_per_layer": round(ms, 4),
+                      "tpot_ms": round(N_LAYERS * ms, 3), "tok_s": round(B / (N_LAYERS * ms * 1e-3), 1),
+                      "hbm_frac": round(by / (ms * 1e-3) / HBM_PEAK, 4)})
+    hist = np.bincount(np.argsort(-I.router_logits(8192, E, seed=13), 1, kind="stable")[:, :2].ravel(), minlength=E)
+    res.update(decode_kv_len=S, decode_curve=curve, prefill_expert_load=hist.tolist())
+    layer.close()
+    return res
+
+
+def run_prefill_on(layer, cfg):
+    T, l_in = 8192, 2048
+    x = H._dev(I.hidden(T, cfg["d_model"], seed=10, dtype="bf16"), "bf16")
+    rl = torch.from_numpy(I.router_logits(T, cfg["n_experts"], seed=13)).cuda()
+    cu = I.uniform_cu_seqlens(T // l_in, l_in)
+    ms = layer.time_prefill(x, cu, iters=8, warmup=3, router_logits=rl)
+    fl = H.prefill_flops(cfg, [l_in] * (T // l_in))
+    pd.pd_profile_enable(layer.h, True)
+    out = torch.empty_like(x)
+    pd.pd_prefill(layer.h, x, cu, out, router_logits=rl)
+    steps = pd.pd_profile_read(layer.h)
+    pd.pd_profile_enable(layer.h, False)
+    return {"experiment": "MoE layer (8 experts, top-2)", "prefill": {
+        "tokens": T, "l_in": l_in, "ms_per_layer": round(ms, 4), "tok_s_model": round(T / (N_LAYERS * ms * 1e-3), 1),
+        "tflops": round(fl / (ms * 1e-3) / 1e12, 1), "mfma_frac": round(fl / (ms * 1e-3) / MFMA_PEAK, 4),
+        "steps_ms": {n: round(t, 4) for n, t in steps}}}
+
+
+def main():
+    which = sys.argv[1] if len(sys.argv) > 1 else "prefill"
+    fn = {"prefill": run_prefill, "longctx": run_longctx, "queue": run_queue, "moe": run_moe}[which]
+    print(json.dumps(fn()))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,160 @@
+"""GPU parity at the benchmark's full shapes, in the launch configuration bench.py times.
+The oracle cannot evaluate 8192 x 8B-shaped rows in seconds, so it produces sampled output rows
+(keys and values of all earlier tokens of the sampled sequences are still computed in full) and
+those rows are compared element by element.  Bound: max|gpu - ref| / max|ref| <= 2e-2 (bf16)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2603_04716_amd as pd
+import pd_inputs as I
+from oracle import layer as O
+from paper_2603_04716_amd import harness as H
+from gpu_util import TOL, relmax, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def llama():
+    cfg = I.CONFIGS["llama8b"]
+    w = I.layer_weights(cfg)
+    layer = H.Layer(cfg, w)
+    yield cfg, w, layer
+    layer.close()
+
+
+@pytest.mark.parametrize("l_in", [2048, 4096, 1024])
+def test_llama8b_prefill_8192_tokens_sampled_rows(llama, l_in):
+    cfg, w, layer = llama
+    T = 8192
+    n_seq = T // l_in
+    x = I.hidden(T, cfg["d_model"], seed=10, dtype="bf16")
+    cu = I.uniform_cu_seqlens(n_seq, l_in)
+    xd = H._dev(x, "bf16")
+    out = torch.empty_like(xd)
+    pd.pd_prefill(layer.h, xd, cu, out)
+    torch.cuda.synchronize()
+    got = to_np(out)
+    assert np.isfinite(got).all()
+    last = (n_seq - 1) * l_in
+    rows = [0, 1, 130, min(l_in, 1500) - 1, last + 7, last + 640]     # first and last sequence
+    ref = O.prefill(O.Layer(cfg, w), x, cu, rows=rows)
+    assert relmax(got[rows], ref) <= TOL["bf16"]
+    for i, r in enumerate(rows):
+        assert relmax(got[r], ref[i]) <= 2 * TOL["bf16"], r
+    # properties that hold at any size: sequences with identical inputs give identical outputs
+    x2 = x.copy()
+    x2[l_in:2 * l_in] = x[:l_in]
+    pd.pd_prefill(layer.h, H._dev(x2, "bf16"), cu, out)
+    torch.cuda.synchronize()
+    got2 = to_np(out)
+    assert np.array_equal(got2[l_in:2 * l_in], got2[:l_in])
+    assert np.array_equal(got2[:l_in], got[:l_in])
+
+
+@pytest.mark.parametrize("B", [256, 8])
+def test_llama8b_decode_kv2048_sampled_rows_graph_replay(llama, B):
+    cfg, w, layer = llama
+    S = 2048
+    hkv, hd = cfg["n_kv_heads"], cfg["head_dim"]
+    cache = layer.new_cache(B, S + 8)
+    sets = [I.kv_fill(hkv, S, hd, seed=40 + j, dtype="bf16") for j in range(4)]
+    dev_sets = [(H._dev(k, "bf16"), H._dev(v, "bf16")) for k, v in sets]
+    for s in range(B):
+        pd.pd_kv_cache_set(cache, s, *dev_sets[s % 4])
+    x = I.hidden(B, cfg["d_model"], seed=41, dtype="bf16")
+    run = layer.make_decode_step(cache, H._dev(x, "bf16"), [S] * B, use_graph=True)
+    run()
+    run()                                    # replays must rewind and reproduce
+    torch.cuda.synchronize()
+    got = to_np(run.out)
+    assert np.isfinite(got).all()
+    sample = sorted(set([0, B // 3, B - 1]))
+    ol = O.Layer(cfg, w)
+    oc = O.KVCache(ol, len(sample), S + 8)
+    for i, b in enumerate(sample):
+        oc.set(i, *sets[b % 4])
+    ref = O.decode_step(ol, x[sample], list(range(len(sample))), oc)
+    assert relmax(got[sample], ref) <= TOL["bf16"]
+    for i, b in enumerate(sample):
+        assert relmax(got[b], ref[i]) <= 2 * TOL["bf16"], b
+    # the appended key/value of a sampled slot equal the oracle's
+    n = S + 1
+    k = torch.empty((hkv, n, hd), dtype=torch.bfloat16, device="cuda")
+    v = torch.empty_like(k)
+    pd.pd_kv_cache_get(cache, sample[-1], k, v)
+    torch.cuda.synchronize()
+    assert relmax(to_np(k)[:, S], oc.k[len(sample) - 1, :, S]) <= TOL["bf16"]
+    assert relmax(to_np(v)[:, S], oc.v[len(sample) - 1, :, S]) <= TOL["bf16"]
+    layer.free_cache(cache)
+
+
+def test_llama8b_decode_ragged_long_context_sampled_rows(llama):
+    """Ragged KV lengths (log-normal prompt + partial generation, capacity 8192) at batch 32."""
+    cfg, w, layer = llama
+    B, cap = 32, 8192
+    hkv, hd = cfg["n_kv_heads"], cfg["head_dim"]
+    lens = I.ragged_kv_lengths(B, cap - 1, seed=2)
+    lens[5] = cap - 1                                   # one sequence at full capacity
+    cache = layer.new_cache(B, cap)
+    k, v = I.kv_fill(hkv, cap - 1, hd, seed=50, dtype="bf16")
+    kd, vd = H._dev(k, "bf16"), H._dev(v, "bf16")
+    layer.fill_cache(cache, lens, kd, vd)
+    x = I.hidden(B, cfg["d_model"], seed=51, dtype="bf16")
+    run = layer.make_decode_step(cache, H._dev(x, "bf16"), lens, use_graph=True)
+    run()
+    torch.cuda.synchronize()
+    got = to_np(run.out)
+    sample = [0, 5, int(np.argmin(lens))]
+    ol = O.Layer(cfg, w)
+    oc = O.KVCache(ol, len(sample), cap)
+    for i, b in enumerate(sample):
+        oc.set(i, k[:, :lens[b]], v[:, :lens[b]])
+    ref = O.decode_step(ol, x[sample], list(range(len(sample))), oc)
+    for i, b in enumerate(sample):
+        assert relmax(got[b], ref[i]) <= TOL["bf16"], (b, int(lens[b]))
+    layer.free_cache(cache)
+
+
+def test_moe_8_experts_full_shape_sampled_rows():
+    cfg = I.CONFIGS["moe"]
+    w = I.layer_weights(cfg)
+    layer = H.Layer(cfg, w)
+    T, l_in = 8192, 2048
+    x = I.hidden(T, cfg["d_model"], seed=60, dtype="bf16")
+    r = I.router_logits(T, cfg["n_experts"], seed=61)
+    cu = I.uniform_cu_seqlens(T // l_in, l_in)
+    xd, rd = H._dev(x, "bf16"), torch.from_numpy(r).cuda()
+    out = torch.empty_like(xd)
+    pd.pd_prefill(layer.h, xd, cu, out, router_logits=rd)
+    torch.cuda.synchronize()
+    got = to_np(out)
+    e = torch.empty((T, 2), dtype=torch.int32, device="cuda")
+    pd.pd_last_expert_choice(layer.h, T, e)
+    torch.cuda.synchronize()
+    rows = [0, 3, 700, 6144 + 11]
+    ol = O.Layer(cfg, w)
+    ref, eref = O.prefill(ol, x, cu, router_logits=r, rows=rows, return_experts=True)
+    assert np.array_equal(e.cpu().numpy()[rows], eref)
+    # every token's experts: the two largest logits (no ties in continuous draws)
+    assert np.array_equal(np.sort(e.cpu().numpy(), 1), np.sort(np.argsort(-r, 1, kind="stable")[:, :2], 1))
+    assert relmax(got[rows], ref) <= TOL["bf16"]
+    # decode step over a filled cache, batch 16
+    B, S = 16, 512
+    cache = layer.new_cache(B, S + 8)
+    k, v = I.kv_fill(cfg["n_kv_heads"], S, cfg["head_dim"], seed=62, dtype="bf16")
+    layer.fill_cache(cache, [S] * B, H._dev(k, "bf16"), H._dev(v, "bf16"))
+    xn = I.hidden(B, cfg["d_model"], seed=63, dtype="bf16")
+    rn = I.router_logits(B, cfg["n_experts"], seed=64)
+    run = layer.make_decode_step(cache, H._dev(xn, "bf16"), [S] * B, router_logits=torch.from_numpy(rn).cuda(),
+                                 use_graph=True)
+    run()
+    torch.cuda.synchronize()
+    sample = [0, 9]
+    oc = O.KVCache(ol, 2, S + 8)
+    for i in range(2):
+        oc.set(i, k, v)
+    refd = O.decode_step(ol, xn[sample], [0, 1], oc, router_logits=rn[sample])
+    assert relmax(to_np(run.out)[sample], refd) <= TOL["bf16"]
+    layer.close()
