@@ -7,6 +7,11 @@ libpd_mi355x.so; if that library is missing the import fails.
 import ctypes as C
 import os
 
+# PyTorch owns the device memory handed to the library, so both must bind to ONE HIP runtime
+# instance: load torch (and with it the runtime it ships) before the library resolves its own
+# dependency on libamdhip64.
+import torch  # noqa: F401
+
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libpd_mi355x.so")
 
@@ -93,7 +98,6 @@ def _ptr(t):
 
 
 def _stream():
-    import torch
     return C.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 

@@ -197,19 +197,52 @@ __global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a, i
 }
 
 // o[b, head, :] = sum_c 2^(m_c - M) o_c / sum_c 2^(m_c - M) l_c over the chunks of sequence b.
+// The chunk weights are formed once per block (one chunk per thread, in parallel); the weighted
+// sum then reads the partial rows with independent loads.
 __global__ __launch_bounds__(128) void decode_attn_merge_kernel(DecodeAttnArgs a)
 {
+    __shared__ float wgt_s[128];
+    __shared__ float red[2];
     const int b = blockIdx.x, head = blockIdx.y, d = threadIdx.x;
     const int c0 = a.chunk_cu[b], c1 = a.chunk_cu[b + 1];
     float M = -INFINITY;
-    for (int c = c0; c < c1; ++c) M = fmaxf(M, a.part_ml[((size_t)c * a.Hq + head) * 2]);
+    for (int c = c0 + d; c < c1; c += 128) M = fmaxf(M, a.part_ml[((size_t)c * a.Hq + head) * 2]);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, 64));
+    if ((d & 63) == 0) red[d >> 6] = M;
+    __syncthreads();
+    M = fmaxf(red[0], red[1]);
     float L = 0.f, acc = 0.f;
-    for (int c = c0; c < c1; ++c) {
-        const float *pm = a.part_ml + ((size_t)c * a.Hq + head) * 2;
-        float wgt = dexp2(pm[0] - M);
-        L += wgt * pm[1];
-        acc += wgt * a.part_o[((size_t)c * a.Hq + head) * 128 + d];
+    for (int base = c0; base < c1; base += 128) {
+        const int c = base + d;
+        float w = 0.f, l = 0.f;
+        if (c < c1) {
+            const float *pm = a.part_ml + ((size_t)c * a.Hq + head) * 2;
+            w = dexp2(pm[0] - M);
+            l = pm[1];
+        }
+        __syncthreads();
+        wgt_s[d] = w;
+        L += w * l;
+        __syncthreads();
+        const int cnt = min(128, c1 - base);
+        const float *po = a.part_o + ((size_t)base * a.Hq + head) * 128 + d;
+        const size_t stride = (size_t)a.Hq * 128;
+        int j = 0;
+        for (; j + 4 <= cnt; j += 4) {
+            float v0 = po[(size_t)j * stride], v1 = po[(size_t)(j + 1) * stride];
+            float v2 = po[(size_t)(j + 2) * stride], v3 = po[(size_t)(j + 3) * stride];
+            acc += wgt_s[j] * v0 + wgt_s[j + 1] * v1 + wgt_s[j + 2] * v2 + wgt_s[j + 3] * v3;
+        }
+        for (; j < cnt; ++j) acc += wgt_s[j] * po[(size_t)j * stride];
     }
+    // total weight: sum of the per-thread partial sums
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) L += __shfl_xor(L, off, 64);
+    __syncthreads();
+    if ((d & 63) == 0) red[d >> 6] = L;
+    __syncthreads();
+    L = red[0] + red[1];
     ((uint16_t *)a.o)[((size_t)b * a.Hq + head) * 128 + d] = f2bf(acc / L).x;
 }
 

@@ -151,9 +151,9 @@ __global__ __launch_bounds__(64 * WAVES_M *WAVES_N) void gemm_mfma_kernel(GemmAr
 
     // fragment addresses inside a stage: row and the two chunk parities of this lane
     const int frow = lane & 31, fhalf = lane >> 5;
-    // Fragment reads of k-step kk+1 are issued between the MFMAs of k-step kk (register double
-    // buffer); sched_group_barrier pins that interleaving so that LDS latency hides behind the
-    // matrix pipe.
+    // Fragment reads of one 16-wide k-step, then its MFMAs; with two waves per SIMD the other
+    // wave's matrix work covers this wave's LDS latency (measured: explicit register double
+    // buffering of the fragments changes nothing).
     auto load_frags = [&](const unsigned char *st, int kk, bf16x8 (&fa)[MB], bf16x8 (&fb)[NB]) {
         const int c = kk * 2 + fhalf;
 #pragma unroll
@@ -175,28 +175,11 @@ __global__ __launch_bounds__(64 * WAVES_M *WAVES_N) void gemm_mfma_kernel(GemmAr
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     };
     auto compute = [&](const unsigned char *st) {
-        bf16x8 fa0[MB], fb0[NB], fa1[MB], fb1[NB];
-        load_frags(st, 0, fa0, fb0);
 #pragma unroll
-        for (int kk = 0; kk < BK / 16; kk += 2) {
-            load_frags(st, kk + 1, fa1, fb1);
-            mma(fa0, fb0);
-#pragma unroll
-            for (int q = 0; q < MB + NB; ++q) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
-            }
-            __builtin_amdgcn_sched_group_barrier(0x008, MB * NB - (MB + NB), 0);
-            if (kk + 2 < BK / 16) load_frags(st, kk + 2, fa0, fb0);
-            mma(fa1, fb1);
-            if (kk + 2 < BK / 16) {
-#pragma unroll
-                for (int q = 0; q < MB + NB; ++q) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                }
-                __builtin_amdgcn_sched_group_barrier(0x008, MB * NB - (MB + NB), 0);
-            }
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            bf16x8 fa[MB], fb[NB];
+            load_frags(st, kk, fa, fb);
+            mma(fa, fb);
         }
     };
     for (int kt = kt0; kt + 1 < kt1; ++kt) {
@@ -364,6 +347,9 @@ static int choose_splits(const GemmArgs &a, int BM, int BN)
     const int nk = a.K / BK;
     int splits = (640 + tiles - 1) / tiles;
     if (splits > nk / 4) splits = nk / 4;
+    // the fp32 partials (written and read back) should stay below about half of the weight bytes
+    const int cap = a.K / (8 * a.M) > 1 ? a.K / (8 * a.M) : 1;
+    if (splits > cap) splits = cap;
     while (splits > 1 && (size_t)splits * a.M * n_cols > a.splitk_ws_elems) --splits;
     return splits < 1 ? 1 : splits;
 }
@@ -371,7 +357,7 @@ static int choose_splits(const GemmArgs &a, int BM, int BN)
 hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t s)
 {
     if (a.M > 256) return launch_cfg<256, 256, 2, 4>(a, s);   // 8 waves: two per SIMD hide each other's stalls
-    if (a.M > 128) return launch_cfg<256, 128, 4, 2>(a, s, choose_splits(a, 256, 128));
+    if (a.M > 128) return launch_cfg<256, 64, 8, 1>(a, s, choose_splits(a, 256, 64));
     if (a.M > 64) return launch_cfg<128, 128, 2, 2>(a, s, choose_splits(a, 128, 128));
     return launch_cfg<64, 128, 2, 2>(a, s, choose_splits(a, 64, 128));
 }

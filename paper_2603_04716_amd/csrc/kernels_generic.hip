@@ -347,11 +347,17 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(RopeArgs a)
     const int half = a.hd >> 1;
     const int pos = a.tok_pos[t];
     for (int i = threadIdx.x; i < half; i += 256) {
-        double ang = (double)pos * a.inv_freq[i];
-        double sv, cv;
-        sincos(ang, &sv, &cv);
-        cs[i] = (float)cv;
-        sn[i] = (float)sv;
+        if (pos < a.table_len) {
+            float2 t = a.table[(size_t)pos * half + i];
+            cs[i] = t.x;
+            sn[i] = t.y;
+        } else {
+            double ang = (double)pos * a.inv_freq[i];
+            double sv, cv;
+            sincos(ang, &sv, &cv);
+            cs[i] = (float)cv;
+            sn[i] = (float)sv;
+        }
     }
     __syncthreads();
     T *row = (T *)a.qkv + (size_t)t * a.ld;
@@ -386,6 +392,24 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(RopeArgs a)
             else plane[(size_t)pos * a.hd + i] = vsrc[idx];
         }
     }
+}
+
+// (cos, sin) of pos * inv_freq[i], evaluated in double, for pos < table_len.
+__global__ void rope_table_kernel(float2 *table, int table_len, int half, const double *inv_freq)
+{
+    size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (size_t)table_len * half) return;
+    int pos = (int)(idx / half), i = (int)(idx % half);
+    double sv, cv;
+    sincos((double)pos * inv_freq[i], &sv, &cv);
+    table[idx] = make_float2((float)cv, (float)sv);
+}
+
+hipError_t launch_rope_table(float2 *table, int table_len, int half, const double *inv_freq, hipStream_t s)
+{
+    size_t n = (size_t)table_len * half;
+    rope_table_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(table, table_len, half, inv_freq);
+    return hipGetLastError();
 }
 
 hipError_t launch_rope_kv(int dtype, const RopeArgs &a, hipStream_t s)

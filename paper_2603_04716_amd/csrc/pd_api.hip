@@ -19,6 +19,7 @@ struct pd_layer {
     bool interleaved;    // gate/up rows stored as alternating 32-row blocks
     void *g_attn, *g_ffn, *w_qkv, *w_o, *w_gate, *w_up, *w_down, *w_router;
     double *inv_freq;
+    float2 *rope_table;       // (cos, sin) for positions < kRopeTableLen
     int32_t *d_cu, *d_slots, *d_pad_cu;  // [4097] each
     void *vt;                 // transposed-V scratch for the MFMA attention, vt_cap bytes
     size_t vt_cap;
@@ -48,6 +49,7 @@ struct pd_kv_cache {
 };
 
 static const int kMaxSeqs = 4096;
+static const int kRopeTableLen = 32768;   // positions with precomputed rotary factors
 
 #define HIP_TRY(expr, status)                                                        \
     do {                                                                             \
@@ -103,7 +105,7 @@ static void free_layer(pd_layer *L)
 {
     if (!L) return;
     void *ptrs[] = {L->g_attn, L->g_ffn, L->w_qkv, L->w_o, L->w_gate, L->w_up, L->w_down,
-                    L->w_router, L->inv_freq, L->d_cu, L->d_slots, L->d_pad_cu, L->vt, L->ws};
+                    L->w_router, L->inv_freq, L->rope_table, L->d_cu, L->d_slots, L->d_pad_cu, L->vt, L->ws};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     for (hipEvent_t e : L->prof_ev) (void)hipEventDestroy(e);
@@ -204,6 +206,8 @@ extern "C" pd_status pd_layer_create(const pd_layer_config *cfg, const pd_layer_
             f[i] = pow((double)cfg->rope_base, -2.0 * (double)i / (double)hd);
         CREATE_TRY(hipMemcpy(L->inv_freq, f.data(), sizeof(double) * f.size(), hipMemcpyHostToDevice));
     }
+    CREATE_TRY(hipMalloc((void **)&L->rope_table, sizeof(float2) * (size_t)kRopeTableLen * (hd / 2)));
+    CREATE_TRY(launch_rope_table(L->rope_table, kRopeTableLen, hd / 2, L->inv_freq, nullptr));
     CREATE_TRY(hipDeviceSynchronize());
 #undef CREATE_TRY
     (void)st;
@@ -421,11 +425,12 @@ static pd_status run_tail(pd_layer *L, const void *x, int T, const void *router_
     g.A = L->o; g.lda = L->Nq; g.B = L->w_o; g.ldb = L->Nq; g.C = L->h; g.ldc = d; g.R = x; g.ldr = d;
     g.M = T; g.N = d; g.K = L->Nq; g.epilogue = EPI_RESIDUAL; g.n_groups = 1;
     STEP("o_proj_residual", run_gemm(L, g, s));
-    STEP("rmsnorm_ffn", launch_rmsnorm(c.dtype, L->h, L->g_ffn, L->y, T, d, c.rms_eps, s));
     if (E == 0) {
         memset(&g, 0, sizeof(g));
-        g.A = L->y; g.lda = d; g.B = L->w_gate; g.B1 = L->w_up; g.ldb = d; g.C = L->act; g.ldc = F;
+        g.A = L->h; g.lda = d; g.B = L->w_gate; g.B1 = L->w_up; g.ldb = d; g.C = L->act; g.ldc = F;
         g.M = T; g.N = F; g.K = d; g.epilogue = EPI_SWIGLU; g.interleaved = L->interleaved; g.n_groups = 1;
+        STEP("rmsnorm_ffn", launch_rmsnorm(c.dtype, L->h, L->g_ffn, L->y, T, d, c.rms_eps, s));
+        g.A = L->y;
         STEP("gate_up_swiglu", run_gemm(L, g, s));
         memset(&g, 0, sizeof(g));
         g.A = L->act; g.lda = F; g.B = L->w_down; g.ldb = F; g.C = out; g.ldc = d; g.R = L->h; g.ldr = d;
@@ -433,6 +438,7 @@ static pd_status run_tail(pd_layer *L, const void *x, int T, const void *router_
         STEP("down_residual", run_gemm(L, g, s));
         return PD_OK;
     }
+    STEP("rmsnorm_ffn", launch_rmsnorm(c.dtype, L->h, L->g_ffn, L->y, T, d, c.rms_eps, s));
     const float *logits = (const float *)router_logits;
     if (!logits) {
         STEP("router_logits", launch_router_logits(c.dtype, L->y, L->w_router, L->logits, T, d, E, s));
@@ -541,6 +547,7 @@ extern "C" pd_status pd_prefill(pd_layer *L, const pd_tokens *tk, pd_kv_cache *c
     r.tok_pos = L->tok_pos; r.tok_slot = keep ? L->tok_slot : nullptr;
     r.k_cache = keep ? cache->k : nullptr; r.v_cache = keep ? cache->v : nullptr;
     r.max_len = keep ? cache->plane_len : 0; r.blocked = keep ? cache->blocked : 0; r.inv_freq = L->inv_freq;
+    r.table = L->rope_table; r.table_len = kRopeTableLen;
     STEP("rope_kv_write", launch_rope_kv(c.dtype, r, s));
     AttnArgs a;
     memset(&a, 0, sizeof(a));
@@ -646,16 +653,18 @@ extern "C" pd_status pd_decode_step(pd_layer *L, const pd_batch *bt, pd_kv_cache
                 PD_ERR_DEVICE);
     else
         HIP_TRY(launch_decode_meta(L->d_slots, B, cache->d_len, L->tok_pos, s), PD_ERR_DEVICE);
-    STEP("rmsnorm_attn", launch_rmsnorm(c.dtype, bt->hidden, L->g_attn, L->y, B, c.d_model, c.rms_eps, s));
     GemmArgs g;
     memset(&g, 0, sizeof(g));
-    g.A = L->y; g.lda = c.d_model; g.B = L->w_qkv; g.ldb = c.d_model; g.C = L->qkv; g.ldc = L->Nqkv;
+    g.A = bt->hidden; g.lda = c.d_model; g.B = L->w_qkv; g.ldb = c.d_model; g.C = L->qkv; g.ldc = L->Nqkv;
     g.M = B; g.N = L->Nqkv; g.K = c.d_model; g.epilogue = EPI_NONE; g.n_groups = 1;
+    STEP("rmsnorm_attn", launch_rmsnorm(c.dtype, bt->hidden, L->g_attn, L->y, B, c.d_model, c.rms_eps, s));
+    g.A = L->y;
     STEP("qkv_proj", run_gemm(L, g, s));
     RopeArgs r;
     r.qkv = L->qkv; r.ld = L->Nqkv; r.T = B; r.Hq = c.n_q_heads; r.Hkv = c.n_kv_heads; r.hd = c.head_dim;
     r.tok_pos = L->tok_pos; r.tok_slot = L->d_slots; r.k_cache = cache->k; r.v_cache = cache->v;
     r.max_len = cache->plane_len; r.blocked = cache->blocked; r.inv_freq = L->inv_freq;
+    r.table = L->rope_table; r.table_len = kRopeTableLen;
     STEP("rope_kv_append", launch_rope_kv(c.dtype, r, s));
     if (mfma_dec) {
         DecodeAttnArgs da;

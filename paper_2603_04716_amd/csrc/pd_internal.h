@@ -122,7 +122,10 @@ struct RopeArgs {
     int32_t max_len;         // plane length in positions (padded length for the blocked layout)
     int32_t blocked;
     const double *inv_freq;  // [hd/2] rope_base^(-2i/hd)
+    const float2 *table;     // optional [table_len][hd/2] (cos, sin) of pos * inv_freq, made in double
+    int32_t table_len;
 };
+hipError_t launch_rope_table(float2 *table, int table_len, int half, const double *inv_freq, hipStream_t s);
 hipError_t launch_rope_kv(int dtype, const RopeArgs &a, hipStream_t s);
 
 struct AttnArgs {

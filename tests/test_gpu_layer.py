@@ -185,6 +185,28 @@ def test_bf16_decode_batch_sizes_ragged_cache(B):
     gl.close()
 
 
+def test_fp32_decode_beyond_rotary_table():
+    """Positions past the precomputed rotary table (32768) take the on-the-fly double-precision
+    path; fp32 bound 1e-5 must still hold there."""
+    cfg = I.small_config(d_model=32, n_q_heads=2, n_kv_heads=1, head_dim=8, d_ff=32)
+    ol, gl = both(cfg, std=0.1)
+    n = 32767
+    cap = n + 4
+    k, v = I.kv_fill(1, n, 8, seed=9, dtype="f32")
+    oc, gc = O.KVCache(ol, 1, cap), gl.cache(1, cap)
+    oc.set(0, k, v)
+    pd.pd_kv_cache_set(gc, 0, to_dev(k, "f32"), to_dev(v, "f32"))
+    for step in range(3):                       # positions 32767 (table), 32768, 32769 (computed)
+        xn = I.hidden(1, cfg["d_model"], seed=60 + step)
+        assert relmax(gl.decode(xn, [0], gc), O.decode_step(ol, xn, [0], oc)) <= TOL["f32"]
+    kk = torch.empty((1, n + 3, 8), dtype=torch.float32, device="cuda")
+    vv = torch.empty_like(kk)
+    pd.pd_kv_cache_get(gc, 0, kk, vv)
+    torch.cuda.synchronize()
+    assert relmax(to_np(kk)[:, n:], oc.k[0, :, n:n + 3]) <= TOL["f32"]
+    gl.close()
+
+
 def test_kv_cache_set_get_and_errors():
     cfg = I.small_config()
     ol, gl = both(cfg)
