@@ -13,8 +13,10 @@
 //                                           from the S^T accumulators in place
 //
 // Workers write un-normalised partial outputs with their running max and sum; a small merge
-// kernel combines the chunks of each (sequence, head).  Chunks have a fixed key count, so ragged
-// batches balance by construction.
+// kernel combines the chunks of each (sequence, head).  A sequence of n keys is cut into
+// ceil(n / chunk_keys) chunks of equal size (rounded up to 64 keys), and chunk_keys is chosen so
+// that one launch has about 2048 workers: one per wave slot of the chip, which measured fastest
+// (more, smaller chunks lose to the per-worker start-up; fewer leave wave slots empty).
 #include "pd_internal.h"
 
 namespace pd {
@@ -86,8 +88,10 @@ __global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a, i
     }
     const int b = lo;
     const int n_keys = a.pos[b] + 1;
-    const int key0 = (cid - a.chunk_cu[b]) * a.chunk_keys;
-    const int key1 = min(n_keys, key0 + a.chunk_keys);
+    const int n_chunks = a.chunk_cu[b + 1] - a.chunk_cu[b];
+    const int csz = ((n_keys + n_chunks - 1) / n_chunks + 63) & ~63;   // equal chunks, 64-key granules
+    const int key0 = (cid - a.chunk_cu[b]) * csz;                       // < n_keys since csz <= chunk_keys
+    const int key1 = min(n_keys, key0 + csz);
     const int group = a.Hq / a.Hkv;
     const int qi = lane & 15, kg = lane >> 4;
 

@@ -632,13 +632,13 @@ extern "C" pd_status pd_decode_step(pd_layer *L, const pd_batch *bt, pd_kv_cache
     hipStream_t s = (hipStream_t)stream;
     L->prof_names.clear();
 
-    // decode attention work split: fixed-size key chunks, about 8192 wavefront-sized workers
+    // decode attention work split: about 2048 wavefront-sized workers (one per wave slot)
     const bool mfma_dec = cache->blocked != 0;
     int chunk_keys = 64, total_chunks = 0;
     if (mfma_dec) {
         long long total_keys = 0;
         for (int b = 0; b < B; ++b) total_keys += cache->h_len[(size_t)bt->slots[b]] + 1;
-        long long ck = (total_keys * c.n_kv_heads / 8192 + 63) / 64 * 64;
+        long long ck = ((total_keys * c.n_kv_heads + 2047) / 2048 + 63) / 64 * 64;
         chunk_keys = (int)(ck < 64 ? 64 : ck);
         for (int b = 0; b < B; ++b)
             total_chunks += (cache->h_len[(size_t)bt->slots[b]] + 1 + chunk_keys - 1) / chunk_keys;
