@@ -6,8 +6,8 @@
 // write instructions) and LDS -> registers with 16-byte reads, with no transposition anywhere.
 // A direct load puts lane i's 16 bytes at LDS offset base + 16*i, so the XOR swizzle that keeps
 // the fragment reads free of bank conflicts is applied on the global side: the lane that owns LDS
-// slot (row, s) fetches chunk s ^ ((row >> 1) & 7) of that row.  LDS is double buffered: the loads
-// of tile k+1 are in flight while the matrix cores work on tile k; one barrier per tile.
+// slot (row, s) fetches chunk s ^ ((row >> 1) & 7) of that row.  LDS holds NS stages: the loads of
+// the next NS-1 k-tiles are in flight while the matrix cores work on tile k; one barrier per tile.
 //
 // Epilogues: plain store, residual add, and SwiGLU.  For SwiGLU the weight is packed at layer
 // creation as alternating 32-row blocks (gate rows j..j+31, then up rows j..j+31); an MFMA output
@@ -33,7 +33,7 @@ __device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >>
 
 __device__ __forceinline__ float silu_fast(float z) { return z / (1.0f + __expf(-z)); }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int NS>
 __global__ __launch_bounds__(64 * WAVES_M *WAVES_N) void gemm_mfma_kernel(GemmArgs a, int tiles_m,
                                                                           int tiles_n, int kt_per_split)
 {
@@ -146,8 +146,25 @@ __global__ __launch_bounds__(64 * WAVES_M *WAVES_N) void gemm_mfma_kernel(GemmAr
 
     const int kt0 = blockIdx.y * kt_per_split;
     const int kt1 = min(a.K / BK, kt0 + kt_per_split);
-    issue_loads(kt0, smem);
-    __syncthreads();
+    // Software pipeline over NS LDS stages: the loads of k-tile kt + NS - 1 are issued while tile
+    // kt is multiplied, so up to NS - 1 tiles are in flight per workgroup.  Direct-to-LDS loads
+    // retire in order through this wave's vector-memory counter, so "tile kt has landed" is
+    // "at most (tiles issued after kt) * loads-per-tile still outstanding", followed by a barrier
+    // that makes every wave's part visible.  The same barrier orders the refill of the stage that
+    // was multiplied in the previous iteration.
+    constexpr int LPS = A_LD + B_LD;                  // load instructions per tile per wave
+    static_assert(LPS * (NS - 1) <= 63, "vector-memory counter range");
+    auto wait_tiles_after = [&](int tiles_after) {
+        // s_waitcnt vmcnt(n): n in bits [3:0] and [15:14]; expcnt / lgkmcnt fields left at "no wait"
+#define PD_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (7 << 4) | (15 << 8) | (((n) >> 4) << 14))
+        if (NS >= 4 && tiles_after >= 2) PD_VMCNT(2 * LPS);
+        else if (NS >= 3 && tiles_after >= 1) PD_VMCNT(1 * LPS);
+        else PD_VMCNT(0);
+#undef PD_VMCNT
+    };
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s)
+        if (kt0 + s < kt1) issue_loads(kt0 + s, smem + s * STAGE);
 
     // fragment addresses inside a stage: row and the two chunk parities of this lane
     const int frow = lane & 31, fhalf = lane >> 5;
@@ -182,13 +199,17 @@ __global__ __launch_bounds__(64 * WAVES_M *WAVES_N) void gemm_mfma_kernel(GemmAr
             mma(fa, fb);
         }
     };
-    for (int kt = kt0; kt + 1 < kt1; ++kt) {
-        issue_loads(kt + 1, smem + ((kt + 1 - kt0) & 1) * STAGE);
+    for (int kt = kt0; kt < kt1; ++kt) {
+        const int issued_after = min(NS - 2, kt1 - 1 - kt);   // tiles already issued beyond kt
+        __builtin_amdgcn_sched_barrier(0);
+        wait_tiles_after(issued_after);
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+        if (kt + NS - 1 < kt1) issue_loads(kt + NS - 1, smem + ((kt + NS - 1 - kt0) % NS) * STAGE);
         __builtin_amdgcn_sched_barrier(0);     // keep the loads ahead of the compute phase
-        compute(smem + ((kt - kt0) & 1) * STAGE);
-        __syncthreads();                       // waits for the loads, then for all waves
+        compute(smem + ((kt - kt0) % NS) * STAGE);
     }
-    compute(smem + ((kt1 - 1 - kt0) & 1) * STAGE);
 
     // ---- epilogue: lane holds column (lane % 32) of each block; register r is row
     //      8*(r/4) + 4*(lane/32) + r%4 ----------------------------------------------------------------
@@ -294,13 +315,13 @@ bool gemm_mfma_supported(const GemmArgs &a)
     return true;
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NS = 2>
 static hipError_t launch_cfg(const GemmArgs &a, hipStream_t s, int splits = 1)
 {
     const int n_cols = a.epilogue == EPI_SWIGLU ? 2 * a.N : a.N;
     const int tiles_n = (n_cols + BN - 1) / BN;
     const int tiles_m = (a.M + BM - 1) / BM + (a.group_offsets ? a.n_groups : 0);
-    const size_t smem = 2 * (size_t)(BM + BN) * BK * 2;
+    const size_t smem = NS * (size_t)(BM + BN) * BK * 2;
     const int nk = a.K / BK;
     const int kt_per = (nk + splits - 1) / splits;
     splits = (nk + kt_per - 1) / kt_per;               // no empty split
@@ -308,7 +329,7 @@ static hipError_t launch_cfg(const GemmArgs &a, hipStream_t s, int splits = 1)
     const dim3 block(64 * WAVES_M * WAVES_N);
 #define LAUNCH(EPI)                                                                              \
     do {                                                                                         \
-        auto kern = gemm_mfma_kernel<BM, BN, WAVES_M, WAVES_N, EPI>;                             \
+        auto kern = gemm_mfma_kernel<BM, BN, WAVES_M, WAVES_N, EPI, NS>;                             \
         static bool attr_set = false;                                                            \
         if (!attr_set) {                                                                         \
             hipError_t e = hipFuncSetAttribute((const void *)kern,                               \
@@ -335,8 +356,10 @@ static hipError_t launch_cfg(const GemmArgs &a, hipStream_t s, int splits = 1)
     return hipGetLastError();
 }
 
-// Split count for decode-sized problems: enough workgroups to keep every CU streaming weights,
-// at least 4 k-tiles per split, and the partials must fit the scratch buffer.
+// Split count for decode-sized problems: about one workgroup per CU (measured: more splits lose
+// to the fp32 partial traffic, fewer leave CUs without a weight stream), at least 4 k-tiles per
+// split, partials (written and read back) below about half of the weight bytes, and they must
+// fit the scratch buffer.
 static int choose_splits(const GemmArgs &a, int BM, int BN)
 {
     if (!a.splitk_ws || a.group_offsets || a.a_gather || a.N % 4 != 0 || a.ldc % 4 != 0 ||
@@ -345,9 +368,8 @@ static int choose_splits(const GemmArgs &a, int BM, int BN)
     const int n_cols = a.epilogue == EPI_SWIGLU ? 2 * a.N : a.N;
     const int tiles = ((a.M + BM - 1) / BM) * ((n_cols + BN - 1) / BN);
     const int nk = a.K / BK;
-    int splits = (640 + tiles - 1) / tiles;
+    int splits = (256 + tiles / 2) / tiles;
     if (splits > nk / 4) splits = nk / 4;
-    // the fp32 partials (written and read back) should stay below about half of the weight bytes
     const int cap = a.K / (8 * a.M) > 1 ? a.K / (8 * a.M) : 1;
     if (splits > cap) splits = cap;
     while (splits > 1 && (size_t)splits * a.M * n_cols > a.splitk_ws_elems) --splits;
@@ -356,10 +378,15 @@ static int choose_splits(const GemmArgs &a, int BM, int BN)
 
 hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t s)
 {
-    if (a.M > 256) return launch_cfg<256, 256, 2, 4>(a, s);   // 8 waves: two per SIMD hide each other's stalls
-    if (a.M > 128) return launch_cfg<256, 64, 8, 1>(a, s, choose_splits(a, 256, 64));
-    if (a.M > 64) return launch_cfg<128, 128, 2, 2>(a, s, choose_splits(a, 128, 128));
-    return launch_cfg<64, 128, 2, 2>(a, s, choose_splits(a, 64, 128));
+    if (a.M > 256) return launch_cfg<256, 256, 2, 4, 2>(a, s);   // 8 waves: two per SIMD hide each other's stalls
+    const int n_cols = a.epilogue == EPI_SWIGLU ? 2 * a.N : a.N;
+    const bool wide = n_cols >= 16384;                            // enough column tiles without splitting K
+    if (a.M > 128) {
+        if (wide) return launch_cfg<256, 128, 4, 2, 3>(a, s, 1);
+        return launch_cfg<256, 64, 8, 1, 3>(a, s, choose_splits(a, 256, 64));
+    }
+    if (a.M > 64) return launch_cfg<128, 64, 4, 1, 4>(a, s, wide ? 1 : choose_splits(a, 128, 64));
+    return launch_cfg<64, 128, 2, 2, 4>(a, s, wide ? 1 : choose_splits(a, 64, 128));
 }
 
 }  // namespace pd
