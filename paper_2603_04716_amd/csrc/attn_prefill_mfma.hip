@@ -171,23 +171,21 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a,
                     sacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[b], 0, 0, 0);
                 }
             }
-            // ---- online softmax (log2 domain) --------------------------------------------------------
+            // ---- online softmax (log2 domain): p = 2^(s * scale*log2e - m) ---------------------------
             const bool diag = k0 + BKV - 1 > wq_lo;
             float mx = -INFINITY;
 #pragma unroll
             for (int b = 0; b < 2; ++b)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    float sv = sacc[b][r] * sl2e;
                     if (diag) {
                         const int key = k0 + 32 * b + 8 * (r >> 2) + 4 * h + (r & 3);
-                        if (key > my_q) sv = -INFINITY;
+                        if (key > my_q) sacc[b][r] = -INFINITY;
                     }
-                    sacc[b][r] = sv;
-                    mx = fmaxf(mx, sv);
+                    mx = fmaxf(mx, sacc[b][r]);
                 }
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m_run, mx);   // finite: key 0 is visible to every query
+            const float m_new = fmaxf(m_run, mx * sl2e);   // finite: key 0 is visible to every query
             const float alpha = fast_exp2(m_run - m_new);
             m_run = m_new;
             float psum = 0.f;
@@ -195,7 +193,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a,
             for (int b = 0; b < 2; ++b)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    float p = fast_exp2(sacc[b][r] - m_new);
+                    float p = fast_exp2(fmaf(sacc[b][r], sl2e, -m_new));
                     sacc[b][r] = p;
                     psum += p;
                 }

@@ -128,6 +128,9 @@ __global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a, i
         for (int vb = 0; vb < 2; ++vb)
 #pragma unroll
             for (int db = 0; db < 8; ++db) vf[vb][db] = *(const bf16x8 *)(vb_ptr + vb * 4096 + db * 512);
+        // all 32 loads (32 KB per wave) are issued before anything consumes them: bytes in flight,
+        // not instruction count, is what this kernel lives on
+        __builtin_amdgcn_sched_barrier(0);
 
         // scores: lane (qi, kg), block kb, register j  <->  key k + 16*kb + 4*kg + j
         f32x4 sacc[4];
@@ -144,14 +147,12 @@ __global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a, i
         for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                float sv = sacc[kb][j] * sl2e;
-                if (tail && k + 16 * kb + 4 * kg + j >= key1) sv = -INFINITY;
-                sacc[kb][j] = sv;
-                mx = fmaxf(mx, sv);
+                if (tail && k + 16 * kb + 4 * kg + j >= key1) sacc[kb][j] = -INFINITY;
+                mx = fmaxf(mx, sacc[kb][j]);
             }
         mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run, mx);      // finite: key k < key1 is always unmasked
+        const float m_new = fmaxf(m_run, mx * sl2e);   // finite: key k < key1 is always unmasked
         const float alpha = dexp2(m_run - m_new);
         m_run = m_new;
         float psum = 0.f;
@@ -159,7 +160,7 @@ __global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a, i
         for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                float p = dexp2(sacc[kb][j] - m_new);
+                float p = dexp2(fmaf(sacc[kb][j], sl2e, -m_new));
                 sacc[kb][j] = p;
                 psum += p;
             }

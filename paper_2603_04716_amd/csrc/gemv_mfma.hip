@@ -61,6 +61,7 @@ __global__ __launch_bounds__(64 * GV_WAVES) void gemv_mfma_kernel(GemmArgs a)
             if (xrow) z = *(const u32x4 *)(xp + (size_t)(s + u) * 32);
             xf[u] = __builtin_bit_cast(bf16x8, z);
         }
+        __builtin_amdgcn_sched_barrier(0);   // every load of the batch is in flight before the first MFMA
 #pragma unroll
         for (int u = 0; u < GV_UNROLL; ++u)
 #pragma unroll

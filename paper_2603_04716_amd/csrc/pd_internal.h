@@ -14,21 +14,19 @@ struct bf16_t {
 
 __device__ __forceinline__ float bf2f(bf16_t v) { return __uint_as_float(((uint32_t)v.x) << 16); }
 __device__ __forceinline__ float bfbits2f(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
-__device__ __forceinline__ bf16_t f2bf(float f)
-{
-    uint32_t u = __float_as_uint(f);
-    bf16_t r;
-    if ((u & 0x7fffffffu) > 0x7f800000u) {  // NaN stays NaN
-        r.x = (uint16_t)((u >> 16) | 0x40u);
-        return r;
-    }
-    u += 0x7fffu + ((u >> 16) & 1u);
-    r.x = (uint16_t)(u >> 16);
-    return r;
-}
+// fp32 -> bf16, round to nearest even: the hardware conversion of gfx950 (v_cvt_pk_bf16_f32)
+typedef __bf16 pd_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float pd_f32x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pack2bf(float lo, float hi)
 {
-    return (uint32_t)f2bf(lo).x | ((uint32_t)f2bf(hi).x << 16);
+    pd_f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, pd_bf16x2));
+}
+__device__ __forceinline__ bf16_t f2bf(float f)
+{
+    bf16_t r;
+    r.x = (uint16_t)(pack2bf(f, 0.f) & 0xffffu);
+    return r;
 }
 
 template <typename T>
