@@ -165,6 +165,7 @@ __global__ __launch_bounds__(64 * WAVES_M *WAVES_N) void gemm_mfma_kernel(GemmAr
 #pragma unroll
     for (int s = 0; s < NS - 1; ++s)
         if (kt0 + s < kt1) issue_loads(kt0 + s, smem + s * STAGE);
+    if (NS == 2) __syncthreads();
 
     // fragment addresses inside a stage: row and the two chunk parities of this lane
     const int frow = lane & 31, fhalf = lane >> 5;
@@ -199,16 +200,27 @@ __global__ __launch_bounds__(64 * WAVES_M *WAVES_N) void gemm_mfma_kernel(GemmAr
             mma(fa, fb);
         }
     };
-    for (int kt = kt0; kt < kt1; ++kt) {
-        const int issued_after = min(NS - 2, kt1 - 1 - kt);   // tiles already issued beyond kt
-        __builtin_amdgcn_sched_barrier(0);
-        wait_tiles_after(issued_after);
-        __builtin_amdgcn_s_barrier();
-        asm volatile("" ::: "memory");
-        __builtin_amdgcn_sched_barrier(0);
-        if (kt + NS - 1 < kt1) issue_loads(kt + NS - 1, smem + ((kt + NS - 1 - kt0) % NS) * STAGE);
-        __builtin_amdgcn_sched_barrier(0);     // keep the loads ahead of the compute phase
-        compute(smem + ((kt - kt0) % NS) * STAGE);
+    if (NS == 2) {
+        // double buffer: the barrier that ends an iteration also waits for the loads issued at its
+        // start; the compiler may sink trailing MFMAs below it, which hides the barrier wait
+        for (int kt = kt0; kt + 1 < kt1; ++kt) {
+            issue_loads(kt + 1, smem + ((kt + 1 - kt0) & 1) * STAGE);
+            __builtin_amdgcn_sched_barrier(0);     // keep the loads ahead of the compute phase
+            compute(smem + ((kt - kt0) & 1) * STAGE);
+            __syncthreads();
+        }
+        compute(smem + ((kt1 - 1 - kt0) & 1) * STAGE);
+    } else {
+        for (int kt = kt0; kt < kt1; ++kt) {
+            const int issued_after = min(NS - 2, kt1 - 1 - kt);   // tiles already issued beyond kt
+            wait_tiles_after(issued_after);
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_sched_barrier(0);
+            if (kt + NS - 1 < kt1) issue_loads(kt + NS - 1, smem + ((kt + NS - 1 - kt0) % NS) * STAGE);
+            __builtin_amdgcn_sched_barrier(0);     // keep the loads ahead of the compute phase
+            compute(smem + ((kt - kt0) % NS) * STAGE);
+        }
     }
 
     // ---- epilogue: lane holds column (lane % 32) of each block; register r is row
