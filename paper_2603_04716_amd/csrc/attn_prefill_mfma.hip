@@ -172,18 +172,20 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a,
                 }
             }
             // ---- online softmax (log2 domain): p = 2^(s * scale*log2e - m) ---------------------------
-            const bool diag = k0 + BKV - 1 > wq_lo;
+            if (k0 + BKV - 1 > wq_lo) {            // wave-uniform: only tiles on the diagonal are masked
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int key = k0 + 32 * b + 8 * (r >> 2) + 4 * h + (r & 3);
+                        if (key > my_q) sacc[b][r] = -INFINITY;
+                    }
+            }
             float mx = -INFINITY;
 #pragma unroll
             for (int b = 0; b < 2; ++b)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    if (diag) {
-                        const int key = k0 + 32 * b + 8 * (r >> 2) + 4 * h + (r & 3);
-                        if (key > my_q) sacc[b][r] = -INFINITY;
-                    }
-                    mx = fmaxf(mx, sacc[b][r]);
-                }
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[b][r]);
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
             const float m_new = fmaxf(m_run, mx * sl2e);   // finite: key 0 is visible to every query
             const float alpha = fast_exp2(m_run - m_new);
