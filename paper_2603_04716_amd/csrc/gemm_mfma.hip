@@ -9,6 +9,10 @@
 // slot (row, s) fetches chunk s ^ ((row >> 1) & 7) of that row.  LDS holds NS stages: the loads of
 // the next NS-1 k-tiles are in flight while the matrix cores work on tile k; one barrier per tile.
 //
+// The weight operand B arrives in the packed block layout of pd_internal.h (1 KB blocks of 16 rows
+// x 32 k): one direct-to-LDS instruction moves one block, blocks sit linearly in LDS, and the
+// fragment reads of 16 consecutive lanes are 256 contiguous bytes, so B needs no swizzle.
+//
 // Epilogues: plain store, residual add, and SwiGLU.  For SwiGLU the weight is packed at layer
 // creation as alternating 32-row blocks (gate rows j..j+31, then up rows j..j+31); an MFMA output
 // block pair then holds gate and up of the same (row, column) in the same lane and register, and
@@ -113,19 +117,21 @@ __global__ __launch_bounds__(64 * WAVES_M *WAVES_N) void gemm_mfma_kernel(GemmAr
         if (a.a_gather) gr = a.a_gather[gr];
         a_off[i] = (uint32_t)gr * (uint32_t)(a.lda * 2) + c * 16;
     }
+    // B: instruction j = i*NW + wave moves packed block (row block j/2, k block j%2 of the tile)
+    const int kblocks = a.K >> 5;                      // 32-k blocks per row block
+    const int last_rb = (n_cols - 1) >> 4;
 #pragma unroll
     for (int i = 0; i < B_LD; ++i) {
-        int r = (i * NW + wave) * 8 + (lane >> 3);
-        int c = swz(r, lane & 7);
-        int gc = col0 + r;
-        if (gc >= n_cols) gc = n_cols - 1;
-        b_off[i] = (uint32_t)gc * (uint32_t)(a.ldb * 2) + c * 16;
+        const int j = i * NW + wave;
+        int rb = (col0 >> 4) + (j >> 1);
+        if (rb > last_rb) rb = last_rb;               // clamp: loaded but never stored
+        b_off[i] = ((uint32_t)rb * (uint32_t)kblocks + (j & 1)) * 1024u + lane * 16;
     }
     typedef const void __attribute__((address_space(1))) *gptr_t;
     typedef void __attribute__((address_space(3))) *lptr_t;
     auto issue_loads = [&](int kt, unsigned char *st) {
         const char *ab = (const char *)A + (size_t)kt * (BK * 2);
-        const char *bb = (const char *)B + (size_t)kt * (BK * 2);
+        const char *bb = (const char *)B + (size_t)kt * 2048;   // two 1 KB k-blocks per tile
 #pragma unroll
         for (int i = 0; i < A_LD; ++i)
             __builtin_amdgcn_global_load_lds((gptr_t)(ab + a_off[i]),
@@ -181,8 +187,9 @@ __global__ __launch_bounds__(64 * WAVES_M *WAVES_N) void gemm_mfma_kernel(GemmAr
         }
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
-            int r = wn * WN + j * 32 + frow;
-            fb[j] = *(const bf16x8 *)(st + A_BYTES + r * 128 + swz(r, c) * 16);
+            // column wn*WN + 32j + frow, k chunk c of the tile, in the linear packed blocks
+            const int rbl = ((wn * WN + j * 32) >> 4) + (frow >> 4);
+            fb[j] = *(const bf16x8 *)(st + A_BYTES + (rbl * 2 + (c >> 2)) * 1024 + (c & 3) * 256 + (frow & 15) * 16);
         }
     };
     auto mma = [&](bf16x8 (&fa)[MB], bf16x8 (&fb)[NB]) {
@@ -323,7 +330,8 @@ bool gemm_mfma_supported(const GemmArgs &a)
     if ((int64_t)a.ldb * 2 * brows >= (1ll << 32)) return false;
     if (!a.a_gather && (int64_t)a.lda * 2 * a.M >= (1ll << 32)) return false;
     if (a.a_gather && (int64_t)a.lda * 2 * a.M >= (1ll << 31)) return false;
-    if (a.epilogue == EPI_SWIGLU) return a.interleaved && a.N % 32 == 0;
+    if (!a.packed || a.ldb != a.K || a.K % 32 != 0 || brows % 16 != 0) return false;
+    if (a.epilogue == EPI_SWIGLU) return a.N % 32 == 0;
     return true;
 }
 

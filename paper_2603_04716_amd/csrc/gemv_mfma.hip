@@ -1,8 +1,9 @@
 // Skinny bf16 GEMM for decode batches of up to 16 rows:  C[M<=16, N] = epilogue(A[M,K] * B[N,K]^T).
 //
 // The step is bound by streaming the weight matrix B from HBM exactly once, so the weights are
-// the MFMA A operand and go straight from global memory into operand registers (16 weight rows x
-// 64 bytes per load instruction, eight k-steps in flight per wave); the (tiny, L2-resident)
+// the MFMA A operand and go straight from global memory into operand registers: in the packed
+// weight layout one 16-row x 32-k block is the register image of the operand, so every load
+// instruction reads 1 KB of contiguous memory (eight blocks in flight per wave); the (tiny, L2-resident)
 // activations are the B operand with the batch as the N dimension of v_mfma_f32_16x16x32_bf16,
 // padded with zero columns.  A workgroup owns 16 weight rows (one output column block); its four
 // waves split K and combine through LDS in a fixed order, so results are deterministic.
@@ -40,9 +41,9 @@ __global__ __launch_bounds__(64 * GV_WAVES) void gemv_mfma_kernel(GemmArgs a)
     const int s_begin = wave * per, s_end = min(ksteps, s_begin + per);
 
     const uint16_t *W = (const uint16_t *)a.B;
-    const uint16_t *wp[RB];
+    const uint16_t *wp[RB];   // block (row0/16, 0) of the packed layout, this lane's 16 bytes
 #pragma unroll
-    for (int i = 0; i < RB; ++i) wp[i] = W + (size_t)(row0[i] + r) * a.ldb + kg * 8;
+    for (int i = 0; i < RB; ++i) wp[i] = W + (size_t)(row0[i] >> 4) * (a.K >> 5) * 512 + lane * 8;
     const bool xrow = r < a.M;
     const uint16_t *xp = (const uint16_t *)a.A + (size_t)(xrow ? r : 0) * a.lda + kg * 8;
 
@@ -56,7 +57,7 @@ __global__ __launch_bounds__(64 * GV_WAVES) void gemv_mfma_kernel(GemmArgs a)
 #pragma unroll
         for (int u = 0; u < GV_UNROLL; ++u) {
 #pragma unroll
-            for (int i = 0; i < RB; ++i) wf[i][u] = *(const bf16x8 *)(wp[i] + (size_t)(s + u) * 32);
+            for (int i = 0; i < RB; ++i) wf[i][u] = *(const bf16x8 *)(wp[i] + (size_t)(s + u) * 512);
             u32x4 z = {0u, 0u, 0u, 0u};
             if (xrow) z = *(const u32x4 *)(xp + (size_t)(s + u) * 32);
             xf[u] = __builtin_bit_cast(bf16x8, z);
@@ -74,7 +75,7 @@ __global__ __launch_bounds__(64 * GV_WAVES) void gemv_mfma_kernel(GemmArgs a)
         bf16x8 xf = __builtin_bit_cast(bf16x8, z);
 #pragma unroll
         for (int i = 0; i < RB; ++i) {
-            bf16x8 wf = *(const bf16x8 *)(wp[i] + (size_t)s * 32);
+            bf16x8 wf = *(const bf16x8 *)(wp[i] + (size_t)s * 512);
             acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xf, acc[i], 0, 0, 0);
         }
     }
@@ -121,7 +122,8 @@ bool gemv_mfma_supported(const GemmArgs &a)
     if (a.M < 1 || a.M > 16 || a.a_gather || a.group_offsets) return false;
     if (a.K % 32 != 0 || a.N % 16 != 0 || a.lda % 8 != 0 || a.ldb % 8 != 0) return false;
     if (a.ldc % 4 != 0 || (a.epilogue == EPI_RESIDUAL && a.ldr % 4 != 0)) return false;
-    if (a.epilogue == EPI_SWIGLU && (!a.interleaved || a.N % 32 != 0)) return false;
+    if (!a.packed || a.ldb != a.K) return false;
+    if (a.epilogue == EPI_SWIGLU && a.N % 32 != 0) return false;
     return true;
 }
 

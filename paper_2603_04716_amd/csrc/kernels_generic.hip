@@ -138,7 +138,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmArgs a)
     const int col0 = blockIdx.x * GT;
     const T *A = (const T *)a.A;
     const T *B = (const T *)a.B + (size_t)group * a.b_group_stride;
-    const T *B1 = EPI == EPI_SWIGLU ? (a.interleaved ? B : (const T *)a.B1 + (size_t)group * a.b_group_stride) : nullptr;
+    const T *B1 = EPI == EPI_SWIGLU ? (const T *)a.B1 + (size_t)group * a.b_group_stride : nullptr;
 
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;
@@ -155,14 +155,8 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmArgs a)
     const bool bcol_ok = bcol < a.N;
     size_t b_off = 0, b1_off = 0;
     if (bcol_ok) {
-        if (EPI == EPI_SWIGLU && a.interleaved) {
-            int pr = (bcol >> 5) * 64 + (bcol & 31);
-            b_off = (size_t)pr * a.ldb;
-            b1_off = (size_t)(pr + 32) * a.ldb;
-        } else {
-            b_off = (size_t)bcol * a.ldb;
-            b1_off = b_off;
-        }
+        b_off = (size_t)bcol * a.ldb;
+        b1_off = b_off;
     }
 
     for (int k0 = 0; k0 < a.K; k0 += GK) {

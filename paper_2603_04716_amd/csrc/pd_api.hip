@@ -16,7 +16,7 @@ struct pd_layer {
     size_t esz;
     int Nq, Nkv, Nqkv;
     bool use_mfma;       // bf16 layer whose shapes fit the MFMA kernels
-    bool interleaved;    // gate/up rows stored as alternating 32-row blocks
+    bool packed;         // weights stored in the matrix-core block layout (gate/up as one interleaved pack)
     void *g_attn, *g_ffn, *w_qkv, *w_o, *w_gate, *w_up, *w_down, *w_router;
     double *inv_freq;
     float2 *rope_table;       // (cos, sin) for positions < kRopeTableLen
@@ -86,18 +86,27 @@ static void prof_end(pd_layer *L, hipStream_t s)
 
 static size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
 
-// dst row (j/32)*64 + j%32 (+32 for `up`) <- src row j; rows are row_bytes long (multiple of 16)
-__global__ void interleave_rows_kernel(uint4 *dst, const uint4 *gate, const uint4 *up, int F,
-                                       int row_vec)
+// Packs a [n_rows, K] bf16 weight matrix into the block layout of wpack_off (one 16-byte chunk per
+// thread).  With `up` != nullptr the packed rows are the 32-row interleave gate[j..j+31],
+// up[j..j+31], ... of two [n_rows/2, K] matrices.
+__global__ void pack_weight_kernel(uint4 *dst, const uint4 *src, const uint4 *up, int n_rows, int K)
 {
-    size_t n = (size_t)F * row_vec;
-    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n;
-         idx += (size_t)gridDim.x * blockDim.x) {
-        int j = (int)(idx / row_vec);
-        int c = (int)(idx % row_vec);
-        size_t pr = (size_t)(j >> 5) * 64 + (j & 31);
-        dst[pr * row_vec + c] = gate[idx];
-        dst[(pr + 32) * row_vec + c] = up[idx];
+    const size_t n_chunks = (size_t)n_rows * (K >> 3);
+    const int row_vec = K >> 3;
+    for (size_t c = (size_t)blockIdx.x * blockDim.x + threadIdx.x; c < n_chunks;
+         c += (size_t)gridDim.x * blockDim.x) {
+        const size_t block = c >> 6;
+        const int kg = (int)(c >> 4) & 3, r = (int)c & 15;
+        const int rb = (int)(block / (K >> 5)), kb = (int)(block % (K >> 5));
+        const int n = rb * 16 + r, k8 = kb * 4 + kg;          // packed row, 8-element k chunk
+        const uint4 *from = src;
+        int row = n;
+        if (up) {
+            const int q = n >> 6, w = n & 63;
+            row = q * 32 + (w & 31);
+            if (w >= 32) from = up;
+        }
+        dst[c] = from[(size_t)row * row_vec + k8];
     }
 }
 
@@ -145,7 +154,7 @@ extern "C" pd_status pd_layer_create(const pd_layer_config *cfg, const pd_layer_
     L->Nqkv = L->Nq + 2 * L->Nkv;
     L->use_mfma = cfg->dtype == PD_BF16 && d % 64 == 0 && F % 64 == 0 && L->Nq % 64 == 0 &&
                   L->Nkv % 64 == 0;
-    L->interleaved = L->use_mfma;
+    L->packed = L->use_mfma;
     const size_t esz = L->esz;
     const int G = E > 0 ? E : 1;
     pd_status st = PD_OK;
@@ -173,24 +182,43 @@ extern "C" pd_status pd_layer_create(const pd_layer_config *cfg, const pd_layer_
     CREATE_TRY(hipMalloc(&L->d_pad_cu, sizeof(int32_t) * (kMaxSeqs + 1)));
     CREATE_TRY(hipMemcpy(L->g_attn, w->g_attn, d * esz, hipMemcpyDeviceToDevice));
     CREATE_TRY(hipMemcpy(L->g_ffn, w->g_ffn, d * esz, hipMemcpyDeviceToDevice));
-    CREATE_TRY(hipMemcpy(L->w_qkv, w->w_q, (size_t)L->Nq * d * esz, hipMemcpyDeviceToDevice));
-    CREATE_TRY(hipMemcpy((char *)L->w_qkv + (size_t)L->Nq * d * esz, w->w_k,
-                         (size_t)L->Nkv * d * esz, hipMemcpyDeviceToDevice));
-    CREATE_TRY(hipMemcpy((char *)L->w_qkv + (size_t)(L->Nq + L->Nkv) * d * esz, w->w_v,
-                         (size_t)L->Nkv * d * esz, hipMemcpyDeviceToDevice));
-    CREATE_TRY(hipMemcpy(L->w_o, w->w_o, (size_t)d * L->Nq * esz, hipMemcpyDeviceToDevice));
-    CREATE_TRY(hipMemcpy(L->w_down, w->w_down, (size_t)G * d * F * esz, hipMemcpyDeviceToDevice));
-    if (L->interleaved) {
+    if (L->packed) {
+        // stack q|k|v plainly in a temporary, then pack every matrix into the block layout
+        void *tmp = nullptr;
+        CREATE_TRY(hipMalloc(&tmp, (size_t)L->Nqkv * d * esz));
+        hipError_t e1 = hipMemcpy(tmp, w->w_q, (size_t)L->Nq * d * esz, hipMemcpyDeviceToDevice);
+        if (e1 == hipSuccess)
+            e1 = hipMemcpy((char *)tmp + (size_t)L->Nq * d * esz, w->w_k, (size_t)L->Nkv * d * esz, hipMemcpyDeviceToDevice);
+        if (e1 == hipSuccess)
+            e1 = hipMemcpy((char *)tmp + (size_t)(L->Nq + L->Nkv) * d * esz, w->w_v, (size_t)L->Nkv * d * esz, hipMemcpyDeviceToDevice);
+        if (e1 == hipSuccess) {
+            pack_weight_kernel<<<2048, 256>>>((uint4 *)L->w_qkv, (const uint4 *)tmp, nullptr, L->Nqkv, d);
+            e1 = hipGetLastError();
+        }
+        if (e1 == hipSuccess) e1 = hipDeviceSynchronize();
+        (void)hipFree(tmp);
+        CREATE_TRY(e1);
+        pack_weight_kernel<<<2048, 256>>>((uint4 *)L->w_o, (const uint4 *)w->w_o, nullptr, d, L->Nq);
+        CREATE_TRY(hipGetLastError());
         CREATE_TRY(hipMalloc(&L->w_gate, (size_t)G * 2 * F * d * esz));
-        const int row_vec = (int)(d * esz / 16);
         for (int g = 0; g < G; ++g) {
-            interleave_rows_kernel<<<1024, 256>>>(
-                (uint4 *)((char *)L->w_gate + (size_t)g * 2 * F * d * esz),
-                (const uint4 *)((const char *)w->w_gate + (size_t)g * F * d * esz),
-                (const uint4 *)((const char *)w->w_up + (size_t)g * F * d * esz), F, row_vec);
+            pack_weight_kernel<<<2048, 256>>>((uint4 *)((char *)L->w_gate + (size_t)g * 2 * F * d * esz),
+                                              (const uint4 *)((const char *)w->w_gate + (size_t)g * F * d * esz),
+                                              (const uint4 *)((const char *)w->w_up + (size_t)g * F * d * esz), 2 * F, d);
+            CREATE_TRY(hipGetLastError());
+            pack_weight_kernel<<<2048, 256>>>((uint4 *)((char *)L->w_down + (size_t)g * d * F * esz),
+                                              (const uint4 *)((const char *)w->w_down + (size_t)g * d * F * esz),
+                                              nullptr, d, F);
             CREATE_TRY(hipGetLastError());
         }
     } else {
+        CREATE_TRY(hipMemcpy(L->w_qkv, w->w_q, (size_t)L->Nq * d * esz, hipMemcpyDeviceToDevice));
+        CREATE_TRY(hipMemcpy((char *)L->w_qkv + (size_t)L->Nq * d * esz, w->w_k,
+                             (size_t)L->Nkv * d * esz, hipMemcpyDeviceToDevice));
+        CREATE_TRY(hipMemcpy((char *)L->w_qkv + (size_t)(L->Nq + L->Nkv) * d * esz, w->w_v,
+                             (size_t)L->Nkv * d * esz, hipMemcpyDeviceToDevice));
+        CREATE_TRY(hipMemcpy(L->w_o, w->w_o, (size_t)d * L->Nq * esz, hipMemcpyDeviceToDevice));
+        CREATE_TRY(hipMemcpy(L->w_down, w->w_down, (size_t)G * d * F * esz, hipMemcpyDeviceToDevice));
         CREATE_TRY(hipMalloc(&L->w_gate, (size_t)G * F * d * esz));
         CREATE_TRY(hipMalloc(&L->w_up, (size_t)G * F * d * esz));
         CREATE_TRY(hipMemcpy(L->w_gate, w->w_gate, (size_t)G * F * d * esz, hipMemcpyDeviceToDevice));
@@ -403,8 +431,13 @@ static hipError_t run_gemm(const pd_layer *L, GemmArgs g, hipStream_t s)
 {
     g.splitk_ws = L->splitk;
     g.splitk_ws_elems = L->splitk_elems;
-    if (L->use_mfma && gemv_mfma_supported(g)) return launch_gemv_mfma(g, s);
-    if (L->use_mfma && gemm_mfma_supported(g)) return launch_gemm_mfma(g, s);
+    g.packed = L->packed ? 1 : 0;
+    if (L->packed) {
+        // packed weights are only understood by the matrix-core kernels
+        if (gemv_mfma_supported(g)) return launch_gemv_mfma(g, s);
+        if (gemm_mfma_supported(g)) return launch_gemm_mfma(g, s);
+        return hipErrorInvalidValue;
+    }
     return launch_gemm_generic(L->cfg.dtype, g, s);
 }
 
@@ -428,7 +461,7 @@ static pd_status run_tail(pd_layer *L, const void *x, int T, const void *router_
     if (E == 0) {
         memset(&g, 0, sizeof(g));
         g.A = L->h; g.lda = d; g.B = L->w_gate; g.B1 = L->w_up; g.ldb = d; g.C = L->act; g.ldc = F;
-        g.M = T; g.N = F; g.K = d; g.epilogue = EPI_SWIGLU; g.interleaved = L->interleaved; g.n_groups = 1;
+        g.M = T; g.N = F; g.K = d; g.epilogue = EPI_SWIGLU; g.n_groups = 1;
         STEP("rmsnorm_ffn", launch_rmsnorm(c.dtype, L->h, L->g_ffn, L->y, T, d, c.rms_eps, s));
         g.A = L->y;
         STEP("gate_up_swiglu", run_gemm(L, g, s));
@@ -451,8 +484,8 @@ static pd_status run_tail(pd_layer *L, const void *x, int T, const void *router_
     const int P = T * c.top_k;
     memset(&g, 0, sizeof(g));
     g.A = L->y; g.lda = d; g.a_gather = L->sorted_token; g.B = L->w_gate; g.B1 = L->w_up; g.ldb = d;
-    g.b_group_stride = (int64_t)(L->interleaved ? 2 : 1) * F * d; g.group_offsets = L->offsets; g.n_groups = E;
-    g.C = L->act; g.ldc = F; g.M = P; g.N = F; g.K = d; g.epilogue = EPI_SWIGLU; g.interleaved = L->interleaved;
+    g.b_group_stride = (int64_t)(L->packed ? 2 : 1) * F * d; g.group_offsets = L->offsets; g.n_groups = E;
+    g.C = L->act; g.ldc = F; g.M = P; g.N = F; g.K = d; g.epilogue = EPI_SWIGLU;
     STEP("moe_gate_up_swiglu", run_gemm(L, g, s));
     memset(&g, 0, sizeof(g));
     g.A = L->act; g.lda = F; g.B = L->w_down; g.ldb = F; g.b_group_stride = (int64_t)d * F;

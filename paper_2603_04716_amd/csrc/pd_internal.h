@@ -60,6 +60,16 @@ __host__ __device__ __forceinline__ size_t vblk_off(int pos, int d)
     return (size_t)(pos >> 5) * 4096 + (size_t)d * 32 + 8 * ((pp >> 2) & 3) + 4 * (pp >> 4) + (pp & 3);
 }
 
+// Packed weight layout of the matrix-core kernels.  A [N, K] matrix is cut into blocks of 16 rows x
+// 32 k (1 KB); inside a block the order is [k/8][row][k%8], i.e. exactly the register image of one
+// v_mfma_f32_16x16x32_bf16 A operand (lane = 16*(k/8) + row holds 8 consecutive k), so a wave reads
+// a block with one fully contiguous 16-byte-per-lane load.  Blocks are ordered [N/16][K/32].  For
+// the SwiGLU pack the rows are first interleaved in 32-row blocks: gate[j..j+31], up[j..j+31], ...
+__host__ __device__ __forceinline__ size_t wpack_off(int n, int k, int K)
+{
+    return ((size_t)(n >> 4) * (K >> 5) + (k >> 5)) * 512 + ((k >> 3) & 3) * 128 + (n & 15) * 8 + (k & 7);
+}
+
 constexpr int kMetaChunk = 255;  // ints carried by value per meta-kernel launch (+1 for cu_seqlens)
 struct IntChunk {
     int32_t v[256];
@@ -72,7 +82,7 @@ enum Epilogue { EPI_NONE = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2, EPI_PARTIAL = 3 
 // (optional): rows [group_offsets[g], group_offsets[g+1]) multiply B + g*b_group_stride.
 struct GemmArgs {
     const void *A;
-    const void *B;        // EPI_SWIGLU: gate rows (or the interleaved gate/up pack)
+    const void *B;        // weights; EPI_SWIGLU: gate rows (plain) or the gate/up pack (packed)
     const void *B1;       // EPI_SWIGLU with plain layout: up rows; else unused
     void *C;
     const void *R;        // EPI_RESIDUAL: residual [M,N]
@@ -83,7 +93,7 @@ struct GemmArgs {
     int32_t M, N, K;               // N = output columns (for SWIGLU: F)
     int32_t lda, ldb, ldc, ldr;
     int32_t epilogue;
-    int32_t interleaved;           // EPI_SWIGLU: B holds 32-row blocks gate,up,gate,up...
+    int32_t packed;                // B is in the MFMA block layout below (matrix-core kernels only)
     float *splitk_ws;              // optional scratch for split-K partials (decode-sized M)
     size_t splitk_ws_elems;
 };
