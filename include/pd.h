@@ -180,6 +180,15 @@ pd_status pd_profile_read(pd_layer *layer, int32_t max_entries, const char **nam
                           int32_t *n);
 
 /*
+ * Plain device-to-device copy of `bytes` bytes (a multiple of 16; both pointers 16-byte aligned,
+ * non-overlapping) as one grid-stride kernel on `stream`.  A measurement aid, not a step of the
+ * layer: a kernel with exactly known HBM traffic (bytes read + bytes written) against which
+ * hardware traffic counters and the streaming ceiling of the device are calibrated.
+ * Errors: PD_ERR_INVALID_ARG for NULL / misaligned / bytes <= 0.
+ */
+pd_status pd_stream_copy(void *dst, const void *src, int64_t bytes, void *stream);
+
+/*
  * Allocation model (host only; needs no GPU).
  *   T_s        = ttft_slo - t_overhead                                         Eq. (12)
  *   TP_prefill = prefill_max_tps - l_in / T_s                                  Eq. (13)

@@ -23,7 +23,7 @@ PD_F32, PD_BF16 = 0, 1
 EXPORTS = [
     "pd_layer_create", "pd_layer_destroy", "pd_layer_reserve", "pd_kv_cache_create",
     "pd_kv_cache_destroy", "pd_kv_cache_set", "pd_kv_cache_set_len", "pd_kv_cache_len",
-    "pd_kv_cache_set_lens", "pd_kv_cache_get", "pd_profile_enable", "pd_profile_read", "pd_prefill", "pd_decode_step", "pd_last_expert_choice", "pd_allocate",
+    "pd_kv_cache_set_lens", "pd_kv_cache_get", "pd_profile_enable", "pd_profile_read", "pd_stream_copy", "pd_prefill", "pd_decode_step", "pd_last_expert_choice", "pd_allocate",
     "pd_fifo_replay", "pd_mm1_sojourn", "pd_status_string", "pd_last_error",
 ]
 
@@ -169,6 +169,14 @@ def pd_profile_read(layer, max_entries=64):
     n = C.c_int32()
     _check(lib.pd_profile_read(layer, C.c_int32(max_entries), names, ms, C.byref(n)))
     return [(names[i].decode(), float(ms[i])) for i in range(n.value)]
+
+
+def pd_stream_copy(dst, src):
+    """dst <- src by the library's plain copy kernel (same byte size, multiple of 16)."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("pd_stream_copy: size mismatch")
+    _check(lib.pd_stream_copy(_ptr(dst), _ptr(src), C.c_int64(nbytes), _stream()))
 
 
 def pd_kv_cache_len(cache, slot):

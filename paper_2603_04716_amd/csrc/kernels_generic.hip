@@ -544,4 +544,20 @@ hipError_t launch_kv_copy(int dtype, void *cache_k, void *cache_v, const void *k
     return hipGetLastError();
 }
 
+// ---- plain copy (traffic-counter calibration) -----------------------------------------------------
+__global__ __launch_bounds__(256) void stream_copy_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src,
+                                                          size_t n)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+
+hipError_t launch_stream_copy(void *dst, const void *src, size_t n_vec16, hipStream_t s)
+{
+    const size_t want = (n_vec16 + 255) / 256;
+    const unsigned grid = (unsigned)(want < 256 * 16 ? (want ? want : 1) : 256 * 16);
+    stream_copy_kernel<<<grid, 256, 0, s>>>((uint4 *)dst, (const uint4 *)src, n_vec16);
+    return hipGetLastError();
+}
+
 }  // namespace pd

@@ -769,6 +769,16 @@ extern "C" pd_status pd_profile_read(pd_layer *L, int32_t max_entries, const cha
     return PD_OK;
 }
 
+extern "C" pd_status pd_stream_copy(void *dst, const void *src, int64_t bytes, void *stream)
+{
+    if (!dst || !src || bytes <= 0 || bytes % 16 != 0 || ((uintptr_t)dst | (uintptr_t)src) % 16 != 0) {
+        set_error("pd_stream_copy: pointers must be non-NULL and 16-byte aligned, bytes a positive multiple of 16");
+        return PD_ERR_INVALID_ARG;
+    }
+    HIP_TRY(launch_stream_copy(dst, src, (size_t)bytes / 16, (hipStream_t)stream), PD_ERR_DEVICE);
+    return PD_OK;
+}
+
 extern "C" pd_status pd_kv_cache_set_lens(pd_kv_cache *c, int32_t n, const int32_t *slots,
                                           const int32_t *lens, void *stream)
 {

@@ -160,6 +160,7 @@ bool attn_prefill_mfma_supported(const AttnArgs &a);
 hipError_t launch_attn_prefill_mfma(const AttnArgs &a, uint16_t *vt, int vt_ld, const int32_t *pad_cu,
                                     hipStream_t s);
 
+hipError_t launch_stream_copy(void *dst, const void *src, size_t n_vec16, hipStream_t s);
 hipError_t launch_kv_copy(int dtype, void *cache_k, void *cache_v, const void *k, const void *v,
                           int slot, int Hkv, int len, int hd, int max_len, int blocked, int to_cache,
                           hipStream_t s);

@@ -1,0 +1,114 @@
+#!/usr/bin/env python3
+"""HBM traffic of the layer's kernels from hardware counters, calibrated by a plain copy.
+
+Run the workload under the profiler once per counter (from /tmp with TMPDIR=/tmp):
+
+    rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d <dir>/fetch -o t -- \
+        python3 -m paper_2603_04716_amd.traffic_probe
+    rocprofv3 --pmc WRITE_SIZE --kernel-trace --output-format csv -d <dir>/write -o t -- \
+        python3 -m paper_2603_04716_amd.traffic_probe
+
+then summarise the two counter files:
+
+    python3 -m paper_2603_04716_amd.traffic_probe --summarise <fetch csv> <write csv>
+
+The workload is the 8B-shaped bf16 layer: a 1 GiB pd_stream_copy (known traffic: 1 GiB read and
+1 GiB written), a prefill of 4 x 2048 tokens and a decode step of 256 sequences over 2048 cached
+tokens, each three times.  A counter reads KiB per dispatch; the copy kernel's reading against its
+known size gives the scale factor applied to every other kernel.
+"""
+import argparse
+import collections
+import csv
+import os
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+sys.path.insert(0, ROOT)
+
+COPY_BYTES = 1 << 30
+L_IN, N_SEQ, KV_LEN, BATCH = 2048, 4, 2048, 256
+
+
+def workload():
+    import torch
+    import pd_inputs as I
+    import paper_2603_04716_amd as pd
+    from paper_2603_04716_amd import harness as H
+
+    cfg = I.CONFIGS["llama8b"]
+    layer = H.Layer(cfg, I.layer_weights(cfg))
+    T = L_IN * N_SEQ
+    x = H._dev(I.hidden(T, cfg["d_model"], seed=10, dtype="bf16"), "bf16")
+    out = torch.empty_like(x)
+    cu = [L_IN * i for i in range(N_SEQ + 1)]
+    pd.pd_layer_reserve(layer.h, T)
+    cache = layer.new_cache(BATCH, KV_LEN + 8)
+    k, v = I.kv_fill(cfg["n_kv_heads"], KV_LEN, cfg["head_dim"], seed=11, dtype="bf16")
+    layer.fill_cache(cache, [KV_LEN] * BATCH, H._dev(k, "bf16"), H._dev(v, "bf16"))
+    xdec = H._dev(I.hidden(BATCH, cfg["d_model"], seed=12, dtype="bf16"), "bf16")
+    odec = torch.empty_like(xdec)
+    src = torch.ones(COPY_BYTES // 2, dtype=torch.bfloat16, device="cuda")
+    dst = torch.empty_like(src)
+    slots = list(range(BATCH))
+    torch.cuda.synchronize()
+    for _ in range(3):
+        pd.pd_stream_copy(dst, src)
+        pd.pd_prefill(layer.h, x, cu, out)
+        pd.pd_kv_cache_set_lens(cache, slots, [KV_LEN] * BATCH)
+        pd.pd_decode_step(layer.h, xdec, slots, cache, odec)
+        torch.cuda.synchronize()
+    layer.close()
+
+
+def short(name):
+    name = name.replace("void ", "").replace("pd::", "")
+    cut = name.find("(")
+    return name if cut < 0 else name[:cut]
+
+
+def read_counter(path, counter):
+    """{(kernel, grid): [KiB per dispatch]} for rows of `counter`."""
+    agg = collections.defaultdict(list)
+    with open(path) as f:
+        for r in csv.DictReader(f):
+            if r["Counter_Name"] != counter:
+                continue
+            agg[(short(r["Kernel_Name"]), int(r["Grid_Size"]))].append(float(r["Counter_Value"]))
+    return agg
+
+
+def summarise(fetch_csv, write_csv):
+    fetch, write = read_counter(fetch_csv, "FETCH_SIZE"), read_counter(write_csv, "WRITE_SIZE")
+    mean = lambda v: sum(v) / len(v)
+    copy_key = next(k for k in fetch if k[0].startswith("stream_copy_kernel"))
+    known_kib = COPY_BYTES / 1024.0
+    f_scale = known_kib / mean(fetch[copy_key])
+    w_scale = known_kib / mean(write[copy_key])
+    print(f"copy kernel: {known_kib:.0f} KiB each way; FETCH_SIZE reads {mean(fetch[copy_key]):.0f}, "
+          f"WRITE_SIZE reads {mean(write[copy_key]):.0f} -> scale factors {f_scale:.4f} (fetch), {w_scale:.4f} (write)")
+    print()
+    print("| kernel | grid (threads) | dispatches | fetched MB | written MB | total MB |")
+    print("|---|---|---|---|---|---|")
+    for key in sorted(fetch, key=lambda k: -mean(fetch[k])):
+        if key not in write:
+            continue
+        fm = mean(fetch[key]) * f_scale * 1024 / 1e6
+        wm = mean(write[key]) * w_scale * 1024 / 1e6
+        if fm + wm < 1.0:
+            continue
+        print(f"| `{key[0]}` | {key[1]} | {len(fetch[key])} | {fm:.1f} | {wm:.1f} | {fm + wm:.1f} |")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--summarise", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"))
+    args = ap.parse_args()
+    if args.summarise:
+        summarise(*args.summarise)
+    else:
+        workload()
+
+
+if __name__ == "__main__":
+    main()

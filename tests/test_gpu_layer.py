@@ -270,3 +270,19 @@ def test_deterministic_across_runs():
     for _ in range(3):
         assert np.array_equal(gl.prefill(x, cu), a)
     gl.close()
+
+
+def test_stream_copy_is_bit_exact_and_checks_arguments():
+    rng = np.random.default_rng(5)
+    src = torch.from_numpy(rng.integers(-2**31, 2**31 - 1, (1 << 20) + 12).astype(np.int32)).cuda()
+    for n in (4, 4 * 257, (1 << 20) + 12):       # 16 bytes, a ragged tail, many grid strides
+        dst = torch.zeros(n + 4, dtype=torch.int32, device="cuda")
+        pd.pd_stream_copy(dst[:n], src[:n])
+        torch.cuda.synchronize()
+        assert torch.equal(dst[:n], src[:n])
+        assert int(dst[n:].abs().max()) == 0     # nothing written past the end
+    with pytest.raises(pd.PdError) as e:
+        pd.pd_stream_copy(torch.zeros(6, dtype=torch.int32, device="cuda"), src[:6])   # 24 bytes
+    assert e.value.status == pd.PD_ERR_INVALID_ARG
+    with pytest.raises(pd.PdError):
+        pd.pd_stream_copy(torch.zeros(9, dtype=torch.int32, device="cuda")[1:], src[:8])  # misaligned
