@@ -133,6 +133,29 @@ def decode_step(layer: Layer, x, slots, cache: KVCache, router_logits=None, retu
     return (out, eidx) if return_experts else out
 
 
+def prefill_chunk(layer: Layer, x, cu_seqlens, slots, cache: KVCache, router_logits=None,
+                  return_experts=False):
+    """Chunked prefill: sequence s continues cache slot slots[s]; its rows take the positions
+    behind the cached prefix, are appended to the cache and attend over prefix + chunk."""
+    x = _f32(x)
+    T, d = x.shape
+    cu = _i32(cu_seqlens)
+    n_seqs = len(cu) - 1
+    sl = _i32(slots)
+    rl = None if router_logits is None else _f32(router_logits)
+    out = np.zeros((T, d), np.float32)
+    k = max(layer.c.top_k, 1)
+    eidx = np.full((T, k), -1, np.int32)
+    rc = lib().orc_prefill_chunk(C.byref(layer.c), C.byref(layer.cw), _p(x), C.c_int(T), C.c_int(n_seqs),
+                                 _p(cu), _p(rl), _p(sl), _p(cache.k), _p(cache.v), _p(cache.lens),
+                                 C.c_int(cache.max_len), _p(out), _p(eidx))
+    if rc == -2:
+        raise OverflowError("KV cache capacity exceeded")
+    if rc != 0:
+        raise ValueError(f"orc_prefill_chunk failed rc={rc}")
+    return (out, eidx) if return_experts else out
+
+
 # ---- stand-alone pieces (for pins) -------------------------------------------------------------
 
 def rmsnorm(x, g, eps=1e-6):

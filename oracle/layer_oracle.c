@@ -1,5 +1,6 @@
 /*
- * CPU oracle for one pre-norm decoder layer (prefill and single-token decode).
+ * CPU oracle for one pre-norm decoder layer (prefill, chunked prefill against a cached
+ * prefix, and single-token decode).
  *
  * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference that the
  * GPU library is compared against.  It shares no code, header, table or
@@ -26,8 +27,8 @@
  *
  * Every function is pinned by tests/test_oracle_layer.py against an
  * independent float64 composition of library primitives, brute-force
- * attention, the decode == prefill-of-extended-sequence identity and
- * textbook invariants.
+ * attention, the decode == prefill-of-extended-sequence identity, the chunked ==
+ * unchunked prefill identity and textbook invariants.
  */
 #include <math.h>
 #include <stdint.h>
@@ -414,6 +415,92 @@ int orc_decode_step(const orc_config *c, const orc_weights *w, const float *x, i
         free(h);
     }
     for (int b = 0; b < B; ++b) lens[slots[b]] += 1;
+    return 0;
+}
+
+/*
+ * Chunked prefill: a packed batch of chunks, each continuing the sequence held in
+ * a cache slot (the paper's "Evaluation" discusses the prefill chunk size; a chunk
+ * is a run of new prompt tokens processed against the prefix already cached).
+ * Sequence s owns rows cu_seqlens[s] .. cu_seqlens[s+1]-1; with P = lens[slots[s]]
+ * cached tokens, its i-th row is the token at position P + i: its rotated key and
+ * its value are stored at that position, and it attends over positions 0 .. P + i
+ * (the whole prefix, the earlier rows of the chunk, itself).  Afterwards
+ * lens[slot] = P + L.  P = 0 is an ordinary prefill; L = 1 is a decode step.
+ * Slots must be distinct.  Returns 0, -1 bad argument, -2 cache capacity exceeded
+ * (nothing is modified in that case).
+ */
+int orc_prefill_chunk(const orc_config *c, const orc_weights *w, const float *x, int T, int n_seqs,
+                      const int32_t *cu_seqlens, const float *router_logits, const int32_t *slots,
+                      float *k_cache, float *v_cache, int32_t *lens, int max_len, float *out,
+                      int32_t *expert_idx)
+{
+    int d = c->d_model, Hq = c->n_q_heads, Hkv = c->n_kv_heads, hd = c->head_dim;
+    if (Hkv <= 0 || Hq % Hkv != 0 || hd % 2 != 0) return -1;
+    if (!slots || cu_seqlens[0] != 0 || cu_seqlens[n_seqs] != T) return -1;
+    size_t dq = (size_t)Hq * hd, dkv = (size_t)Hkv * hd;
+    for (int s = 0; s < n_seqs; ++s) {
+        if (cu_seqlens[s + 1] < cu_seqlens[s]) return -1;
+        for (int r = 0; r < s; ++r)
+            if (slots[r] == slots[s]) return -1;
+    }
+    for (int s = 0; s < n_seqs; ++s)
+        if (lens[slots[s]] + (cu_seqlens[s + 1] - cu_seqlens[s]) > max_len) return -2;
+
+    int32_t *seq_of = (int32_t *)malloc(sizeof(int32_t) * (size_t)(T > 0 ? T : 1));
+    for (int s = 0; s < n_seqs; ++s)
+        for (int t = cu_seqlens[s]; t < cu_seqlens[s + 1]; ++t) seq_of[t] = s;
+
+    /* pass 1: keys and values of the new tokens go into the cache behind the prefix */
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int t = 0; t < T; ++t) {
+        int s = seq_of[t], slot = slots[s];
+        int pos = lens[slot] + (t - cu_seqlens[s]);
+        float *y = (float *)malloc(sizeof(float) * (size_t)d);
+        float *k = (float *)malloc(sizeof(float) * dkv);
+        float *v = (float *)malloc(sizeof(float) * dkv);
+        orc_rmsnorm_row(x + (size_t)t * d, w->g_attn, d, c->rms_eps, y);
+        orc_linear_row(y, w->w_k, d, (int)dkv, k);
+        orc_linear_row(y, w->w_v, d, (int)dkv, v);
+        orc_rope_row(k, Hkv, hd, pos, c->rope_base);
+        size_t base = (size_t)slot * Hkv * (size_t)max_len * hd;
+        for (int g = 0; g < Hkv; ++g) {
+            memcpy(k_cache + base + ((size_t)g * max_len + pos) * hd, k + (size_t)g * hd,
+                   sizeof(float) * (size_t)hd);
+            memcpy(v_cache + base + ((size_t)g * max_len + pos) * hd, v + (size_t)g * hd,
+                   sizeof(float) * (size_t)hd);
+        }
+        free(y);
+        free(k);
+        free(v);
+    }
+
+    /* pass 2: each new token attends over cache positions 0 .. its own */
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int t = 0; t < T; ++t) {
+        int s = seq_of[t], slot = slots[s];
+        int pos = lens[slot] + (t - cu_seqlens[s]);
+        float *y = (float *)malloc(sizeof(float) * (size_t)d);
+        float *q = (float *)malloc(sizeof(float) * dq);
+        float *o = (float *)malloc(sizeof(float) * dq);
+        float *h = (float *)malloc(sizeof(float) * (size_t)d);
+        orc_rmsnorm_row(x + (size_t)t * d, w->g_attn, d, c->rms_eps, y);
+        orc_linear_row(y, w->w_q, d, (int)dq, q);
+        orc_rope_row(q, Hq, hd, pos, c->rope_base);
+        size_t base = (size_t)slot * Hkv * (size_t)max_len * hd;
+        orc_attend_row(q, k_cache + base, v_cache + base, (size_t)hd, (size_t)max_len * hd, pos + 1,
+                       Hq, Hkv, hd, o);
+        orc_linear_row(o, w->w_o, (int)dq, d, h);
+        for (int i = 0; i < d; ++i) h[i] = (float)((double)x[(size_t)t * d + i] + (double)h[i]);
+        ffn_block_row(c, w, h, router_logits ? router_logits + (size_t)t * c->n_experts : NULL,
+                      out + (size_t)t * d, expert_idx ? expert_idx + (size_t)t * c->top_k : NULL);
+        free(y);
+        free(q);
+        free(o);
+        free(h);
+    }
+    for (int s = 0; s < n_seqs; ++s) lens[slots[s]] += cu_seqlens[s + 1] - cu_seqlens[s];
+    free(seq_of);
     return 0;
 }
 

@@ -158,6 +158,71 @@ def test_decode_capacity_error_leaves_state():
     assert cache.lens[1] == 4 and np.array_equal(before, cache.k)
 
 
+# ---- chunked prefill == unchunked prefill -------------------------------------------------------------
+
+@pytest.mark.parametrize("over", [dict(), dict(n_q_heads=4, n_kv_heads=4), dict(n_experts=4, top_k=2, d_ff=64)])
+def test_chunked_prefill_equals_unchunked(over):
+    cfg = I.small_config(**over)
+    w = I.layer_weights(cfg, std=0.08, with_router=True)
+    L = O.Layer(cfg, w)
+    lens = [13, 1, 22]
+    xs = [I.hidden(n, cfg["d_model"], seed=40 + i) for i, n in enumerate(lens)]
+    slots = [3, 0, 1]
+    # three calls with ragged chunk lengths, one of them empty for a sequence
+    plan = [[5, 1, 7], [8, 0, 4], [0, 0, 11]]
+    cache = O.KVCache(L, n_slots=4, max_len=24)
+    done = [0, 0, 0]
+    got = [[] for _ in lens]
+    for chunk in plan:
+        x = np.concatenate([xs[i][done[i]:done[i] + chunk[i]] for i in range(3)])
+        cu = np.concatenate([[0], np.cumsum(chunk)]).astype(np.int32)
+        out = O.prefill_chunk(L, x, cu, slots, cache)
+        for i in range(3):
+            got[i].append(out[cu[i]:cu[i + 1]])
+            done[i] += chunk[i]
+        assert [int(cache.lens[s]) for s in slots] == done
+    full_cache = O.KVCache(L, n_slots=4, max_len=24)
+    for i in range(3):
+        full = O.prefill(L, xs[i], np.array([0, lens[i]], np.int32), cache=full_cache, slots=[slots[i]])
+        assert relmax(np.concatenate(got[i]), full) < 1e-6
+        # and against the independent float64 composition of library routines
+        ref = torch_layer(cfg, w, xs[i], [0, lens[i]])
+        assert relmax(np.concatenate(got[i]), ref) < 2e-6
+    for sl, n in zip(slots, lens):                           # the caches hold the same keys and values
+        assert np.array_equal(cache.k[sl, :, :n], full_cache.k[sl, :, :n])
+        assert np.array_equal(cache.v[sl, :, :n], full_cache.v[sl, :, :n])
+
+
+def test_chunk_of_one_token_is_a_decode_step_and_empty_prefix_is_a_prefill():
+    cfg = I.small_config()
+    w = I.layer_weights(cfg, std=0.08)
+    L = O.Layer(cfg, w)
+    x = I.hidden(12, cfg["d_model"], seed=50)
+    a, b = O.KVCache(L, 2, 16), O.KVCache(L, 2, 16)
+    p1 = O.prefill(L, x[:9], np.array([0, 4, 9], np.int32), cache=a, slots=[1, 0])
+    p2 = O.prefill_chunk(L, x[:9], np.array([0, 4, 9], np.int32), [1, 0], b)
+    assert np.array_equal(p1, p2) and np.array_equal(a.k, b.k) and np.array_equal(a.lens, b.lens)
+    d1 = O.decode_step(L, x[9:11], [0, 1], a)
+    d2 = O.prefill_chunk(L, x[9:11], np.array([0, 1, 2], np.int32), [0, 1], b)
+    assert np.array_equal(d1, d2) and np.array_equal(a.k, b.k) and np.array_equal(a.v, b.v)
+    assert list(a.lens) == list(b.lens) == [6, 5]
+
+
+def test_chunk_capacity_and_argument_errors_leave_state():
+    cfg = I.small_config()
+    L = O.Layer(cfg, I.layer_weights(cfg))
+    cache = O.KVCache(L, 2, 6)
+    O.prefill(L, I.hidden(4, cfg["d_model"], 1), np.array([0, 4], np.int32), cache=cache, slots=[1])
+    before_k, before_len = cache.k.copy(), cache.lens.copy()
+    with pytest.raises(OverflowError):
+        O.prefill_chunk(L, I.hidden(4, cfg["d_model"], 2), np.array([0, 1, 4], np.int32), [0, 1], cache)
+    with pytest.raises(ValueError):                          # repeated slot
+        O.prefill_chunk(L, I.hidden(2, cfg["d_model"], 2), np.array([0, 1, 2], np.int32), [1, 1], cache)
+    assert np.array_equal(before_k, cache.k) and np.array_equal(before_len, cache.lens)
+    O.prefill_chunk(L, I.hidden(2, cfg["d_model"], 2), np.array([0, 2], np.int32), [1], cache)   # exactly full
+    assert cache.lens[1] == 6
+
+
 # ---- invariants -------------------------------------------------------------------------------------
 
 def test_rmsnorm_unit_rms_and_gain():
