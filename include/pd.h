@@ -147,6 +147,20 @@ pd_status pd_prefill(pd_layer *layer, const pd_tokens *tokens, pd_kv_cache *cach
                      void *out_hidden, void *stream);
 
 /*
+ * Chunked prefill: the same forward over a packed batch of chunks, each continuing the sequence
+ * that a cache slot already holds (the paper's evaluation varies the prefill chunk size; a chunk is
+ * a run of new prompt tokens processed against the cached prefix).  With P = the current length
+ * of slots[s], row i of sequence s is the token at position P + i: its rotated key and its value
+ * are appended at that position and it attends over positions 0 .. P + i.  Afterwards the slot's
+ * length is P + L_s.  An empty slot makes this an ordinary prefill that keeps its KV; a chunk of
+ * one token is a decode step.  cache and tokens->slots are required; a sequence may be empty.
+ * Errors as pd_prefill; PD_ERR_KV_CAPACITY if P + L_s exceeds max_len for any sequence (checked
+ * before anything is enqueued, nothing changes).
+ */
+pd_status pd_prefill_chunk(pd_layer *layer, const pd_tokens *tokens, pd_kv_cache *cache,
+                           void *out_hidden, void *stream);
+
+/*
  * One decode step (section "Acquire decode throughput under TPOT constraints": TPOT is measured as
  * a function of the decode batch).  Row b is the newest token of the sequence in slots[b], at
  * position p = len(slot).  Its rotated key and its value are appended at p, the row attends over

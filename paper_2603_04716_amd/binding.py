@@ -23,7 +23,7 @@ PD_F32, PD_BF16 = 0, 1
 EXPORTS = [
     "pd_layer_create", "pd_layer_destroy", "pd_layer_reserve", "pd_kv_cache_create",
     "pd_kv_cache_destroy", "pd_kv_cache_set", "pd_kv_cache_set_len", "pd_kv_cache_len",
-    "pd_kv_cache_set_lens", "pd_kv_cache_get", "pd_profile_enable", "pd_profile_read", "pd_stream_copy", "pd_prefill", "pd_decode_step", "pd_last_expert_choice", "pd_allocate",
+    "pd_kv_cache_set_lens", "pd_kv_cache_get", "pd_profile_enable", "pd_profile_read", "pd_stream_copy", "pd_prefill", "pd_prefill_chunk", "pd_decode_step", "pd_last_expert_choice", "pd_allocate",
     "pd_fifo_replay", "pd_mm1_sojourn", "pd_status_string", "pd_last_error",
 ]
 
@@ -196,6 +196,15 @@ def pd_prefill(layer, hidden, cu_seqlens, out, cache=None, slots=None, router_lo
                    sl if sl is not None else C.POINTER(C.c_int32)(),
                    None if router_logits is None else router_logits.data_ptr())
     _check(lib.pd_prefill(layer, C.byref(tk), cache, _ptr(out), _stream()))
+    return out
+
+
+def pd_prefill_chunk(layer, hidden, cu_seqlens, slots, cache, out, router_logits=None):
+    cu = _i32_array(cu_seqlens)
+    sl = _i32_array(slots)
+    tk = pd_tokens(None if hidden is None else hidden.data_ptr(), len(cu_seqlens) - 1, cu, sl,
+                   None if router_logits is None else router_logits.data_ptr())
+    _check(lib.pd_prefill_chunk(layer, C.byref(tk), cache, _ptr(out), _stream()))
     return out
 
 

@@ -86,6 +86,8 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a,
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int seq = blockIdx.z, head = blockIdx.y;
     const int s0 = a.d_cu[seq], L = a.d_cu[seq + 1] - s0;
+    const int P = a.prefix ? a.prefix[seq] : 0;    // keys ahead of the first query (chunked prefill)
+    const int Lk = P + L;                          // keys of the sequence
     const int nqb = (L + BQ - 1) / BQ;
     if ((int)blockIdx.x >= nqb) return;
     const int qb = nqb - 1 - blockIdx.x;           // longest rows first
@@ -109,7 +111,9 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a,
     // ---- tile loaders ------------------------------------------------------------------------------
     // K tile: 64 rows x 16 slots; one wave instruction = 4 rows; wave w issues rows 16*i + 4*w ..
     // V^T tile: 128 rows x 8 slots; one wave instruction = 8 rows; wave w issues rows 32*i + 8*w ..
-    const char *kbase = (const char *)(qkv + (size_t)s0 * ld + (a.Hq + g) * HD);
+    const char *kbase = a.kx ? (const char *)((const uint16_t *)a.kx + (size_t)a.k_cu[seq] * a.kx_ld + g * HD)
+                             : (const char *)(qkv + (size_t)s0 * ld + (a.Hq + g) * HD);
+    const size_t k_stride = (size_t)(a.kx ? a.kx_ld : ld) * 2;
     const char *vbase = (const char *)(vt + (size_t)g * HD * vt_ld + pad_cu[seq]);
     uint32_t k_row[4], k_chunk[4], v_off[4];
 #pragma unroll
@@ -126,8 +130,8 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a,
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             int kr = k0 + (int)k_row[i];
-            if (kr >= L) kr = L - 1;               // clamped rows are masked by causality
-            __builtin_amdgcn_global_load_lds((gptr_t)(kbase + (size_t)kr * (ld * 2) + k_chunk[i]),
+            if (kr >= Lk) kr = Lk - 1;             // clamped rows are masked by causality
+            __builtin_amdgcn_global_load_lds((gptr_t)(kbase + (size_t)kr * k_stride + k_chunk[i]),
                                              (lptr_t)(st + (16 * i + 4 * wave) * 256), 16, 0, 0);
         }
         const char *vb = vbase + (size_t)k0 * 2;
@@ -145,10 +149,12 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a,
     float m_run = -INFINITY, l_run = 0.f;          // log2-domain running max; this half's sum
     const float sl2e = a.scale * 1.4426950408889634f;
 
-    const int q_hi_blk = min(q0 + BQ, L);          // keys needed: 0 .. q_hi_blk-1
-    const int n_tiles = (q_hi_blk + BKV - 1) / BKV;
-    const int wq_lo = q0 + wave * 32, wq_hi = wq_lo + 31;
-    const int my_q = wq_lo + n;
+    const int q_hi_blk = min(q0 + BQ, L);          // keys needed: 0 .. P + q_hi_blk - 1
+    const int n_tiles = (P + q_hi_blk + BKV - 1) / BKV;
+    // last visible key of this wave's first / last query and of this lane's query
+    const int wq_lo = P + q0 + wave * 32, wq_hi = wq_lo + 31;
+    const int my_q = q0 + wave * 32 + n;
+    const int my_last = P + my_q;
 
     issue_loads(0, smem);
     __syncthreads();
@@ -178,7 +184,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a,
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int key = k0 + 32 * b + 8 * (r >> 2) + 4 * h + (r & 3);
-                        if (key > my_q) sacc[b][r] = -INFINITY;
+                        if (key > my_last) sacc[b][r] = -INFINITY;
                     }
             }
             float mx = -INFINITY;
@@ -256,6 +262,54 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a,
     }
 }
 
+// Chunked prefill: keys and values of positions 0 .. prefix[s] + L_s - 1 of every sequence's cache
+// slot, out of the blocked cache, as plain key rows kx[pad_cu[s] + pos][Hkv*128] and transposed
+// values vt[g][d][pad_cu[s] + pos] (zero past the end).  One block = 64 positions of one kv head.
+__global__ __launch_bounds__(256) void kv_gather_blocked_kernel(const uint16_t *__restrict__ kc,
+                                                                const uint16_t *__restrict__ vc,
+                                                                size_t plane, const int32_t *__restrict__ slots,
+                                                                const int32_t *__restrict__ cu,
+                                                                const int32_t *__restrict__ prefix,
+                                                                const int32_t *__restrict__ pad_cu, int n_seqs,
+                                                                int Hkv, uint16_t *__restrict__ kx,
+                                                                uint16_t *__restrict__ vt, int vt_ld)
+{
+    const int p0 = blockIdx.x * 64, g = blockIdx.y;
+    int lo = 0, hi = n_seqs;   // largest s with pad_cu[s] <= p0
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (pad_cu[mid] <= p0) lo = mid; else hi = mid;
+    }
+    const int s = lo;
+    const int Lk = prefix[s] + cu[s + 1] - cu[s];
+    const int pos0 = p0 - pad_cu[s];               // a multiple of 64
+    const uint16_t *kp = kc + ((size_t)slots[s] * Hkv + g) * plane;
+    const uint16_t *vp = vc + ((size_t)slots[s] * Hkv + g) * plane;
+    const int tid = threadIdx.x;
+    // keys: 64 positions x 16 chunks of 8 channels
+    for (int e = tid; e < 64 * 16; e += 256) {
+        const int r = e >> 4, c8 = (e & 15) * 8;
+        if (pos0 + r < Lk)
+            *(uint4 *)(kx + (size_t)(p0 + r) * (Hkv * HD) + g * HD + c8) =
+                *(const uint4 *)(kp + kblk_off(pos0 + r, c8));
+    }
+    // values: vt row d, 64 consecutive positions = two cache blocks of 32 positions, whose 32
+    // entries per channel are stored in the order sigma(16a + 4q + j) = 8q + 4a + j
+    for (int e = tid; e < HD * 8; e += 256) {
+        const int d = e >> 3, c8 = (e & 7) * 8;    // positions pos0 + c8 .. + 7
+        uint16_t w[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int pos = pos0 + c8 + j;
+            w[j] = pos < Lk ? vp[vblk_off(pos, d)] : (uint16_t)0;
+        }
+        uint4 o;
+        o.x = w[0] | ((uint32_t)w[1] << 16); o.y = w[2] | ((uint32_t)w[3] << 16);
+        o.z = w[4] | ((uint32_t)w[5] << 16); o.w = w[6] | ((uint32_t)w[7] << 16);
+        *(uint4 *)(vt + ((size_t)g * HD + d) * vt_ld + p0 + c8) = o;
+    }
+}
+
 bool attn_prefill_mfma_supported(const AttnArgs &a)
 {
     return a.hd == HD && !a.decode && a.ld % 8 == 0 && a.T > 0 &&
@@ -271,6 +325,31 @@ hipError_t launch_attn_prefill_mfma(const AttnArgs &a, uint16_t *vt, int vt_ld, 
                                                                a.n_seqs, vt, vt_ld);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    static bool attr_set = false;
+    const int smem = 2 * ASTAGE;
+    if (!attr_set) {
+        e = hipFuncSetAttribute((const void *)attn_prefill_mfma_kernel,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int nqb = (a.max_seq_len + BQ - 1) / BQ;
+    attn_prefill_mfma_kernel<<<dim3(nqb, a.Hq, a.n_seqs), 256, smem, s>>>(a, vt, vt_ld, pad_cu);
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_chunk_mfma(const AttnArgs &a_in, const int32_t *d_slots, uint16_t *kx, uint16_t *vt,
+                                  int vt_ld, const int32_t *pad_cu, hipStream_t s)
+{
+    AttnArgs a = a_in;
+    kv_gather_blocked_kernel<<<dim3(vt_ld / 64, a.Hkv), 256, 0, s>>>(
+        (const uint16_t *)a.k_cache, (const uint16_t *)a.v_cache, (size_t)a.max_len * HD, d_slots, a.d_cu,
+        a.prefix, pad_cu, a.n_seqs, a.Hkv, kx, vt, vt_ld);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    a.kx = kx;
+    a.kx_ld = a.Hkv * HD;
+    a.k_cu = pad_cu;
     static bool attr_set = false;
     const int smem = 2 * ASTAGE;
     if (!attr_set) {

@@ -272,7 +272,8 @@ hipError_t launch_scatter_ints(int32_t *dst, const int32_t *host_idx, const int3
 }
 
 __global__ void token_meta_kernel(const int32_t *__restrict__ cu, const int32_t *__restrict__ slots,
-                                  int n_seqs, int T, int32_t *__restrict__ tok_seq,
+                                  const int32_t *__restrict__ prefix, int n_seqs, int T,
+                                  int32_t *__restrict__ tok_seq,
                                   int32_t *__restrict__ tok_pos, int32_t *__restrict__ tok_slot)
 {
     int t = blockIdx.x * blockDim.x + threadIdx.x;
@@ -283,16 +284,17 @@ __global__ void token_meta_kernel(const int32_t *__restrict__ cu, const int32_t 
         if (cu[mid] <= t) lo = mid; else hi = mid;
     }
     tok_seq[t] = lo;
-    tok_pos[t] = t - cu[lo];
+    tok_pos[t] = t - cu[lo] + (prefix ? prefix[lo] : 0);
     if (slots) tok_slot[t] = slots[lo];
 }
 
-hipError_t launch_token_meta(const int32_t *d_cu, const int32_t *d_slots, int n_seqs, int T,
-                             int32_t *tok_seq, int32_t *tok_pos, int32_t *tok_slot, hipStream_t s)
+hipError_t launch_token_meta(const int32_t *d_cu, const int32_t *d_slots, const int32_t *d_prefix,
+                             int n_seqs, int T, int32_t *tok_seq, int32_t *tok_pos, int32_t *tok_slot,
+                             hipStream_t s)
 {
     if (T <= 0) return hipSuccess;
-    token_meta_kernel<<<(T + 255) / 256, 256, 0, s>>>(d_cu, d_slots, n_seqs, T, tok_seq, tok_pos,
-                                                      tok_slot);
+    token_meta_kernel<<<(T + 255) / 256, 256, 0, s>>>(d_cu, d_slots, d_prefix, n_seqs, T, tok_seq,
+                                                      tok_pos, tok_slot);
     return hipGetLastError();
 }
 
@@ -315,16 +317,16 @@ hipError_t launch_decode_meta(const int32_t *d_slots, int B, int32_t *d_len, int
 }
 
 __global__ void prefill_set_len_kernel(const int32_t *__restrict__ slots,
-                                       const int32_t *__restrict__ cu, int n, int32_t *len)
+                                       const int32_t *__restrict__ cu, int n, int32_t *len, int add)
 {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) len[slots[i]] = cu[i + 1] - cu[i];
+    if (i < n) len[slots[i]] = (add ? len[slots[i]] : 0) + cu[i + 1] - cu[i];   // slots are distinct
 }
 
 hipError_t launch_prefill_set_len(const int32_t *d_slots, const int32_t *d_cu, int n_seqs,
-                                  int32_t *d_len, hipStream_t s)
+                                  int32_t *d_len, int add, hipStream_t s)
 {
-    prefill_set_len_kernel<<<(n_seqs + 255) / 256, 256, 0, s>>>(d_slots, d_cu, n_seqs, d_len);
+    prefill_set_len_kernel<<<(n_seqs + 255) / 256, 256, 0, s>>>(d_slots, d_cu, n_seqs, d_len, add);
     return hipGetLastError();
 }
 

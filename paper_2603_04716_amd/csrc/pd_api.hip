@@ -20,7 +20,7 @@ struct pd_layer {
     void *g_attn, *g_ffn, *w_qkv, *w_o, *w_gate, *w_up, *w_down, *w_router;
     double *inv_freq;
     float2 *rope_table;       // (cos, sin) for positions < kRopeTableLen
-    int32_t *d_cu, *d_slots, *d_pad_cu;  // [4097] each
+    int32_t *d_cu, *d_slots, *d_pad_cu, *d_prefix;  // [4097] each
     void *vt;                 // transposed-V scratch for the MFMA attention, vt_cap bytes
     size_t vt_cap;
     float *dec_part;          // partial outputs of the decode attention chunks (inside ws)
@@ -114,7 +114,7 @@ static void free_layer(pd_layer *L)
 {
     if (!L) return;
     void *ptrs[] = {L->g_attn, L->g_ffn, L->w_qkv, L->w_o, L->w_gate, L->w_up, L->w_down,
-                    L->w_router, L->inv_freq, L->rope_table, L->d_cu, L->d_slots, L->d_pad_cu, L->vt, L->ws};
+                    L->w_router, L->inv_freq, L->rope_table, L->d_cu, L->d_slots, L->d_pad_cu, L->d_prefix, L->vt, L->ws};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     for (hipEvent_t e : L->prof_ev) (void)hipEventDestroy(e);
@@ -180,6 +180,7 @@ extern "C" pd_status pd_layer_create(const pd_layer_config *cfg, const pd_layer_
     CREATE_TRY(hipMalloc(&L->d_cu, sizeof(int32_t) * (kMaxSeqs + 1)));
     CREATE_TRY(hipMalloc(&L->d_slots, sizeof(int32_t) * (kMaxSeqs + 1)));
     CREATE_TRY(hipMalloc(&L->d_pad_cu, sizeof(int32_t) * (kMaxSeqs + 1)));
+    CREATE_TRY(hipMalloc(&L->d_prefix, sizeof(int32_t) * (kMaxSeqs + 1)));
     CREATE_TRY(hipMemcpy(L->g_attn, w->g_attn, d * esz, hipMemcpyDeviceToDevice));
     CREATE_TRY(hipMemcpy(L->g_ffn, w->g_ffn, d * esz, hipMemcpyDeviceToDevice));
     if (L->packed) {
@@ -496,8 +497,10 @@ static pd_status run_tail(pd_layer *L, const void *x, int T, const void *router_
     return PD_OK;
 }
 
-extern "C" pd_status pd_prefill(pd_layer *L, const pd_tokens *tk, pd_kv_cache *cache, void *out,
-                                void *stream)
+// Shared body of pd_prefill (chunk = false: positions from 0, a cache slot is overwritten) and
+// pd_prefill_chunk (chunk = true: positions behind the slot's cached prefix, appended).
+static pd_status prefill_common(pd_layer *L, const pd_tokens *tk, pd_kv_cache *cache, void *out,
+                                void *stream, bool chunk)
 {
     if (!L || !tk || !tk->cu_seqlens) {
         set_error("pd_prefill: NULL argument");
@@ -522,7 +525,12 @@ extern "C" pd_status pd_prefill(pd_layer *L, const pd_tokens *tk, pd_kv_cache *c
         if (Ls > max_L) max_L = Ls;
     }
     const int T = tk->cu_seqlens[n];
+    if (chunk && (!cache || !tk->slots)) {
+        set_error("pd_prefill_chunk: needs a cache and one slot per sequence");
+        return PD_ERR_INVALID_ARG;
+    }
     const bool keep = cache && tk->slots;
+    std::vector<int32_t> prefix((size_t)n, 0);
     if (keep) {
         if (!cache_matches(L, cache)) {
             set_error("pd_prefill: cache was created for a different layer shape");
@@ -537,13 +545,19 @@ extern "C" pd_status pd_prefill(pd_layer *L, const pd_tokens *tk, pd_kv_cache *c
             }
             seen[(size_t)sl] = 1;
         }
-        if (max_L > cache->max_len) {
-            set_error("pd_prefill: a sequence of %d tokens exceeds the cache's max_len %d", max_L, cache->max_len);
-            return PD_ERR_KV_CAPACITY;
+        if (chunk)
+            for (int s = 0; s < n; ++s) prefix[(size_t)s] = cache->h_len[(size_t)tk->slots[s]];
+        for (int s = 0; s < n; ++s) {
+            const int Ls = tk->cu_seqlens[s + 1] - tk->cu_seqlens[s];
+            if (prefix[(size_t)s] + Ls > cache->max_len) {
+                set_error("pd_prefill: sequence %d would hold %d tokens, the cache's max_len is %d", s,
+                          prefix[(size_t)s] + Ls, cache->max_len);
+                return PD_ERR_KV_CAPACITY;
+            }
         }
     }
     if (T == 0) {
-        if (keep)
+        if (keep && !chunk)
             for (int s = 0; s < n; ++s) {
                 pd_status st = pd_kv_cache_set_len(cache, tk->slots[s], 0, stream);
                 if (st != PD_OK) return st;
@@ -566,8 +580,9 @@ extern "C" pd_status pd_prefill(pd_layer *L, const pd_tokens *tk, pd_kv_cache *c
 
     HIP_TRY(launch_write_ints(L->d_cu, tk->cu_seqlens, n + 1, s), PD_ERR_DEVICE);
     if (keep) HIP_TRY(launch_write_ints(L->d_slots, tk->slots, n, s), PD_ERR_DEVICE);
-    HIP_TRY(launch_token_meta(L->d_cu, keep ? L->d_slots : nullptr, n, T, L->tok_seq, L->tok_pos,
-                              L->tok_slot, s),
+    if (chunk) HIP_TRY(launch_write_ints(L->d_prefix, prefix.data(), n, s), PD_ERR_DEVICE);
+    HIP_TRY(launch_token_meta(L->d_cu, keep ? L->d_slots : nullptr, chunk ? L->d_prefix : nullptr, n, T,
+                              L->tok_seq, L->tok_pos, L->tok_slot, s),
             PD_ERR_DEVICE);
     STEP("rmsnorm_attn", launch_rmsnorm(c.dtype, tk->hidden, L->g_attn, L->y, T, c.d_model, c.rms_eps, s));
     GemmArgs g;
@@ -587,14 +602,26 @@ extern "C" pd_status pd_prefill(pd_layer *L, const pd_tokens *tk, pd_kv_cache *c
     a.qkv = L->qkv; a.ld = L->Nqkv; a.o = L->o; a.T = T; a.Hq = c.n_q_heads; a.Hkv = c.n_kv_heads;
     a.hd = c.head_dim; a.scale = (float)(1.0 / sqrt((double)c.head_dim)); a.tok_pos = L->tok_pos;
     a.decode = 0; a.d_cu = L->d_cu; a.n_seqs = n; a.max_seq_len = max_L;
-    if (L->use_mfma && attn_prefill_mfma_supported(a)) {
-        // padded sequence starts (multiples of 64) for the transposed-V scratch
+    if (chunk && !cache->blocked) {
+        // plain cache layout: every row reads keys 0 .. its own position of its slot
+        a.decode = 1; a.tok_slot = L->tok_slot; a.k_cache = cache->k; a.v_cache = cache->v;
+        a.max_len = cache->max_len;
+        STEP("prefill_attention", launch_attn_generic(c.dtype, a, s));
+    } else if (chunk || (L->use_mfma && attn_prefill_mfma_supported(a))) {
+        if (chunk && !attn_prefill_mfma_supported(a)) {
+            set_error("pd_prefill_chunk: blocked cache without the matrix-core attention path");
+            return PD_ERR_SHAPE;
+        }
+        // padded key-row starts of the sequences (multiples of 64) for the transposed-V scratch
+        // (and, chunked, the gathered key rows)
         std::vector<int32_t> pad((size_t)n + 1);
         pad[0] = 0;
         for (int q = 0; q < n; ++q)
-            pad[(size_t)q + 1] = pad[(size_t)q] + (tk->cu_seqlens[q + 1] - tk->cu_seqlens[q] + 63) / 64 * 64;
+            pad[(size_t)q + 1] = pad[(size_t)q] +
+                                 (prefix[(size_t)q] + tk->cu_seqlens[q + 1] - tk->cu_seqlens[q] + 63) / 64 * 64;
         const int vt_ld = pad[(size_t)n];
-        const size_t need = (size_t)c.n_kv_heads * c.head_dim * vt_ld * 2;
+        const size_t vt_bytes = (size_t)c.n_kv_heads * c.head_dim * vt_ld * 2;
+        const size_t need = chunk ? 2 * vt_bytes : vt_bytes;
         if (need > L->vt_cap) {
             HIP_TRY(hipDeviceSynchronize(), PD_ERR_DEVICE);
             if (L->vt) (void)hipFree(L->vt);
@@ -608,19 +635,38 @@ extern "C" pd_status pd_prefill(pd_layer *L, const pd_tokens *tk, pd_kv_cache *c
             L->vt_cap = need;
         }
         HIP_TRY(launch_write_ints(L->d_pad_cu, pad.data(), n + 1, s), PD_ERR_DEVICE);
-        STEP("prefill_attention", launch_attn_prefill_mfma(a, (uint16_t *)L->vt, vt_ld, L->d_pad_cu, s));
+        if (chunk) {
+            a.prefix = L->d_prefix; a.k_cache = cache->k; a.v_cache = cache->v; a.max_len = cache->plane_len;
+            STEP("prefill_attention",
+                 launch_attn_chunk_mfma(a, L->d_slots, (uint16_t *)((char *)L->vt + vt_bytes), (uint16_t *)L->vt,
+                                        vt_ld, L->d_pad_cu, s));
+        } else {
+            STEP("prefill_attention", launch_attn_prefill_mfma(a, (uint16_t *)L->vt, vt_ld, L->d_pad_cu, s));
+        }
     } else {
         STEP("prefill_attention", launch_attn_generic(c.dtype, a, s));
     }
     st = run_tail(L, tk->hidden, T, tk->router_logits, out, s);
     if (st != PD_OK) return st;
     if (keep) {
-        HIP_TRY(launch_prefill_set_len(L->d_slots, L->d_cu, n, cache->d_len, s), PD_ERR_DEVICE);
+        HIP_TRY(launch_prefill_set_len(L->d_slots, L->d_cu, n, cache->d_len, chunk ? 1 : 0, s), PD_ERR_DEVICE);
         for (int q = 0; q < n; ++q)
-            cache->h_len[(size_t)tk->slots[q]] = tk->cu_seqlens[q + 1] - tk->cu_seqlens[q];
+            cache->h_len[(size_t)tk->slots[q]] = prefix[(size_t)q] + tk->cu_seqlens[q + 1] - tk->cu_seqlens[q];
     }
     L->last_rows = T;
     return PD_OK;
+}
+
+extern "C" pd_status pd_prefill(pd_layer *L, const pd_tokens *tk, pd_kv_cache *cache, void *out,
+                                void *stream)
+{
+    return prefill_common(L, tk, cache, out, stream, false);
+}
+
+extern "C" pd_status pd_prefill_chunk(pd_layer *L, const pd_tokens *tk, pd_kv_cache *cache, void *out,
+                                      void *stream)
+{
+    return prefill_common(L, tk, cache, out, stream, true);
 }
 
 extern "C" pd_status pd_decode_step(pd_layer *L, const pd_batch *bt, pd_kv_cache *cache, void *out,

@@ -107,8 +107,10 @@ hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t s);   // bf16 only
 bool gemv_mfma_supported(const GemmArgs &a);                      // bf16, M <= 16
 hipError_t launch_gemv_mfma(const GemmArgs &a, hipStream_t s);
 // per token row: its sequence, its position inside it and (if d_slots) its cache slot
-hipError_t launch_token_meta(const int32_t *d_cu, const int32_t *d_slots, int n_seqs, int T,
-                             int32_t *tok_seq, int32_t *tok_pos, int32_t *tok_slot, hipStream_t s);
+// d_prefix (optional, [n_seqs]): positions start at d_prefix[seq] instead of 0
+hipError_t launch_token_meta(const int32_t *d_cu, const int32_t *d_slots, const int32_t *d_prefix,
+                             int n_seqs, int T, int32_t *tok_seq, int32_t *tok_pos, int32_t *tok_slot,
+                             hipStream_t s);
 hipError_t launch_write_ints(int32_t *dst, const int32_t *host_src, int n, hipStream_t s);
 // dst[idx[i]] = val[i] for i < n (host arrays, carried by value in the kernel arguments)
 hipError_t launch_scatter_ints(int32_t *dst, const int32_t *host_idx, const int32_t *host_val, int n,
@@ -116,9 +118,9 @@ hipError_t launch_scatter_ints(int32_t *dst, const int32_t *host_idx, const int3
 // decode meta: for b in [0,B): pos[b] = len[slot[b]]; len[slot[b]] += 1
 hipError_t launch_decode_meta(const int32_t *d_slots, int B, int32_t *d_len, int32_t *d_pos,
                               hipStream_t s);
-// prefill: len[slot[s]] = cu[s+1]-cu[s]
+// prefill: len[slot[s]] = cu[s+1]-cu[s]  (add != 0: += instead of =)
 hipError_t launch_prefill_set_len(const int32_t *d_slots, const int32_t *d_cu, int n_seqs,
-                                  int32_t *d_len, hipStream_t s);
+                                  int32_t *d_len, int add, hipStream_t s);
 
 struct RopeArgs {
     void *qkv;               // [T, (Hq+2Hkv)*hd]; q and k rotated in place
@@ -152,6 +154,13 @@ struct AttnArgs {
     // prefill tiling helpers
     const int32_t *d_cu;     // [n_seqs+1]
     int32_t n_seqs, max_seq_len;
+    // chunked prefill on the matrix-core kernel (all null / 0 for an ordinary prefill): the keys of
+    // sequence s are rows k_cu[s] .. k_cu[s] + prefix[s] + L_s - 1 of the plain key buffer kx
+    // ([rows][Hkv*128], row stride kx_ld), and query i of the sequence sees keys 0 .. prefix[s] + i
+    const void *kx;
+    int32_t kx_ld;
+    const int32_t *k_cu;     // [n_seqs+1]
+    const int32_t *prefix;   // [n_seqs]
 };
 hipError_t launch_attn_generic(int dtype, const AttnArgs &a, hipStream_t s);
 bool attn_prefill_mfma_supported(const AttnArgs &a);
@@ -159,6 +168,12 @@ bool attn_prefill_mfma_supported(const AttnArgs &a);
 // (each sequence start rounded up to a multiple of 64); pad_cu: device [n_seqs+1] padded starts.
 hipError_t launch_attn_prefill_mfma(const AttnArgs &a, uint16_t *vt, int vt_ld, const int32_t *pad_cu,
                                     hipStream_t s);
+// Chunked prefill over a blocked cache: copies the keys (as plain rows kx[pad_cu[s] + pos][Hkv*128])
+// and the values (transposed, vt[g][d][pad_cu[s] + pos], zero past the end) of positions
+// 0 .. prefix[s] + L_s - 1 of every sequence's slot out of the cache, then runs the prefill kernel
+// with the prefix offsets.  pad_cu: padded key-row starts (multiples of 64) of the sequences.
+hipError_t launch_attn_chunk_mfma(const AttnArgs &a, const int32_t *d_slots, uint16_t *kx, uint16_t *vt,
+                                  int vt_ld, const int32_t *pad_cu, hipStream_t s);
 
 hipError_t launch_stream_copy(void *dst, const void *src, size_t n_vec16, hipStream_t s);
 hipError_t launch_kv_copy(int dtype, void *cache_k, void *cache_v, const void *k, const void *v,

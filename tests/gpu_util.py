@@ -44,6 +44,14 @@ class GpuLayer:
         torch.cuda.synchronize()
         return to_np(out)
 
+    def prefill_chunk(self, x, cu, slots, cache, router_logits=None):
+        xd = to_dev(x, self.dtype)
+        out = torch.empty_like(xd)
+        rl = None if router_logits is None else torch.from_numpy(router_logits).cuda().contiguous()
+        pd.pd_prefill_chunk(self.h, xd, cu, slots, cache, out, rl)
+        torch.cuda.synchronize()
+        return to_np(out)
+
     def decode(self, x, slots, cache, router_logits=None):
         xd = to_dev(x, self.dtype)
         out = torch.empty_like(xd)
