@@ -396,13 +396,32 @@ static int choose_splits(const GemmArgs &a, int BM, int BN)
     return splits < 1 ? 1 : splits;
 }
 
+// Split count for chunk-sized problems (a few hundred to a few thousand rows): these are bound by
+// the matrix pipe, but 256 x 256 tiles alone leave most CUs idle, so K is split until about one
+// workgroup per CU exists (at least 8 k-tiles per split; the fp32 partials must fit the scratch).
+static int choose_splits_mid(const GemmArgs &a)
+{
+    if (!a.splitk_ws || a.group_offsets || a.a_gather || a.N % 4 != 0 || a.ldc % 4 != 0 ||
+        (a.epilogue == EPI_RESIDUAL && a.ldr % 4 != 0))
+        return 1;
+    const int n_cols = a.epilogue == EPI_SWIGLU ? 2 * a.N : a.N;
+    const int tiles = ((a.M + 255) / 256) * ((n_cols + 255) / 256);
+    if (tiles >= 192) return 1;
+    int splits = (256 + tiles / 2) / tiles;
+    const int nk = a.K / BK;
+    if (splits > nk / 8) splits = nk / 8;
+    while (splits > 1 && (size_t)splits * a.M * n_cols > a.splitk_ws_elems) --splits;
+    return splits < 1 ? 1 : splits;
+}
+
 hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t s)
 {
     if (a.M > 256) {
         // 8 waves (two per SIMD hide each other's stalls); short-K problems spend relatively more time in
         // the prologue / epilogue, where 16 waves measured 5-8 % faster
-        if (a.K <= 4096 && a.epilogue != EPI_SWIGLU && !a.group_offsets) return launch_cfg<256, 256, 4, 4, 2>(a, s);
-        return launch_cfg<256, 256, 2, 4, 2>(a, s);
+        const int splits = choose_splits_mid(a);
+        if (a.K <= 4096 && a.epilogue != EPI_SWIGLU && !a.group_offsets) return launch_cfg<256, 256, 4, 4, 2>(a, s, splits);
+        return launch_cfg<256, 256, 2, 4, 2>(a, s, splits);
     }
     const int n_cols = a.epilogue == EPI_SWIGLU ? 2 * a.N : a.N;
     const bool wide = n_cols >= 16384;                            // enough column tiles without splitting K

@@ -182,9 +182,48 @@ def run_prefill_on(layer, cfg):
         "steps_ms": {n: round(t, 4) for n, t in steps}}}
 
 
+def run_chunk(l_in=8192, chunks=(256, 512, 1024, 2048, 4096, 8192), reps=5):
+    """Prefill of one l_in-token prompt chunk by chunk (pd_prefill_chunk against the growing cached
+    prefix): throughput against the chunk size."""
+    cfg, layer = _layer("llama8b")
+    x = H._dev(I.hidden(l_in, cfg["d_model"], seed=10, dtype="bf16"), "bf16")
+    out = torch.empty_like(x)
+    cache = layer.new_cache(1, l_in)
+    pd.pd_layer_reserve(layer.h, l_in)
+    fl = H.prefill_flops(cfg, [l_in])
+    pts = []
+    for C in chunks:
+        def once():
+            pd.pd_kv_cache_set_len(cache, 0, 0)
+            for a in range(0, l_in, C):
+                b = min(l_in, a + C)
+                pd.pd_prefill_chunk(layer.h, x[a:b], [0, b - a], [0], cache, out[a:b])
+        for _ in range(2):
+            once()
+        ts = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            once()
+            e1.record()
+            e1.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        ms = H.median(ts)
+        pts.append({"chunk": C, "calls": (l_in + C - 1) // C, "ms_per_layer": round(ms, 4),
+                    "tok_s_model": round(l_in / (N_LAYERS * ms * 1e-3), 1),
+                    "tflops": round(fl / (ms * 1e-3) / 1e12, 1), "mfma_frac": round(fl / (ms * 1e-3) / MFMA_PEAK, 4)})
+    # the same prompt in one unchunked call, for reference
+    ms_full = layer.time_prefill(x, [0, l_in], iters=5, warmup=2)
+    layer.close()
+    return {"experiment": "chunked prefill: throughput vs chunk size", "l_in": l_in, "points": pts,
+            "unchunked_ms_per_layer": round(ms_full, 4)}
+
+
 def main():
     which = sys.argv[1] if len(sys.argv) > 1 else "prefill"
-    fn = {"prefill": run_prefill, "longctx": run_longctx, "queue": run_queue, "moe": run_moe}[which]
+    fn = {"prefill": run_prefill, "longctx": run_longctx, "queue": run_queue, "moe": run_moe,
+          "chunk": run_chunk}[which]
     print(json.dumps(fn()))
 
 
