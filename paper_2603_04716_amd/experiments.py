@@ -220,10 +220,108 @@ def run_chunk(l_in=8192, chunks=(256, 512, 1024, 2048, 4096, 8192), reps=5):
             "unchunked_ms_per_layer": round(ms_full, 4)}
 
 
+def run_stack(n_layers=32, n_weight_sets=4, batches=(1, 8, 64, 256), kv_len=2048):
+    """A real stack of n_layers resident layers (distinct device copies of a few seeded weight
+    sets, one KV cache per layer), each layer's output feeding the next: measured prefill time and
+    TPOT of the whole stack beside n_layers x the single-layer time that the sweeps scale up."""
+    cfg = I.CONFIGS["llama8b"]
+    d = cfg["d_model"]
+    host_sets = [I.layer_weights(cfg, seed=s0) for s0 in range(n_weight_sets)]
+    layers = [H.Layer(cfg, host_sets[i % n_weight_sets]) for i in range(n_layers)]
+    del host_sets
+    T, l_in = 8192, 2048
+    cu = I.uniform_cu_seqlens(T // l_in, l_in)
+    x = H._dev(I.hidden(T, d, seed=10, dtype="bf16"), "bf16")
+    bufs = [torch.empty_like(x), torch.empty_like(x)]
+    for L in layers:
+        pd.pd_layer_reserve(L.h, T)
+
+    def prefill_stack():
+        src = x
+        for i, L in enumerate(layers):
+            pd.pd_prefill(L.h, src, cu, bufs[i & 1])
+            src = bufs[i & 1]
+
+    def timed(fn, reps):
+        ts = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            e1.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        return H.median(ts)
+
+    prefill_stack()
+    ms_stack = timed(prefill_stack, 5)
+    ms_one = layers[0].time_prefill(x, cu, iters=10, warmup=3)
+    res = {"experiment": "resident layer stack vs single layer scaled up", "n_layers": n_layers,
+           "prefill": {"tokens": T, "l_in": l_in, "stack_ms": round(ms_stack, 3),
+                       "single_layer_ms_x_layers": round(ms_one * n_layers, 3),
+                       "tok_s_stack": round(T / (ms_stack * 1e-3), 1),
+                       "tok_s_scaled": round(T / (ms_one * n_layers * 1e-3), 1)}, "decode": []}
+    finite = bool(torch.isfinite(bufs[(n_layers - 1) & 1].float()).all())
+    res["prefill"]["output_finite"] = finite
+
+    bmax = max(batches)
+    k, v = I.kv_fill(cfg["n_kv_heads"], kv_len, cfg["head_dim"], seed=11, dtype="bf16")
+    kd, vd = H._dev(k, "bf16"), H._dev(v, "bf16")
+    caches = [L.new_cache(bmax, kv_len + 8) for L in layers]
+    for L, c in zip(layers, caches):
+        L.fill_cache(c, [kv_len] * bmax, kd, vd)
+    xdec = H._dev(I.hidden(bmax, d, seed=12, dtype="bf16"), "bf16")
+    for B in batches:
+        slots, lens = list(range(B)), [kv_len] * B
+        xb = xdec[:B].contiguous()
+        dbuf = [torch.empty_like(xb), torch.empty_like(xb)]
+
+        def rewind():
+            for c in caches:
+                pd.pd_kv_cache_set_lens(c, slots, lens)
+
+        def step():
+            src = xb
+            for i, (L, c) in enumerate(zip(layers, caches)):
+                pd.pd_decode_step(L.h, src, slots, c, dbuf[i & 1])
+                src = dbuf[i & 1]
+
+        for _ in range(2):
+            rewind()
+            step()
+        rewind()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(7):
+            rewind()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            graph.replay()
+            e1.record()
+            e1.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        tpot = H.median(ts)
+        one = layers[0].make_decode_step(caches[0], xb, lens)
+        ms_one_d = H.median([one() for _ in range(7)])
+        by = H.decode_bytes(cfg, lens) * n_layers
+        res["decode"].append({"batch": B, "tpot_ms_stack": round(tpot, 3),
+                              "tpot_ms_scaled": round(ms_one_d * n_layers, 3),
+                              "tok_s_stack": round(B / (tpot * 1e-3), 1),
+                              "hbm_frac_stack": round(by / (tpot * 1e-3) / HBM_PEAK, 4)})
+        del graph
+    for L in layers:
+        L.close()
+    return res
+
+
 def main():
     which = sys.argv[1] if len(sys.argv) > 1 else "prefill"
     fn = {"prefill": run_prefill, "longctx": run_longctx, "queue": run_queue, "moe": run_moe,
-          "chunk": run_chunk}[which]
+          "chunk": run_chunk, "stack": run_stack}[which]
     print(json.dumps(fn()))
 
 
