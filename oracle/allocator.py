@@ -122,3 +122,43 @@ def fifo_replay(arrivals, services):
         done = start + s
         out.append(done - a)
     return out
+
+
+def fifo_replay_batched(arrivals, batch_service, max_batch):
+    """One server that, whenever it becomes free, takes the first min(max_batch, waiting) requests
+    of the FIFO queue and serves them together (the regime the paper's "Acquire prefill throughput
+    under TTFT constraints" describes for a chunked prefill size much larger than the request
+    length: several queued requests are batched into one chunk).  batch_service[b-1] is the service
+    time of a batch of b equal-length requests; every request of a batch completes at the batch's
+    end.  An idle server starts as soon as one request is present.  Returns each request's
+    sojourn time (completion - arrival), in arrival order.  max_batch = 1 is fifo_replay with a
+    constant service time."""
+    n = len(arrivals)
+    out = [0.0] * n
+    free_at = -math.inf
+    i = 0
+    while i < n:
+        start = arrivals[i] if arrivals[i] > free_at else free_at
+        b = 1
+        while b < max_batch and i + b < n and arrivals[i + b] <= start:
+            b += 1
+        done = start + batch_service[b - 1]
+        for j in range(i, i + b):
+            out[j] = done - arrivals[j]
+        free_at = done
+        i += b
+    return out
+
+
+def effective_prefill_throughput_dp(tp_prefill_max, l_in, ttft, t_overhead, groups):
+    """Eq. (13) with prefill-side data parallelism: each of `groups` DP groups is its own M/M/1
+    queue with 1/groups of the instance's maximum throughput and of its arrivals (the paper's
+    remark under Eq. (8)), so per group TP = TP_max/groups - l_in/T_s and the instance achieves
+    groups times that."""
+    t_s = ttft - t_overhead
+    if not (t_s > 0.0):
+        raise TTFTInfeasible("TTFT - T_overhead <= 0")
+    per_group = (tp_prefill_max / groups) - (l_in / t_s)
+    if not (per_group > 0.0):
+        raise TTFTInfeasible("Eq. (13) per DP group <= 0")
+    return groups * per_group

@@ -178,3 +178,70 @@ def test_fifo_replay_brute_force_and_mm1_limit():
     assert A.mg1_sojourn(lam, 1 / mu, 2 / mu ** 2) == pytest.approx(A.mm1_sojourn(mu, lam), rel=1e-12)
     # ... and to the M/D/1 value for constant service
     assert A.mg1_sojourn(0.5, 1.0, 1.0) == pytest.approx(1.0 + 0.5 / (2 * 0.5), rel=1e-12)
+
+
+# ---- queue-model variants -------------------------------------------------------------------------
+
+def brute_batched(arrivals, batch_service, max_batch):
+    """Event-by-event simulation with an explicit queue, written independently of the oracle's loop."""
+    n = len(arrivals)
+    done = [None] * n
+    queue, t, nxt, busy_until, serving = [], 0.0, 0, None, []
+    while any(d is None for d in done):
+        # next event: an arrival or the end of the running batch
+        ta = arrivals[nxt] if nxt < n else math.inf
+        tb = busy_until if busy_until is not None else math.inf
+        if tb <= ta:
+            t = tb
+            for j in serving:
+                done[j] = t - arrivals[j]
+            serving, busy_until = [], None
+        else:
+            t = ta
+            queue.append(nxt)
+            nxt += 1
+            while nxt < n and arrivals[nxt] == t:
+                queue.append(nxt)
+                nxt += 1
+        if busy_until is None and queue:
+            serving, queue = queue[:max_batch], queue[max_batch:]
+            busy_until = t + batch_service[len(serving) - 1]
+    return done
+
+
+def test_batched_replay_against_event_simulation_and_unbatched():
+    rng = np.random.default_rng(3)
+    for trial in range(40):
+        n = int(rng.integers(1, 60))
+        arr = np.cumsum(rng.exponential(1.0, n)).tolist()
+        if trial % 5 == 0:
+            arr = sorted(round(a, 0) for a in arr)              # ties in arrival time
+        mb = int(rng.integers(1, 5))
+        bs = np.cumsum(rng.uniform(0.2, 1.5, mb)).tolist()      # longer batches take longer
+        got = A.fifo_replay_batched(arr, bs, mb)
+        ref = brute_batched(arr, bs, mb)
+        assert np.allclose(got, ref, rtol=0, atol=1e-12), trial
+    arr = np.cumsum(rng.exponential(0.7, 200)).tolist()
+    assert A.fifo_replay_batched(arr, [0.6], 1) == A.fifo_replay(arr, [0.6] * 200)
+
+
+def test_batching_never_hurts_when_a_batch_costs_no_more_than_its_requests_in_turn():
+    rng = np.random.default_rng(4)
+    arr = np.cumsum(rng.exponential(0.5, 3000)).tolist()
+    one = np.mean(A.fifo_replay_batched(arr, [0.45], 1))
+    three = np.mean(A.fifo_replay_batched(arr, [0.45, 0.9, 1.35], 3))      # exactly additive cost
+    sub = np.mean(A.fifo_replay_batched(arr, [0.45, 0.8, 1.1], 3))         # batching is cheaper
+    assert sub < three
+    assert sub < one
+
+
+def test_dp_groups_reduce_to_eq13_and_keep_the_mm1_identity():
+    tp, l_in, ttft, tov = 28300.0, 6144.0, 2.0, 0.1
+    assert A.effective_prefill_throughput_dp(tp, l_in, ttft, tov, 1) == A.effective_prefill_throughput(tp, l_in, ttft, tov)
+    for g in (2, 4, 8):
+        total = A.effective_prefill_throughput_dp(tp, l_in, ttft, tov, g)
+        lam_g, mu_g = (total / g) / l_in, (tp / g) / l_in       # per-group rates, Eq. (9)
+        assert abs(A.mm1_sojourn(mu_g, lam_g) - (ttft - tov)) < 1e-9
+        assert total < A.effective_prefill_throughput(tp, l_in, ttft, tov)   # each split queue idles more
+    with pytest.raises(A.TTFTInfeasible):
+        A.effective_prefill_throughput_dp(tp, l_in, ttft, tov, 16)           # 28300/16 < 6144/1.9
