@@ -252,6 +252,30 @@ pd_status pd_fifo_replay(int32_t n, const double *arrival_s, const double *servi
                          double *sojourn_s);
 pd_status pd_mm1_sojourn(double prefill_max_tps, double l_in, double lambda_rps, double *t_s);
 
+/*
+ * Queue-model variants (host only).
+ * pd_fifo_replay_batched: one server that, whenever it becomes free, takes the first
+ * min(max_batch, waiting) requests of the FIFO queue and serves them together in
+ * batch_service_s[b-1] seconds (host [max_batch]; equal-length requests); every request of a batch
+ * completes at the batch's end; an idle server starts as soon as one request is present.  This is
+ * the regime the paper describes for a chunked prefill size much larger than the request length
+ * (section "Acquire prefill throughput under TTFT constraints").  Writes each request's sojourn
+ * time in arrival order.  max_batch = 1 is pd_fifo_replay with a constant service time.
+ * pd_prefill_throughput_dp: Eq. (13) with prefill-side data parallelism, each of dp_groups groups
+ * its own M/M/1 queue with 1/dp_groups of the maximum throughput and of the arrivals (the remark
+ * under Eq. (8)): dp_groups * (prefill_max_tps / dp_groups - l_in / (ttft_slo_s - t_overhead_s)).
+ * pd_mg1_sojourn: the Pollaczek-Khinchine mean sojourn time E[S] + lambda E[S^2] / (2 (1 - rho)),
+ * context beside Eq. (12) for service times that are not exponential (not part of the paper).
+ * Errors: PD_ERR_INVALID_ARG; PD_ERR_TTFT_INFEASIBLE where no stable queue / positive throughput
+ * exists.  Outputs untouched on error.
+ */
+pd_status pd_fifo_replay_batched(int32_t n, const double *arrival_s, int32_t max_batch,
+                                 const double *batch_service_s, double *sojourn_s);
+pd_status pd_prefill_throughput_dp(double prefill_max_tps, double l_in, double ttft_slo_s,
+                                   double t_overhead_s, int32_t dp_groups, double *tp_prefill);
+pd_status pd_mg1_sojourn(double lambda_rps, double mean_service_s, double mean_service_sq_s2,
+                         double *t_s);
+
 const char *pd_status_string(pd_status s);
 const char *pd_last_error(void);
 

@@ -24,7 +24,7 @@ EXPORTS = [
     "pd_layer_create", "pd_layer_destroy", "pd_layer_reserve", "pd_kv_cache_create",
     "pd_kv_cache_destroy", "pd_kv_cache_set", "pd_kv_cache_set_len", "pd_kv_cache_len",
     "pd_kv_cache_set_lens", "pd_kv_cache_get", "pd_profile_enable", "pd_profile_read", "pd_stream_copy", "pd_prefill", "pd_prefill_chunk", "pd_decode_step", "pd_last_expert_choice", "pd_allocate",
-    "pd_fifo_replay", "pd_mm1_sojourn", "pd_status_string", "pd_last_error",
+    "pd_fifo_replay", "pd_mm1_sojourn", "pd_fifo_replay_batched", "pd_prefill_throughput_dp", "pd_mg1_sojourn", "pd_status_string", "pd_last_error",
 ]
 
 
@@ -86,6 +86,8 @@ lib.pd_layer_destroy.argtypes = [C.c_void_p]
 lib.pd_kv_cache_destroy.argtypes = [C.c_void_p]
 lib.pd_allocate.argtypes = [C.c_double] * 5 + [C.POINTER(pd_measured_curves), C.POINTER(pd_allocation)]
 lib.pd_mm1_sojourn.argtypes = [C.c_double] * 3 + [C.POINTER(C.c_double)]
+lib.pd_mg1_sojourn.argtypes = [C.c_double] * 3 + [C.POINTER(C.c_double)]
+lib.pd_prefill_throughput_dp.argtypes = [C.c_double] * 4 + [C.c_int32, C.POINTER(C.c_double)]
 
 
 def _check(status):
@@ -247,4 +249,28 @@ def pd_fifo_replay(arrival_s, service_s):
 def pd_mm1_sojourn(prefill_max_tps, l_in, lambda_rps):
     t = C.c_double()
     _check(lib.pd_mm1_sojourn(float(prefill_max_tps), float(l_in), float(lambda_rps), C.byref(t)))
+    return t.value
+
+
+def pd_fifo_replay_batched(arrival_s, batch_service_s, max_batch):
+    n = len(arrival_s)
+    a = (C.c_double * max(n, 1))(*[float(x) for x in arrival_s])
+    bs = (C.c_double * max(len(batch_service_s), 1))(*[float(x) for x in batch_service_s])
+    o = (C.c_double * max(n, 1))()
+    if len(batch_service_s) < max_batch:
+        raise ValueError("pd_fifo_replay_batched: batch_service_s shorter than max_batch")
+    _check(lib.pd_fifo_replay_batched(C.c_int32(n), a, C.c_int32(max_batch), bs, o))
+    return [o[i] for i in range(n)]
+
+
+def pd_prefill_throughput_dp(prefill_max_tps, l_in, ttft_slo_s, t_overhead_s, dp_groups):
+    t = C.c_double()
+    _check(lib.pd_prefill_throughput_dp(float(prefill_max_tps), float(l_in), float(ttft_slo_s),
+                                        float(t_overhead_s), C.c_int32(dp_groups), C.byref(t)))
+    return t.value
+
+
+def pd_mg1_sojourn(lambda_rps, mean_service_s, mean_service_sq_s2):
+    t = C.c_double()
+    _check(lib.pd_mg1_sojourn(float(lambda_rps), float(mean_service_s), float(mean_service_sq_s2), C.byref(t)))
     return t.value

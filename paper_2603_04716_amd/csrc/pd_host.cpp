@@ -160,6 +160,79 @@ extern "C" pd_status pd_fifo_replay(int32_t n, const double *arrival_s, const do
     return PD_OK;
 }
 
+extern "C" pd_status pd_fifo_replay_batched(int32_t n, const double *arrival_s, int32_t max_batch,
+                                            const double *batch_service_s, double *sojourn_s)
+{
+    if (n < 0 || max_batch < 1 || !batch_service_s || (n > 0 && (!arrival_s || !sojourn_s))) {
+        pd::set_error("pd_fifo_replay_batched: bad arguments");
+        return PD_ERR_INVALID_ARG;
+    }
+    for (int32_t b = 0; b < max_batch; ++b)
+        if (!std::isfinite(batch_service_s[b]) || batch_service_s[b] < 0.0) {
+            pd::set_error("pd_fifo_replay_batched: bad service time for a batch of %d", b + 1);
+            return PD_ERR_INVALID_ARG;
+        }
+    double prev_a = -INFINITY;
+    for (int32_t i = 0; i < n; ++i) {
+        if (!std::isfinite(arrival_s[i]) || arrival_s[i] < prev_a) {
+            pd::set_error("pd_fifo_replay_batched: request %d has a bad arrival time", i);
+            return PD_ERR_INVALID_ARG;
+        }
+        prev_a = arrival_s[i];
+    }
+    double free_at = -INFINITY;
+    int32_t i = 0;
+    while (i < n) {
+        const double start = arrival_s[i] > free_at ? arrival_s[i] : free_at;
+        int32_t b = 1;
+        while (b < max_batch && i + b < n && arrival_s[i + b] <= start) ++b;
+        const double done = start + batch_service_s[b - 1];
+        for (int32_t j = i; j < i + b; ++j) sojourn_s[j] = done - arrival_s[j];
+        free_at = done;
+        i += b;
+    }
+    return PD_OK;
+}
+
+extern "C" pd_status pd_prefill_throughput_dp(double prefill_max_tps, double l_in, double ttft_slo_s,
+                                              double t_overhead_s, int32_t dp_groups, double *tp_prefill)
+{
+    if (!tp_prefill || !pos_finite(prefill_max_tps) || !pos_finite(l_in) || !pos_finite(ttft_slo_s) ||
+        !std::isfinite(t_overhead_s) || t_overhead_s < 0.0 || dp_groups < 1) {
+        pd::set_error("pd_prefill_throughput_dp: bad arguments");
+        return PD_ERR_INVALID_ARG;
+    }
+    const double t_s = ttft_slo_s - t_overhead_s;                       // Eq. (12)
+    if (!(t_s > 0.0)) {
+        pd::set_error("pd_prefill_throughput_dp: TTFT - T_overhead = %g <= 0", t_s);
+        return PD_ERR_TTFT_INFEASIBLE;
+    }
+    const double per_group = (prefill_max_tps / dp_groups) - (l_in / t_s);   // Eq. (13) of one group
+    if (!(per_group > 0.0)) {
+        pd::set_error("pd_prefill_throughput_dp: a group's bare compute time exceeds TTFT - T_overhead");
+        return PD_ERR_TTFT_INFEASIBLE;
+    }
+    *tp_prefill = dp_groups * per_group;
+    return PD_OK;
+}
+
+extern "C" pd_status pd_mg1_sojourn(double lambda_rps, double mean_service_s, double mean_service_sq_s2,
+                                    double *t_s)
+{
+    if (!t_s || !std::isfinite(lambda_rps) || lambda_rps < 0.0 || !pos_finite(mean_service_s) ||
+        !pos_finite(mean_service_sq_s2)) {
+        pd::set_error("pd_mg1_sojourn: bad arguments");
+        return PD_ERR_INVALID_ARG;
+    }
+    const double rho = lambda_rps * mean_service_s;
+    if (!(rho < 1.0)) {
+        pd::set_error("pd_mg1_sojourn: utilisation %g >= 1", rho);
+        return PD_ERR_TTFT_INFEASIBLE;
+    }
+    *t_s = mean_service_s + lambda_rps * mean_service_sq_s2 / (2.0 * (1.0 - rho));
+    return PD_OK;
+}
+
 extern "C" pd_status pd_mm1_sojourn(double prefill_max_tps, double l_in, double lambda_rps,
                                     double *t_s)
 {

@@ -220,6 +220,43 @@ def run_chunk(l_in=8192, chunks=(256, 512, 1024, 2048, 4096, 8192), reps=5):
             "unchunked_ms_per_layer": round(ms_full, 4)}
 
 
+def run_queue_fixed(n_req=2000):
+    """The paper's own queue check: a fixed request input length, (a) chunked prefill size equal to
+    it (requests served one by one), (b) a chunk several times larger (queued requests are batched
+    into one prefill call).  Service times of batches of 1..k requests are measured on the GPU
+    (x N_LAYERS), arrivals are Poisson, the queue is replayed in virtual time; mean TTFT beside
+    Eq. (12) and the Pollaczek-Khinchine value for the constant service time."""
+    cfg, layer = _layer("llama8b")
+    d = cfg["d_model"]
+    out = {"experiment": "queue check at a fixed input length, chunk = L_in and chunk = k L_in", "requests": n_req,
+           "cases": []}
+    for l_in, k in ((4096, 3), (6144, 4)):
+        x = H._dev(I.hidden(l_in * k, d, seed=10, dtype="bf16"), "bf16")
+        svc = []
+        for b in range(1, k + 1):
+            ms = layer.time_prefill(x[:l_in * b], I.uniform_cu_seqlens(b, l_in), iters=8, warmup=3)
+            svc.append(N_LAYERS * ms * 1e-3)
+        mu = 1.0 / svc[0]
+        case = {"l_in": l_in, "chunk_batched": l_in * k, "batch_service_s": [round(t, 5) for t in svc],
+                "tp_prefill_max_tok_s": round(l_in * mu, 1), "mu_req_s": round(mu, 4), "rates": []}
+        for f in (0.3, 0.5, 0.7, 0.9):
+            lam = f * mu
+            arr = I.poisson_arrivals(n_req, lam, seed=int(100 * f) + l_in)
+            one = pd.pd_fifo_replay_batched(arr, svc[:1], 1)
+            bat = pd.pd_fifo_replay_batched(arr, svc, k)
+            mm1 = pd.pd_mm1_sojourn(l_in * mu, l_in, lam)
+            pk = pd.pd_mg1_sojourn(lam, svc[0], svc[0] * svc[0])
+            case["rates"].append({"load": f, "lambda_req_s": round(lam, 4),
+                                  "mean_ttft_chunk_eq_lin_s": round(float(np.mean(one)), 5),
+                                  "mean_ttft_chunk_k_lin_s": round(float(np.mean(bat)), 5),
+                                  "mm1_pred_s": round(mm1, 5), "md1_pk_s": round(pk, 5),
+                                  "ratio_unbatched_over_mm1": round(float(np.mean(one)) / mm1, 4),
+                                  "ratio_batched_over_mm1": round(float(np.mean(bat)) / mm1, 4)})
+        out["cases"].append(case)
+    layer.close()
+    return out
+
+
 def run_stack(n_layers=32, n_weight_sets=4, batches=(1, 8, 64, 256), kv_len=2048):
     """A real stack of n_layers resident layers (distinct device copies of a few seeded weight
     sets, one KV cache per layer), each layer's output feeding the next: measured prefill time and
@@ -321,7 +358,7 @@ def run_stack(n_layers=32, n_weight_sets=4, batches=(1, 8, 64, 256), kv_len=2048
 def main():
     which = sys.argv[1] if len(sys.argv) > 1 else "prefill"
     fn = {"prefill": run_prefill, "longctx": run_longctx, "queue": run_queue, "moe": run_moe,
-          "chunk": run_chunk, "stack": run_stack}[which]
+          "chunk": run_chunk, "stack": run_stack, "queue_fixed": run_queue_fixed}[which]
     print(json.dumps(fn()))
 
 

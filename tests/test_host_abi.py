@@ -104,3 +104,33 @@ def test_fifo_replay_and_mm1_match_oracle():
     with pytest.raises(pd.PdError) as e:
         pd.pd_mm1_sojourn(28300, 6144, 28300 / 6144)
     assert e.value.status == pd.PD_ERR_TTFT_INFEASIBLE
+
+
+def test_queue_variants_bit_exact_against_oracle():
+    rng = np.random.default_rng(11)
+    for trial in range(200):
+        n = int(rng.integers(0, 80))
+        arr = np.cumsum(rng.exponential(1.0, n)).tolist()
+        if trial % 4 == 0:
+            arr = sorted(round(a, 0) for a in arr)
+        mb = int(rng.integers(1, 6))
+        bs = np.cumsum(rng.uniform(0.1, 1.5, mb)).tolist()
+        assert pd.pd_fifo_replay_batched(arr, bs, mb) == A.fifo_replay_batched(arr, bs, mb)
+    for trial in range(500):
+        tp, l_in = float(rng.uniform(1e3, 3e5)), float(rng.integers(16, 16384))
+        ttft, tov, g = float(rng.uniform(0.05, 5)), float(rng.uniform(0, 0.2)), int(rng.integers(1, 9))
+        try:
+            ref = A.effective_prefill_throughput_dp(tp, l_in, ttft, tov, g)
+        except A.TTFTInfeasible:
+            with pytest.raises(pd.PdError) as e:
+                pd.pd_prefill_throughput_dp(tp, l_in, ttft, tov, g)
+            assert e.value.status == pd.PD_ERR_TTFT_INFEASIBLE
+            continue
+        assert pd.pd_prefill_throughput_dp(tp, l_in, ttft, tov, g) == ref
+        lam, ms = float(rng.uniform(0.1, 5)), float(rng.uniform(0.01, 0.15))
+        ms2 = ms * ms * float(rng.uniform(1.0, 3.0))
+        assert pd.pd_mg1_sojourn(lam, ms, ms2) == A.mg1_sojourn(lam, ms, ms2)
+    with pytest.raises(pd.PdError):
+        pd.pd_fifo_replay_batched([2.0, 1.0], [0.5], 1)              # arrivals not sorted
+    with pytest.raises(pd.PdError):
+        pd.pd_mg1_sojourn(10.0, 0.2, 0.05)                           # utilisation 2
