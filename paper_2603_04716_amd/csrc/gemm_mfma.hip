@@ -382,11 +382,13 @@ static hipError_t launch_cfg(const GemmArgs &a, hipStream_t s, int splits = 1)
 // fit the scratch buffer.
 static int choose_splits(const GemmArgs &a, int BM, int BN)
 {
-    if (!a.splitk_ws || a.group_offsets || a.a_gather || a.N % 4 != 0 || a.ldc % 4 != 0 ||
-        (a.epilogue == EPI_RESIDUAL && a.ldr % 4 != 0))
+    if (!a.splitk_ws || a.N % 4 != 0 || a.ldc % 4 != 0 || (a.epilogue == EPI_RESIDUAL && a.ldr % 4 != 0))
         return 1;
     const int n_cols = a.epilogue == EPI_SWIGLU ? 2 * a.N : a.N;
-    const int tiles = ((a.M + BM - 1) / BM) * ((n_cols + BN - 1) / BN);
+    // row tiles that do work: for a grouped problem at most one per group and per row (rows are few here)
+    int row_tiles = (a.M + BM - 1) / BM;
+    if (a.group_offsets) row_tiles = a.M < a.n_groups ? a.M : a.n_groups;
+    const int tiles = row_tiles * ((n_cols + BN - 1) / BN);
     const int nk = a.K / BK;
     int splits = (256 + tiles / 2) / tiles;
     if (splits > nk / 4) splits = nk / 4;
@@ -416,7 +418,10 @@ static int choose_splits_mid(const GemmArgs &a)
 
 hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t s)
 {
-    if (a.M > 256) {
+    // rows that share a weight matrix: for a grouped problem the mean group size picks the tile
+    // (larger groups take several row tiles)
+    const int rows = a.group_offsets ? (a.M + a.n_groups - 1) / a.n_groups : a.M;
+    if (rows > 256) {
         // 8 waves (two per SIMD hide each other's stalls); short-K problems spend relatively more time in
         // the prologue / epilogue, where 16 waves measured 5-8 % faster
         const int splits = choose_splits_mid(a);
@@ -425,11 +430,11 @@ hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t s)
     }
     const int n_cols = a.epilogue == EPI_SWIGLU ? 2 * a.N : a.N;
     const bool wide = n_cols >= 16384;                            // enough column tiles without splitting K
-    if (a.M > 128) {
+    if (rows > 128) {
         if (wide) return launch_cfg<256, 128, 4, 2, 3>(a, s, 1);
         return launch_cfg<256, 64, 8, 1, 3>(a, s, choose_splits(a, 256, 64));
     }
-    if (a.M > 64) return launch_cfg<128, 64, 4, 1, 4>(a, s, wide ? 1 : choose_splits(a, 128, 64));
+    if (rows > 64) return launch_cfg<128, 64, 4, 1, 4>(a, s, wide ? 1 : choose_splits(a, 128, 64));
     return launch_cfg<64, 128, 2, 2, 4>(a, s, wide ? 1 : choose_splits(a, 64, 128));
 }
 

@@ -9,6 +9,12 @@
 // waves split K and combine through LDS in a fixed order, so results are deterministic.
 // Epilogues as in the tiled GEMM; for SwiGLU the workgroup takes the gate block and the matching
 // up block of the interleaved weight pack.
+//
+// Grouped form (mixture-of-experts decode): blockIdx.y is the group; its rows
+// group_offsets[g] .. group_offsets[g+1]-1 (gathered through a_gather) multiply the group's own
+// weight matrix, 16 rows per pass over the weights (a group of more than 16 rows streams them
+// again, so the launcher takes this kernel only while groups average 8 rows or fewer); a group
+// without rows exits at once, so only the experts that were chosen are streamed.
 #include "pd_internal.h"
 
 namespace pd {
@@ -40,12 +46,23 @@ __global__ __launch_bounds__(64 * GV_WAVES) void gemv_mfma_kernel(GemmArgs a)
     const int per = (ksteps + GV_WAVES - 1) / GV_WAVES;
     const int s_begin = wave * per, s_end = min(ksteps, s_begin + per);
 
+    // rows of this workgroup: all M, or the rows of group blockIdx.y
+    int lo = 0, n_rows = a.M;
     const uint16_t *W = (const uint16_t *)a.B;
+    if (a.group_offsets) {
+        lo = a.group_offsets[blockIdx.y];
+        n_rows = a.group_offsets[blockIdx.y + 1] - lo;
+        if (n_rows <= 0) return;                      // uniform over the workgroup
+        W += (size_t)blockIdx.y * a.b_group_stride;
+    }
     const uint16_t *wp[RB];   // block (row0/16, 0) of the packed layout, this lane's 16 bytes
 #pragma unroll
     for (int i = 0; i < RB; ++i) wp[i] = W + (size_t)(row0[i] >> 4) * (a.K >> 5) * 512 + lane * 8;
-    const bool xrow = r < a.M;
-    const uint16_t *xp = (const uint16_t *)a.A + (size_t)(xrow ? r : 0) * a.lda + kg * 8;
+    for (int rb0 = 0; rb0 < n_rows; rb0 += 16) {      // one pass per 16 rows (uniform over the workgroup)
+    const bool xrow = rb0 + r < n_rows;
+    int arow = xrow ? lo + rb0 + r : lo;
+    if (a.a_gather) arow = a.a_gather[arow];
+    const uint16_t *xp = (const uint16_t *)a.A + (size_t)arow * a.lda + kg * 8;
 
     f32x4 acc[RB];
 #pragma unroll
@@ -82,44 +99,52 @@ __global__ __launch_bounds__(64 * GV_WAVES) void gemv_mfma_kernel(GemmArgs a)
 #pragma unroll
     for (int i = 0; i < RB; ++i) red[wave][i][lane] = acc[i];
     __syncthreads();
-    if (wave != 0) return;
-    f32x4 tot[RB];
+    if (wave == 0 && xrow) {
+        f32x4 tot[RB];
 #pragma unroll
-    for (int i = 0; i < RB; ++i) {
-        tot[i] = red[0][i][lane];
+        for (int i = 0; i < RB; ++i) {
+            tot[i] = red[0][i][lane];
 #pragma unroll
-        for (int w = 1; w < GV_WAVES; ++w) tot[i] += red[w][i][lane];
-    }
-    // lane (batch row b = r, kg): register j is weight row 4*kg + j of the block
-    if (!xrow) return;
-    uint16_t *C = (uint16_t *)a.C + (size_t)r * a.ldc;
-    const int col = blk * 16 + 4 * kg;                // first of 4 consecutive output columns
-    float v[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        if (EPI == EPI_SWIGLU) {
-            float gte = tot[0][j];
-            v[j] = gte / (1.0f + __expf(-gte)) * tot[RB - 1][j];
-        } else {
-            v[j] = tot[0][j];
+            for (int w = 1; w < GV_WAVES; ++w) tot[i] += red[w][i][lane];
         }
+        // lane (batch row rb0 + r, kg): register j is weight row 4*kg + j of the block
+        const int m = lo + rb0 + r;
+        uint16_t *C = (uint16_t *)a.C + (size_t)m * a.ldc;
+        const int col = blk * 16 + 4 * kg;            // first of 4 consecutive output columns
+        float v[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (EPI == EPI_SWIGLU) {
+                float gte = tot[0][j];
+                v[j] = gte / (1.0f + __expf(-gte)) * tot[RB - 1][j];
+            } else {
+                v[j] = tot[0][j];
+            }
+        }
+        if (EPI == EPI_RESIDUAL) {
+            uint2 rr = *(const uint2 *)((const uint16_t *)a.R + (size_t)m * a.ldr + col);
+            v[0] += bfbits2f(rr.x & 0xffffu);
+            v[1] += bfbits2f(rr.x >> 16);
+            v[2] += bfbits2f(rr.y & 0xffffu);
+            v[3] += bfbits2f(rr.y >> 16);
+        }
+        uint2 o;
+        o.x = pack2bf(v[0], v[1]);
+        o.y = pack2bf(v[2], v[3]);
+        *(uint2 *)(C + col) = o;
     }
-    if (EPI == EPI_RESIDUAL) {
-        uint2 rr = *(const uint2 *)((const uint16_t *)a.R + (size_t)r * a.ldr + col);
-        v[0] += bfbits2f(rr.x & 0xffffu);
-        v[1] += bfbits2f(rr.x >> 16);
-        v[2] += bfbits2f(rr.y & 0xffffu);
-        v[3] += bfbits2f(rr.y >> 16);
+    __syncthreads();                                  // red is reused by the next pass
     }
-    uint2 o;
-    o.x = pack2bf(v[0], v[1]);
-    o.y = pack2bf(v[2], v[3]);
-    *(uint2 *)(C + col) = o;
 }
 
 bool gemv_mfma_supported(const GemmArgs &a)
 {
-    if (a.M < 1 || a.M > 16 || a.a_gather || a.group_offsets) return false;
+    if (a.M < 1) return false;
+    if (a.group_offsets) {
+        if (a.n_groups < 1 || a.n_groups > 65535 || a.M > 8 * a.n_groups) return false;
+    } else if (a.M > 16 || a.a_gather) {
+        return false;
+    }
     if (a.K % 32 != 0 || a.N % 16 != 0 || a.lda % 8 != 0 || a.ldb % 8 != 0) return false;
     if (a.ldc % 4 != 0 || (a.epilogue == EPI_RESIDUAL && a.ldr % 4 != 0)) return false;
     if (!a.packed || a.ldb != a.K) return false;
@@ -129,7 +154,7 @@ bool gemv_mfma_supported(const GemmArgs &a)
 
 hipError_t launch_gemv_mfma(const GemmArgs &a, hipStream_t s)
 {
-    const dim3 grid(a.N / 16), block(64 * GV_WAVES);
+    const dim3 grid(a.N / 16, a.group_offsets ? a.n_groups : 1), block(64 * GV_WAVES);
     switch (a.epilogue) {
     case EPI_NONE: gemv_mfma_kernel<EPI_NONE><<<grid, block, 0, s>>>(a); break;
     case EPI_RESIDUAL: gemv_mfma_kernel<EPI_RESIDUAL><<<grid, block, 0, s>>>(a); break;

@@ -286,3 +286,60 @@ def test_stream_copy_is_bit_exact_and_checks_arguments():
     assert e.value.status == pd.PD_ERR_INVALID_ARG
     with pytest.raises(pd.PdError):
         pd.pd_stream_copy(torch.zeros(9, dtype=torch.int32, device="cuda")[1:], src[:8])  # misaligned
+
+
+@pytest.mark.parametrize("B", [1, 3, 8, 9, 40])
+def test_bf16_moe_decode_batch_sizes(B):
+    """Mixture-of-experts decode on the matrix-core path: up to 16 (token, expert) pairs run the
+    grouped skinny GEMM (only chosen experts are streamed), more run the grouped tiled GEMM with
+    tiles sized by the mean group; routing decisions are compared bit for bit."""
+    cfg = I.small_config(dtype="bf16", d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=128, d_ff=256,
+                         n_experts=8, top_k=2)
+    ol, gl = both(cfg, std=0.05)
+    rng = np.random.default_rng(100 + B)
+    lens = rng.integers(1, 200, B)
+    cap = 208
+    oc, gc = O.KVCache(ol, B, cap), gl.cache(B, cap)
+    for i, n in enumerate(lens):
+        k, v = I.kv_fill(2, int(n), 128, seed=2000 + i, dtype="bf16")
+        oc.set(i, k, v)
+        pd.pd_kv_cache_set(gc, i, to_dev(k, "bf16"), to_dev(v, "bf16"))
+    slots = list(range(B))
+    for step in range(2):
+        xn = I.hidden(B, cfg["d_model"], seed=41 + step, dtype="bf16")
+        rn = I.router_logits(B, 8, seed=51 + step)
+        if B >= 3:
+            rn[1] = rn[0]                         # two tokens with the same experts
+            rn[2, :] = 0.5                        # all-equal logits: experts 0 and 1
+        ref, eref = O.decode_step(ol, xn, slots, oc, router_logits=rn, return_experts=True)
+        got = gl.decode(xn, slots, gc, router_logits=rn)
+        assert np.array_equal(gl.experts(B), eref)
+        assert relmax(got, ref) <= TOL["bf16"]
+        assert max(relmax(got[i], ref[i]) for i in range(B)) <= 2 * TOL["bf16"]
+    gl.close()
+
+
+def test_bf16_moe_decode_all_tokens_on_two_experts():
+    """20 tokens that all choose experts 3 and 5: groups of 20 rows, i.e. two passes of the grouped
+    skinny GEMM over those experts' weights, and six experts that are never read."""
+    cfg = I.small_config(dtype="bf16", d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=128, d_ff=256,
+                         n_experts=8, top_k=2)
+    ol, gl = both(cfg, std=0.05)
+    B, cap = 20, 80
+    oc, gc = O.KVCache(ol, B, cap), gl.cache(B, cap)
+    for i in range(B):
+        k, v = I.kv_fill(2, 10 + 3 * i, 128, seed=3000 + i, dtype="bf16")
+        oc.set(i, k, v)
+        pd.pd_kv_cache_set(gc, i, to_dev(k, "bf16"), to_dev(v, "bf16"))
+    xn = I.hidden(B, cfg["d_model"], seed=43, dtype="bf16")
+    rn = I.router_logits(B, 8, seed=53) * 0.1
+    rn[:, 3] += 5.0
+    rn[:, 5] += 4.0
+    slots = list(range(B))
+    ref, eref = O.decode_step(ol, xn, slots, oc, router_logits=rn, return_experts=True)
+    got = gl.decode(xn, slots, gc, router_logits=rn)
+    assert np.array_equal(eref, np.tile([3, 5], (B, 1)))
+    assert np.array_equal(gl.experts(B), eref)
+    assert relmax(got, ref) <= TOL["bf16"]
+    assert max(relmax(got[i], ref[i]) for i in range(B)) <= 2 * TOL["bf16"]
+    gl.close()
