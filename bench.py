@@ -30,7 +30,7 @@ DECODE_REPS = 3                    # decode steps per batch size per step; media
 # the FETCH_SIZE / WRITE_SIZE counters scaled by a plain copy (paper_2603_04716_amd/traffic_probe.py).
 # Valid only for the kernel source the counters were taken on.
 TRAFFIC = {"source": os.path.join("paper_2603_04716_amd", "csrc", "gemm_mfma.hip"),
-           "sha256": "c13fa8e1f6d64911787516aed0c9e48374e2bd2ba9ad8fd9e2e6dcbdfaade3a1",
+           "sha256": "e519bd919fcaa1f121e7d82e83dbfcf5e415650f78526e7bca37c19826265818",
            "bytes_per_launch": 3053.7e6}
 
 
