@@ -22,7 +22,7 @@ HBM_PEAK_GBPS = 8000.0
 N_LAYERS = 32
 L_IN, N_SEQ = 2048, 4              # prefill workload: 4 x 2048 = 8192 tokens
 KV_LEN = 2048
-BATCHES = [1, 2, 4, 8, 16, 32, 64, 128, 256]
+BATCHES = [1, 2, 4, 8, 16, 32, 64, 128, 192, 224, 256]   # powers of two, refined below the largest
 TTFT_SLO, TPOT_SLO, L_OUT = 2.0, 0.020, 512.0
 PREFILL_REPS = 12                  # back-to-back prefill calls per step (each the full 8192 tokens); median
 DECODE_REPS = 3                    # decode steps per batch size per step; median
@@ -30,7 +30,7 @@ DECODE_REPS = 3                    # decode steps per batch size per step; media
 # the FETCH_SIZE / WRITE_SIZE counters scaled by a plain copy (paper_2603_04716_amd/traffic_probe.py).
 # Valid only for the kernel source the counters were taken on.
 TRAFFIC = {"source": os.path.join("paper_2603_04716_amd", "csrc", "gemm_mfma.hip"),
-           "sha256": "e519bd919fcaa1f121e7d82e83dbfcf5e415650f78526e7bca37c19826265818",
+           "sha256": "713a8bbedc35746f687f81dda155b5a38ea26467f67230eaca4fef48531e6bad",
            "bytes_per_launch": 3053.7e6}
 
 

@@ -187,7 +187,19 @@ __global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a, i
 
     float l_tot = l_run + __shfl_xor(l_run, 16, 64);
     l_tot += __shfl_xor(l_tot, 32, 64);
-    if (qi < group) {
+    if (qi < group && n_chunks == 1) {
+        // the only chunk of its sequence: normalise and store the output row directly
+        const int head = g * group + qi;
+        const float inv = 1.0f / l_tot;
+        uint16_t *op = (uint16_t *)a.o + ((size_t)b * a.Hq + head) * 128 + 4 * kg;
+#pragma unroll
+        for (int db = 0; db < 8; ++db) {
+            uint2 w2;
+            w2.x = pack2bf(oacc[db][0] * inv, oacc[db][1] * inv);
+            w2.y = pack2bf(oacc[db][2] * inv, oacc[db][3] * inv);
+            *(uint2 *)(op + 16 * db) = w2;            // channels 16*db + 4*kg + j
+        }
+    } else if (qi < group) {
         const int head = g * group + qi;
         float *po = a.part_o + ((size_t)cid * a.Hq + head) * 128;
 #pragma unroll
@@ -201,7 +213,8 @@ __global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a, i
     }
 }
 
-// o[b, head, :] = sum_c 2^(m_c - M) o_c / sum_c 2^(m_c - M) l_c over the chunks of sequence b.
+// o[b, head, :] = sum_c 2^(m_c - M) o_c / sum_c 2^(m_c - M) l_c over the chunks of sequence b
+// (sequences with a single chunk are finished by the attention kernel and skipped here).
 // The chunk weights are formed once per block (one chunk per thread, in parallel); the weighted
 // sum then reads the partial rows with independent loads.
 __global__ __launch_bounds__(128) void decode_attn_merge_kernel(DecodeAttnArgs a)
@@ -210,6 +223,7 @@ __global__ __launch_bounds__(128) void decode_attn_merge_kernel(DecodeAttnArgs a
     __shared__ float red[2];
     const int b = blockIdx.x, head = blockIdx.y, d = threadIdx.x;
     const int c0 = a.chunk_cu[b], c1 = a.chunk_cu[b + 1];
+    if (c1 - c0 == 1) return;                          // written by the attention kernel itself
     float M = -INFINITY;
     for (int c = c0 + d; c < c1; c += 128) M = fmaxf(M, a.part_ml[((size_t)c * a.Hq + head) * 2]);
 #pragma unroll

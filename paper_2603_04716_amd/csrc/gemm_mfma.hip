@@ -434,7 +434,10 @@ hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t s)
         if (wide) return launch_cfg<256, 128, 4, 2, 3>(a, s, 1);
         return launch_cfg<256, 64, 8, 1, 3>(a, s, choose_splits(a, 256, 64));
     }
-    if (rows > 64) return launch_cfg<128, 64, 4, 1, 4>(a, s, wide ? 1 : choose_splits(a, 128, 64));
+    if (rows > 64) {
+        if (wide) return launch_cfg<128, 128, 2, 2, 3>(a, s, 1);     // measured 52 vs 62 us on the gate/up shape
+        return launch_cfg<128, 64, 4, 1, 4>(a, s, choose_splits(a, 128, 64));
+    }
     return launch_cfg<64, 128, 2, 2, 4>(a, s, wide ? 1 : choose_splits(a, 64, 128));
 }
 
