@@ -162,3 +162,19 @@ def effective_prefill_throughput_dp(tp_prefill_max, l_in, ttft, t_overhead, grou
     if not (per_group > 0.0):
         raise TTFTInfeasible("Eq. (13) per DP group <= 0")
     return groups * per_group
+
+
+def allocate_stages(tp_total, l_in, l_out, stage_work, stage_tps, rounding=0):
+    """Eqs. (5), (6) for any number of independently deployed pipeline stages (the paper's
+    conclusion names encode / prefill / decode disaggregation as the generalisation): requests
+    arrive at tp_total / (l_in + l_out) per second (Eq. (1)); stage k does stage_work[k] units of
+    work per request (tokens, images, ...) at stage_tps[k] units per second per instance, and
+    every stage takes the same time (Eq. (4)), so N_k = (tp_total * work_k) / ((l_in + l_out) * tps_k).
+    Returns (real counts, integer counts)."""
+    vals = [tp_total, l_in, l_out] + list(stage_work) + list(stage_tps)
+    if len(stage_work) == 0 or len(stage_work) != len(stage_tps):
+        raise ValueError("bad stage lists")
+    if any((not math.isfinite(v)) or v <= 0.0 for v in vals):
+        raise ValueError("non-positive or non-finite input")
+    real = [(tp_total * w) / ((l_in + l_out) * t) for w, t in zip(stage_work, stage_tps)]
+    return real, [round_count(n, rounding) for n in real]

@@ -245,3 +245,20 @@ def test_dp_groups_reduce_to_eq13_and_keep_the_mm1_identity():
         assert total < A.effective_prefill_throughput(tp, l_in, ttft, tov)   # each split queue idles more
     with pytest.raises(A.TTFTInfeasible):
         A.effective_prefill_throughput_dp(tp, l_in, ttft, tov, 16)           # 28300/16 < 6144/1.9
+
+
+def test_stage_allocation_reduces_to_eqs_5_6_and_balances_every_stage():
+    # the worked example's two stages
+    real, cnt = A.allocate_stages(5e6 / 60.0, 6144.0, 512.0, [6144.0, 512.0], [25066.315789473683, 1700.0])
+    ref = A.allocate(5e6 / 60.0, 6144.0, 512.0, 2.0, 0.02, 28300.0, [34], [0.02], 0.1)
+    assert real[0] == ref["n_prefill_real"] and real[1] == ref["n_decode_real"] and cnt == [3, 4]
+    # three stages (encode: 2 images per request at 40 images/s per instance): stage times equal, Eq. (4)
+    tp_total, l_in, l_out = 2.0e5, 3000.0, 400.0
+    work, tps = [2.0, 3000.0, 400.0], [40.0, 21000.0, 1500.0]
+    real, cnt = A.allocate_stages(tp_total, l_in, l_out, work, tps, rounding=1)
+    req_rate = tp_total / (l_in + l_out)
+    for w, t, n in zip(work, tps, real):
+        assert abs(req_rate * w / (t * n) - 1.0) < 1e-12      # each stage exactly saturated
+    assert cnt == [math.ceil(n) for n in real]
+    with pytest.raises(ValueError):
+        A.allocate_stages(tp_total, l_in, l_out, [1.0], [1.0, 2.0])
