@@ -242,6 +242,21 @@ pd_status pd_allocate(double tp_total_tps, double l_in, double l_out, double ttf
                       double tpot_slo_s, const pd_measured_curves *curves, pd_allocation *out);
 
 /*
+ * Eqs. (5), (6) for any number of independently deployed pipeline stages (host only; the paper's
+ * conclusion names encode / prefill / decode disaggregation as the generalisation).  Requests
+ * arrive at tp_total_tps / (l_in + l_out) per second (Eq. (1)); stage k does work_per_request[k]
+ * units per request at stage_tps[k] units per second per instance (already SLO-constrained, e.g.
+ * Eq. (13) for prefill), and every stage takes the same time (Eq. (4)):
+ *   n_real[k] = (tp_total_tps * work_per_request[k]) / ((l_in + l_out) * stage_tps[k]),
+ * n_instances[k] rounded as in pd_allocate.  With the stages (l_in, TP_prefill), (l_out, TP_decode)
+ * this is exactly pd_allocate's pair of counts.  All arrays are host [n_stages].
+ * Errors: PD_ERR_INVALID_ARG; outputs untouched on error.
+ */
+pd_status pd_allocate_stages(int32_t n_stages, double tp_total_tps, double l_in, double l_out,
+                             const double *work_per_request, const double *stage_tps, int32_t rounding,
+                             double *n_real, int32_t *n_instances);
+
+/*
  * Queue check helpers (host only).  pd_fifo_replay serves n requests in arrival order on one
  * server in virtual time, D_i = max(A_i, D_{i-1}) + S_i, and writes each request's sojourn time
  * D_i - A_i (the queueing + computation part of TTFT, Eq. (8)).  pd_mm1_sojourn is Eq. (12),

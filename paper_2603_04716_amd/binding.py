@@ -24,7 +24,7 @@ EXPORTS = [
     "pd_layer_create", "pd_layer_destroy", "pd_layer_reserve", "pd_kv_cache_create",
     "pd_kv_cache_destroy", "pd_kv_cache_set", "pd_kv_cache_set_len", "pd_kv_cache_len",
     "pd_kv_cache_set_lens", "pd_kv_cache_get", "pd_profile_enable", "pd_profile_read", "pd_stream_copy", "pd_prefill", "pd_prefill_chunk", "pd_decode_step", "pd_last_expert_choice", "pd_allocate",
-    "pd_fifo_replay", "pd_mm1_sojourn", "pd_fifo_replay_batched", "pd_prefill_throughput_dp", "pd_mg1_sojourn", "pd_status_string", "pd_last_error",
+    "pd_fifo_replay", "pd_mm1_sojourn", "pd_fifo_replay_batched", "pd_prefill_throughput_dp", "pd_mg1_sojourn", "pd_allocate_stages", "pd_status_string", "pd_last_error",
 ]
 
 
@@ -274,3 +274,16 @@ def pd_mg1_sojourn(lambda_rps, mean_service_s, mean_service_sq_s2):
     t = C.c_double()
     _check(lib.pd_mg1_sojourn(float(lambda_rps), float(mean_service_s), float(mean_service_sq_s2), C.byref(t)))
     return t.value
+
+
+def pd_allocate_stages(tp_total_tps, l_in, l_out, work_per_request, stage_tps, rounding=0):
+    n = len(work_per_request)
+    if len(stage_tps) != n:
+        raise ValueError("pd_allocate_stages: list lengths differ")
+    w = (C.c_double * max(n, 1))(*[float(x) for x in work_per_request])
+    t = (C.c_double * max(n, 1))(*[float(x) for x in stage_tps])
+    real = (C.c_double * max(n, 1))()
+    cnt = (C.c_int32 * max(n, 1))()
+    _check(lib.pd_allocate_stages(C.c_int32(n), C.c_double(tp_total_tps), C.c_double(l_in), C.c_double(l_out),
+                                  w, t, C.c_int32(rounding), real, cnt))
+    return [real[i] for i in range(n)], [cnt[i] for i in range(n)]

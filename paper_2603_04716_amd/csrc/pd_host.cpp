@@ -160,6 +160,28 @@ extern "C" pd_status pd_fifo_replay(int32_t n, const double *arrival_s, const do
     return PD_OK;
 }
 
+extern "C" pd_status pd_allocate_stages(int32_t n_stages, double tp_total_tps, double l_in, double l_out,
+                                        const double *work_per_request, const double *stage_tps,
+                                        int32_t rounding, double *n_real, int32_t *n_instances)
+{
+    if (n_stages < 1 || !work_per_request || !stage_tps || !n_real || !n_instances ||
+        (rounding != 0 && rounding != 1) || !pos_finite(tp_total_tps) || !pos_finite(l_in) || !pos_finite(l_out)) {
+        pd::set_error("pd_allocate_stages: bad arguments");
+        return PD_ERR_INVALID_ARG;
+    }
+    for (int32_t k = 0; k < n_stages; ++k)
+        if (!pos_finite(work_per_request[k]) || !pos_finite(stage_tps[k])) {
+            pd::set_error("pd_allocate_stages: stage %d has a non-positive work or throughput", k);
+            return PD_ERR_INVALID_ARG;
+        }
+    for (int32_t k = 0; k < n_stages; ++k) {
+        const double n = (tp_total_tps * work_per_request[k]) / ((l_in + l_out) * stage_tps[k]);   // Eqs. (5), (6)
+        n_real[k] = n;
+        n_instances[k] = to_count(n, rounding);
+    }
+    return PD_OK;
+}
+
 extern "C" pd_status pd_fifo_replay_batched(int32_t n, const double *arrival_s, int32_t max_batch,
                                             const double *batch_service_s, double *sojourn_s)
 {

@@ -134,3 +134,17 @@ def test_queue_variants_bit_exact_against_oracle():
         pd.pd_fifo_replay_batched([2.0, 1.0], [0.5], 1)              # arrivals not sorted
     with pytest.raises(pd.PdError):
         pd.pd_mg1_sojourn(10.0, 0.2, 0.05)                           # utilisation 2
+
+
+def test_stage_allocation_bit_exact_against_oracle():
+    rng = np.random.default_rng(12)
+    for trial in range(500):
+        n = int(rng.integers(1, 5))
+        tp, l_in, l_out = float(rng.uniform(1e3, 1e6)), float(rng.integers(16, 16384)), float(rng.integers(1, 4096))
+        work = [float(rng.uniform(1, 8000)) for _ in range(n)]
+        tps = [float(rng.uniform(10, 1e5)) for _ in range(n)]
+        rounding = int(rng.integers(0, 2))
+        assert pd.pd_allocate_stages(tp, l_in, l_out, work, tps, rounding) == \
+            tuple(A.allocate_stages(tp, l_in, l_out, work, tps, rounding))
+    with pytest.raises(pd.PdError):
+        pd.pd_allocate_stages(1e5, 100.0, 10.0, [1.0, -2.0], [5.0, 5.0])
