@@ -49,6 +49,7 @@ struct pd_kv_cache {
 };
 
 static const int kMaxSeqs = 4096;
+static const int kShortChunk = 8;   // chunks up to this many tokens use the decode attention kernel per row
 static const int kRopeTableLen = 32768;   // positions with precomputed rotary factors
 
 #define HIP_TRY(expr, status)                                                        \
@@ -607,6 +608,39 @@ static pd_status prefill_common(pd_layer *L, const pd_tokens *tk, pd_kv_cache *c
         a.decode = 1; a.tok_slot = L->tok_slot; a.k_cache = cache->k; a.v_cache = cache->v;
         a.max_len = cache->max_len;
         STEP("prefill_attention", launch_attn_generic(c.dtype, a, s));
+    } else if (chunk && max_L <= kShortChunk) {
+        // A few new tokens per sequence over a blocked cache (multi-token decode): every token row is
+        // an independent decode query over positions 0 .. its own of its slot, so the decode
+        // attention kernel runs with one "sequence" per row.  The cache is streamed once per row,
+        // which for short chunks is less than gathering the prefix for the prefill kernel.
+        long long total_keys = 0;
+        for (int q = 0; q < n; ++q) {
+            const long long Ls = tk->cu_seqlens[q + 1] - tk->cu_seqlens[q];
+            total_keys += Ls * prefix[(size_t)q] + Ls * (Ls + 1) / 2;
+        }
+        long long ck = ((total_keys * c.n_kv_heads + 2047) / 2048 + 63) / 64 * 64;
+        const int chunk_keys = (int)(ck < 64 ? 64 : ck);
+        std::vector<int32_t> ccu((size_t)T + 1);
+        ccu[0] = 0;
+        for (int q = 0; q < n; ++q)
+            for (int t = tk->cu_seqlens[q]; t < tk->cu_seqlens[q + 1]; ++t) {
+                const int keys = prefix[(size_t)q] + (t - tk->cu_seqlens[q]) + 1;
+                ccu[(size_t)t + 1] = ccu[(size_t)t] + (keys + chunk_keys - 1) / chunk_keys;
+            }
+        const int total_chunks = ccu[(size_t)T];
+        if ((size_t)total_chunks > decode_chunk_bound(L, T)) {
+            set_error("pd_prefill_chunk: internal chunk bound exceeded (%d chunks)", total_chunks);
+            return PD_ERR_DEVICE;
+        }
+        HIP_TRY(launch_write_ints(L->chunk_cu, ccu.data(), T + 1, s), PD_ERR_DEVICE);
+        DecodeAttnArgs da;
+        da.qkv = L->qkv; da.ld = L->Nqkv; da.o = L->o; da.B = T; da.Hq = c.n_q_heads; da.Hkv = c.n_kv_heads;
+        da.scale = a.scale; da.slots = L->tok_slot; da.pos = L->tok_pos;
+        da.chunk_cu = L->chunk_cu; da.chunk_keys = chunk_keys; da.total_chunks = total_chunks;
+        da.k_cache = cache->k; da.v_cache = cache->v; da.max_len_pad = cache->plane_len;
+        da.part_o = L->dec_part;
+        da.part_ml = L->dec_part + (size_t)total_chunks * c.n_q_heads * 128;
+        STEP("prefill_attention", launch_decode_attn_mfma(da, s));
     } else if (chunk || (L->use_mfma && attn_prefill_mfma_supported(a))) {
         if (chunk && !attn_prefill_mfma_supported(a)) {
             set_error("pd_prefill_chunk: blocked cache without the matrix-core attention path");

@@ -140,3 +140,19 @@ def test_llama8b_chunk_against_cached_prefix_sampled_rows():
         for j in range(len(rows)):
             assert relmax(mine[j], ref[j]) <= 2 * TOL["bf16"], (i, rows[j])
     layer.close()
+
+
+@pytest.mark.parametrize("hq,hkv", [(4, 1), (8, 2)])
+def test_bf16_multi_token_decode_steps(hq, hkv):
+    """Chunks of at most 8 tokens over a blocked cache take the decode attention kernel, one query
+    row per new token: steps of ragged size (0..8 tokens per sequence) after a long first chunk,
+    crossing 16-, 32- and 64-position block boundaries of the cache."""
+    cfg = I.small_config(dtype="bf16", d_model=256, n_q_heads=hq, n_kv_heads=hkv, head_dim=128, d_ff=512)
+    lens = [200 + 4 + 3 + 8 + 8, 61 + 8 + 0 + 8 + 2, 130 + 1 + 8 + 8 + 7]
+    plan = [[200, 61, 130], [4, 8, 1], [3, 0, 8], [8, 8, 8], [8, 2, 7]]
+    ol, gl, oc, gc, xs = run_plan(cfg, lens, plan, [1, 2, 0], cap=256)
+    xn = I.hidden(3, cfg["d_model"], seed=301, dtype="bf16")
+    ref = O.decode_step(ol, xn, [1, 2, 0], oc)
+    got = gl.decode(xn, [1, 2, 0], gc)
+    assert relmax(got, ref) <= TOL["bf16"]
+    gl.close()
