@@ -75,6 +75,7 @@ hipError_t launch_decode_meta_chunks(const int32_t *d_slots, int B, int32_t *d_l
     return hipGetLastError();
 }
 
+template <bool MULTI>
 __global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a, int n_workers)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -87,22 +88,31 @@ __global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a, i
         if (a.chunk_cu[mid] <= cid) lo = mid; else hi = mid;
     }
     const int b = lo;
-    const int n_keys = a.pos[b] + 1;
+    const int ntok = MULTI ? a.u_ntok[b] : 1;
+    const int n_keys = a.pos[b] + ntok;                // keys visible to the unit's last token
     const int n_chunks = a.chunk_cu[b + 1] - a.chunk_cu[b];
     const int csz = ((n_keys + n_chunks - 1) / n_chunks + 63) & ~63;   // equal chunks, 64-key granules
     const int key0 = (cid - a.chunk_cu[b]) * csz;                       // < n_keys since csz <= chunk_keys
     const int key1 = min(n_keys, key0 + csz);
     const int group = a.Hq / a.Hkv;
     const int qi = lane & 15, kg = lane >> 4;
+    // MFMA column qi: head qh of the group (and, multi-token, token qt of the unit)
+    const int qt = MULTI ? qi / group : 0, qh = MULTI ? qi - qt * group : qi;
+    const bool col_ok = MULTI ? qt < ntok : qi < group;
+    const int row = MULTI ? a.u_row0[b] + qt : b;      // row of qkv / o
+    // keys this column may see: all n_keys (one token), or 0 .. pos + qt
+    const int limit = MULTI ? min(n_keys, a.pos[b] + qt + 1) : n_keys;
+    const int limit_min = MULTI ? a.pos[b] + 1 : n_keys;
 
-    // query rows of the group as B operand: lane (n = qi, kg) holds channels 32s + 8kg .. +7
+    // query rows as B operand: lane (n = qi, kg) holds channels 32s + 8kg .. +7
     bf16x8 qf[4];
     {
-        const uint16_t *qp = (const uint16_t *)a.qkv + (size_t)b * a.ld + (size_t)(g * group + qi) * 128 + kg * 8;
+        const uint16_t *qp = (const uint16_t *)a.qkv + (size_t)(col_ok ? row : 0) * a.ld +
+                             (size_t)(g * group + (col_ok ? qh : 0)) * 128 + kg * 8;
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             u32x4 z = {0u, 0u, 0u, 0u};
-            if (qi < group) z = *(const u32x4 *)(qp + 32 * s);
+            if (col_ok) z = *(const u32x4 *)(qp + 32 * s);
             qf[s] = __builtin_bit_cast(bf16x8, z);
         }
     }
@@ -141,20 +151,25 @@ __global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a, i
             for (int s = 0; s < 4; ++s)
                 sacc[kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kb][s], qf[s], sacc[kb], 0, 0, 0);
         }
-        const bool tail = k + 64 > key1;
+        const int last = MULTI ? min(key1, limit) : key1;    // first key this column must not see
+        const bool tail = k + 64 > (MULTI ? min(key1, limit_min) : key1);
         float mx = -INFINITY;
 #pragma unroll
         for (int kb = 0; kb < 4; ++kb)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                if (tail && k + 16 * kb + 4 * kg + j >= key1) sacc[kb][j] = -INFINITY;
+                if (tail && k + 16 * kb + 4 * kg + j >= last) sacc[kb][j] = -INFINITY;
                 mx = fmaxf(mx, sacc[kb][j]);
             }
         mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run, mx * sl2e);   // finite: key k < key1 is always unmasked
-        const float alpha = dexp2(m_run - m_new);
+        // one token: finite, key k < key1 is always unmasked.  Multi-token: a later chunk may hold
+        // no key that an early token sees; its running max then stays -inf and every weight is 0
+        float m_new = fmaxf(m_run, mx * sl2e);
+        const float m_ref = (MULTI && m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = dexp2(m_run - m_ref);
         m_run = m_new;
+        m_new = m_ref;
         float psum = 0.f;
 #pragma unroll
         for (int kb = 0; kb < 4; ++kb)
@@ -187,11 +202,11 @@ __global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a, i
 
     float l_tot = l_run + __shfl_xor(l_run, 16, 64);
     l_tot += __shfl_xor(l_tot, 32, 64);
-    if (qi < group && n_chunks == 1) {
+    if (col_ok && n_chunks == 1) {
         // the only chunk of its sequence: normalise and store the output row directly
-        const int head = g * group + qi;
+        const int head = g * group + qh;
         const float inv = 1.0f / l_tot;
-        uint16_t *op = (uint16_t *)a.o + ((size_t)b * a.Hq + head) * 128 + 4 * kg;
+        uint16_t *op = (uint16_t *)a.o + ((size_t)row * a.Hq + head) * 128 + 4 * kg;
 #pragma unroll
         for (int db = 0; db < 8; ++db) {
             uint2 w2;
@@ -199,14 +214,15 @@ __global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a, i
             w2.y = pack2bf(oacc[db][2] * inv, oacc[db][3] * inv);
             *(uint2 *)(op + 16 * db) = w2;            // channels 16*db + 4*kg + j
         }
-    } else if (qi < group) {
-        const int head = g * group + qi;
-        float *po = a.part_o + ((size_t)cid * a.Hq + head) * 128;
+    } else if (col_ok) {
+        // partial row index: (chunk, head), or multi-token (chunk, kv head, column)
+        const size_t pidx = MULTI ? ((size_t)cid * a.Hkv + g) * 16 + qi : (size_t)cid * a.Hq + g * group + qi;
+        float *po = a.part_o + pidx * 128;
 #pragma unroll
         for (int db = 0; db < 8; ++db)
             *(f32x4 *)(po + 16 * db + 4 * kg) = oacc[db];   // rows 16*db + 4*kg + j of O^T
         if (kg == 0) {
-            float *pm = a.part_ml + ((size_t)cid * a.Hq + head) * 2;
+            float *pm = a.part_ml + pidx * 2;
             pm[0] = m_run;
             pm[1] = l_tot;
         }
@@ -217,15 +233,27 @@ __global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a, i
 // (sequences with a single chunk are finished by the attention kernel and skipped here).
 // The chunk weights are formed once per block (one chunk per thread, in parallel); the weighted
 // sum then reads the partial rows with independent loads.
+template <bool MULTI>
 __global__ __launch_bounds__(128) void decode_attn_merge_kernel(DecodeAttnArgs a)
 {
     __shared__ float wgt_s[128];
     __shared__ float red[2];
-    const int b = blockIdx.x, head = blockIdx.y, d = threadIdx.x;
+    // one token: blockIdx.y = head.  Multi-token: blockIdx.y = 16 * kv head + column (token, head of group)
+    const int b = blockIdx.x, d = threadIdx.x;
     const int c0 = a.chunk_cu[b], c1 = a.chunk_cu[b + 1];
     if (c1 - c0 == 1) return;                          // written by the attention kernel itself
+    const int group = a.Hq / a.Hkv;
+    int head = blockIdx.y, row = b, pstride = a.Hq, pcol = blockIdx.y;
+    if (MULTI) {
+        const int g = blockIdx.y >> 4, col = blockIdx.y & 15;
+        const int qt = col / group;
+        if (qt >= a.u_ntok[b]) return;
+        head = g * group + (col - qt * group);
+        row = a.u_row0[b] + qt;
+        pstride = a.Hkv * 16;
+    }
     float M = -INFINITY;
-    for (int c = c0 + d; c < c1; c += 128) M = fmaxf(M, a.part_ml[((size_t)c * a.Hq + head) * 2]);
+    for (int c = c0 + d; c < c1; c += 128) M = fmaxf(M, a.part_ml[((size_t)c * pstride + pcol) * 2]);
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, 64));
     if ((d & 63) == 0) red[d >> 6] = M;
@@ -236,7 +264,7 @@ __global__ __launch_bounds__(128) void decode_attn_merge_kernel(DecodeAttnArgs a
         const int c = base + d;
         float w = 0.f, l = 0.f;
         if (c < c1) {
-            const float *pm = a.part_ml + ((size_t)c * a.Hq + head) * 2;
+            const float *pm = a.part_ml + ((size_t)c * pstride + pcol) * 2;
             w = dexp2(pm[0] - M);
             l = pm[1];
         }
@@ -245,8 +273,8 @@ __global__ __launch_bounds__(128) void decode_attn_merge_kernel(DecodeAttnArgs a
         L += w * l;
         __syncthreads();
         const int cnt = min(128, c1 - base);
-        const float *po = a.part_o + ((size_t)base * a.Hq + head) * 128 + d;
-        const size_t stride = (size_t)a.Hq * 128;
+        const float *po = a.part_o + ((size_t)base * pstride + pcol) * 128 + d;
+        const size_t stride = (size_t)pstride * 128;
         int j = 0;
         for (; j + 4 <= cnt; j += 4) {
             float v0 = po[(size_t)j * stride], v1 = po[(size_t)(j + 1) * stride];
@@ -262,17 +290,24 @@ __global__ __launch_bounds__(128) void decode_attn_merge_kernel(DecodeAttnArgs a
     if ((d & 63) == 0) red[d >> 6] = L;
     __syncthreads();
     L = red[0] + red[1];
-    ((uint16_t *)a.o)[((size_t)b * a.Hq + head) * 128 + d] = f2bf(acc / L).x;
+    ((uint16_t *)a.o)[((size_t)row * a.Hq + head) * 128 + d] = f2bf(acc / L).x;
 }
 
 hipError_t launch_decode_attn_mfma(const DecodeAttnArgs &a, hipStream_t s)
 {
     const int n_workers = a.total_chunks * a.Hkv;
     if (n_workers <= 0) return hipSuccess;
-    decode_attn_kernel<<<(n_workers + 3) / 4, 256, 0, s>>>(a, n_workers);
+    if (a.u_ntok) {
+        decode_attn_kernel<true><<<(n_workers + 3) / 4, 256, 0, s>>>(a, n_workers);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        decode_attn_merge_kernel<true><<<dim3(a.B, a.Hkv * 16), 128, 0, s>>>(a);
+        return hipGetLastError();
+    }
+    decode_attn_kernel<false><<<(n_workers + 3) / 4, 256, 0, s>>>(a, n_workers);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    decode_attn_merge_kernel<<<dim3(a.B, a.Hq), 128, 0, s>>>(a);
+    decode_attn_merge_kernel<false><<<dim3(a.B, a.Hq), 128, 0, s>>>(a);
     return hipGetLastError();
 }
 

@@ -21,6 +21,7 @@ struct pd_layer {
     double *inv_freq;
     float2 *rope_table;       // (cos, sin) for positions < kRopeTableLen
     int32_t *d_cu, *d_slots, *d_pad_cu, *d_prefix;  // [4097] each
+    int32_t *units;           // [4][ws_tokens]: slot, first position, first row, token count of multi-token units
     void *vt;                 // transposed-V scratch for the MFMA attention, vt_cap bytes
     size_t vt_cap;
     float *dec_part;          // partial outputs of the decode attention chunks (inside ws)
@@ -281,7 +282,7 @@ extern "C" pd_status pd_layer_reserve(pd_layer *L, int32_t max_tokens)
            o_eo = carve(E > 0 ? T * K * d * esz : 0), o_seq = carve(T * 4), o_pos = carve(T * 4),
            o_slot = carve(T * 4), o_eidx = carve(T * K * 4), o_sorted = carve(T * K * 4),
            o_pp = carve(T * K * 4), o_off = carve(65 * 4 + 4), o_log = carve(T * (E > 0 ? E : 1) * 4),
-           o_ew = carve(T * K * 4), o_ccu = carve((T + 1) * 4),
+           o_ew = carve(T * K * 4), o_ccu = carve((T + 1) * 4), o_units = carve(4 * T * 4),
            o_part = carve(decode_chunk_bound(L, max_tokens) * L->cfg.n_q_heads * 130 * sizeof(float));
     // split-K scratch: splits * columns never exceeds 640 tiles * 128 columns + one row of tiles
     size_t maxn = (size_t)L->Nqkv;
@@ -315,6 +316,7 @@ extern "C" pd_status pd_layer_reserve(pd_layer *L, int32_t max_tokens)
     L->logits = (float *)(nw + o_log);
     L->ew = (float *)(nw + o_ew);
     L->chunk_cu = (int32_t *)(nw + o_ccu);
+    L->units = (int32_t *)(nw + o_units);
     L->dec_part = (float *)(nw + o_part);
     L->splitk = sk_elems ? (float *)(nw + o_sk) : nullptr;
     L->splitk_elems = sk_elems;
@@ -609,37 +611,53 @@ static pd_status prefill_common(pd_layer *L, const pd_tokens *tk, pd_kv_cache *c
         a.max_len = cache->max_len;
         STEP("prefill_attention", launch_attn_generic(c.dtype, a, s));
     } else if (chunk && max_L <= kShortChunk) {
-        // A few new tokens per sequence over a blocked cache (multi-token decode): every token row is
-        // an independent decode query over positions 0 .. its own of its slot, so the decode
-        // attention kernel runs with one "sequence" per row.  The cache is streamed once per row,
-        // which for short chunks is less than gathering the prefix for the prefill kernel.
+        // A few new tokens per sequence over a blocked cache (multi-token decode): the decode
+        // attention kernel streams the cache once per unit of a few tokens instead of gathering the
+        // prefix for the prefill kernel.
+        // Units of up to 16 / group consecutive tokens of one sequence share one pass over the cache:
+        // their (token, head) pairs are the 16 MFMA columns of the decode attention kernel.
+        const int tb = 16 / (c.n_q_heads / c.n_kv_heads);
+        std::vector<int32_t> u_slot, u_pos, u_row, u_cnt;
         long long total_keys = 0;
         for (int q = 0; q < n; ++q) {
-            const long long Ls = tk->cu_seqlens[q + 1] - tk->cu_seqlens[q];
-            total_keys += Ls * prefix[(size_t)q] + Ls * (Ls + 1) / 2;
+            const int Ls = tk->cu_seqlens[q + 1] - tk->cu_seqlens[q];
+            for (int i0 = 0; i0 < Ls; i0 += tb) {
+                const int cnt = Ls - i0 < tb ? Ls - i0 : tb;
+                u_slot.push_back(tk->slots[q]);
+                u_pos.push_back(prefix[(size_t)q] + i0);
+                u_row.push_back(tk->cu_seqlens[q] + i0);
+                u_cnt.push_back(cnt);
+                total_keys += prefix[(size_t)q] + i0 + cnt;
+            }
         }
+        const int nu = (int)u_slot.size();
         long long ck = ((total_keys * c.n_kv_heads + 2047) / 2048 + 63) / 64 * 64;
         const int chunk_keys = (int)(ck < 64 ? 64 : ck);
-        std::vector<int32_t> ccu((size_t)T + 1);
+        std::vector<int32_t> ccu((size_t)nu + 1);
         ccu[0] = 0;
-        for (int q = 0; q < n; ++q)
-            for (int t = tk->cu_seqlens[q]; t < tk->cu_seqlens[q + 1]; ++t) {
-                const int keys = prefix[(size_t)q] + (t - tk->cu_seqlens[q]) + 1;
-                ccu[(size_t)t + 1] = ccu[(size_t)t] + (keys + chunk_keys - 1) / chunk_keys;
-            }
-        const int total_chunks = ccu[(size_t)T];
-        if ((size_t)total_chunks > decode_chunk_bound(L, T)) {
+        for (int u = 0; u < nu; ++u)
+            ccu[(size_t)u + 1] = ccu[(size_t)u] + (u_pos[(size_t)u] + u_cnt[(size_t)u] + chunk_keys - 1) / chunk_keys;
+        const int total_chunks = ccu[(size_t)nu];
+        // partial rows: [chunk][kv head][16 columns]; the reserved buffer is counted in [chunk][q head] rows
+        if ((size_t)total_chunks * c.n_kv_heads * 16 > decode_chunk_bound(L, T) * c.n_q_heads) {
             set_error("pd_prefill_chunk: internal chunk bound exceeded (%d chunks)", total_chunks);
             return PD_ERR_DEVICE;
         }
-        HIP_TRY(launch_write_ints(L->chunk_cu, ccu.data(), T + 1, s), PD_ERR_DEVICE);
+        const size_t ws_t = (size_t)L->ws_tokens;
+        HIP_TRY(launch_write_ints(L->chunk_cu, ccu.data(), nu + 1, s), PD_ERR_DEVICE);
+        HIP_TRY(launch_write_ints(L->units, u_slot.data(), nu, s), PD_ERR_DEVICE);
+        HIP_TRY(launch_write_ints(L->units + ws_t, u_pos.data(), nu, s), PD_ERR_DEVICE);
+        HIP_TRY(launch_write_ints(L->units + 2 * ws_t, u_row.data(), nu, s), PD_ERR_DEVICE);
+        HIP_TRY(launch_write_ints(L->units + 3 * ws_t, u_cnt.data(), nu, s), PD_ERR_DEVICE);
         DecodeAttnArgs da;
-        da.qkv = L->qkv; da.ld = L->Nqkv; da.o = L->o; da.B = T; da.Hq = c.n_q_heads; da.Hkv = c.n_kv_heads;
-        da.scale = a.scale; da.slots = L->tok_slot; da.pos = L->tok_pos;
+        memset(&da, 0, sizeof(da));
+        da.qkv = L->qkv; da.ld = L->Nqkv; da.o = L->o; da.B = nu; da.Hq = c.n_q_heads; da.Hkv = c.n_kv_heads;
+        da.scale = a.scale; da.slots = L->units; da.pos = L->units + ws_t;
+        da.u_row0 = L->units + 2 * ws_t; da.u_ntok = L->units + 3 * ws_t;
         da.chunk_cu = L->chunk_cu; da.chunk_keys = chunk_keys; da.total_chunks = total_chunks;
         da.k_cache = cache->k; da.v_cache = cache->v; da.max_len_pad = cache->plane_len;
         da.part_o = L->dec_part;
-        da.part_ml = L->dec_part + (size_t)total_chunks * c.n_q_heads * 128;
+        da.part_ml = L->dec_part + (size_t)total_chunks * c.n_kv_heads * 16 * 128;
         STEP("prefill_attention", launch_decode_attn_mfma(da, s));
     } else if (chunk || (L->use_mfma && attn_prefill_mfma_supported(a))) {
         if (chunk && !attn_prefill_mfma_supported(a)) {
@@ -781,6 +799,7 @@ extern "C" pd_status pd_decode_step(pd_layer *L, const pd_batch *bt, pd_kv_cache
     STEP("rope_kv_append", launch_rope_kv(c.dtype, r, s));
     if (mfma_dec) {
         DecodeAttnArgs da;
+        memset(&da, 0, sizeof(da));
         da.qkv = L->qkv; da.ld = L->Nqkv; da.o = L->o; da.B = B; da.Hq = c.n_q_heads; da.Hkv = c.n_kv_heads;
         da.scale = (float)(1.0 / sqrt((double)c.head_dim)); da.slots = L->d_slots; da.pos = L->tok_pos;
         da.chunk_cu = L->chunk_cu; da.chunk_keys = chunk_keys; da.total_chunks = total_chunks;

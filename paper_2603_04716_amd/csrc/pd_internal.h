@@ -196,6 +196,12 @@ struct DecodeAttnArgs {
     int32_t max_len_pad;
     float *part_o;             // [total_chunks][Hq][128]
     float *part_ml;            // [total_chunks][Hq][2]
+    // Multi-token form (all null for the one-token step): "sequence" b is a unit of u_ntok[b] <= 16/group
+    // consecutive new tokens of one cache slot; token i of the unit is row u_row0[b] + i of qkv / o,
+    // sits at position pos[b] + i and sees keys 0 .. pos[b] + i.  The 16 MFMA columns are
+    // (token, head of the group) pairs; partials are then [total_chunks][Hkv][16][128] / [..][2].
+    const int32_t *u_row0;
+    const int32_t *u_ntok;
 };
 hipError_t launch_decode_attn_mfma(const DecodeAttnArgs &a, hipStream_t s);
 // pos[b] = len[slot[b]]; len[slot[b]] += 1; chunk_cu = prefix sum of ceil((pos+1)/chunk_keys)

@@ -142,11 +142,12 @@ def test_llama8b_chunk_against_cached_prefix_sampled_rows():
     layer.close()
 
 
-@pytest.mark.parametrize("hq,hkv", [(4, 1), (8, 2)])
+@pytest.mark.parametrize("hq,hkv", [(4, 1), (8, 2), (2, 2), (8, 1), (16, 1)])
 def test_bf16_multi_token_decode_steps(hq, hkv):
-    """Chunks of at most 8 tokens over a blocked cache take the decode attention kernel, one query
-    row per new token: steps of ragged size (0..8 tokens per sequence) after a long first chunk,
-    crossing 16-, 32- and 64-position block boundaries of the cache."""
+    """Chunks of at most 8 tokens over a blocked cache take the decode attention kernel with units
+    of 16 / group tokens sharing one pass over the cache (group 4: 4 tokens, 1: 16, 8: 2, 16: 1):
+    steps of ragged size (0..8 tokens per sequence) after a long first chunk, crossing 16-, 32- and
+    64-position block boundaries of the cache."""
     cfg = I.small_config(dtype="bf16", d_model=256, n_q_heads=hq, n_kv_heads=hkv, head_dim=128, d_ff=512)
     lens = [200 + 4 + 3 + 8 + 8, 61 + 8 + 0 + 8 + 2, 130 + 1 + 8 + 8 + 7]
     plan = [[200, 61, 130], [4, 8, 1], [3, 0, 8], [8, 8, 8], [8, 2, 7]]
