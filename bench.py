@@ -45,12 +45,12 @@ def counted_traffic():
 
 
 def cpu_baseline(cfg, weights):
-    """The oracle, as it stands, timed on a bounded sample: prefill of 2 x 1024 tokens through the
-    full 8B-shaped layer on the host cores."""
+    """The oracle, as it stands, timed on a bounded sample: prefill of 2 x 2048 tokens (two of the
+    step's four sequences) through the full 8B-shaped layer on the host cores."""
     import numpy as np
     import pd_inputs as I
     from oracle import layer as O
-    n = 2048
+    n = 2 * L_IN
     x = I.hidden(n, cfg["d_model"], seed=99, dtype="bf16")
     L = O.Layer(cfg, weights)
     t0 = time.perf_counter()

@@ -3,9 +3,9 @@
 // The step is bound by streaming the weight matrix B from HBM exactly once, so the weights are
 // the MFMA A operand and go straight from global memory into operand registers: in the packed
 // weight layout one 16-row x 32-k block is the register image of the operand, so every load
-// instruction reads 1 KB of contiguous memory (eight blocks in flight per wave); the (tiny, L2-resident)
+// instruction reads 1 KB of contiguous memory (several blocks in flight per wave); the (tiny, L2-resident)
 // activations are the B operand with the batch as the N dimension of v_mfma_f32_16x16x32_bf16,
-// padded with zero columns.  A workgroup owns 16 weight rows (one output column block); its four
+// padded with zero columns.  A workgroup owns 16 weight rows (one output column block); its
 // waves split K and combine through LDS in a fixed order, so results are deterministic.
 // Epilogues as in the tiled GEMM; for SwiGLU the workgroup takes the gate block and the matching
 // up block of the interleaved weight pack.
@@ -23,10 +23,10 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int GV_WAVES = 4;
-constexpr int GV_UNROLL = 8;
-
-template <int EPI>
+// GV_WAVES waves split K; each keeps GV_UNROLL blocks per row block in flight.  Measured on the 8B
+// shapes: the SwiGLU pair streams fastest with 2 waves x 16 blocks, a long K (the down projection)
+// with 8 waves x 4, the short square ones with 4 x 8.
+template <int EPI, int GV_WAVES, int GV_UNROLL>
 __global__ __launch_bounds__(64 * GV_WAVES) void gemv_mfma_kernel(GemmArgs a)
 {
     constexpr int RB = EPI == EPI_SWIGLU ? 2 : 1;
@@ -154,11 +154,18 @@ bool gemv_mfma_supported(const GemmArgs &a)
 
 hipError_t launch_gemv_mfma(const GemmArgs &a, hipStream_t s)
 {
-    const dim3 grid(a.N / 16, a.group_offsets ? a.n_groups : 1), block(64 * GV_WAVES);
+    const dim3 grid(a.N / 16, a.group_offsets ? a.n_groups : 1);
+    const bool long_k = a.K >= 8192;
     switch (a.epilogue) {
-    case EPI_NONE: gemv_mfma_kernel<EPI_NONE><<<grid, block, 0, s>>>(a); break;
-    case EPI_RESIDUAL: gemv_mfma_kernel<EPI_RESIDUAL><<<grid, block, 0, s>>>(a); break;
-    default: gemv_mfma_kernel<EPI_SWIGLU><<<grid, block, 0, s>>>(a); break;
+    case EPI_NONE:
+        if (long_k) gemv_mfma_kernel<EPI_NONE, 8, 4><<<grid, 512, 0, s>>>(a);
+        else gemv_mfma_kernel<EPI_NONE, 4, 8><<<grid, 256, 0, s>>>(a);
+        break;
+    case EPI_RESIDUAL:
+        if (long_k) gemv_mfma_kernel<EPI_RESIDUAL, 8, 4><<<grid, 512, 0, s>>>(a);
+        else gemv_mfma_kernel<EPI_RESIDUAL, 4, 8><<<grid, 256, 0, s>>>(a);
+        break;
+    default: gemv_mfma_kernel<EPI_SWIGLU, 2, 16><<<grid, 128, 0, s>>>(a); break;
     }
     return hipGetLastError();
 }
