@@ -163,7 +163,10 @@ __global__ __launch_bounds__(64 * WAVES_M *WAVES_N) void gemm_mfma_kernel(GemmAr
     auto wait_tiles_after = [&](int tiles_after) {
         // s_waitcnt vmcnt(n): n in bits [3:0] and [15:14]; expcnt / lgkmcnt fields left at "no wait"
 #define PD_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (7 << 4) | (15 << 8) | (((n) >> 4) << 14))
-        if (NS >= 4 && tiles_after >= 2) PD_VMCNT(2 * LPS);
+        if (NS >= 7 && tiles_after >= 5) PD_VMCNT((5 * LPS) & 63);
+        else if (NS >= 6 && tiles_after >= 4) PD_VMCNT((4 * LPS) & 63);
+        else if (NS >= 5 && tiles_after >= 3) PD_VMCNT((3 * LPS) & 63);
+        else if (NS >= 4 && tiles_after >= 2) PD_VMCNT(2 * LPS);
         else if (NS >= 3 && tiles_after >= 1) PD_VMCNT(1 * LPS);
         else PD_VMCNT(0);
 #undef PD_VMCNT
@@ -378,8 +381,8 @@ static hipError_t launch_cfg(const GemmArgs &a, hipStream_t s, int splits = 1)
 
 // Split count for decode-sized problems: about one workgroup per CU (measured: more splits lose
 // to the fp32 partial traffic, fewer leave CUs without a weight stream), at least 4 k-tiles per
-// split, partials (written and read back) below about half of the weight bytes, and they must
-// fit the scratch buffer.
+// split, partials (written and read back) below about the weight bytes, and they must fit the
+// scratch buffer.
 static int choose_splits(const GemmArgs &a, int BM, int BN)
 {
     if (!a.splitk_ws || a.N % 4 != 0 || a.ldc % 4 != 0 || (a.epilogue == EPI_RESIDUAL && a.ldr % 4 != 0))
@@ -390,9 +393,9 @@ static int choose_splits(const GemmArgs &a, int BM, int BN)
     if (a.group_offsets) row_tiles = a.M < a.n_groups ? a.M : a.n_groups;
     const int tiles = row_tiles * ((n_cols + BN - 1) / BN);
     const int nk = a.K / BK;
-    int splits = (256 + tiles / 2) / tiles;
-    if (splits > nk / 4) splits = nk / 4;
-    const int cap = a.K / (8 * a.M) > 1 ? a.K / (8 * a.M) : 1;
+    int splits = 256 / tiles;                      // never more workgroups than CUs: a second, nearly
+    if (splits > nk / 4) splits = nk / 4;          // empty round costs more than the idle CUs
+    const int cap = a.K / (4 * a.M) > 1 ? a.K / (4 * a.M) : 1;
     if (splits > cap) splits = cap;
     while (splits > 1 && (size_t)splits * a.M * n_cols > a.splitk_ws_elems) --splits;
     return splits < 1 ? 1 : splits;
