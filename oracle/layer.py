@@ -76,18 +76,29 @@ class Layer:
 class KVCache:
     """fp32 cache [n_slots][Hkv][max_len][hd] for keys (rotated) and values, plus lengths."""
 
-    def __init__(self, layer: Layer, n_slots: int, max_len: int):
+    def __init__(self, layer: Layer, n_slots: int, max_len: int, fp8_scales=None):
+        """fp8_scales = (k_scale, v_scale): the cache holds 8-bit E4M3 numbers with these static
+        scales (every stored element reads back as scale * fp8(x / scale)); None: exact storage."""
         c = layer.c
         self.k = np.zeros((n_slots, c.n_kv_heads, max_len, c.head_dim), np.float32)
         self.v = np.zeros_like(self.k)
         self.lens = np.zeros(n_slots, np.int32)
         self.max_len = max_len
+        self.fp8 = 0 if fp8_scales is None else 1
+        self.k_scale, self.v_scale = (1.0, 1.0) if fp8_scales is None else map(float, fp8_scales)
+
+    def q(self):
+        return C.c_int(self.fp8), C.c_double(self.k_scale), C.c_double(self.v_scale)
 
     def set(self, slot, k, v):
         """k, v: [Hkv, len, hd] already-rotated keys and values."""
         n = k.shape[1]
-        self.k[slot, :, :n] = k
-        self.v[slot, :, :n] = v
+        kk, vv = _f32(k).copy(), _f32(v).copy()
+        if self.fp8:
+            lib().orc_cache_quantise(_p(kk), C.c_size_t(kk.size), C.c_double(self.k_scale))
+            lib().orc_cache_quantise(_p(vv), C.c_size_t(vv.size), C.c_double(self.v_scale))
+        self.k[slot, :, :n] = kk
+        self.v[slot, :, :n] = vv
         self.lens[slot] = n
 
 
@@ -109,7 +120,8 @@ def prefill(layer: Layer, x, cu_seqlens, router_logits=None, rows=None, cache: K
                            _p(cache.k) if cache is not None and sl is not None else None,
                            _p(cache.v) if cache is not None and sl is not None else None,
                            _p(cache.lens) if cache is not None and sl is not None else None,
-                           C.c_int(cache.max_len if cache is not None else 0), _p(out), _p(eidx))
+                           C.c_int(cache.max_len if cache is not None else 0), _p(out), _p(eidx),
+                           *(cache.q() if cache is not None else (C.c_int(0), C.c_double(1.0), C.c_double(1.0))))
     if rc != 0:
         raise ValueError(f"orc_prefill failed rc={rc}")
     return (out, eidx) if return_experts else out
@@ -125,7 +137,7 @@ def decode_step(layer: Layer, x, slots, cache: KVCache, router_logits=None, retu
     eidx = np.full((B, k), -1, np.int32)
     rc = lib().orc_decode_step(C.byref(layer.c), C.byref(layer.cw), _p(x), C.c_int(B), _p(sl),
                                _p(cache.k), _p(cache.v), _p(cache.lens), C.c_int(cache.max_len),
-                               _p(rl), _p(out), _p(eidx))
+                               _p(rl), _p(out), _p(eidx), *cache.q())
     if rc == -2:
         raise OverflowError("KV cache capacity exceeded")
     if rc != 0:
@@ -148,12 +160,27 @@ def prefill_chunk(layer: Layer, x, cu_seqlens, slots, cache: KVCache, router_log
     eidx = np.full((T, k), -1, np.int32)
     rc = lib().orc_prefill_chunk(C.byref(layer.c), C.byref(layer.cw), _p(x), C.c_int(T), C.c_int(n_seqs),
                                  _p(cu), _p(rl), _p(sl), _p(cache.k), _p(cache.v), _p(cache.lens),
-                                 C.c_int(cache.max_len), _p(out), _p(eidx))
+                                 C.c_int(cache.max_len), _p(out), _p(eidx), *cache.q())
     if rc == -2:
         raise OverflowError("KV cache capacity exceeded")
     if rc != 0:
         raise ValueError(f"orc_prefill_chunk failed rc={rc}")
     return (out, eidx) if return_experts else out
+
+
+def fp8_e4m3_encode(x):
+    """uint8 E4M3 codes of an array (round to nearest even, saturating at +-448)."""
+    a = np.ascontiguousarray(x, np.float64).ravel()
+    f = lib().orc_fp8_e4m3_encode
+    f.restype, f.argtypes = C.c_uint8, [C.c_double]
+    return np.array([f(float(v)) for v in a], np.uint8).reshape(np.shape(x))
+
+
+def fp8_e4m3_decode(codes):
+    c = np.ascontiguousarray(codes, np.uint8).ravel()
+    f = lib().orc_fp8_e4m3_decode
+    f.restype, f.argtypes = C.c_double, [C.c_uint8]
+    return np.array([f(int(v)) for v in c], np.float64).reshape(np.shape(codes))
 
 
 # ---- stand-alone pieces (for pins) -------------------------------------------------------------

@@ -56,6 +56,64 @@ typedef struct {
 } orc_weights;
 
 /* y[i] = x[i] / sqrt(mean_j x[j]^2 + eps) * g[i]   (one row) */
+/*
+ * OCP 8-bit floating point, E4M3 ("fn" variant: no infinities, one NaN code per sign): 1 sign
+ * bit, 4 exponent bits (bias 7), 3 mantissa bits; normal values 2^(e-7) (1 + m/8) for e >= 1,
+ * subnormals m * 2^-9 for e = 0, largest finite value 448 (code 0x7E).  Encoding rounds to the
+ * nearest representable value, ties to the even mantissa, and saturates at +-448 (the usual rule
+ * for a quantised KV cache; NaN maps to the NaN code).
+ */
+double orc_fp8_e4m3_decode(uint8_t code)
+{
+    int sign = code >> 7, e = (code >> 3) & 15, m = code & 7;
+    double v;
+    if (e == 15 && m == 7) return NAN;
+    if (e == 0) v = ldexp((double)m, -9);
+    else v = ldexp(1.0 + m / 8.0, e - 7);
+    return sign ? -v : v;
+}
+
+uint8_t orc_fp8_e4m3_encode(double x)
+{
+    if (isnan(x)) return 0x7F;
+    uint8_t sign = signbit(x) ? 0x80 : 0;
+    double a = fabs(x);
+    if (a >= 448.0) return sign | 0x7E;
+    /* spacing of representable values around a: 2^-9 below 2^-6, else 2^(floor(log2 a) - 3) */
+    int ex;
+    frexp(a, &ex);                       /* a = f * 2^ex, f in [0.5, 1)  ->  floor(log2 a) = ex - 1 */
+    int e_unb = ex - 1;
+    if (e_unb < -6) e_unb = -6;
+    double step = ldexp(1.0, e_unb - 3);
+    double q = nearbyint(a / step);      /* default rounding mode: to nearest, ties to even */
+    double r = q * step;                 /* may carry into the next binade, still representable */
+    if (r >= 448.0) return sign | 0x7E;
+    if (r < ldexp(1.0, -6)) return sign | (uint8_t)q;          /* subnormal: q = mantissa (0..7), or 8 = 2^-6 */
+    int er;
+    double fr = frexp(r, &er);           /* r = fr * 2^er */
+    int e = er - 1 + 7;
+    int m = (int)nearbyint((fr * 2.0 - 1.0) * 8.0);
+    return sign | (uint8_t)(e << 3) | (uint8_t)m;
+}
+
+/* value a cache position holds for input x: x itself, or scale * fp8(x / scale) */
+static float cache_value(float x, int fp8, double scale)
+{
+    if (!fp8) return x;
+    return (float)(scale * orc_fp8_e4m3_decode(orc_fp8_e4m3_encode((double)x / scale)));
+}
+
+static void cache_store(float *dst, const float *src, int n, int fp8, double scale)
+{
+    for (int i = 0; i < n; ++i) dst[i] = cache_value(src[i], fp8, scale);
+}
+
+/* exposed for the cache-fill helper of the tests */
+void orc_cache_quantise(float *x, size_t n, double scale)
+{
+    for (size_t i = 0; i < n; ++i) x[i] = cache_value(x[i], 1, scale);
+}
+
 void orc_rmsnorm_row(const float *x, const float *g, int d, double eps, float *y)
 {
     double ss = 0.0;
@@ -261,7 +319,8 @@ static void ffn_block_row(const orc_config *c, const orc_weights *w, const float
 int orc_prefill(const orc_config *c, const orc_weights *w, const float *x, int T, int n_seqs,
                 const int32_t *cu_seqlens, const float *router_logits, const int32_t *rows,
                 int n_rows, const int32_t *slots, float *k_cache, float *v_cache, int32_t *lens,
-                int max_len, float *out, int32_t *expert_idx)
+                int max_len, float *out, int32_t *expert_idx, int kv_fp8, double k_scale,
+                double v_scale)
 {
     int d = c->d_model, Hq = c->n_q_heads, Hkv = c->n_kv_heads, hd = c->head_dim;
     if (Hkv <= 0 || Hq % Hkv != 0 || hd % 2 != 0) return -1;
@@ -317,8 +376,8 @@ int orc_prefill(const orc_config *c, const orc_weights *w, const float *x, int T
                 for (int g = 0; g < Hkv; ++g) {
                     size_t dst = base + ((size_t)g * max_len + p) * hd;
                     size_t src = (size_t)(cu_seqlens[s] + p) * dkv + (size_t)g * hd;
-                    memcpy(k_cache + dst, kbuf + src, sizeof(float) * (size_t)hd);
-                    memcpy(v_cache + dst, vbuf + src, sizeof(float) * (size_t)hd);
+                    cache_store(k_cache + dst, kbuf + src, hd, kv_fp8, k_scale);
+                    cache_store(v_cache + dst, vbuf + src, hd, kv_fp8, v_scale);
                 }
             lens[slots[s]] = L;
         }
@@ -372,7 +431,8 @@ int orc_prefill(const orc_config *c, const orc_weights *w, const float *x, int T
  */
 int orc_decode_step(const orc_config *c, const orc_weights *w, const float *x, int B,
                     const int32_t *slots, float *k_cache, float *v_cache, int32_t *lens,
-                    int max_len, const float *router_logits, float *out, int32_t *expert_idx)
+                    int max_len, const float *router_logits, float *out, int32_t *expert_idx,
+                    int kv_fp8, double k_scale, double v_scale)
 {
     int d = c->d_model, Hq = c->n_q_heads, Hkv = c->n_kv_heads, hd = c->head_dim;
     if (Hkv <= 0 || Hq % Hkv != 0 || hd % 2 != 0) return -1;
@@ -396,10 +456,8 @@ int orc_decode_step(const orc_config *c, const orc_weights *w, const float *x, i
         orc_rope_row(k, Hkv, hd, p, c->rope_base);
         size_t base = (size_t)slot * Hkv * (size_t)max_len * hd;
         for (int g = 0; g < Hkv; ++g) {
-            memcpy(k_cache + base + ((size_t)g * max_len + p) * hd, k + (size_t)g * hd,
-                   sizeof(float) * (size_t)hd);
-            memcpy(v_cache + base + ((size_t)g * max_len + p) * hd, v + (size_t)g * hd,
-                   sizeof(float) * (size_t)hd);
+            cache_store(k_cache + base + ((size_t)g * max_len + p) * hd, k + (size_t)g * hd, hd, kv_fp8, k_scale);
+            cache_store(v_cache + base + ((size_t)g * max_len + p) * hd, v + (size_t)g * hd, hd, kv_fp8, v_scale);
         }
         orc_attend_row(q, k_cache + base, v_cache + base, (size_t)hd, (size_t)max_len * hd, p + 1,
                        Hq, Hkv, hd, o);
@@ -429,11 +487,16 @@ int orc_decode_step(const orc_config *c, const orc_weights *w, const float *x, i
  * lens[slot] = P + L.  P = 0 is an ordinary prefill; L = 1 is a decode step.
  * Slots must be distinct.  Returns 0, -1 bad argument, -2 cache capacity exceeded
  * (nothing is modified in that case).
+ *
+ * kv_fp8 != 0 (here, in orc_prefill and in orc_decode_step): the cache holds keys and values as
+ * 8-bit E4M3 numbers with the static scales k_scale / v_scale, i.e. a stored element reads back
+ * as scale * fp8(x / scale).  Whatever attention reads from the cache is the quantised value;
+ * orc_prefill's own attention works on the fresh keys and values and only its stores quantise.
  */
 int orc_prefill_chunk(const orc_config *c, const orc_weights *w, const float *x, int T, int n_seqs,
                       const int32_t *cu_seqlens, const float *router_logits, const int32_t *slots,
                       float *k_cache, float *v_cache, int32_t *lens, int max_len, float *out,
-                      int32_t *expert_idx)
+                      int32_t *expert_idx, int kv_fp8, double k_scale, double v_scale)
 {
     int d = c->d_model, Hq = c->n_q_heads, Hkv = c->n_kv_heads, hd = c->head_dim;
     if (Hkv <= 0 || Hq % Hkv != 0 || hd % 2 != 0) return -1;
@@ -465,10 +528,8 @@ int orc_prefill_chunk(const orc_config *c, const orc_weights *w, const float *x,
         orc_rope_row(k, Hkv, hd, pos, c->rope_base);
         size_t base = (size_t)slot * Hkv * (size_t)max_len * hd;
         for (int g = 0; g < Hkv; ++g) {
-            memcpy(k_cache + base + ((size_t)g * max_len + pos) * hd, k + (size_t)g * hd,
-                   sizeof(float) * (size_t)hd);
-            memcpy(v_cache + base + ((size_t)g * max_len + pos) * hd, v + (size_t)g * hd,
-                   sizeof(float) * (size_t)hd);
+            cache_store(k_cache + base + ((size_t)g * max_len + pos) * hd, k + (size_t)g * hd, hd, kv_fp8, k_scale);
+            cache_store(v_cache + base + ((size_t)g * max_len + pos) * hd, v + (size_t)g * hd, hd, kv_fp8, v_scale);
         }
         free(y);
         free(k);

@@ -379,3 +379,60 @@ def test_input_module_bf16_rounding_is_rne():
     ref = torch.from_numpy(a).to(torch.bfloat16).to(torch.float32).numpy()
     assert np.array_equal(I.round_to_bf16(a), ref)
     assert np.array_equal(I.bf16_bits_to_f32(I.f32_to_bf16_bits(a)), ref)
+
+
+# ---- 8-bit E4M3 cache storage ---------------------------------------------------------------------
+
+def test_fp8_e4m3_codec_against_the_format_and_a_library_conversion():
+    codes = np.arange(256, dtype=np.uint8)
+    vals = O.fp8_e4m3_decode(codes)
+    # the format's landmarks: 1.0, largest finite, smallest normal, smallest subnormal, NaN codes
+    assert vals[0x38] == 1.0 and vals[0x7E] == 448.0 and vals[0x08] == 2.0 ** -6 and vals[0x01] == 2.0 ** -9
+    assert np.isnan(vals[0x7F]) and np.isnan(vals[0xFF]) and vals[0xFE] == -448.0
+    finite = ~np.isnan(vals)
+    assert np.array_equal(O.fp8_e4m3_encode(vals[finite]), codes[finite])          # round trip of every code
+    pos = vals[:0x7F]
+    assert np.all(np.diff(pos) > 0)                                                # strictly increasing
+    # an independent conversion: PyTorch's CPU float8_e4m3fn cast (in range; it does not saturate)
+    rng = np.random.default_rng(0)
+    x = np.concatenate([rng.standard_normal(20000) * rng.choice([1e-3, 0.05, 1.0, 30.0], 20000),
+                        (pos[:-1] + pos[1:]) / 2, -(pos[:-1] + pos[1:]) / 2,     # exact ties
+                        pos, -pos]).astype(np.float32)
+    x = x[np.abs(x) <= 448.0]
+    lib = torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    mine = O.fp8_e4m3_encode(x)
+    both_zero = (O.fp8_e4m3_decode(mine) == 0) & (O.fp8_e4m3_decode(lib) == 0)     # +0 / -0 of tiny inputs
+    assert np.array_equal(mine[~both_zero], lib[~both_zero])
+    # saturation and NaN
+    assert list(O.fp8_e4m3_encode([1e9, -500.0, 448.0, 463.9, float("nan")])) == [0x7E, 0xFE, 0x7E, 0x7E, 0x7F]
+
+
+def test_fp8_cache_stores_quantised_values_and_prefill_itself_is_unchanged():
+    cfg = I.small_config()
+    w = I.layer_weights(cfg, std=0.08)
+    L = O.Layer(cfg, w)
+    x = I.hidden(30, cfg["d_model"], seed=90)
+    cu = np.array([0, 11, 30], np.int32)
+    exact, q8 = O.KVCache(L, 2, 40), O.KVCache(L, 2, 40, fp8_scales=(0.5, 2.0))
+    out_e = O.prefill(L, x, cu, cache=exact, slots=[0, 1])
+    out_q = O.prefill(L, x, cu, cache=q8, slots=[0, 1])
+    assert np.array_equal(out_e, out_q)                 # prefill attends over the fresh keys and values
+    for cache_t, ref_t, s in ((q8.k, exact.k, 0.5), (q8.v, exact.v, 2.0)):
+        lib = torch.from_numpy(ref_t / s).to(torch.float8_e4m3fn).float().numpy() * s
+        assert np.array_equal(cache_t, lib.astype(np.float32))
+    # decode and a chunk over the quantised cache: close to the exact run, not equal to it
+    xn = I.hidden(2, cfg["d_model"], seed=91)
+    d_e, d_q = O.decode_step(L, xn, [0, 1], exact), O.decode_step(L, xn, [0, 1], q8)
+    assert 0 < relmax(d_q, d_e) < 0.05
+    xc = I.hidden(7, cfg["d_model"], seed=92)
+    c_e = O.prefill_chunk(L, xc, np.array([0, 3, 7], np.int32), [0, 1], exact)
+    c_q = O.prefill_chunk(L, xc, np.array([0, 3, 7], np.int32), [0, 1], q8)
+    assert 0 < relmax(c_q, c_e) < 0.05
+    # the appended positions are quantised too: every stored element is a representable value
+    for cache_t, s in ((q8.k, 0.5), (q8.v, 2.0)):
+        held = cache_t[0, :, :int(q8.lens[0])] / s
+        assert np.array_equal(O.fp8_e4m3_decode(O.fp8_e4m3_encode(held)).astype(np.float32), held)
+    # set(): the benchmark fill goes through the same quantiser
+    k, v = I.kv_fill(cfg["n_kv_heads"], 5, cfg["head_dim"], seed=3)
+    q8.set(1, k, v)
+    assert np.array_equal(q8.k[1, :, :5], torch.from_numpy(k / 0.5).to(torch.float8_e4m3fn).float().numpy() * 0.5)
