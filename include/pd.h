@@ -102,6 +102,22 @@ pd_status pd_layer_reserve(pd_layer *layer, int32_t max_tokens);
  */
 pd_status pd_kv_cache_create(const pd_layer *layer, int32_t max_seqs, int32_t max_len,
                              pd_kv_cache **out);
+/*
+ * The same cache stored as 8-bit floating point (OCP E4M3: 4 exponent bits with bias 7, 3 mantissa
+ * bits, no infinities, largest finite value 448) with one static scale for keys and one for
+ * values: an element x is held as the code nearest to x / scale (ties to the even mantissa,
+ * saturating at +-448) and read as scale * value(code).  Decode is bound by reading the cache
+ * (Section 2.1's memory-bound decode stage), so halving its bytes halves that part of a step.
+ * Everything attention reads from such a cache (pd_decode_step, pd_prefill_chunk, pd_kv_cache_get)
+ * is the quantised value; pd_prefill's own attention works on the fresh keys and values and only
+ * its stores quantise.  pd_kv_cache_set / _get still take and return tensors in the layer's dtype.
+ * All other cache calls behave as for pd_kv_cache_create.
+ * Errors: PD_ERR_INVALID_ARG (NULL, non-positive sizes, scales not positive and finite),
+ * PD_ERR_DTYPE (layer is not bf16 with head_dim 128, at most 16 query heads per kv head and
+ * dimensions that are multiples of 64), PD_ERR_OOM, PD_ERR_DEVICE.
+ */
+pd_status pd_kv_cache_create_fp8(const pd_layer *layer, int32_t max_seqs, int32_t max_len,
+                                 double k_scale, double v_scale, pd_kv_cache **out);
 void pd_kv_cache_destroy(pd_kv_cache *cache);
 
 /*

@@ -21,7 +21,7 @@ PD_ERR_KV_CAPACITY, PD_ERR_TTFT_INFEASIBLE, PD_ERR_TPOT_INFEASIBLE = 6, 7, 8
 PD_F32, PD_BF16 = 0, 1
 
 EXPORTS = [
-    "pd_layer_create", "pd_layer_destroy", "pd_layer_reserve", "pd_kv_cache_create",
+    "pd_layer_create", "pd_layer_destroy", "pd_layer_reserve", "pd_kv_cache_create", "pd_kv_cache_create_fp8",
     "pd_kv_cache_destroy", "pd_kv_cache_set", "pd_kv_cache_set_len", "pd_kv_cache_len",
     "pd_kv_cache_set_lens", "pd_kv_cache_get", "pd_profile_enable", "pd_profile_read", "pd_stream_copy", "pd_prefill", "pd_prefill_chunk", "pd_decode_step", "pd_last_expert_choice", "pd_allocate",
     "pd_fifo_replay", "pd_mm1_sojourn", "pd_fifo_replay_batched", "pd_prefill_throughput_dp", "pd_mg1_sojourn", "pd_allocate_stages", "pd_status_string", "pd_last_error",
@@ -73,7 +73,7 @@ class pd_allocation(C.Structure):
 
 
 if not os.path.exists(LIB_PATH):
-    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2603_04716_amd.build` "
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python paper_2603_04716_amd/build.py` "
                       "(there is no fallback path)")
 lib = C.CDLL(LIB_PATH)
 for _n in EXPORTS:
@@ -140,6 +140,13 @@ def pd_layer_reserve(layer, max_tokens):
 def pd_kv_cache_create(layer, max_seqs, max_len):
     h = C.c_void_p()
     _check(lib.pd_kv_cache_create(layer, C.c_int32(max_seqs), C.c_int32(max_len), C.byref(h)))
+    return h
+
+
+def pd_kv_cache_create_fp8(layer, max_seqs, max_len, k_scale, v_scale):
+    h = C.c_void_p()
+    _check(lib.pd_kv_cache_create_fp8(layer, C.c_int32(max_seqs), C.c_int32(max_len), C.c_double(k_scale),
+                                      C.c_double(v_scale), C.byref(h)))
     return h
 
 

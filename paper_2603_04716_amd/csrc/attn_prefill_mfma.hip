@@ -310,6 +310,58 @@ __global__ __launch_bounds__(256) void kv_gather_blocked_kernel(const uint16_t *
     }
 }
 
+// The same gather out of the 8-bit E4M3 blocked cache: codes are expanded to bf16 (code * scale).
+__global__ __launch_bounds__(256) void kv_gather_blocked_fp8_kernel(
+    const uint8_t *__restrict__ kc, const uint8_t *__restrict__ vc, size_t plane,
+    const int32_t *__restrict__ slots, const int32_t *__restrict__ cu, const int32_t *__restrict__ prefix,
+    const int32_t *__restrict__ pad_cu, int n_seqs, int Hkv, uint16_t *__restrict__ kx,
+    uint16_t *__restrict__ vt, int vt_ld, float k_scale, float v_scale)
+{
+    const int p0 = blockIdx.x * 64, g = blockIdx.y;
+    int lo = 0, hi = n_seqs;   // largest s with pad_cu[s] <= p0
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (pad_cu[mid] <= p0) lo = mid; else hi = mid;
+    }
+    const int s = lo;
+    const int Lk = prefix[s] + cu[s + 1] - cu[s];
+    const int pos0 = p0 - pad_cu[s];               // a multiple of 64
+    const uint8_t *kp = kc + ((size_t)slots[s] * Hkv + g) * plane;
+    const uint8_t *vp = vc + ((size_t)slots[s] * Hkv + g) * plane;
+    const int tid = threadIdx.x;
+    // keys: 64 positions x 16 runs of 8 channels (8 consecutive bytes of the cache)
+    for (int e = tid; e < 64 * 16; e += 256) {
+        const int r = e >> 4, c8 = (e & 15) * 8;
+        if (pos0 + r < Lk) {
+            const uint2 w = *(const uint2 *)(kp + kblk8_off(pos0 + r, c8));
+            uint4 o;
+            auto f = __builtin_amdgcn_cvt_pk_f32_fp8((int)w.x, false);
+            o.x = pack2bf(f[0] * k_scale, f[1] * k_scale);
+            f = __builtin_amdgcn_cvt_pk_f32_fp8((int)w.x, true);
+            o.y = pack2bf(f[0] * k_scale, f[1] * k_scale);
+            f = __builtin_amdgcn_cvt_pk_f32_fp8((int)w.y, false);
+            o.z = pack2bf(f[0] * k_scale, f[1] * k_scale);
+            f = __builtin_amdgcn_cvt_pk_f32_fp8((int)w.y, true);
+            o.w = pack2bf(f[0] * k_scale, f[1] * k_scale);
+            *(uint4 *)(kx + (size_t)(p0 + r) * (Hkv * HD) + g * HD + c8) = o;
+        }
+    }
+    // values: vt row d, 8 consecutive positions per thread
+    for (int e = tid; e < HD * 8; e += 256) {
+        const int d = e >> 3, c8 = (e & 7) * 8;    // positions pos0 + c8 .. + 7
+        float w[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int pos = pos0 + c8 + j;
+            w[j] = pos < Lk ? e4m3_decode(vp[vblk8_off(pos, d)]) * v_scale : 0.f;
+        }
+        uint4 o;
+        o.x = pack2bf(w[0], w[1]); o.y = pack2bf(w[2], w[3]);
+        o.z = pack2bf(w[4], w[5]); o.w = pack2bf(w[6], w[7]);
+        *(uint4 *)(vt + ((size_t)g * HD + d) * vt_ld + p0 + c8) = o;
+    }
+}
+
 bool attn_prefill_mfma_supported(const AttnArgs &a)
 {
     return a.hd == HD && !a.decode && a.ld % 8 == 0 && a.T > 0 &&
@@ -342,9 +394,14 @@ hipError_t launch_attn_chunk_mfma(const AttnArgs &a_in, const int32_t *d_slots, 
                                   int vt_ld, const int32_t *pad_cu, hipStream_t s)
 {
     AttnArgs a = a_in;
-    kv_gather_blocked_kernel<<<dim3(vt_ld / 64, a.Hkv), 256, 0, s>>>(
-        (const uint16_t *)a.k_cache, (const uint16_t *)a.v_cache, (size_t)a.max_len * HD, d_slots, a.d_cu,
-        a.prefix, pad_cu, a.n_seqs, a.Hkv, kx, vt, vt_ld);
+    if (a.kv_fp8)
+        kv_gather_blocked_fp8_kernel<<<dim3(vt_ld / 64, a.Hkv), 256, 0, s>>>(
+            (const uint8_t *)a.k_cache, (const uint8_t *)a.v_cache, (size_t)a.max_len * HD, d_slots, a.d_cu,
+            a.prefix, pad_cu, a.n_seqs, a.Hkv, kx, vt, vt_ld, a.k_scale, a.v_scale);
+    else
+        kv_gather_blocked_kernel<<<dim3(vt_ld / 64, a.Hkv), 256, 0, s>>>(
+            (const uint16_t *)a.k_cache, (const uint16_t *)a.v_cache, (size_t)a.max_len * HD, d_slots, a.d_cu,
+            a.prefix, pad_cu, a.n_seqs, a.Hkv, kx, vt, vt_ld);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     a.kx = kx;

@@ -75,7 +75,21 @@ hipError_t launch_decode_meta_chunks(const int32_t *d_slots, int B, int32_t *d_l
     return hipGetLastError();
 }
 
-template <bool MULTI>
+// 8 consecutive E4M3 codes (two words) -> one bf16 operand register set (every code is exact in bf16)
+__device__ __forceinline__ bf16x8 fp8x8_to_bf16(unsigned w0, unsigned w1)
+{
+    auto f0 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w0, false);
+    auto f1 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w0, true);
+    auto f2 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w1, false);
+    auto f3 = __builtin_amdgcn_cvt_pk_f32_fp8((int)w1, true);
+    u32x4 r = {pack2bf(f0[0], f0[1]), pack2bf(f1[0], f1[1]), pack2bf(f2[0], f2[1]), pack2bf(f3[0], f3[1])};
+    return __builtin_bit_cast(bf16x8, r);
+}
+
+// FP8: the cache holds E4M3 codes in the 8-bit blocked layout (half the bytes per key); the codes are
+// widened to bf16 in registers, the key scale is folded into the score scale and the value scale
+// into the final normalisation.
+template <bool MULTI, bool FP8>
 __global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a, int n_workers)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -119,15 +133,42 @@ __global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a, i
     const size_t plane = ((size_t)a.slots[b] * a.Hkv + g) * (size_t)a.max_len_pad * 128;
     const uint16_t *Kp = (const uint16_t *)a.k_cache + plane + qi * 32 + kg * 8;
     const uint16_t *Vp = (const uint16_t *)a.v_cache + plane + qi * 32 + kg * 8;
+    const uint8_t *Kp8 = (const uint8_t *)a.k_cache + plane + lane * 16;
+    const uint8_t *Vp8 = (const uint8_t *)a.v_cache + plane + lane * 16;
 
     f32x4 oacc[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) oacc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
     float m_run = -INFINITY, l_run = 0.f;
-    const float sl2e = a.scale * 1.4426950408889634f;
+    const float sl2e = a.scale * 1.4426950408889634f * (FP8 ? a.k_scale : 1.f);
+    const float o_scale = FP8 ? a.v_scale : 1.f;
 
     for (int k = key0; k < key1; k += 64) {
         bf16x8 kf[4][4], vf[2][8];
+        if (FP8) {
+            u32x4 kr[4][2], vr[8];
+            const uint8_t *kb_ptr = Kp8 + (size_t)(k >> 4) * 2048;
+            const uint8_t *vb_ptr = Vp8 + (size_t)(k >> 6) * 8192;
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+                for (int t = 0; t < 2; ++t) kr[kb][t] = *(const u32x4 *)(kb_ptr + kb * 2048 + t * 1024);
+#pragma unroll
+            for (int db = 0; db < 8; ++db) vr[db] = *(const u32x4 *)(vb_ptr + db * 1024);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    kf[kb][2 * t] = fp8x8_to_bf16(kr[kb][t][0], kr[kb][t][1]);
+                    kf[kb][2 * t + 1] = fp8x8_to_bf16(kr[kb][t][2], kr[kb][t][3]);
+                }
+#pragma unroll
+            for (int db = 0; db < 8; ++db) {
+                vf[0][db] = fp8x8_to_bf16(vr[db][0], vr[db][1]);
+                vf[1][db] = fp8x8_to_bf16(vr[db][2], vr[db][3]);
+            }
+        } else {
         const uint16_t *kb_ptr = Kp + (size_t)(k >> 4) * 2048;
         const uint16_t *vb_ptr = Vp + (size_t)(k >> 5) * 4096;
 #pragma unroll
@@ -138,6 +179,7 @@ __global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a, i
         for (int vb = 0; vb < 2; ++vb)
 #pragma unroll
             for (int db = 0; db < 8; ++db) vf[vb][db] = *(const bf16x8 *)(vb_ptr + vb * 4096 + db * 512);
+        }
         // all 32 loads (32 KB per wave) are issued before anything consumes them: bytes in flight,
         // not instruction count, is what this kernel lives on
         __builtin_amdgcn_sched_barrier(0);
@@ -205,7 +247,7 @@ __global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a, i
     if (col_ok && n_chunks == 1) {
         // the only chunk of its sequence: normalise and store the output row directly
         const int head = g * group + qh;
-        const float inv = 1.0f / l_tot;
+        const float inv = o_scale / l_tot;
         uint16_t *op = (uint16_t *)a.o + ((size_t)row * a.Hq + head) * 128 + 4 * kg;
 #pragma unroll
         for (int db = 0; db < 8; ++db) {
@@ -290,25 +332,31 @@ __global__ __launch_bounds__(128) void decode_attn_merge_kernel(DecodeAttnArgs a
     if ((d & 63) == 0) red[d >> 6] = L;
     __syncthreads();
     L = red[0] + red[1];
-    ((uint16_t *)a.o)[((size_t)row * a.Hq + head) * 128 + d] = f2bf(acc / L).x;
+    ((uint16_t *)a.o)[((size_t)row * a.Hq + head) * 128 + d] = f2bf(acc / L * (a.fp8 ? a.v_scale : 1.f)).x;
+}
+
+template <bool FP8>
+static hipError_t launch_decode_attn_t(const DecodeAttnArgs &a, int n_workers, hipStream_t s)
+{
+    if (a.u_ntok) {
+        decode_attn_kernel<true, FP8><<<(n_workers + 3) / 4, 256, 0, s>>>(a, n_workers);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        decode_attn_merge_kernel<true><<<dim3(a.B, a.Hkv * 16), 128, 0, s>>>(a);
+        return hipGetLastError();
+    }
+    decode_attn_kernel<false, FP8><<<(n_workers + 3) / 4, 256, 0, s>>>(a, n_workers);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    decode_attn_merge_kernel<false><<<dim3(a.B, a.Hq), 128, 0, s>>>(a);
+    return hipGetLastError();
 }
 
 hipError_t launch_decode_attn_mfma(const DecodeAttnArgs &a, hipStream_t s)
 {
     const int n_workers = a.total_chunks * a.Hkv;
     if (n_workers <= 0) return hipSuccess;
-    if (a.u_ntok) {
-        decode_attn_kernel<true><<<(n_workers + 3) / 4, 256, 0, s>>>(a, n_workers);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return e;
-        decode_attn_merge_kernel<true><<<dim3(a.B, a.Hkv * 16), 128, 0, s>>>(a);
-        return hipGetLastError();
-    }
-    decode_attn_kernel<false><<<(n_workers + 3) / 4, 256, 0, s>>>(a, n_workers);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    decode_attn_merge_kernel<false><<<dim3(a.B, a.Hq), 128, 0, s>>>(a);
-    return hipGetLastError();
+    return a.fp8 ? launch_decode_attn_t<true>(a, n_workers, s) : launch_decode_attn_t<false>(a, n_workers, s);
 }
 
 }  // namespace pd

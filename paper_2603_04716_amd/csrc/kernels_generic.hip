@@ -370,7 +370,11 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(RopeArgs a)
         if (slot >= 0 && h >= a.Hq) {
             int g = h - a.Hq;
             T *plane = (T *)a.k_cache + ((size_t)slot * a.Hkv + g) * a.max_len * a.hd;
-            if (a.blocked) {
+            if (a.fp8) {
+                uint8_t *p8 = (uint8_t *)a.k_cache + ((size_t)slot * a.Hkv + g) * a.max_len * a.hd;
+                p8[kblk8_off(pos, i)] = (uint8_t)e4m3_encode((double)y0 / a.k_scale);
+                p8[kblk8_off(pos, i + half)] = (uint8_t)e4m3_encode((double)y1 / a.k_scale);
+            } else if (a.blocked) {
                 Elem<T>::st(plane + kblk_off(pos, i), y0);
                 Elem<T>::st(plane + kblk_off(pos, i + half), y1);
             } else {
@@ -384,7 +388,10 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(RopeArgs a)
         for (int idx = threadIdx.x; idx < a.Hkv * a.hd; idx += 256) {
             int g = idx / a.hd, i = idx - g * a.hd;
             T *plane = (T *)a.v_cache + ((size_t)slot * a.Hkv + g) * a.max_len * a.hd;
-            if (a.blocked) plane[vblk_off(pos, i)] = vsrc[idx];
+            if (a.fp8)
+                ((uint8_t *)a.v_cache)[((size_t)slot * a.Hkv + g) * a.max_len * a.hd + vblk8_off(pos, i)] =
+                    (uint8_t)e4m3_encode((double)Elem<T>::ld(vsrc + idx) / a.v_scale);
+            else if (a.blocked) plane[vblk_off(pos, i)] = vsrc[idx];
             else plane[(size_t)pos * a.hd + i] = vsrc[idx];
         }
     }
@@ -543,6 +550,43 @@ hipError_t launch_kv_copy(int dtype, void *cache_k, void *cache_v, const void *k
         kv_copy_kernel<uint16_t><<<grid, 256, 0, s>>>((uint16_t *)cache_k, (uint16_t *)cache_v,
                                                       (uint16_t *)k, (uint16_t *)v, slot, Hkv, len,
                                                       hd, max_len, blocked, to_cache);
+    return hipGetLastError();
+}
+
+// [Hkv, len, 128] bf16 tensor <-> one slot of the 8-bit E4M3 blocked cache.  Into the cache: the
+// code of x / scale; out of it: scale * value(code), formed in double and rounded once to float
+// and once to bf16.
+__global__ void kv_copy_fp8_kernel(uint8_t *ck, uint8_t *cv, bf16_t *k, bf16_t *v, int slot, int Hkv,
+                                   int len, int max_len_pad, double k_scale, double v_scale, int to_cache)
+{
+    size_t n = (size_t)Hkv * len * 128;
+    for (size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x; idx < n;
+         idx += (size_t)gridDim.x * blockDim.x) {
+        int i = (int)(idx & 127);
+        size_t r = idx >> 7;
+        int p = (int)(r % len);
+        int g = (int)(r / len);
+        size_t plane = ((size_t)slot * Hkv + g) * max_len_pad * 128;
+        size_t c = plane + kblk8_off(p, i), cvo = plane + vblk8_off(p, i);
+        if (to_cache) {
+            ck[c] = (uint8_t)e4m3_encode((double)bf2f(k[idx]) / k_scale);
+            cv[cvo] = (uint8_t)e4m3_encode((double)bf2f(v[idx]) / v_scale);
+        } else {
+            k[idx] = f2bf((float)(k_scale * (double)e4m3_decode(ck[c])));
+            v[idx] = f2bf((float)(v_scale * (double)e4m3_decode(cv[cvo])));
+        }
+    }
+}
+
+hipError_t launch_kv_copy_fp8(void *cache_k, void *cache_v, const void *k, const void *v, int slot, int Hkv,
+                              int len, int max_len_pad, double k_scale, double v_scale, int to_cache,
+                              hipStream_t s)
+{
+    size_t n = (size_t)Hkv * len * 128;
+    if (n == 0) return hipSuccess;
+    unsigned grid = (unsigned)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
+    kv_copy_fp8_kernel<<<grid, 256, 0, s>>>((uint8_t *)cache_k, (uint8_t *)cache_v, (bf16_t *)k, (bf16_t *)v,
+                                            slot, Hkv, len, max_len_pad, k_scale, v_scale, to_cache);
     return hipGetLastError();
 }
 

@@ -2,6 +2,7 @@
 // pd_decode_step.  Each call validates on the host, then enqueues the layer's kernels on the
 // caller's stream in the order of the layer definition in pd.h.
 #include <math.h>
+#include <cmath>
 #include <string.h>
 
 #include <vector>
@@ -44,6 +45,8 @@ struct pd_kv_cache {
     int dtype, Hkv, hd, max_seqs, max_len;
     int blocked;       // bf16 / head_dim 128: blocked layout for the matrix-core decode attention
     int plane_len;     // positions per (slot, kv head) plane: max_len, or padded to 64 when blocked
+    int fp8;           // elements are 8-bit E4M3 codes of x / scale (blocked 8-bit layout)
+    double k_scale, v_scale;
     void *k, *v;
     int32_t *d_len;
     std::vector<int32_t> h_len;
@@ -325,12 +328,25 @@ extern "C" pd_status pd_layer_reserve(pd_layer *L, int32_t max_tokens)
 
 // ---- KV cache ------------------------------------------------------------------------------------
 
-extern "C" pd_status pd_kv_cache_create(const pd_layer *L, int32_t max_seqs, int32_t max_len,
-                                        pd_kv_cache **out)
+static pd_status cache_create(const pd_layer *L, int32_t max_seqs, int32_t max_len, int fp8, double k_scale,
+                              double v_scale, pd_kv_cache **out)
 {
     if (!L || !out || max_seqs <= 0 || max_len <= 0) {
         set_error("pd_kv_cache_create: bad argument");
         return PD_ERR_INVALID_ARG;
+    }
+    const bool can_block = L->cfg.dtype == PD_BF16 && L->cfg.head_dim == 128 &&
+                           L->cfg.n_q_heads / L->cfg.n_kv_heads <= 16;
+    if (fp8) {
+        if (!(k_scale > 0.0) || !(v_scale > 0.0) || !std::isfinite(k_scale) || !std::isfinite(v_scale)) {
+            set_error("pd_kv_cache_create_fp8: scales must be positive and finite");
+            return PD_ERR_INVALID_ARG;
+        }
+        if (!can_block || !L->use_mfma) {
+            set_error("pd_kv_cache_create_fp8: needs a bf16 layer with head_dim 128, at most 16 query heads per "
+                      "kv head and the matrix-core plan");
+            return PD_ERR_DTYPE;
+        }
     }
     pd_kv_cache *c = new pd_kv_cache();
     c->dtype = L->cfg.dtype;
@@ -338,11 +354,14 @@ extern "C" pd_status pd_kv_cache_create(const pd_layer *L, int32_t max_seqs, int
     c->hd = L->cfg.head_dim;
     c->max_seqs = max_seqs;
     c->max_len = max_len;
-    c->blocked = (L->cfg.dtype == PD_BF16 && c->hd == 128 && L->cfg.n_q_heads / c->Hkv <= 16) ? 1 : 0;
+    c->blocked = can_block ? 1 : 0;
     c->plane_len = c->blocked ? (max_len + 63) / 64 * 64 : max_len;
+    c->fp8 = fp8;
+    c->k_scale = fp8 ? k_scale : 1.0;
+    c->v_scale = fp8 ? v_scale : 1.0;
     c->k = c->v = nullptr;
     c->d_len = nullptr;
-    size_t bytes = (size_t)max_seqs * c->Hkv * c->plane_len * c->hd * L->esz;
+    size_t bytes = (size_t)max_seqs * c->Hkv * c->plane_len * c->hd * (fp8 ? 1 : L->esz);
     hipError_t e = hipMalloc(&c->k, bytes);
     if (e == hipSuccess) e = hipMalloc(&c->v, bytes);
     // zero fill: positions past a slot's length are multiplied by zero weights and must be finite
@@ -362,6 +381,18 @@ extern "C" pd_status pd_kv_cache_create(const pd_layer *L, int32_t max_seqs, int
     c->h_len.assign((size_t)max_seqs, 0);
     *out = c;
     return PD_OK;
+}
+
+extern "C" pd_status pd_kv_cache_create(const pd_layer *L, int32_t max_seqs, int32_t max_len,
+                                        pd_kv_cache **out)
+{
+    return cache_create(L, max_seqs, max_len, 0, 1.0, 1.0, out);
+}
+
+extern "C" pd_status pd_kv_cache_create_fp8(const pd_layer *L, int32_t max_seqs, int32_t max_len,
+                                            double k_scale, double v_scale, pd_kv_cache **out)
+{
+    return cache_create(L, max_seqs, max_len, 1, k_scale, v_scale, out);
 }
 
 extern "C" void pd_kv_cache_destroy(pd_kv_cache *c)
@@ -400,9 +431,14 @@ extern "C" pd_status pd_kv_cache_set(pd_kv_cache *c, int32_t slot, int32_t len, 
         set_error("pd_kv_cache_set: len %d > max_len %d", len, c->max_len);
         return PD_ERR_KV_CAPACITY;
     }
-    HIP_TRY(launch_kv_copy(c->dtype, c->k, c->v, k, v, slot, c->Hkv, len, c->hd, c->plane_len,
-                           c->blocked, 1, (hipStream_t)stream),
-            PD_ERR_DEVICE);
+    if (c->fp8)
+        HIP_TRY(launch_kv_copy_fp8(c->k, c->v, k, v, slot, c->Hkv, len, c->plane_len, c->k_scale, c->v_scale, 1,
+                                   (hipStream_t)stream),
+                PD_ERR_DEVICE);
+    else
+        HIP_TRY(launch_kv_copy(c->dtype, c->k, c->v, k, v, slot, c->Hkv, len, c->hd, c->plane_len,
+                               c->blocked, 1, (hipStream_t)stream),
+                PD_ERR_DEVICE);
     return pd_kv_cache_set_len(c, slot, len, stream);
 }
 
@@ -413,9 +449,14 @@ extern "C" pd_status pd_kv_cache_get(const pd_kv_cache *c, int32_t slot, int32_t
         set_error("pd_kv_cache_get: bad argument");
         return PD_ERR_INVALID_ARG;
     }
-    HIP_TRY(launch_kv_copy(c->dtype, c->k, c->v, k, v, slot, c->Hkv, len, c->hd, c->plane_len,
-                           c->blocked, 0, (hipStream_t)stream),
-            PD_ERR_DEVICE);
+    if (c->fp8)
+        HIP_TRY(launch_kv_copy_fp8(c->k, c->v, k, v, slot, c->Hkv, len, c->plane_len, c->k_scale, c->v_scale, 0,
+                                   (hipStream_t)stream),
+                PD_ERR_DEVICE);
+    else
+        HIP_TRY(launch_kv_copy(c->dtype, c->k, c->v, k, v, slot, c->Hkv, len, c->hd, c->plane_len,
+                               c->blocked, 0, (hipStream_t)stream),
+                PD_ERR_DEVICE);
     return PD_OK;
 }
 
@@ -598,6 +639,7 @@ static pd_status prefill_common(pd_layer *L, const pd_tokens *tk, pd_kv_cache *c
     r.tok_pos = L->tok_pos; r.tok_slot = keep ? L->tok_slot : nullptr;
     r.k_cache = keep ? cache->k : nullptr; r.v_cache = keep ? cache->v : nullptr;
     r.max_len = keep ? cache->plane_len : 0; r.blocked = keep ? cache->blocked : 0; r.inv_freq = L->inv_freq;
+    r.fp8 = keep ? cache->fp8 : 0; r.k_scale = keep ? cache->k_scale : 1.0; r.v_scale = keep ? cache->v_scale : 1.0;
     r.table = L->rope_table; r.table_len = kRopeTableLen;
     STEP("rope_kv_write", launch_rope_kv(c.dtype, r, s));
     AttnArgs a;
@@ -656,6 +698,7 @@ static pd_status prefill_common(pd_layer *L, const pd_tokens *tk, pd_kv_cache *c
         da.u_row0 = L->units + 2 * ws_t; da.u_ntok = L->units + 3 * ws_t;
         da.chunk_cu = L->chunk_cu; da.chunk_keys = chunk_keys; da.total_chunks = total_chunks;
         da.k_cache = cache->k; da.v_cache = cache->v; da.max_len_pad = cache->plane_len;
+        da.fp8 = cache->fp8; da.k_scale = (float)cache->k_scale; da.v_scale = (float)cache->v_scale;
         da.part_o = L->dec_part;
         da.part_ml = L->dec_part + (size_t)total_chunks * c.n_kv_heads * 16 * 128;
         STEP("prefill_attention", launch_decode_attn_mfma(da, s));
@@ -689,6 +732,7 @@ static pd_status prefill_common(pd_layer *L, const pd_tokens *tk, pd_kv_cache *c
         HIP_TRY(launch_write_ints(L->d_pad_cu, pad.data(), n + 1, s), PD_ERR_DEVICE);
         if (chunk) {
             a.prefix = L->d_prefix; a.k_cache = cache->k; a.v_cache = cache->v; a.max_len = cache->plane_len;
+            a.kv_fp8 = cache->fp8; a.k_scale = (float)cache->k_scale; a.v_scale = (float)cache->v_scale;
             STEP("prefill_attention",
                  launch_attn_chunk_mfma(a, L->d_slots, (uint16_t *)((char *)L->vt + vt_bytes), (uint16_t *)L->vt,
                                         vt_ld, L->d_pad_cu, s));
@@ -795,6 +839,7 @@ extern "C" pd_status pd_decode_step(pd_layer *L, const pd_batch *bt, pd_kv_cache
     r.qkv = L->qkv; r.ld = L->Nqkv; r.T = B; r.Hq = c.n_q_heads; r.Hkv = c.n_kv_heads; r.hd = c.head_dim;
     r.tok_pos = L->tok_pos; r.tok_slot = L->d_slots; r.k_cache = cache->k; r.v_cache = cache->v;
     r.max_len = cache->plane_len; r.blocked = cache->blocked; r.inv_freq = L->inv_freq;
+    r.fp8 = cache->fp8; r.k_scale = cache->k_scale; r.v_scale = cache->v_scale;
     r.table = L->rope_table; r.table_len = kRopeTableLen;
     STEP("rope_kv_append", launch_rope_kv(c.dtype, r, s));
     if (mfma_dec) {
@@ -804,6 +849,7 @@ extern "C" pd_status pd_decode_step(pd_layer *L, const pd_batch *bt, pd_kv_cache
         da.scale = (float)(1.0 / sqrt((double)c.head_dim)); da.slots = L->d_slots; da.pos = L->tok_pos;
         da.chunk_cu = L->chunk_cu; da.chunk_keys = chunk_keys; da.total_chunks = total_chunks;
         da.k_cache = cache->k; da.v_cache = cache->v; da.max_len_pad = cache->plane_len;
+        da.fp8 = cache->fp8; da.k_scale = (float)cache->k_scale; da.v_scale = (float)cache->v_scale;
         da.part_o = L->dec_part;
         da.part_ml = L->dec_part + (size_t)total_chunks * c.n_q_heads * 128;
         STEP("decode_attention", launch_decode_attn_mfma(da, s));

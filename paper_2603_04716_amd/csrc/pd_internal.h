@@ -60,6 +60,54 @@ __host__ __device__ __forceinline__ size_t vblk_off(int pos, int d)
     return (size_t)(pos >> 5) * 4096 + (size_t)d * 32 + 8 * ((pp >> 2) & 3) + 4 * (pp >> 4) + (pp & 3);
 }
 
+// The same cache held as 8-bit E4M3 codes (one byte per element, byte offsets inside a plane of
+// max_len_pad * 128 bytes).  A 16-byte-per-lane load still fills whole operand registers:
+//   keys:   blocks of 16 positions (2 KB) = two 1 KB halves t; lane 16*kg + position%16 of half t
+//           holds channels 64t + 8kg .. +7 (bytes 0-7) and 64t + 32 + 8kg .. +7 (bytes 8-15), i.e.
+//           its A operands of k-steps 2t and 2t+1.
+//   values: blocks of 64 positions (8 KB) = eight 1 KB groups of 16 channels; lane 16*kg + channel%16
+//           holds the 8 keys sigma^-1(8kg .. 8kg+7) of the first 32 positions (bytes 0-7) and of the
+//           second 32 positions (bytes 8-15).
+__host__ __device__ __forceinline__ size_t kblk8_off(int pos, int c)
+{
+    return (size_t)(pos >> 4) * 2048 + (size_t)(c >> 6) * 1024 + ((c >> 3) & 3) * 256 + (pos & 15) * 16 +
+           ((c >> 5) & 1) * 8 + (c & 7);
+}
+__host__ __device__ __forceinline__ size_t vblk8_off(int pos, int d)
+{
+    const int pp = pos & 31;
+    const int sg = 8 * ((pp >> 2) & 3) + 4 * (pp >> 4) + (pp & 3);
+    return (size_t)(pos >> 6) * 8192 + (size_t)(d >> 4) * 1024 + (sg >> 3) * 256 + (d & 15) * 16 +
+           ((pos >> 5) & 1) * 8 + (sg & 7);
+}
+
+// OCP FP8 E4M3 ("fn": no infinities, NaN = 0x7F / 0xFF, largest finite 448): nearest code of q,
+// ties to the even mantissa, saturating.  Works on the bit pattern of the double: the 53-bit
+// significand is cut at the quantum 2^(max(exponent, -6) - 3) and rounded on the discarded bits;
+// a carry out of the mantissa lands in the exponent field by plain addition.
+__device__ __forceinline__ uint32_t e4m3_encode(double q)
+{
+    uint64_t b = (uint64_t)__double_as_longlong(q);
+    const uint32_t sign = (uint32_t)(b >> 56) & 0x80u;
+    b &= 0x7FFFFFFFFFFFFFFFull;
+    if (b > 0x7FF0000000000000ull) return sign | 0x7Fu;        // NaN
+    if (b >= 0x407C000000000000ull) return sign | 0x7Eu;        // |q| >= 448
+    const int ex = (int)(b >> 52) - 1023;
+    if (ex < -10) return sign;                                  // below half the smallest subnormal
+    const uint64_t mant = (b & 0x000FFFFFFFFFFFFFull) | 0x0010000000000000ull;
+    const int E = ex < -6 ? -6 : ex;
+    const int sh = 49 + (E - ex);                               // 49 .. 53
+    uint32_t n = (uint32_t)(mant >> sh);
+    const uint64_t rem = mant & ((1ull << sh) - 1), half = 1ull << (sh - 1);
+    if (rem > half || (rem == half && (n & 1u))) ++n;
+    return sign | (uint32_t)(((E + 7) << 3) + (int)n - 8);
+}
+// value of one code (hardware conversion; exact for every code)
+__device__ __forceinline__ float e4m3_decode(uint32_t code)
+{
+    return __builtin_amdgcn_cvt_pk_f32_fp8((int)code, false)[0];
+}
+
 // Packed weight layout of the matrix-core kernels.  A [N, K] matrix is cut into blocks of 16 rows x
 // 32 k (1 KB); inside a block the order is [k/8][row][k%8], i.e. exactly the register image of one
 // v_mfma_f32_16x16x32_bf16 A operand (lane = 16*(k/8) + row holds 8 consecutive k), so a wave reads
@@ -131,6 +179,8 @@ struct RopeArgs {
     void *k_cache, *v_cache; // [slots][Hkv][max_len][hd], or the blocked layout above
     int32_t max_len;         // plane length in positions (padded length for the blocked layout)
     int32_t blocked;
+    int32_t fp8;             // blocked cache of E4M3 codes: element stored = code of x / scale
+    double k_scale, v_scale;
     const double *inv_freq;  // [hd/2] rope_base^(-2i/hd)
     const float2 *table;     // optional [table_len][hd/2] (cos, sin) of pos * inv_freq, made in double
     int32_t table_len;
@@ -161,6 +211,9 @@ struct AttnArgs {
     int32_t kx_ld;
     const int32_t *k_cu;     // [n_seqs+1]
     const int32_t *prefix;   // [n_seqs]
+    // chunked prefill source is the 8-bit E4M3 blocked cache: gathered values are code * scale
+    int32_t kv_fp8;
+    float k_scale, v_scale;
 };
 hipError_t launch_attn_generic(int dtype, const AttnArgs &a, hipStream_t s);
 bool attn_prefill_mfma_supported(const AttnArgs &a);
@@ -179,6 +232,10 @@ hipError_t launch_stream_copy(void *dst, const void *src, size_t n_vec16, hipStr
 hipError_t launch_kv_copy(int dtype, void *cache_k, void *cache_v, const void *k, const void *v,
                           int slot, int Hkv, int len, int hd, int max_len, int blocked, int to_cache,
                           hipStream_t s);
+// the same for the 8-bit E4M3 blocked cache (bf16 tensors outside, head_dim 128)
+hipError_t launch_kv_copy_fp8(void *cache_k, void *cache_v, const void *k, const void *v, int slot, int Hkv,
+                              int len, int max_len_pad, double k_scale, double v_scale, int to_cache,
+                              hipStream_t s);
 
 // ---- matrix-core decode attention over the blocked cache (bf16, head_dim 128, group <= 16) ---------
 struct DecodeAttnArgs {
@@ -202,6 +259,9 @@ struct DecodeAttnArgs {
     // (token, head of the group) pairs; partials are then [total_chunks][Hkv][16][128] / [..][2].
     const int32_t *u_row0;
     const int32_t *u_ntok;
+    // E4M3 cache (the 8-bit blocked layout): value = code * scale
+    int32_t fp8;
+    float k_scale, v_scale;
 };
 hipError_t launch_decode_attn_mfma(const DecodeAttnArgs &a, hipStream_t s);
 // pos[b] = len[slot[b]]; len[slot[b]] += 1; chunk_cu = prefix sum of ceil((pos+1)/chunk_keys)

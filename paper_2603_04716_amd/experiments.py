@@ -6,6 +6,8 @@
     python -m paper_2603_04716_amd.experiments queue        # Poisson arrivals served FIFO by the GPU prefill,
                                                             # mean TTFT vs the M/M/1 prediction of Eq. (12)
     python -m paper_2603_04716_amd.experiments moe          # 8-expert top-2 layer: prefill + decode sweep
+    python -m paper_2603_04716_amd.experiments fp8kv        # decode curve over the KV cache held as 8-bit E4M3
+                                                            # codes beside the bf16 cache, KV 2048 and 8192
 
 Each run prints one JSON document.  Inputs are the seeded synthetic draws of pd_inputs.
 """
@@ -355,10 +357,64 @@ def run_stack(n_layers=32, n_weight_sets=4, batches=(1, 8, 64, 256), kv_len=2048
     return res
 
 
+def run_fp8kv():
+    """Decode TPOT curve and largest batch under TPOT 20 ms with the cache in bf16 and as E4M3 codes."""
+    cfg, layer = _layer("llama8b")
+    hkv, hd, d = cfg["n_kv_heads"], cfg["head_dim"], cfg["d_model"]
+    out = {"experiment": "decode over a bf16 vs an 8-bit E4M3 KV cache", "cases": []}
+    for S, bmax, batches in ((2048, 512, (64, 128, 256, 320, 384, 512)), (8192, 128, (16, 32, 64, 128))):
+        xall = H._dev(I.hidden(bmax, d, seed=12, dtype="bf16"), "bf16")
+        k, v = I.kv_fill(hkv, S, hd, seed=11, dtype="bf16")
+        kd, vd = H._dev(k, "bf16"), H._dev(v, "bf16")
+        for kind in ("bf16", "fp8_e4m3"):
+            cache = layer.new_cache(bmax, S + 8, fp8_scales=None if kind == "bf16" else (0.5, 0.125))
+            layer.fill_cache(cache, [S] * bmax, kd, vd)
+            kv_esz = 2 if kind == "bf16" else 1
+            pts = {}
+
+            def tpot(B):
+                if B not in pts:
+                    run = layer.make_decode_step(cache, xall[:B].contiguous(), [S] * B)
+                    pts[B] = H.median([run() for _ in range(7)])
+                return N_LAYERS * pts[B] * 1e-3
+
+            curve = []
+            for B in batches:
+                t = tpot(B)
+                by = H.decode_bytes(cfg, [S] * B, kv_esz=kv_esz)
+                curve.append({"batch": B, "ms_per_layer": round(pts[B], 4), "tpot_ms": round(t * 1e3, 3),
+                              "tok_s": round(B / t, 1), "hbm_frac": round(by / (t / N_LAYERS) / HBM_PEAK, 4)})
+            b, t, _ = H.largest_feasible_batch(tpot, 0.020, bmax)
+            best = {"tpot_slo_ms": 20.0, "max_batch": b}
+            if b:
+                best.update(tpot_ms=round(t * 1e3, 3), tok_s=round(b / t, 1), capped=(b == bmax))
+            # attention's own share at the largest batch of the curve, from the library's step timers
+            B = batches[-1]
+            slots = list(range(B))
+            o = torch.empty_like(xall[:B])
+            pd.pd_profile_enable(layer.h, True)
+            att = []
+            for _ in range(5):
+                pd.pd_kv_cache_set_lens(cache, slots, [S] * B)
+                pd.pd_decode_step(layer.h, xall[:B].contiguous(), slots, cache, o)
+                torch.cuda.synchronize()
+                att.append(dict(pd.pd_profile_read(layer.h))["decode_attention"])
+            pd.pd_profile_enable(layer.h, False)
+            att_ms = H.median(att)
+            kv_bytes = 2.0 * hkv * hd * kv_esz * (S + 1) * B
+            out["cases"].append({"kv_len": S, "cache": kind, "curve": curve, "target": best,
+                                 "attention": {"batch": B, "ms": round(att_ms, 4),
+                                               "cache_gbps": round(kv_bytes / (att_ms * 1e-3) / 1e9, 1)}})
+            layer.free_cache(cache)
+        del kd, vd, xall
+    layer.close()
+    return out
+
+
 def main():
     which = sys.argv[1] if len(sys.argv) > 1 else "prefill"
     fn = {"prefill": run_prefill, "longctx": run_longctx, "queue": run_queue, "moe": run_moe,
-          "chunk": run_chunk, "stack": run_stack, "queue_fixed": run_queue_fixed}[which]
+          "chunk": run_chunk, "stack": run_stack, "queue_fixed": run_queue_fixed, "fp8kv": run_fp8kv}[which]
     print(json.dumps(fn()))
 
 

@@ -35,12 +35,14 @@ def prefill_flops(cfg, seq_lens):
     return fl
 
 
-def decode_bytes(cfg, kv_lens, experts_touched=None, esz=2):
-    """Weights touched once + every cached key/value row once (the new row included)."""
+def decode_bytes(cfg, kv_lens, experts_touched=None, esz=2, kv_esz=None):
+    """Weights touched once + every cached key/value row once (the new row included); kv_esz:
+    bytes per cached element when it differs from the weights' (1 for the 8-bit cache)."""
+    kv_esz = esz if kv_esz is None else kv_esz
     attn, ffn = layer_params(cfg)
     n_ffn = experts_touched if cfg.get("n_experts", 0) else 1
     w = (attn + n_ffn * ffn) * esz
-    kv = sum(2 * cfg["n_kv_heads"] * cfg["head_dim"] * esz * (int(s) + 1) for s in kv_lens)
+    kv = sum(2 * cfg["n_kv_heads"] * cfg["head_dim"] * kv_esz * (int(s) + 1) for s in kv_lens)
     return float(w + kv)
 
 
@@ -68,8 +70,12 @@ class Layer:
         self.caches = []
         pd.pd_layer_destroy(self.h)
 
-    def new_cache(self, n_slots, max_len):
-        c = pd.pd_kv_cache_create(self.h, n_slots, max_len)
+    def new_cache(self, n_slots, max_len, fp8_scales=None):
+        """fp8_scales = (k_scale, v_scale): the cache holds 8-bit E4M3 codes with these static scales."""
+        if fp8_scales is None:
+            c = pd.pd_kv_cache_create(self.h, n_slots, max_len)
+        else:
+            c = pd.pd_kv_cache_create_fp8(self.h, n_slots, max_len, *fp8_scales)
         self.caches.append(c)
         return c
 

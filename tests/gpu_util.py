@@ -31,8 +31,11 @@ class GpuLayer:
         self.h = pd.pd_layer_create(cfg, self.dev_w)
         self.caches = []
 
-    def cache(self, n_slots, max_len):
-        c = pd.pd_kv_cache_create(self.h, n_slots, max_len)
+    def cache(self, n_slots, max_len, fp8_scales=None):
+        if fp8_scales is None:
+            c = pd.pd_kv_cache_create(self.h, n_slots, max_len)
+        else:
+            c = pd.pd_kv_cache_create_fp8(self.h, n_slots, max_len, *fp8_scales)
         self.caches.append(c)
         return c
 
