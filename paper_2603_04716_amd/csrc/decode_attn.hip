@@ -14,9 +14,9 @@
 //
 // Workers write un-normalised partial outputs with their running max and sum; a small merge
 // kernel combines the chunks of each (sequence, head).  A sequence of n keys is cut into
-// ceil(n / chunk_keys) chunks of equal size (rounded up to 64 keys), and chunk_keys is chosen so
-// that one launch has about 2048 workers: one per wave slot of the chip, which measured fastest
-// (more, smaller chunks lose to the per-worker start-up; fewer leave wave slots empty).
+// ceil(n / chunk_keys) chunks of equal size (rounded up to 64 keys); the caller picks chunk_keys
+// so that a launch has enough workers to saturate the memory system and no more (each extra
+// chunk costs a start-up and a row of partials to merge).
 #include "pd_internal.h"
 
 namespace pd {

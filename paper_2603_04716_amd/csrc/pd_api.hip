@@ -53,6 +53,11 @@ struct pd_kv_cache {
 };
 
 static const int kMaxSeqs = 4096;
+// Wavefront-sized workers one decode attention launch aims for.  A lone worker streams about
+// 13 GB/s, so some 500 of them saturate the memory system; beyond that the time is the bytes moved,
+// and more, smaller chunks only add start-up and merge work.  768 measured best from batch 4 to
+// 128 at 2048 cached tokens (bf16 and 8-bit caches); larger batches have one chunk per sequence.
+static const int kDecodeWorkers = 768;
 static const int kShortChunk = 8;   // chunks up to this many tokens use the decode attention kernel per row
 static const int kRopeTableLen = 32768;   // positions with precomputed rotary factors
 
@@ -673,7 +678,7 @@ static pd_status prefill_common(pd_layer *L, const pd_tokens *tk, pd_kv_cache *c
             }
         }
         const int nu = (int)u_slot.size();
-        long long ck = ((total_keys * c.n_kv_heads + 2047) / 2048 + 63) / 64 * 64;
+        long long ck = ((total_keys * c.n_kv_heads + kDecodeWorkers - 1) / kDecodeWorkers + 63) / 64 * 64;
         const int chunk_keys = (int)(ck < 64 ? 64 : ck);
         std::vector<int32_t> ccu((size_t)nu + 1);
         ccu[0] = 0;
@@ -807,13 +812,13 @@ extern "C" pd_status pd_decode_step(pd_layer *L, const pd_batch *bt, pd_kv_cache
     hipStream_t s = (hipStream_t)stream;
     L->prof_names.clear();
 
-    // decode attention work split: about 2048 wavefront-sized workers (one per wave slot)
+    // decode attention work split: about kDecodeWorkers wavefront-sized workers
     const bool mfma_dec = cache->blocked != 0;
     int chunk_keys = 64, total_chunks = 0;
     if (mfma_dec) {
         long long total_keys = 0;
         for (int b = 0; b < B; ++b) total_keys += cache->h_len[(size_t)bt->slots[b]] + 1;
-        long long ck = ((total_keys * c.n_kv_heads + 2047) / 2048 + 63) / 64 * 64;
+        long long ck = ((total_keys * c.n_kv_heads + kDecodeWorkers - 1) / kDecodeWorkers + 63) / 64 * 64;
         chunk_keys = (int)(ck < 64 ? 64 : ck);
         for (int b = 0; b < B; ++b)
             total_chunks += (cache->h_len[(size_t)bt->slots[b]] + 1 + chunk_keys - 1) / chunk_keys;
