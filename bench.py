@@ -30,8 +30,8 @@ DECODE_REPS = 3                    # decode steps per batch size per step; media
 # the FETCH_SIZE / WRITE_SIZE counters scaled by a plain copy (paper_2603_04716_amd/traffic_probe.py).
 # Valid only for the kernel source the counters were taken on.
 TRAFFIC = {"source": os.path.join("paper_2603_04716_amd", "csrc", "gemm_mfma.hip"),
-           "sha256": "037a06574c398a6833fd2b76fadcf425a5588280d048ef56742fdecd68b6993f",
-           "bytes_per_launch": 3053.7e6}
+           "sha256": "cc77504d529ca0108747937a039102e0b204da152b9f4881f48ee14faec0d22d",
+           "bytes_per_launch": 3053.6e6}
 
 
 def counted_traffic():

@@ -363,6 +363,8 @@ static hipError_t launch_cfg(const GemmArgs &a, hipStream_t s, int splits = 1)
         kern<<<grid, block, smem, s>>>(a, tiles_m, tiles_n, kt_per);                             \
     } while (0)
     if (splits > 1) {
+        // fp32 partials of every split must fit the scratch buffer
+        if (!a.splitk_ws || (size_t)splits * a.M * n_cols > a.splitk_ws_elems) return hipErrorInvalidValue;
         LAUNCH(EPI_PARTIAL);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
