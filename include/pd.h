@@ -307,6 +307,22 @@ pd_status pd_prefill_throughput_dp(double prefill_max_tps, double l_in, double t
 pd_status pd_mg1_sojourn(double lambda_rps, double mean_service_s, double mean_service_sq_s2,
                          double *t_s);
 
+/*
+ * The overhead term of Eq. (8) as a model instead of a given scalar (host only).  The paper names
+ * its parts: the request's input / output transmission between the user and the server, and the
+ * transmission of the KV cache from the prefill to the decode instance.  Here
+ *   t_overhead = fixed_s + l_in * n_layers * 2 * n_kv_heads * head_dim * bytes_per_elem / link_bytes_per_s
+ * (the keys and values of all l_in prompt tokens of every layer cross one link of the given rate;
+ * fixed_s holds everything that does not grow with the prompt: user-side transmission, connection
+ * set-up).  bytes_per_elem is 2 for a bf16 cache, 1 for the 8-bit one; l_in may be fractional
+ * (a mean).  The result is what pd_measured_curves.t_overhead_s takes.
+ * Errors: PD_ERR_INVALID_ARG (NULL, negative or non-finite values, non-positive sizes or rate);
+ * output untouched on error.
+ */
+pd_status pd_kv_transfer_overhead(double l_in, int32_t n_layers, int32_t n_kv_heads, int32_t head_dim,
+                                  double bytes_per_elem, double link_bytes_per_s, double fixed_s,
+                                  double *t_overhead_s);
+
 const char *pd_status_string(pd_status s);
 const char *pd_last_error(void);
 

@@ -113,6 +113,13 @@ def mg1_sojourn(lam, mean_s, mean_s2):
     return mean_s + lam * mean_s2 / (2.0 * (1.0 - rho))
 
 
+def kv_transfer_overhead(l_in, n_layers, n_kv_heads, head_dim, bytes_per_elem, link_bytes_per_s, fixed_s=0.0):
+    """The overhead term of Eq. (8) modelled from its named parts: a fixed part (user-side
+    transmission) plus the prompt's keys and values of every layer over one link."""
+    kv_bytes = l_in * (n_layers * 2.0 * n_kv_heads * head_dim * bytes_per_elem)
+    return fixed_s + kv_bytes / link_bytes_per_s
+
+
 def fifo_replay(arrivals, services):
     """Single FIFO server in virtual time: D_i = max(A_i, D_{i-1}) + S_i; returns D_i - A_i."""
     out = []

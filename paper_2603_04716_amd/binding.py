@@ -24,7 +24,7 @@ EXPORTS = [
     "pd_layer_create", "pd_layer_destroy", "pd_layer_reserve", "pd_kv_cache_create", "pd_kv_cache_create_fp8",
     "pd_kv_cache_destroy", "pd_kv_cache_set", "pd_kv_cache_set_len", "pd_kv_cache_len",
     "pd_kv_cache_set_lens", "pd_kv_cache_get", "pd_profile_enable", "pd_profile_read", "pd_stream_copy", "pd_prefill", "pd_prefill_chunk", "pd_decode_step", "pd_last_expert_choice", "pd_allocate",
-    "pd_fifo_replay", "pd_mm1_sojourn", "pd_fifo_replay_batched", "pd_prefill_throughput_dp", "pd_mg1_sojourn", "pd_allocate_stages", "pd_status_string", "pd_last_error",
+    "pd_fifo_replay", "pd_mm1_sojourn", "pd_fifo_replay_batched", "pd_prefill_throughput_dp", "pd_mg1_sojourn", "pd_kv_transfer_overhead", "pd_allocate_stages", "pd_status_string", "pd_last_error",
 ]
 
 
@@ -87,6 +87,7 @@ lib.pd_kv_cache_destroy.argtypes = [C.c_void_p]
 lib.pd_allocate.argtypes = [C.c_double] * 5 + [C.POINTER(pd_measured_curves), C.POINTER(pd_allocation)]
 lib.pd_mm1_sojourn.argtypes = [C.c_double] * 3 + [C.POINTER(C.c_double)]
 lib.pd_mg1_sojourn.argtypes = [C.c_double] * 3 + [C.POINTER(C.c_double)]
+lib.pd_kv_transfer_overhead.argtypes = ([C.c_double] + [C.c_int32] * 3 + [C.c_double] * 3 + [C.POINTER(C.c_double)])
 lib.pd_prefill_throughput_dp.argtypes = [C.c_double] * 4 + [C.c_int32, C.POINTER(C.c_double)]
 
 
@@ -280,6 +281,13 @@ def pd_prefill_throughput_dp(prefill_max_tps, l_in, ttft_slo_s, t_overhead_s, dp
 def pd_mg1_sojourn(lambda_rps, mean_service_s, mean_service_sq_s2):
     t = C.c_double()
     _check(lib.pd_mg1_sojourn(float(lambda_rps), float(mean_service_s), float(mean_service_sq_s2), C.byref(t)))
+    return t.value
+
+
+def pd_kv_transfer_overhead(l_in, n_layers, n_kv_heads, head_dim, bytes_per_elem, link_bytes_per_s, fixed_s=0.0):
+    t = C.c_double()
+    _check(lib.pd_kv_transfer_overhead(float(l_in), C.c_int32(n_layers), C.c_int32(n_kv_heads), C.c_int32(head_dim),
+                                       float(bytes_per_elem), float(link_bytes_per_s), float(fixed_s), C.byref(t)))
     return t.value
 
 

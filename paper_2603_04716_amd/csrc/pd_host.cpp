@@ -255,6 +255,22 @@ extern "C" pd_status pd_mg1_sojourn(double lambda_rps, double mean_service_s, do
     return PD_OK;
 }
 
+extern "C" pd_status pd_kv_transfer_overhead(double l_in, int32_t n_layers, int32_t n_kv_heads,
+                                             int32_t head_dim, double bytes_per_elem,
+                                             double link_bytes_per_s, double fixed_s, double *t_overhead_s)
+{
+    if (!t_overhead_s || !std::isfinite(l_in) || l_in < 0.0 || n_layers <= 0 || n_kv_heads <= 0 ||
+        head_dim <= 0 || !pos_finite(bytes_per_elem) || !pos_finite(link_bytes_per_s) ||
+        !std::isfinite(fixed_s) || fixed_s < 0.0) {
+        pd::set_error("pd_kv_transfer_overhead: bad arguments");
+        return PD_ERR_INVALID_ARG;
+    }
+    // bytes of keys and values per prompt token over all layers, then the whole prompt over the link
+    const double per_token = (double)n_layers * 2.0 * (double)n_kv_heads * (double)head_dim * bytes_per_elem;
+    *t_overhead_s = fixed_s + l_in * per_token / link_bytes_per_s;
+    return PD_OK;
+}
+
 extern "C" pd_status pd_mm1_sojourn(double prefill_max_tps, double l_in, double lambda_rps,
                                     double *t_s)
 {

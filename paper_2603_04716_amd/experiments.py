@@ -8,6 +8,8 @@
     python -m paper_2603_04716_amd.experiments moe          # 8-expert top-2 layer: prefill + decode sweep
     python -m paper_2603_04716_amd.experiments fp8kv        # decode curve over the KV cache held as 8-bit E4M3
                                                             # codes beside the bf16 cache, KV 2048 and 8192
+    python -m paper_2603_04716_amd.experiments kvxfer       # KV hand-off: cache export / import per layer, the
+                                                            # modelled link, Eq. (13) with that overhead
 
 Each run prints one JSON document.  Inputs are the seeded synthetic draws of pd_inputs.
 """
@@ -411,10 +413,61 @@ def run_fp8kv():
     return out
 
 
+def run_kvxfer():
+    """The KV hand-off from a prefill to a decode instance as far as one GPU shows it: reading a
+    sequence's keys and values out of the (blocked) cache into one contiguous buffer and writing
+    such a buffer into another cache, per layer; the link itself is the model of
+    pd_kv_transfer_overhead.  Then Eq. (13) with the modelled overhead instead of a given scalar."""
+    cfg, layer = _layer("llama8b")
+    hkv, hd, d = cfg["n_kv_heads"], cfg["head_dim"], cfg["d_model"]
+    out = {"experiment": "KV hand-off: cache export / import on the GPU, modelled link, effect on Eq. (13)", "cases": []}
+    T = 8192
+    x = H._dev(I.hidden(T, d, seed=10, dtype="bf16"), "bf16")
+    for l_in in (2048, 6144):
+        src, dst = layer.new_cache(2, l_in), layer.new_cache(2, l_in)
+        k, v = I.kv_fill(hkv, l_in, hd, seed=11, dtype="bf16")
+        kd, vd = H._dev(k, "bf16"), H._dev(v, "bf16")
+        pd.pd_kv_cache_set(src, 0, kd, vd)
+        kb, vb = torch.empty_like(kd), torch.empty_like(vd)
+        e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        exp_ms, imp_ms = [], []
+        for _ in range(9):
+            e0.record()
+            pd.pd_kv_cache_get(src, 0, kb, vb)
+            e1.record()
+            pd.pd_kv_cache_set(dst, 1, kb, vb)
+            e2.record()
+            e2.synchronize()
+            exp_ms.append(e0.elapsed_time(e1))
+            imp_ms.append(e1.elapsed_time(e2))
+        assert torch.equal(kb, kd) and torch.equal(vb, vd)
+        layer_bytes = 2.0 * hkv * hd * 2 * l_in
+        ex, im = H.median(exp_ms), H.median(imp_ms)
+        n_seq = T // l_in if T % l_in == 0 else 1
+        cu = I.uniform_cu_seqlens(n_seq, l_in)
+        ms = layer.time_prefill(x[:n_seq * l_in].contiguous(), cu, iters=8, warmup=3)
+        tp_max = n_seq * l_in / (N_LAYERS * ms * 1e-3)
+        case = {"l_in": l_in, "kv_mb_per_layer": round(layer_bytes / 1e6, 2), "export_ms_per_layer": round(ex, 4),
+                "import_ms_per_layer": round(im, 4), "export_gbps": round(2 * layer_bytes / (ex * 1e-3) / 1e9, 1),
+                "import_gbps": round(2 * layer_bytes / (im * 1e-3) / 1e9, 1),
+                "on_gpu_ms_model": round(N_LAYERS * (ex + im), 3), "prefill_max_tok_s": round(tp_max, 1), "links": []}
+        for name, bw, esz in (("400 Gb/s, bf16 cache", 50e9, 2.0), ("400 Gb/s, 8-bit cache", 50e9, 1.0),
+                              ("100 Gb/s, bf16 cache", 12.5e9, 2.0)):
+            tov = pd.pd_kv_transfer_overhead(l_in, N_LAYERS, hkv, hd, esz, bw, N_LAYERS * (ex + im) * 1e-3)
+            case["links"].append({"link": name, "t_overhead_ms": round(tov * 1e3, 2),
+                                  "tp_prefill_eq13": round(pd.pd_prefill_throughput_dp(tp_max, l_in, 2.0, tov, 1), 1)})
+        case["tp_prefill_eq13_no_overhead"] = round(pd.pd_prefill_throughput_dp(tp_max, l_in, 2.0, 0.0, 1), 1)
+        out["cases"].append(case)
+        layer.free_cache(src)
+        layer.free_cache(dst)
+    layer.close()
+    return out
+
+
 def main():
     which = sys.argv[1] if len(sys.argv) > 1 else "prefill"
     fn = {"prefill": run_prefill, "longctx": run_longctx, "queue": run_queue, "moe": run_moe,
-          "chunk": run_chunk, "stack": run_stack, "queue_fixed": run_queue_fixed, "fp8kv": run_fp8kv}[which]
+          "chunk": run_chunk, "stack": run_stack, "queue_fixed": run_queue_fixed, "fp8kv": run_fp8kv, "kvxfer": run_kvxfer}[which]
     print(json.dumps(fn()))
 
 

@@ -130,6 +130,15 @@ def test_queue_variants_bit_exact_against_oracle():
         lam, ms = float(rng.uniform(0.1, 5)), float(rng.uniform(0.01, 0.15))
         ms2 = ms * ms * float(rng.uniform(1.0, 3.0))
         assert pd.pd_mg1_sojourn(lam, ms, ms2) == A.mg1_sojourn(lam, ms, ms2)
+        l_in = float(rng.uniform(0, 20000))
+        args = (l_in, int(rng.integers(1, 100)), int(rng.integers(1, 65)), int(rng.integers(1, 257)),
+                float(rng.choice([1.0, 2.0, 4.0])), float(rng.uniform(1e9, 1e12)), float(rng.uniform(0, 0.2)))
+        assert pd.pd_kv_transfer_overhead(*args) == A.kv_transfer_overhead(*args)
+    for bad in [(-1.0, 32, 8, 128, 2.0, 5e10, 0.0), (10.0, 0, 8, 128, 2.0, 5e10, 0.0), (10.0, 32, 8, 128, 2.0, 0.0, 0.0),
+                (10.0, 32, 8, 128, 2.0, 5e10, -0.1), (float("nan"), 32, 8, 128, 2.0, 5e10, 0.0)]:
+        with pytest.raises(pd.PdError) as e:
+            pd.pd_kv_transfer_overhead(*bad)
+        assert e.value.status == pd.PD_ERR_INVALID_ARG
     with pytest.raises(pd.PdError):
         pd.pd_fifo_replay_batched([2.0, 1.0], [0.5], 1)              # arrivals not sorted
     with pytest.raises(pd.PdError):

@@ -262,3 +262,25 @@ def test_stage_allocation_reduces_to_eqs_5_6_and_balances_every_stage():
     assert cnt == [math.ceil(n) for n in real]
     with pytest.raises(ValueError):
         A.allocate_stages(tp_total, l_in, l_out, [1.0], [1.0, 2.0])
+
+
+def test_kv_transfer_overhead_closed_forms_and_effect_on_the_worked_example():
+    """The modelled overhead of Eq. (8): hand-computed byte counts, linearity in the prompt length,
+    and the paper's worked example recovered when the model is set to give its 100 ms."""
+    # 8B-shaped model: 32 layers x 2 (K and V) x 8 kv heads x 128 x 2 bytes = 131072 bytes per token
+    t = A.kv_transfer_overhead(6144, 32, 8, 128, 2, 50e9)
+    assert t == pytest.approx(6144 * 131072 / 50e9, rel=1e-15)
+    assert t == pytest.approx(0.016106127, rel=1e-6)
+    # an 8-bit cache halves the variable part, the fixed part stays
+    assert A.kv_transfer_overhead(6144, 32, 8, 128, 1, 50e9, 0.01) == pytest.approx(0.01 + t / 2, rel=1e-15)
+    assert A.kv_transfer_overhead(0, 32, 8, 128, 2, 50e9, 0.03) == 0.03
+    assert A.kv_transfer_overhead(2 * 6144, 32, 8, 128, 2, 50e9) == pytest.approx(2 * t, rel=1e-15)
+    # a link rate that makes the 6144-token transfer take 100 ms reproduces the example's Eq. (13)
+    bw = 6144 * 131072 / 0.1
+    tov = A.kv_transfer_overhead(6144, 32, 8, 128, 2, bw)
+    assert tov == pytest.approx(0.1, rel=1e-15)
+    assert A.effective_prefill_throughput(28300.0, 6144.0, 2.0, tov) == pytest.approx(25066.3, abs=0.05)
+    # a larger overhead always lowers the effective prefill throughput (Eq. (13))
+    tp = [A.effective_prefill_throughput(28300.0, 6144.0, 2.0, A.kv_transfer_overhead(6144, 32, 8, 128, 2, r))
+          for r in (5e9, 10e9, 50e9, 400e9)]
+    assert tp == sorted(tp)
