@@ -219,6 +219,30 @@ pd_status pd_profile_read(pd_layer *layer, int32_t max_entries, const char **nam
 pd_status pd_stream_copy(void *dst, const void *src, int64_t bytes, void *stream);
 
 /*
+ * The two ends of the decoder stack around the layers (the paper's measured throughputs are those
+ * of whole served models; Section "Acquire ... throughput" times them end to end): the token
+ * embedding in front and, behind the last layer, the final RMSNorm and the vocabulary projection.
+ *   pd_embed:    hidden[t, :] = w_embed[token_ids[t], :]
+ *   pd_lm_head:  logits[t, :] = RMSNorm(hidden[t, :]; g_final, rms_eps) . w_lm^T      (no bias)
+ * pd_head_create copies (and for bf16 repacks) g_final [d_model], w_lm [vocab, d_model] and, when
+ * given, w_embed [vocab, d_model] (device pointers, row-major, `dtype` elements; w_embed may be
+ * NULL if pd_embed is not used, and may equal w_lm for tied weights) into memory the handle owns,
+ * plus a workspace for max_rows normalised rows, so the two calls allocate nothing and only
+ * enqueue on `stream`.  token_ids is a DEVICE array of T int32; an id outside 0 .. vocab-1 yields
+ * a row of zeros (checked in the kernel; ids never index outside the table).  hidden and logits
+ * are device tensors [T, d_model] and [T, vocab] in `dtype`; T = 0 is a no-op.
+ * Errors: PD_ERR_INVALID_ARG (NULL, T < 0, T > max_rows for pd_lm_head, pd_embed without
+ * w_embed), PD_ERR_SHAPE (non-positive sizes), PD_ERR_DTYPE, PD_ERR_OOM, PD_ERR_DEVICE.
+ */
+typedef struct pd_head pd_head; /* opaque */
+pd_status pd_head_create(int32_t d_model, int32_t vocab, float rms_eps, pd_dtype dtype,
+                         const void *g_final, const void *w_embed, const void *w_lm,
+                         int32_t max_rows, pd_head **out);
+void pd_head_destroy(pd_head *head);
+pd_status pd_embed(pd_head *head, const int32_t *token_ids, int32_t T, void *hidden, void *stream);
+pd_status pd_lm_head(pd_head *head, const void *hidden, int32_t T, void *logits, void *stream);
+
+/*
  * Allocation model (host only; needs no GPU).
  *   T_s        = ttft_slo - t_overhead                                         Eq. (12)
  *   TP_prefill = prefill_max_tps - l_in / T_s                                  Eq. (13)

@@ -201,6 +201,27 @@ def linear(x, W):
     return y
 
 
+def embed(table, ids):
+    """hidden[t] = table[ids[t]]; raises on an id outside the table."""
+    table, ids = _f32(table), _i32(ids)
+    out = np.empty((ids.shape[0], table.shape[1]), np.float32)
+    f = lib().orc_embed
+    f.restype = C.c_int
+    rc = f(_p(table), _p(ids), C.c_int(ids.shape[0]), C.c_int(table.shape[1]), C.c_int(table.shape[0]), _p(out))
+    if rc != 0:
+        raise ValueError("token id outside the embedding table")
+    return out
+
+
+def lm_head(hidden, g, W, eps=1e-6):
+    """logits = RMSNorm(hidden; g, eps) @ W^T, W [V, d]."""
+    hidden, g, W = _f32(hidden), _f32(g), _f32(W)
+    out = np.empty((hidden.shape[0], W.shape[0]), np.float32)
+    lib().orc_lm_head(_p(hidden), _p(g), _p(W), C.c_int(hidden.shape[0]), C.c_int(hidden.shape[1]),
+                      C.c_int(W.shape[0]), C.c_double(eps), _p(out))
+    return out
+
+
 def rope(x, pos, base=10000.0):
     """x [T, H, hd] -> rotated copy."""
     y = _f32(x).copy()

@@ -140,6 +140,32 @@ void orc_linear_row(const float *x, const float *W, int n_in, int n_out, float *
     }
 }
 
+/*
+ * Ends of the decoder stack (the layers sit between them):
+ *   embedding  hidden[t, :] = E[id[t], :]                                  (-1 if an id is outside 0 .. V-1)
+ *   LM head    logits[t, :] = RMSNorm(hidden[t, :]; g, eps) . W^T          (W [V, d], no bias)
+ */
+int orc_embed(const float *E, const int32_t *ids, int T, int d, int V, float *hidden)
+{
+    for (int t = 0; t < T; ++t)
+        if (ids[t] < 0 || ids[t] >= V) return -1;
+    for (int t = 0; t < T; ++t)
+        for (int j = 0; j < d; ++j) hidden[(size_t)t * d + j] = E[(size_t)ids[t] * d + j];
+    return 0;
+}
+
+void orc_lm_head(const float *hidden, const float *g, const float *W, int T, int d, int V, double eps,
+                 float *logits)
+{
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int t = 0; t < T; ++t) {
+        float *y = (float *)malloc(sizeof(float) * (size_t)d);
+        orc_rmsnorm_row(hidden + (size_t)t * d, g, d, eps, y);
+        orc_linear_row(y, W, d, V, logits + (size_t)t * V);
+        free(y);
+    }
+}
+
 void orc_linear(const float *x, const float *W, int T, int n_in, int n_out, float *y)
 {
 #pragma omp parallel for schedule(static)

@@ -23,7 +23,7 @@ PD_F32, PD_BF16 = 0, 1
 EXPORTS = [
     "pd_layer_create", "pd_layer_destroy", "pd_layer_reserve", "pd_kv_cache_create", "pd_kv_cache_create_fp8",
     "pd_kv_cache_destroy", "pd_kv_cache_set", "pd_kv_cache_set_len", "pd_kv_cache_len",
-    "pd_kv_cache_set_lens", "pd_kv_cache_get", "pd_profile_enable", "pd_profile_read", "pd_stream_copy", "pd_prefill", "pd_prefill_chunk", "pd_decode_step", "pd_last_expert_choice", "pd_allocate",
+    "pd_kv_cache_set_lens", "pd_kv_cache_get", "pd_profile_enable", "pd_profile_read", "pd_stream_copy", "pd_head_create", "pd_head_destroy", "pd_embed", "pd_lm_head", "pd_prefill", "pd_prefill_chunk", "pd_decode_step", "pd_last_expert_choice", "pd_allocate",
     "pd_fifo_replay", "pd_mm1_sojourn", "pd_fifo_replay_batched", "pd_prefill_throughput_dp", "pd_mg1_sojourn", "pd_kv_transfer_overhead", "pd_allocate_stages", "pd_status_string", "pd_last_error",
 ]
 
@@ -84,6 +84,8 @@ lib.pd_layer_destroy.restype = None
 lib.pd_kv_cache_destroy.restype = None
 lib.pd_layer_destroy.argtypes = [C.c_void_p]
 lib.pd_kv_cache_destroy.argtypes = [C.c_void_p]
+lib.pd_head_destroy.restype = None
+lib.pd_head_destroy.argtypes = [C.c_void_p]
 lib.pd_allocate.argtypes = [C.c_double] * 5 + [C.POINTER(pd_measured_curves), C.POINTER(pd_allocation)]
 lib.pd_mm1_sojourn.argtypes = [C.c_double] * 3 + [C.POINTER(C.c_double)]
 lib.pd_mg1_sojourn.argtypes = [C.c_double] * 3 + [C.POINTER(C.c_double)]
@@ -179,6 +181,28 @@ def pd_profile_read(layer, max_entries=64):
     n = C.c_int32()
     _check(lib.pd_profile_read(layer, C.c_int32(max_entries), names, ms, C.byref(n)))
     return [(names[i].decode(), float(ms[i])) for i in range(n.value)]
+
+
+def pd_head_create(d_model, vocab, rms_eps, dtype, g_final, w_lm, w_embed=None, max_rows=256):
+    """dtype: "f32" / "bf16"; tensors are device tensors of that dtype."""
+    h = C.c_void_p()
+    _check(lib.pd_head_create(C.c_int32(d_model), C.c_int32(vocab), C.c_float(rms_eps),
+                              C.c_int(PD_BF16 if dtype == "bf16" else PD_F32), _ptr(g_final),
+                              None if w_embed is None else _ptr(w_embed), _ptr(w_lm), C.c_int32(max_rows), C.byref(h)))
+    return h
+
+
+def pd_head_destroy(head):
+    lib.pd_head_destroy(head)
+
+
+def pd_embed(head, token_ids, hidden):
+    """token_ids: device int32 tensor [T]; hidden: device tensor [T, d_model]."""
+    _check(lib.pd_embed(head, _ptr(token_ids), C.c_int32(token_ids.shape[0]), _ptr(hidden), _stream()))
+
+
+def pd_lm_head(head, hidden, logits):
+    _check(lib.pd_lm_head(head, _ptr(hidden), C.c_int32(hidden.shape[0]), _ptr(logits), _stream()))
 
 
 def pd_stream_copy(dst, src):

@@ -590,6 +590,26 @@ hipError_t launch_kv_copy_fp8(void *cache_k, void *cache_v, const void *k, const
     return hipGetLastError();
 }
 
+// ---- embedding: one block per token row, 4-byte words ----------------------------------------------
+__global__ __launch_bounds__(256) void embed_rows_kernel(uint32_t *__restrict__ out, const uint32_t *__restrict__ table,
+                                                         const int32_t *__restrict__ ids, int n_rows, int row_words)
+{
+    const int t = blockIdx.x;
+    const int id = ids[t];
+    const bool ok = id >= 0 && id < n_rows;
+    const uint32_t *src = table + (size_t)(ok ? id : 0) * row_words;
+    uint32_t *dst = out + (size_t)t * row_words;
+    for (int i = threadIdx.x; i < row_words; i += 256) dst[i] = ok ? src[i] : 0u;
+}
+
+hipError_t launch_embed_rows(void *out, const void *table, const int32_t *ids, int T, int n_rows,
+                             size_t row_bytes, hipStream_t s)
+{
+    if (T <= 0) return hipSuccess;
+    embed_rows_kernel<<<T, 256, 0, s>>>((uint32_t *)out, (const uint32_t *)table, ids, n_rows, (int)(row_bytes / 4));
+    return hipGetLastError();
+}
+
 // ---- plain copy (traffic-counter calibration) -----------------------------------------------------
 __global__ __launch_bounds__(256) void stream_copy_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src,
                                                           size_t n)

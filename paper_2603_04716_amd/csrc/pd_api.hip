@@ -929,6 +929,132 @@ extern "C" pd_status pd_stream_copy(void *dst, const void *src, int64_t bytes, v
     return PD_OK;
 }
 
+// ---- stack ends: embedding, final norm + vocabulary projection -------------------------------------
+
+struct pd_head {
+    int dtype, d, vocab, max_rows, device;
+    float eps;
+    size_t esz;
+    bool packed;        // bf16 with shapes the matrix-core kernels take: w_lm is in the block layout
+    void *g, *w_lm, *w_embed, *y;
+};
+
+static void free_head(pd_head *h)
+{
+    if (!h) return;
+    void *ptrs[] = {h->g, h->w_lm, h->w_embed, h->y};
+    for (void *p : ptrs)
+        if (p) (void)hipFree(p);
+    delete h;
+}
+
+extern "C" pd_status pd_head_create(int32_t d_model, int32_t vocab, float rms_eps, pd_dtype dtype,
+                                    const void *g_final, const void *w_embed, const void *w_lm,
+                                    int32_t max_rows, pd_head **out)
+{
+    if (!g_final || !w_lm || !out || max_rows <= 0) {
+        set_error("pd_head_create: NULL argument or max_rows <= 0");
+        return PD_ERR_INVALID_ARG;
+    }
+    if (dtype != PD_F32 && dtype != PD_BF16) {
+        set_error("pd_head_create: dtype %d is neither fp32 nor bf16", (int)dtype);
+        return PD_ERR_DTYPE;
+    }
+    if (d_model <= 0 || vocab <= 0 || !(rms_eps >= 0.f)) {
+        set_error("pd_head_create: unsupported shape (d=%d vocab=%d)", d_model, vocab);
+        return PD_ERR_SHAPE;
+    }
+    pd_head *h = new pd_head();
+    h->dtype = dtype; h->d = d_model; h->vocab = vocab; h->max_rows = max_rows; h->eps = rms_eps;
+    h->esz = dtype == PD_F32 ? 4 : 2;
+    h->packed = dtype == PD_BF16 && d_model % 64 == 0 && vocab % 16 == 0 &&
+                (int64_t)d_model * 2 * vocab < (1ll << 32);
+    const size_t wbytes = (size_t)vocab * d_model * h->esz;
+#define HEAD_TRY(expr)                                                                 \
+    do {                                                                               \
+        hipError_t e__ = (expr);                                                       \
+        if (e__ != hipSuccess) {                                                       \
+            set_error("pd_head_create: %s failed: %s", #expr, hipGetErrorString(e__)); \
+            free_head(h);                                                              \
+            return e__ == hipErrorOutOfMemory ? PD_ERR_OOM : PD_ERR_DEVICE;            \
+        }                                                                              \
+    } while (0)
+    HEAD_TRY(hipGetDevice(&h->device));
+    HEAD_TRY(hipMalloc(&h->g, d_model * h->esz));
+    HEAD_TRY(hipMalloc(&h->w_lm, wbytes));
+    HEAD_TRY(hipMalloc(&h->y, (size_t)max_rows * d_model * h->esz));
+    HEAD_TRY(hipMemcpy(h->g, g_final, d_model * h->esz, hipMemcpyDeviceToDevice));
+    if (h->packed) {
+        pack_weight_kernel<<<2048, 256>>>((uint4 *)h->w_lm, (const uint4 *)w_lm, nullptr, vocab, d_model);
+        HEAD_TRY(hipGetLastError());
+    } else {
+        HEAD_TRY(hipMemcpy(h->w_lm, w_lm, wbytes, hipMemcpyDeviceToDevice));
+    }
+    if (w_embed) {
+        HEAD_TRY(hipMalloc(&h->w_embed, wbytes));
+        HEAD_TRY(hipMemcpy(h->w_embed, w_embed, wbytes, hipMemcpyDeviceToDevice));
+    }
+    HEAD_TRY(hipDeviceSynchronize());
+#undef HEAD_TRY
+    *out = h;
+    return PD_OK;
+}
+
+extern "C" void pd_head_destroy(pd_head *h)
+{
+    if (!h) return;
+    (void)hipDeviceSynchronize();
+    free_head(h);
+}
+
+extern "C" pd_status pd_embed(pd_head *h, const int32_t *token_ids, int32_t T, void *hidden, void *stream)
+{
+    if (!h || T < 0 || (T > 0 && (!token_ids || !hidden))) {
+        set_error("pd_embed: bad argument");
+        return PD_ERR_INVALID_ARG;
+    }
+    if (!h->w_embed) {
+        set_error("pd_embed: the head was created without an embedding table");
+        return PD_ERR_INVALID_ARG;
+    }
+    HIP_TRY(launch_embed_rows(hidden, h->w_embed, token_ids, T, h->vocab, (size_t)h->d * h->esz,
+                              (hipStream_t)stream),
+            PD_ERR_DEVICE);
+    return PD_OK;
+}
+
+extern "C" pd_status pd_lm_head(pd_head *h, const void *hidden, int32_t T, void *logits, void *stream)
+{
+    if (!h || T < 0 || (T > 0 && (!hidden || !logits))) {
+        set_error("pd_lm_head: bad argument");
+        return PD_ERR_INVALID_ARG;
+    }
+    if (T > h->max_rows) {
+        set_error("pd_lm_head: %d rows > max_rows %d", T, h->max_rows);
+        return PD_ERR_INVALID_ARG;
+    }
+    if (T == 0) return PD_OK;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(launch_rmsnorm(h->dtype, hidden, h->g, h->y, T, h->d, h->eps, s), PD_ERR_DEVICE);
+    GemmArgs g;
+    memset(&g, 0, sizeof(g));
+    g.A = h->y; g.lda = h->d; g.B = h->w_lm; g.ldb = h->d; g.C = logits; g.ldc = h->vocab;
+    g.M = T; g.N = h->vocab; g.K = h->d; g.epilogue = EPI_NONE; g.n_groups = 1;
+    g.packed = h->packed ? 1 : 0;
+    if (h->packed) {
+        // packed weights are only understood by the matrix-core kernels
+        if (gemv_mfma_supported(g)) HIP_TRY(launch_gemv_mfma(g, s), PD_ERR_DEVICE);
+        else if (gemm_mfma_supported(g)) HIP_TRY(launch_gemm_mfma(g, s), PD_ERR_DEVICE);
+        else {
+            set_error("pd_lm_head: shape not covered by the matrix-core kernels");
+            return PD_ERR_SHAPE;
+        }
+    } else {
+        HIP_TRY(launch_gemm_generic(h->dtype, g, s), PD_ERR_DEVICE);
+    }
+    return PD_OK;
+}
+
 extern "C" pd_status pd_kv_cache_set_lens(pd_kv_cache *c, int32_t n, const int32_t *slots,
                                           const int32_t *lens, void *stream)
 {

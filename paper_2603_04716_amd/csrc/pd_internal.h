@@ -229,6 +229,9 @@ hipError_t launch_attn_chunk_mfma(const AttnArgs &a, const int32_t *d_slots, uin
                                   int vt_ld, const int32_t *pad_cu, hipStream_t s);
 
 hipError_t launch_stream_copy(void *dst, const void *src, size_t n_vec16, hipStream_t s);
+// out[t, :] = table[ids[t], :] (rows of row_bytes bytes, a multiple of 4); ids outside 0 .. n_rows-1 give zeros
+hipError_t launch_embed_rows(void *out, const void *table, const int32_t *ids, int T, int n_rows,
+                             size_t row_bytes, hipStream_t s);
 hipError_t launch_kv_copy(int dtype, void *cache_k, void *cache_v, const void *k, const void *v,
                           int slot, int Hkv, int len, int hd, int max_len, int blocked, int to_cache,
                           hipStream_t s);

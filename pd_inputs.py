@@ -90,6 +90,15 @@ def layer_weights(cfg, seed=None, std=0.02, with_router=False):
     return w
 
 
+def head_weights(d_model, vocab, seed, dtype="f32", std=0.02):
+    """Final-norm gain (around 1), LM-head matrix [vocab, d_model] and embedding table (tied to the
+    LM head, as in the 8B model family's smaller members) of a seeded stack end."""
+    rng = np.random.default_rng(seed)
+    g = _storage(1.0 + 0.1 * rng.standard_normal(d_model, dtype=np.float32), dtype)
+    w = _storage(std * rng.standard_normal((vocab, d_model), dtype=np.float32), dtype)
+    return {"g_final": g, "w_lm": w, "w_embed": w}
+
+
 def hidden(n_rows, d, seed, dtype="f32"):
     """Hidden-state rows ~ N(0,1)."""
     rng = np.random.default_rng(seed)

@@ -436,3 +436,46 @@ def test_fp8_cache_stores_quantised_values_and_prefill_itself_is_unchanged():
     k, v = I.kv_fill(cfg["n_kv_heads"], 5, cfg["head_dim"], seed=3)
     q8.set(1, k, v)
     assert np.array_equal(q8.k[1, :, :5], torch.from_numpy(k / 0.5).to(torch.float8_e4m3fn).float().numpy() * 0.5)
+
+
+# ---- stack ends: embedding and LM head -------------------------------------------------------------
+
+def test_lm_head_against_library_composition_and_closed_forms():
+    d, V, T = 96, 333, 7
+    hw = I.head_weights(d, V, seed=3, std=0.1)
+    x = I.hidden(T, d, seed=4)
+    got = O.lm_head(x, hw["g_final"], hw["w_lm"], eps=1e-6)
+    xt = torch.from_numpy(x).double()
+    ref = torch.nn.functional.rms_norm(xt, (d,), torch.from_numpy(hw["g_final"]).double(), 1e-6) @ \
+        torch.from_numpy(hw["w_lm"]).double().T
+    assert np.max(np.abs(got - ref.numpy())) <= 2e-6 * float(ref.abs().max())
+    # identity projection and unit gain: the logits are the unit-RMS rows themselves
+    eye = np.eye(d, dtype=np.float32)
+    y = O.lm_head(x, np.ones(d, np.float32), eye, eps=0.0)
+    assert np.allclose(np.sqrt(np.mean(y.astype(np.float64) ** 2, axis=1)), 1.0, atol=1e-6)
+    assert np.allclose(y * np.sqrt(np.mean(x.astype(np.float64) ** 2, axis=1))[:, None], x, atol=1e-5)
+    # the norm removes the scale of the input (eps = 0); the gain scales one input channel
+    assert np.allclose(O.lm_head(8.0 * x, hw["g_final"], hw["w_lm"], eps=0.0),
+                       O.lm_head(x, hw["g_final"], hw["w_lm"], eps=0.0), rtol=1e-5, atol=1e-6)
+    g2 = hw["g_final"].copy()
+    g2[5] = 0.0
+    w5 = hw["w_lm"].copy()
+    w5[:, 5] = 0.0
+    assert np.allclose(O.lm_head(x, g2, hw["w_lm"]), O.lm_head(x, hw["g_final"], w5), atol=1e-6)
+    # a constant row c: every normalised element is c / sqrt(c^2 + eps); one-hot W row picks g_j times it
+    c, eps = 0.5, 0.25
+    row = np.full((1, d), c, np.float32)
+    pick = np.zeros((1, d), np.float32)
+    pick[0, 11] = 1.0
+    assert O.lm_head(row, hw["g_final"], pick, eps=eps)[0, 0] == pytest.approx(
+        c / np.sqrt(c * c + eps) * float(hw["g_final"][11]), rel=1e-6)
+
+
+def test_embedding_is_a_row_lookup():
+    d, V = 24, 50
+    hw = I.head_weights(d, V, seed=5)
+    ids = np.array([0, 49, 7, 7, 13], np.int32)
+    assert np.array_equal(O.embed(hw["w_embed"], ids), hw["w_embed"][ids])
+    for bad in ([3, 50], [-1, 2]):
+        with pytest.raises(ValueError):
+            O.embed(hw["w_embed"], np.array(bad, np.int32))
