@@ -276,12 +276,28 @@ def run_stack(n_layers=32, n_weight_sets=4, batches=(1, 8, 64, 256), kv_len=2048
     bufs = [torch.empty_like(x), torch.empty_like(x)]
     for L in layers:
         pd.pd_layer_reserve(L.h, T)
+    # the stack's two ends: token embedding in front, final norm + vocabulary projection behind
+    vocab = 128256
+    hw = I.head_weights(d, vocab, seed=99, dtype="bf16")
+    w_lm = H._dev(hw["w_lm"], "bf16")
+    head = pd.pd_head_create(d, vocab, cfg["rms_eps"], "bf16", H._dev(hw["g_final"], "bf16"), w_lm, w_lm,
+                             max_rows=max(max(batches), T // l_in))
+    del hw, w_lm
+    ids = torch.from_numpy(np.random.default_rng(5).integers(0, vocab, T).astype(np.int32)).cuda()
+    last_rows = torch.tensor([l_in * (i + 1) - 1 for i in range(T // l_in)], device="cuda")
+    logits_p = torch.empty((T // l_in, vocab), dtype=torch.bfloat16, device="cuda")
+    xe = torch.empty_like(x)
 
-    def prefill_stack():
+    def prefill_stack(ends=False):
         src = x
+        if ends:
+            pd.pd_embed(head, ids, xe)
+            src = xe
         for i, L in enumerate(layers):
             pd.pd_prefill(L.h, src, cu, bufs[i & 1])
             src = bufs[i & 1]
+        if ends:       # only the last token of each prompt is projected onto the vocabulary
+            pd.pd_lm_head(head, src.index_select(0, last_rows), logits_p)
 
     def timed(fn, reps):
         ts = []
@@ -296,10 +312,13 @@ def run_stack(n_layers=32, n_weight_sets=4, batches=(1, 8, 64, 256), kv_len=2048
 
     prefill_stack()
     ms_stack = timed(prefill_stack, 5)
+    prefill_stack(True)
+    ms_model = timed(lambda: prefill_stack(True), 5)
     ms_one = layers[0].time_prefill(x, cu, iters=10, warmup=3)
     res = {"experiment": "resident layer stack vs single layer scaled up", "n_layers": n_layers,
            "prefill": {"tokens": T, "l_in": l_in, "stack_ms": round(ms_stack, 3),
                        "single_layer_ms_x_layers": round(ms_one * n_layers, 3),
+                       "with_embedding_and_lm_head_ms": round(ms_model, 3),
                        "tok_s_stack": round(T / (ms_stack * 1e-3), 1),
                        "tok_s_scaled": round(T / (ms_one * n_layers * 1e-3), 1)}, "decode": []}
     finite = bool(torch.isfinite(bufs[(n_layers - 1) & 1].float()).all())
@@ -321,41 +340,69 @@ def run_stack(n_layers=32, n_weight_sets=4, batches=(1, 8, 64, 256), kv_len=2048
             for c in caches:
                 pd.pd_kv_cache_set_lens(c, slots, lens)
 
-        def step():
+        ids_b = ids[:B].contiguous()
+        xeb = torch.empty_like(xb)
+        logits = torch.empty((B, vocab), dtype=torch.bfloat16, device="cuda")
+
+        def step(ends=False):
             src = xb
+            if ends:
+                pd.pd_embed(head, ids_b, xeb)
+                src = xeb
             for i, (L, c) in enumerate(zip(layers, caches)):
                 pd.pd_decode_step(L.h, src, slots, c, dbuf[i & 1])
                 src = dbuf[i & 1]
+            if ends:
+                pd.pd_lm_head(head, src, logits)
 
-        for _ in range(2):
+        def graph_time(ends):
+            for _ in range(2):
+                rewind()
+                step(ends)
             rewind()
-            step()
-        rewind()
-        torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            step()
-        torch.cuda.synchronize()
-        ts = []
-        for _ in range(7):
-            rewind()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            graph.replay()
-            e1.record()
-            e1.synchronize()
-            ts.append(e0.elapsed_time(e1))
-        tpot = H.median(ts)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                step(ends)
+            torch.cuda.synchronize()
+            ts = []
+            for _ in range(3):                   # clocks settle over the first replays after a pause
+                rewind()
+                graph.replay()
+            for _ in range(7):
+                rewind()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                graph.replay()
+                e1.record()
+                e1.synchronize()
+                ts.append(e0.elapsed_time(e1))
+            del graph
+            return H.median(ts)
+
+        tpot = graph_time(False)
+        tpot_model = graph_time(True)
+
+        def ends_only():
+            pd.pd_embed(head, ids_b, xeb)
+            pd.pd_lm_head(head, xb, logits)
+
+        ends_only()
+        ends_ms = timed(ends_only, 15)
         one = layers[0].make_decode_step(caches[0], xb, lens)
         ms_one_d = H.median([one() for _ in range(7)])
         by = H.decode_bytes(cfg, lens) * n_layers
         res["decode"].append({"batch": B, "tpot_ms_stack": round(tpot, 3),
                               "tpot_ms_scaled": round(ms_one_d * n_layers, 3),
+                              "tpot_ms_with_embedding_and_lm_head": round(tpot_model, 3),
+                              "embedding_and_lm_head_alone_ms": round(ends_ms, 4),
+                              "lm_head_weight_gbps": round(2.0 * vocab * d / (ends_ms * 1e-3) / 1e9, 1),
+                              "logits_finite": bool(torch.isfinite(logits.float()).all()),
                               "tok_s_stack": round(B / (tpot * 1e-3), 1),
                               "hbm_frac_stack": round(by / (tpot * 1e-3) / HBM_PEAK, 4)})
-        del graph
     for L in layers:
         L.close()
+    pd.pd_head_destroy(head)
     return res
 
 
