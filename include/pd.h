@@ -91,6 +91,19 @@ typedef struct pd_kv_cache pd_kv_cache; /* opaque */
  * PD_ERR_OOM, PD_ERR_DEVICE.
  */
 pd_status pd_layer_create(const pd_layer_config *cfg, const pd_layer_weights *w, pd_layer **out);
+/*
+ * The same layer with 8-bit weights: every projection matrix (W_q, W_k, W_v, W_o, gate, up, down;
+ * not the norm gains, not the router) is held as OCP E4M3 codes with one scale per output row,
+ * the smallest power of two s with max|w_row| / s <= 448 (1 for a row of zeros); the layer then
+ * computes with w' = s * value(code) everywhere (activations stay bf16).  Decode is bound by
+ * reading the weights (Section 2.1), so calls of up to 16 rows stream the codes (half the bytes)
+ * through the skinny kernel and widen them in registers; larger calls use a bf16 copy of w' and
+ * give the same results as a layer created from w' with pd_layer_create.  All other calls take
+ * such a layer unchanged.
+ * Errors: as pd_layer_create, plus PD_ERR_DTYPE if the layer is not bf16 with d_model, d_ff and the
+ * head dimensions multiples of 64.
+ */
+pd_status pd_layer_create_w8(const pd_layer_config *cfg, const pd_layer_weights *w, pd_layer **out);
 void pd_layer_destroy(pd_layer *layer);
 
 /* Pre-sizes the layer's workspace for calls of up to max_tokens rows (prefill T or decode B). */

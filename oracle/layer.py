@@ -201,6 +201,26 @@ def linear(x, W):
     return y
 
 
+W8_NAMES = ("w_q", "w_k", "w_v", "w_o", "w_gate", "w_up", "w_down")
+
+
+def quantise_rows(W):
+    """(W', scales): every row of W (last axis = input features) replaced by s * fp8(w / s) with the
+    row's power-of-two scale s (smallest with max|row| / s <= 448)."""
+    W = _f32(W).copy()
+    K = W.shape[-1]
+    n_rows = W.size // K
+    scales = np.empty(n_rows, np.float32)
+    lib().orc_quantise_rows(_p(W), C.c_int(n_rows), C.c_int(K), _p(scales))
+    return W, scales.reshape(W.shape[:-1])
+
+
+def quantise_layer_weights(weights):
+    """The weight set an 8-bit-weight layer computes with: projection matrices quantised row by row,
+    norm gains and router unchanged."""
+    return {k: (quantise_rows(v)[0] if k in W8_NAMES and v is not None else v) for k, v in weights.items()}
+
+
 def embed(table, ids):
     """hidden[t] = table[ids[t]]; raises on an id outside the table."""
     table, ids = _f32(table), _i32(ids)

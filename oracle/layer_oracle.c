@@ -114,6 +114,29 @@ void orc_cache_quantise(float *x, size_t n, double scale)
     for (size_t i = 0; i < n; ++i) x[i] = cache_value(x[i], 1, scale);
 }
 
+/*
+ * 8-bit weights: every row of a [n_rows, K] matrix is replaced by s * fp8(w / s) with the row's own
+ * scale s, the smallest power of two with max|w_row| / s <= 448 (1 for a row of zeros).  The layer
+ * then runs unchanged on the replaced weights.
+ */
+void orc_quantise_rows(float *W, int n_rows, int K, float *scales)
+{
+    for (int n = 0; n < n_rows; ++n) {
+        float *w = W + (size_t)n * K;
+        double m = 0.0;
+        for (int k = 0; k < K; ++k)
+            if (fabs((double)w[k]) > m) m = fabs((double)w[k]);
+        double s = 1.0;
+        if (m > 0.0 && isfinite(m)) {
+            int e;
+            double f = frexp(m / 448.0, &e);          /* m / 448 = f * 2^e, f in [0.5, 1) */
+            s = ldexp(1.0, f == 0.5 ? e - 1 : e);     /* smallest power of two >= m / 448 */
+        }
+        for (int k = 0; k < K; ++k) w[k] = cache_value(w[k], 1, s);
+        if (scales) scales[n] = (float)s;
+    }
+}
+
 void orc_rmsnorm_row(const float *x, const float *g, int d, double eps, float *y)
 {
     double ss = 0.0;

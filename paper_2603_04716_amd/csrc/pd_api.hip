@@ -19,6 +19,11 @@ struct pd_layer {
     bool use_mfma;       // bf16 layer whose shapes fit the MFMA kernels
     bool packed;         // weights stored in the matrix-core block layout (gate/up as one interleaved pack)
     void *g_attn, *g_ffn, *w_qkv, *w_o, *w_gate, *w_up, *w_down, *w_router;
+    // 8-bit weights: E4M3 codes of the four packed matrices (for the skinny kernel) and one
+    // power-of-two scale per packed row; the bf16 packs above then hold scale * value(code)
+    bool w8;
+    void *q_qkv, *q_o, *q_gate, *q_down;
+    float *s_qkv, *s_o, *s_gate, *s_down;
     double *inv_freq;
     float2 *rope_table;       // (cos, sin) for positions < kRopeTableLen
     int32_t *d_cu, *d_slots, *d_pad_cu, *d_prefix;  // [4097] each
@@ -120,10 +125,83 @@ __global__ void pack_weight_kernel(uint4 *dst, const uint4 *src, const uint4 *up
     }
 }
 
+// Per packed row n of a [n_rows, K] bf16 matrix (row mapping as in pack_weight_kernel): the smallest
+// power of two s with max_k |w[n, k]| / s <= 448, the largest E4M3 value (1 for a row of zeros).
+// One wavefront per row.
+__global__ __launch_bounds__(256) void w8_row_scale_kernel(float *scale, const uint16_t *src, const uint16_t *up,
+                                                           int n_rows, int K)
+{
+    const int n = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (n >= n_rows) return;
+    const uint16_t *from = src;
+    int row = n;
+    if (up) {
+        const int q = n >> 6, w = n & 63;
+        row = q * 32 + (w & 31);
+        if (w >= 32) from = up;
+    }
+    const uint16_t *p = from + (size_t)row * K;
+    float m = 0.f;
+    for (int k = lane; k < K; k += 64) m = fmaxf(m, fabsf(bfbits2f(p[k])));
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+    if (lane == 0) {
+        float s = 1.f;
+        if (m > 0.f && m < INFINITY) {
+            int e;
+            const double f = frexp((double)m / 448.0, &e);    // m / 448 = f * 2^e, f in [0.5, 1)
+            s = (float)ldexp(1.0, f == 0.5 ? e - 1 : e);
+        }
+        scale[n] = s;
+    }
+}
+
+// Quantises and packs in one pass: per 8-element chunk of packed row n, the E4M3 codes of w / scale[n]
+// into the 8-bit layout and scale[n] * value(code) as bf16 into the block layout of wpack_off.
+__global__ void pack_weight_w8_kernel(uint4 *dst, uint8_t *dst8, const uint4 *src, const uint4 *up,
+                                      const float *scale, int n_rows, int K)
+{
+    const size_t n_chunks = (size_t)n_rows * (K >> 3);
+    const int row_vec = K >> 3;
+    for (size_t c = (size_t)blockIdx.x * blockDim.x + threadIdx.x; c < n_chunks;
+         c += (size_t)gridDim.x * blockDim.x) {
+        const size_t block = c >> 6;
+        const int kg = (int)(c >> 4) & 3, r = (int)c & 15;
+        const int rb = (int)(block / (K >> 5)), kb = (int)(block % (K >> 5));
+        const int n = rb * 16 + r, k8 = kb * 4 + kg;
+        const uint4 *from = src;
+        int row = n;
+        if (up) {
+            const int q = n >> 6, w = n & 63;
+            row = q * 32 + (w & 31);
+            if (w >= 32) from = up;
+        }
+        const uint4 v = from[(size_t)row * row_vec + k8];
+        const uint32_t w32[4] = {v.x, v.y, v.z, v.w};
+        const double s = (double)scale[n];
+        uint32_t code[8], outw[4];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t bits = (w32[j >> 1] >> (16 * (j & 1))) & 0xffffu;
+            code[j] = e4m3_encode((double)bfbits2f(bits) / s);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            outw[j] = pack2bf((float)(s * (double)e4m3_decode(code[2 * j])),
+                              (float)(s * (double)e4m3_decode(code[2 * j + 1])));
+        dst[c] = make_uint4(outw[0], outw[1], outw[2], outw[3]);
+        uint2 q8;
+        q8.x = code[0] | (code[1] << 8) | (code[2] << 16) | (code[3] << 24);
+        q8.y = code[4] | (code[5] << 8) | (code[6] << 16) | (code[7] << 24);
+        *(uint2 *)(dst8 + w8pack_off(n, k8 * 8, K)) = q8;
+    }
+}
+
 static void free_layer(pd_layer *L)
 {
     if (!L) return;
-    void *ptrs[] = {L->g_attn, L->g_ffn, L->w_qkv, L->w_o, L->w_gate, L->w_up, L->w_down,
+    void *ptrs[] = {L->q_qkv, L->q_o, L->q_gate, L->q_down, L->s_qkv, L->s_o, L->s_gate, L->s_down,
+                    L->g_attn, L->g_ffn, L->w_qkv, L->w_o, L->w_gate, L->w_up, L->w_down,
                     L->w_router, L->inv_freq, L->rope_table, L->d_cu, L->d_slots, L->d_pad_cu, L->d_prefix, L->vt, L->ws};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
@@ -131,8 +209,21 @@ static void free_layer(pd_layer *L)
     delete L;
 }
 
+static pd_status layer_create(const pd_layer_config *cfg, const pd_layer_weights *w, bool w8, pd_layer **out);
+
 extern "C" pd_status pd_layer_create(const pd_layer_config *cfg, const pd_layer_weights *w,
                                      pd_layer **out)
+{
+    return layer_create(cfg, w, false, out);
+}
+
+extern "C" pd_status pd_layer_create_w8(const pd_layer_config *cfg, const pd_layer_weights *w,
+                                        pd_layer **out)
+{
+    return layer_create(cfg, w, true, out);
+}
+
+static pd_status layer_create(const pd_layer_config *cfg, const pd_layer_weights *w, bool w8, pd_layer **out)
 {
     if (!cfg || !w || !out) {
         set_error("pd_layer_create: NULL argument");
@@ -165,6 +256,12 @@ extern "C" pd_status pd_layer_create(const pd_layer_config *cfg, const pd_layer_
     L->use_mfma = cfg->dtype == PD_BF16 && d % 64 == 0 && F % 64 == 0 && L->Nq % 64 == 0 &&
                   L->Nkv % 64 == 0;
     L->packed = L->use_mfma;
+    L->w8 = w8;
+    if (w8 && !L->use_mfma) {
+        set_error("pd_layer_create_w8: needs a bf16 layer whose dimensions are multiples of 64");
+        delete L;
+        return PD_ERR_DTYPE;
+    }
     const size_t esz = L->esz;
     const int G = E > 0 ? E : 1;
     pd_status st = PD_OK;
@@ -194,6 +291,31 @@ extern "C" pd_status pd_layer_create(const pd_layer_config *cfg, const pd_layer_
     CREATE_TRY(hipMemcpy(L->g_attn, w->g_attn, d * esz, hipMemcpyDeviceToDevice));
     CREATE_TRY(hipMemcpy(L->g_ffn, w->g_ffn, d * esz, hipMemcpyDeviceToDevice));
     if (L->packed) {
+        // packs one [n_rows, K] matrix (gate/up interleaved when up != nullptr); for 8-bit weights
+        // also its row scales and codes, the bf16 pack then holding the dequantised values
+        auto pack = [&](void *dst, const void *src, const void *up, int n_rows, int K, void *dst8,
+                        float *scale) -> hipError_t {
+            if (w8) {
+                w8_row_scale_kernel<<<(n_rows + 3) / 4, 256>>>(scale, (const uint16_t *)src, (const uint16_t *)up, n_rows, K);
+                hipError_t e = hipGetLastError();
+                if (e != hipSuccess) return e;
+                pack_weight_w8_kernel<<<2048, 256>>>((uint4 *)dst, (uint8_t *)dst8, (const uint4 *)src,
+                                                     (const uint4 *)up, scale, n_rows, K);
+            } else {
+                pack_weight_kernel<<<2048, 256>>>((uint4 *)dst, (const uint4 *)src, (const uint4 *)up, n_rows, K);
+            }
+            return hipGetLastError();
+        };
+        if (w8) {
+            CREATE_TRY(hipMalloc(&L->q_qkv, (size_t)L->Nqkv * d));
+            CREATE_TRY(hipMalloc(&L->q_o, (size_t)d * L->Nq));
+            CREATE_TRY(hipMalloc(&L->q_gate, (size_t)G * 2 * F * d));
+            CREATE_TRY(hipMalloc(&L->q_down, (size_t)G * d * F));
+            CREATE_TRY(hipMalloc((void **)&L->s_qkv, sizeof(float) * L->Nqkv));
+            CREATE_TRY(hipMalloc((void **)&L->s_o, sizeof(float) * d));
+            CREATE_TRY(hipMalloc((void **)&L->s_gate, sizeof(float) * (size_t)G * 2 * F));
+            CREATE_TRY(hipMalloc((void **)&L->s_down, sizeof(float) * (size_t)G * d));
+        }
         // stack q|k|v plainly in a temporary, then pack every matrix into the block layout
         void *tmp = nullptr;
         CREATE_TRY(hipMalloc(&tmp, (size_t)L->Nqkv * d * esz));
@@ -202,25 +324,22 @@ extern "C" pd_status pd_layer_create(const pd_layer_config *cfg, const pd_layer_
             e1 = hipMemcpy((char *)tmp + (size_t)L->Nq * d * esz, w->w_k, (size_t)L->Nkv * d * esz, hipMemcpyDeviceToDevice);
         if (e1 == hipSuccess)
             e1 = hipMemcpy((char *)tmp + (size_t)(L->Nq + L->Nkv) * d * esz, w->w_v, (size_t)L->Nkv * d * esz, hipMemcpyDeviceToDevice);
-        if (e1 == hipSuccess) {
-            pack_weight_kernel<<<2048, 256>>>((uint4 *)L->w_qkv, (const uint4 *)tmp, nullptr, L->Nqkv, d);
-            e1 = hipGetLastError();
-        }
+        if (e1 == hipSuccess) e1 = pack(L->w_qkv, tmp, nullptr, L->Nqkv, d, L->q_qkv, L->s_qkv);
         if (e1 == hipSuccess) e1 = hipDeviceSynchronize();
         (void)hipFree(tmp);
         CREATE_TRY(e1);
-        pack_weight_kernel<<<2048, 256>>>((uint4 *)L->w_o, (const uint4 *)w->w_o, nullptr, d, L->Nq);
-        CREATE_TRY(hipGetLastError());
+        CREATE_TRY(pack(L->w_o, w->w_o, nullptr, d, L->Nq, L->q_o, L->s_o));
         CREATE_TRY(hipMalloc(&L->w_gate, (size_t)G * 2 * F * d * esz));
         for (int g = 0; g < G; ++g) {
-            pack_weight_kernel<<<2048, 256>>>((uint4 *)((char *)L->w_gate + (size_t)g * 2 * F * d * esz),
-                                              (const uint4 *)((const char *)w->w_gate + (size_t)g * F * d * esz),
-                                              (const uint4 *)((const char *)w->w_up + (size_t)g * F * d * esz), 2 * F, d);
-            CREATE_TRY(hipGetLastError());
-            pack_weight_kernel<<<2048, 256>>>((uint4 *)((char *)L->w_down + (size_t)g * d * F * esz),
-                                              (const uint4 *)((const char *)w->w_down + (size_t)g * d * F * esz),
-                                              nullptr, d, F);
-            CREATE_TRY(hipGetLastError());
+            CREATE_TRY(pack((char *)L->w_gate + (size_t)g * 2 * F * d * esz,
+                            (const char *)w->w_gate + (size_t)g * F * d * esz,
+                            (const char *)w->w_up + (size_t)g * F * d * esz, 2 * F, d,
+                            w8 ? (char *)L->q_gate + (size_t)g * 2 * F * d : nullptr,
+                            w8 ? L->s_gate + (size_t)g * 2 * F : nullptr));
+            CREATE_TRY(pack((char *)L->w_down + (size_t)g * d * F * esz,
+                            (const char *)w->w_down + (size_t)g * d * F * esz, nullptr, d, F,
+                            w8 ? (char *)L->q_down + (size_t)g * d * F : nullptr,
+                            w8 ? L->s_down + (size_t)g * d : nullptr));
         }
     } else {
         CREATE_TRY(hipMemcpy(L->w_qkv, w->w_q, (size_t)L->Nq * d * esz, hipMemcpyDeviceToDevice));
@@ -484,6 +603,13 @@ static hipError_t run_gemm(const pd_layer *L, GemmArgs g, hipStream_t s)
     g.packed = L->packed ? 1 : 0;
     if (L->packed) {
         // packed weights are only understood by the matrix-core kernels
+        if (L->w8) {
+            // the skinny kernel streams the 8-bit twin of the matrix; the tiled kernels take the bf16 pack
+            if (g.B == L->w_qkv) { g.B8 = L->q_qkv; g.b_scale = L->s_qkv; }
+            else if (g.B == L->w_o) { g.B8 = L->q_o; g.b_scale = L->s_o; }
+            else if (g.B == L->w_gate) { g.B8 = L->q_gate; g.b_scale = L->s_gate; }
+            else if (g.B == L->w_down) { g.B8 = L->q_down; g.b_scale = L->s_down; }
+        }
         if (gemv_mfma_supported(g)) return launch_gemv_mfma(g, s);
         if (gemm_mfma_supported(g)) return launch_gemm_mfma(g, s);
         return hipErrorInvalidValue;

@@ -118,6 +118,15 @@ __host__ __device__ __forceinline__ size_t wpack_off(int n, int k, int K)
     return ((size_t)(n >> 4) * (K >> 5) + (k >> 5)) * 512 + ((k >> 3) & 3) * 128 + (n & 15) * 8 + (k & 7);
 }
 
+// 8-bit packed weights: blocks of 16 rows x 64 k (1 KB), ordered [N/16][K/64]; lane 16*(k/8 % 4) + row
+// of a block owns 16 bytes: k = 64b + 8kg .. +7 (bytes 0-7) and 64b + 32 + 8kg .. +7 (bytes 8-15), its
+// A operands of two consecutive 32-wide k-steps.  Byte offset of element (n, k):
+__host__ __device__ __forceinline__ size_t w8pack_off(int n, int k, int K)
+{
+    return ((size_t)(n >> 4) * (K >> 6) + (k >> 6)) * 1024 + ((k >> 3) & 3) * 256 + (n & 15) * 16 +
+           ((k >> 5) & 1) * 8 + (k & 7);
+}
+
 constexpr int kMetaChunk = 255;  // ints carried by value per meta-kernel launch (+1 for cu_seqlens)
 struct IntChunk {
     int32_t v[256];
@@ -144,6 +153,11 @@ struct GemmArgs {
     int32_t packed;                // B is in the MFMA block layout below (matrix-core kernels only)
     float *splitk_ws;              // optional scratch for split-K partials (decode-sized M)
     size_t splitk_ws_elems;
+    // 8-bit twin of the packed weights (skinny kernel only; null = none): E4M3 codes in the layout
+    // of w8pack_off, and one power-of-two scale per packed weight row; weight = scale * value(code).
+    // Groups are b_group_stride codes and (2N for SwiGLU, else N) scales apart.
+    const void *B8;
+    const float *b_scale;
 };
 
 // ---- launchers (each returns hipGetLastError() after the launch) ------------------------------

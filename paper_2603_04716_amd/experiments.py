@@ -8,6 +8,7 @@
     python -m paper_2603_04716_amd.experiments moe          # 8-expert top-2 layer: prefill + decode sweep
     python -m paper_2603_04716_amd.experiments fp8kv        # decode curve over the KV cache held as 8-bit E4M3
                                                             # codes beside the bf16 cache, KV 2048 and 8192
+    python -m paper_2603_04716_amd.experiments w8           # small-batch decode with 8-bit projection weights
     python -m paper_2603_04716_amd.experiments kvxfer       # KV hand-off: cache export / import per layer, the
                                                             # modelled link, Eq. (13) with that overhead
 
@@ -460,6 +461,52 @@ def run_fp8kv():
     return out
 
 
+def run_w8():
+    """Small-batch decode with the projection weights as 8-bit codes beside bf16 weights (both with the
+    bf16 cache and, for the 8-bit weights, also the 8-bit cache), KV 2048, with per-step timings."""
+    cfg = I.CONFIGS["llama8b"]
+    hkv, hd, d = cfg["n_kv_heads"], cfg["head_dim"], cfg["d_model"]
+    S, bmax = 2048, 32
+    batches = (1, 2, 4, 8, 16, 32)
+    host_w = I.layer_weights(cfg)
+    xall = H._dev(I.hidden(bmax, d, seed=12, dtype="bf16"), "bf16")
+    k, v = I.kv_fill(hkv, S, hd, seed=11, dtype="bf16")
+    kd, vd = H._dev(k, "bf16"), H._dev(v, "bf16")
+    attn_p, ffn_p = H.layer_params(cfg)
+    out = {"experiment": "decode with 8-bit projection weights (skinny kernel, <= 16 rows)", "kv_len": S, "cases": []}
+    for w8, fp8kv in ((False, False), (True, False), (True, True)):
+        layer = H.Layer(cfg, host_w, w8=w8)
+        cache = layer.new_cache(bmax, S + 8, fp8_scales=(0.5, 0.125) if fp8kv else None)
+        layer.fill_cache(cache, [S] * bmax, kd, vd)
+        curve = []
+        for B in batches:
+            run = layer.make_decode_step(cache, xall[:B].contiguous(), [S] * B)
+            ms = H.median([run() for _ in range(9)])
+            wbytes = (attn_p + ffn_p) * (1 if (w8 and B <= 16) else 2)
+            kvbytes = 2.0 * hkv * hd * (1 if fp8kv else 2) * (S + 1) * B
+            curve.append({"batch": B, "ms_per_layer": round(ms, 4), "tpot_ms": round(N_LAYERS * ms, 3),
+                          "tok_s": round(B / (N_LAYERS * ms * 1e-3), 1),
+                          "hbm_frac": round((wbytes + kvbytes) / (ms * 1e-3) / HBM_PEAK, 4)})
+        # per-step timings at B = 8
+        B = 8
+        slots = list(range(B))
+        o = torch.empty_like(xall[:B])
+        pd.pd_profile_enable(layer.h, True)
+        acc = {}
+        for it in range(7):
+            pd.pd_kv_cache_set_lens(cache, slots, [S] * B)
+            pd.pd_decode_step(layer.h, xall[:B].contiguous(), slots, cache, o)
+            torch.cuda.synchronize()
+            if it >= 2:
+                for n, t in pd.pd_profile_read(layer.h):
+                    acc.setdefault(n, []).append(t)
+        pd.pd_profile_enable(layer.h, False)
+        out["cases"].append({"weights": "e4m3 + row scales" if w8 else "bf16", "cache": "e4m3" if fp8kv else "bf16",
+                             "curve": curve, "steps_us_b8": {n: round(1e3 * H.median(t), 1) for n, t in acc.items()}})
+        layer.close()
+    return out
+
+
 def run_kvxfer():
     """The KV hand-off from a prefill to a decode instance as far as one GPU shows it: reading a
     sequence's keys and values out of the (blocked) cache into one contiguous buffer and writing
@@ -514,7 +561,7 @@ def run_kvxfer():
 def main():
     which = sys.argv[1] if len(sys.argv) > 1 else "prefill"
     fn = {"prefill": run_prefill, "longctx": run_longctx, "queue": run_queue, "moe": run_moe,
-          "chunk": run_chunk, "stack": run_stack, "queue_fixed": run_queue_fixed, "fp8kv": run_fp8kv, "kvxfer": run_kvxfer}[which]
+          "chunk": run_chunk, "stack": run_stack, "queue_fixed": run_queue_fixed, "fp8kv": run_fp8kv, "kvxfer": run_kvxfer, "w8": run_w8}[which]
     print(json.dumps(fn()))
 
 

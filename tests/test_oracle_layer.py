@@ -479,3 +479,51 @@ def test_embedding_is_a_row_lookup():
     for bad in ([3, 50], [-1, 2]):
         with pytest.raises(ValueError):
             O.embed(hw["w_embed"], np.array(bad, np.int32))
+
+
+# ---- 8-bit weights ---------------------------------------------------------------------------------
+
+def test_row_quantisation_scales_and_values():
+    """Per-row power-of-two scales and E4M3 values of quantise_rows, against the format's own facts
+    and a library conversion."""
+    rng = np.random.default_rng(21)
+    W = (rng.standard_normal((37, 200)) * np.exp(rng.uniform(-8, 3, (37, 1)))).astype(np.float32)
+    W[5] = 0.0                                   # a row of zeros keeps scale 1
+    W[6, :] = 0.0
+    W[6, 17] = 448.0 * 2.0 ** -3                 # maximum exactly on a power-of-two boundary
+    W[7, 3] = 448.0 * 2.0 ** -3 * (1 + 2.0 ** -20)    # and just above it
+    Wq, s = O.quantise_rows(W)
+    assert s[5] == 1.0 and np.all(Wq[5] == 0.0)
+    assert s[6] == 2.0 ** -3 and Wq[6, 17] == W[6, 17]
+    m = np.max(np.abs(W), axis=1)
+    live = m > 0
+    # powers of two, the smallest that keep the row inside +-448
+    assert np.all(np.log2(s[live]) == np.round(np.log2(s[live])))
+    assert np.all(m[live] / s[live] <= 448.0) and np.all(m[live] / (s[live] / 2) > 448.0)
+    # every value is a representable E4M3 number times the scale: the library's conversion agrees
+    t = torch.from_numpy(W / s[:, None]).to(torch.float8_e4m3fn).float().numpy() * s[:, None]
+    assert np.array_equal(Wq, t.astype(np.float32))
+    # nearest representable value: error at most half the local spacing (2^-3 relative at most), and
+    # quantising twice changes nothing
+    a = np.abs(W[live] / s[live, None])
+    spacing = 2.0 ** (np.floor(np.log2(np.maximum(a, 2.0 ** -6))) - 3)
+    assert np.all(np.abs(Wq[live] - W[live]) / s[live, None] <= spacing / 2 + 1e-12)
+    Wq2, s2 = O.quantise_rows(Wq)
+    assert np.array_equal(Wq2, Wq)
+    # leading axes are rows too (mixture-of-experts weights [E, F, d])
+    W3 = W[:36].reshape(3, 12, 200)
+    assert np.array_equal(O.quantise_rows(W3)[0].reshape(36, 200), Wq[:36])
+
+
+def test_layer_with_quantised_weights_is_the_layer_on_the_replaced_weights():
+    cfg = I.small_config()
+    w = I.layer_weights(cfg, std=0.1)
+    wq = O.quantise_layer_weights(w)
+    assert np.array_equal(wq["g_attn"], w["g_attn"]) and not np.array_equal(wq["w_q"], w["w_q"])
+    x = I.hidden(9, cfg["d_model"], seed=2)
+    cu = np.array([0, 4, 9], np.int32)
+    a = O.prefill(O.Layer(cfg, wq), x, cu)
+    b = O.prefill(O.Layer(cfg, w), x, cu)
+    # the quantised layer is close to, and different from, the exact one (3 mantissa bits per weight)
+    err = np.max(np.abs(a - b)) / np.max(np.abs(b))
+    assert 1e-4 < err < 0.1
