@@ -5,6 +5,7 @@
 #include <cmath>
 #include <string.h>
 
+#include <algorithm>
 #include <vector>
 
 #include "pd_internal.h"
@@ -58,11 +59,45 @@ struct pd_kv_cache {
 };
 
 static const int kMaxSeqs = 4096;
-// Wavefront-sized workers one decode attention launch aims for.  A lone worker streams about
-// 13 GB/s, so some 500 of them saturate the memory system; beyond that the time is the bytes moved,
-// and more, smaller chunks only add start-up and merge work.  768 measured best from batch 4 to
-// 128 at 2048 cached tokens (bf16 and 8-bit caches); larger batches have one chunk per sequence.
+// Work split of the decode attention: a sequence of n keys is cut into ceil(n / chunk_keys) equal
+// chunks, one wavefront-sized worker per (chunk, kv head).  Two measured effects set chunk_keys
+// (8B shape, 2048 .. 16384 keys, batch 4 .. 256, both cache formats):
+//  - a lone worker streams about 13 GB/s, so some 500 workers saturate the memory system; beyond
+//    that the time is the bytes moved and more, smaller chunks only add start-up and merge work.
+//    Best for equal lengths: about kDecodeWorkers workers, one chunk per sequence from there on.
+//  - all workers start together, so with ragged lengths the short ones finish first and the few
+//    long ones left run latency-bound: a tail.  Chunks of at most mean^2 / max keys (the mean
+//    length shrunk by how far the longest sequence sticks out; equal lengths: no limit) keep
+//    enough equal workers running to the end: 10 - 30 % faster from batch 64 up on log-normal
+//    lengths with mean 3 k and maximum 8 k.
+// max_chunks: what the partial-output workspace holds; the chunk size is raised until the step fits
+// (one chunk per sequence always does).
 static const int kDecodeWorkers = 768;
+
+static int pick_chunk_keys(const std::vector<int32_t> &keys, int n_kv_heads, size_t max_chunks)
+{
+    long long total = 0;
+    int max_k = 1;
+    for (int32_t k : keys) {
+        total += k;
+        max_k = std::max(max_k, (int)k);
+    }
+    const double mean = keys.empty() ? 1.0 : (double)total / (double)keys.size();
+    const long long by_workers = (total * n_kv_heads + kDecodeWorkers - 1) / kDecodeWorkers;
+    const long long by_tail = (long long)(mean * mean / (double)max_k) + 1;
+    long long ck = (std::min(by_workers, by_tail) + 63) / 64 * 64;
+    if (ck < 64) ck = 64;
+    const long long whole = ((long long)max_k + 63) / 64 * 64;
+    if (ck > whole) ck = whole;
+    auto chunks = [&](long long c) {
+        size_t n = 0;
+        for (int32_t k : keys) n += (size_t)((k + c - 1) / c);
+        return n;
+    };
+    while (ck < whole && chunks(ck) > max_chunks) ck = std::min(whole, 2 * ck);
+    return (int)ck;
+}
+
 static const int kShortChunk = 8;   // chunks up to this many tokens use the decode attention kernel per row
 static const int kRopeTableLen = 32768;   // positions with precomputed rotary factors
 
@@ -380,9 +415,8 @@ extern "C" void pd_layer_destroy(pd_layer *layer)
     free_layer(layer);
 }
 
-// Decode attention splits the keys of a step into at most 8192 / n_kv_heads fixed-size chunks plus
-// one ragged tail per sequence; the workspace holds partial outputs for that many chunks, so a
-// decode step never allocates.
+// Chunks of one decode attention launch whose partial outputs the workspace holds (the chunk size
+// is chosen so that a step fits), so a decode step never allocates.
 static size_t decode_chunk_bound(const pd_layer *L, int batch)
 {
     return (size_t)(8192 / L->cfg.n_kv_heads + 1) + (size_t)batch;
@@ -790,8 +824,7 @@ static pd_status prefill_common(pd_layer *L, const pd_tokens *tk, pd_kv_cache *c
         // Units of up to 16 / group consecutive tokens of one sequence share one pass over the cache:
         // their (token, head) pairs are the 16 MFMA columns of the decode attention kernel.
         const int tb = 16 / (c.n_q_heads / c.n_kv_heads);
-        std::vector<int32_t> u_slot, u_pos, u_row, u_cnt;
-        long long total_keys = 0;
+        std::vector<int32_t> u_slot, u_pos, u_row, u_cnt, u_keys;
         for (int q = 0; q < n; ++q) {
             const int Ls = tk->cu_seqlens[q + 1] - tk->cu_seqlens[q];
             for (int i0 = 0; i0 < Ls; i0 += tb) {
@@ -800,12 +833,13 @@ static pd_status prefill_common(pd_layer *L, const pd_tokens *tk, pd_kv_cache *c
                 u_pos.push_back(prefix[(size_t)q] + i0);
                 u_row.push_back(tk->cu_seqlens[q] + i0);
                 u_cnt.push_back(cnt);
-                total_keys += prefix[(size_t)q] + i0 + cnt;
+                u_keys.push_back(prefix[(size_t)q] + i0 + cnt);
             }
         }
         const int nu = (int)u_slot.size();
-        long long ck = ((total_keys * c.n_kv_heads + kDecodeWorkers - 1) / kDecodeWorkers + 63) / 64 * 64;
-        const int chunk_keys = (int)(ck < 64 ? 64 : ck);
+        // partial rows are [chunk][kv head][16 columns]; the reserved buffer is counted in [chunk][q head] rows
+        const int chunk_keys = pick_chunk_keys(u_keys, c.n_kv_heads,
+                                               decode_chunk_bound(L, T) * c.n_q_heads / ((size_t)c.n_kv_heads * 16));
         std::vector<int32_t> ccu((size_t)nu + 1);
         ccu[0] = 0;
         for (int u = 0; u < nu; ++u)
@@ -938,14 +972,13 @@ extern "C" pd_status pd_decode_step(pd_layer *L, const pd_batch *bt, pd_kv_cache
     hipStream_t s = (hipStream_t)stream;
     L->prof_names.clear();
 
-    // decode attention work split: about kDecodeWorkers wavefront-sized workers
+    // decode attention work split (see pick_chunk_keys)
     const bool mfma_dec = cache->blocked != 0;
     int chunk_keys = 64, total_chunks = 0;
     if (mfma_dec) {
-        long long total_keys = 0;
-        for (int b = 0; b < B; ++b) total_keys += cache->h_len[(size_t)bt->slots[b]] + 1;
-        long long ck = ((total_keys * c.n_kv_heads + kDecodeWorkers - 1) / kDecodeWorkers + 63) / 64 * 64;
-        chunk_keys = (int)(ck < 64 ? 64 : ck);
+        std::vector<int32_t> keys((size_t)B);
+        for (int b = 0; b < B; ++b) keys[(size_t)b] = cache->h_len[(size_t)bt->slots[b]] + 1;
+        chunk_keys = pick_chunk_keys(keys, c.n_kv_heads, decode_chunk_bound(L, B));
         for (int b = 0; b < B; ++b)
             total_chunks += (cache->h_len[(size_t)bt->slots[b]] + 1 + chunk_keys - 1) / chunk_keys;
         if ((size_t)total_chunks > decode_chunk_bound(L, B)) {
