@@ -27,10 +27,13 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float dexp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// One block: pos / len update and the prefix sum of chunks per sequence (B <= 4096).
-__global__ __launch_bounds__(1024) void decode_meta_chunks_kernel(const int32_t *__restrict__ slots,
-                                                                  int B, int32_t *len, int32_t *pos,
-                                                                  int32_t *chunk_cu, int chunk_keys)
+// One block: pos / len update and the prefix sum of chunks per sequence (B <= 4096).  BYVAL: the
+// slots arrive in the kernel arguments (B <= 256) and are also stored to slots_out for the kernels
+// that follow, which saves the separate upload launch of a small decode step.
+template <bool BYVAL>
+__global__ __launch_bounds__(1024) void decode_meta_chunks_kernel(const int32_t *__restrict__ slots, IntChunk sv,
+                                                                  int32_t *slots_out, int B, int32_t *len,
+                                                                  int32_t *pos, int32_t *chunk_cu, int chunk_keys)
 {
     __shared__ int wave_tot[16];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -40,7 +43,13 @@ __global__ __launch_bounds__(1024) void decode_meta_chunks_kernel(const int32_t 
         int b = tid * 4 + i;
         cnt[i] = 0;
         if (b < B) {
-            int s = slots[b];
+            int s;
+            if (BYVAL) {
+                s = sv.v[b];
+                slots_out[b] = s;
+            } else {
+                s = slots[b];
+            }
             int p = len[s];
             pos[b] = p;
             len[s] = p + 1;
@@ -71,7 +80,19 @@ __global__ __launch_bounds__(1024) void decode_meta_chunks_kernel(const int32_t 
 hipError_t launch_decode_meta_chunks(const int32_t *d_slots, int B, int32_t *d_len, int32_t *d_pos,
                                      int32_t *chunk_cu, int chunk_keys, hipStream_t s)
 {
-    decode_meta_chunks_kernel<<<1, 1024, 0, s>>>(d_slots, B, d_len, d_pos, chunk_cu, chunk_keys);
+    IntChunk none;
+    none.v[0] = 0;
+    decode_meta_chunks_kernel<false><<<1, 1024, 0, s>>>(d_slots, none, nullptr, B, d_len, d_pos, chunk_cu, chunk_keys);
+    return hipGetLastError();
+}
+
+hipError_t launch_decode_meta_chunks_upload(const int32_t *host_slots, int32_t *d_slots, int B, int32_t *d_len,
+                                            int32_t *d_pos, int32_t *chunk_cu, int chunk_keys, hipStream_t s)
+{
+    if (B > 256) return hipErrorInvalidValue;
+    IntChunk sv;
+    for (int i = 0; i < B; ++i) sv.v[i] = host_slots[i];
+    decode_meta_chunks_kernel<true><<<1, 256, 0, s>>>(nullptr, sv, d_slots, B, d_len, d_pos, chunk_cu, chunk_keys);
     return hipGetLastError();
 }
 

@@ -332,7 +332,10 @@ hipError_t launch_prefill_set_len(const int32_t *d_slots, const int32_t *d_cu, i
 
 // ---------------------------------------------------------------------------------------------
 // Rotary embedding (rotate-half pairing) of q and k in place + write of k, v into the cache.
-// One block per token row.  The angle pos * inv_freq[i] and its sine / cosine are evaluated in
+// blockIdx.x is the token row; the gridDim.y blocks of a row share its (head, pair) and value
+// elements round-robin, so that no thread has more than a few dependent memory round trips (a
+// lone block per row spent most of a decode step's rope time waiting).  The angle pos *
+// inv_freq[i] and its sine / cosine are evaluated in
 // double so that the fp32 configuration stays inside its 1e-5 budget at any position.
 // ---------------------------------------------------------------------------------------------
 template <typename T>
@@ -359,7 +362,8 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(RopeArgs a)
     T *row = (T *)a.qkv + (size_t)t * a.ld;
     const int slot = a.tok_slot ? a.tok_slot[t] : -1;
     const int n_rot = (a.Hq + a.Hkv) * half;
-    for (int idx = threadIdx.x; idx < n_rot; idx += 256) {
+    const int part = blockIdx.y * 256 + threadIdx.x, stride = gridDim.y * 256;
+    for (int idx = part; idx < n_rot; idx += stride) {
         int h = idx / half, i = idx - h * half;
         T *v = row + (size_t)h * a.hd;
         float x0 = Elem<T>::ld(v + i), x1 = Elem<T>::ld(v + i + half);
@@ -385,7 +389,7 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(RopeArgs a)
     }
     if (slot >= 0) {
         const T *vsrc = row + (size_t)(a.Hq + a.Hkv) * a.hd;
-        for (int idx = threadIdx.x; idx < a.Hkv * a.hd; idx += 256) {
+        for (int idx = part; idx < a.Hkv * a.hd; idx += stride) {
             int g = idx / a.hd, i = idx - g * a.hd;
             T *plane = (T *)a.v_cache + ((size_t)slot * a.Hkv + g) * a.max_len * a.hd;
             if (a.fp8)
@@ -418,8 +422,14 @@ hipError_t launch_rope_table(float2 *table, int table_len, int half, const doubl
 hipError_t launch_rope_kv(int dtype, const RopeArgs &a, hipStream_t s)
 {
     if (a.T <= 0) return hipSuccess;
-    if (dtype == PD_F32) rope_kv_kernel<float><<<a.T, 256, 0, s>>>(a);
-    else rope_kv_kernel<bf16_t><<<a.T, 256, 0, s>>>(a);
+    // about two (head, pair) elements per thread; rows are plentiful in a prefill, so fewer slices there
+    const int n_rot = (a.Hq + a.Hkv) * (a.hd / 2);
+    int slices = (n_rot + 511) / 512;
+    if (a.T >= 1024 && slices > 2) slices = 2;
+    if (slices < 1) slices = 1;
+    const dim3 grid((unsigned)a.T, (unsigned)slices);
+    if (dtype == PD_F32) rope_kv_kernel<float><<<grid, 256, 0, s>>>(a);
+    else rope_kv_kernel<bf16_t><<<grid, 256, 0, s>>>(a);
     return hipGetLastError();
 }
 

@@ -1000,12 +1000,18 @@ extern "C" pd_status pd_decode_step(pd_layer *L, const pd_batch *bt, pd_kv_cache
             return PD_ERR_DEVICE;
         }
     }
-    HIP_TRY(launch_write_ints(L->d_slots, bt->slots, B, s), PD_ERR_DEVICE);
-    if (mfma_dec)
-        HIP_TRY(launch_decode_meta_chunks(L->d_slots, B, cache->d_len, L->tok_pos, L->chunk_cu, chunk_keys, s),
+    if (mfma_dec && B <= 256) {
+        HIP_TRY(launch_decode_meta_chunks_upload(bt->slots, L->d_slots, B, cache->d_len, L->tok_pos, L->chunk_cu,
+                                                 chunk_keys, s),
                 PD_ERR_DEVICE);
-    else
-        HIP_TRY(launch_decode_meta(L->d_slots, B, cache->d_len, L->tok_pos, s), PD_ERR_DEVICE);
+    } else {
+        HIP_TRY(launch_write_ints(L->d_slots, bt->slots, B, s), PD_ERR_DEVICE);
+        if (mfma_dec)
+            HIP_TRY(launch_decode_meta_chunks(L->d_slots, B, cache->d_len, L->tok_pos, L->chunk_cu, chunk_keys, s),
+                    PD_ERR_DEVICE);
+        else
+            HIP_TRY(launch_decode_meta(L->d_slots, B, cache->d_len, L->tok_pos, s), PD_ERR_DEVICE);
+    }
     GemmArgs g;
     memset(&g, 0, sizeof(g));
     g.A = bt->hidden; g.lda = c.d_model; g.B = L->w_qkv; g.ldb = c.d_model; g.C = L->qkv; g.ldc = L->Nqkv;

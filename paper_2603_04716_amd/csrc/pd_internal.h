@@ -284,6 +284,9 @@ hipError_t launch_decode_attn_mfma(const DecodeAttnArgs &a, hipStream_t s);
 // pos[b] = len[slot[b]]; len[slot[b]] += 1; chunk_cu = prefix sum of ceil((pos+1)/chunk_keys)
 hipError_t launch_decode_meta_chunks(const int32_t *d_slots, int B, int32_t *d_len, int32_t *d_pos,
                                      int32_t *chunk_cu, int chunk_keys, hipStream_t s);
+// the same for B <= 256 with the slots taken from the host array (and stored to d_slots): one launch
+hipError_t launch_decode_meta_chunks_upload(const int32_t *host_slots, int32_t *d_slots, int B, int32_t *d_len,
+                                            int32_t *d_pos, int32_t *chunk_cu, int chunk_keys, hipStream_t s);
 
 // ---- MoE -----------------------------------------------------------------------------------------
 struct MoeRouteArgs {
