@@ -422,10 +422,10 @@ hipError_t launch_rope_table(float2 *table, int table_len, int half, const doubl
 hipError_t launch_rope_kv(int dtype, const RopeArgs &a, hipStream_t s)
 {
     if (a.T <= 0) return hipSuccess;
-    // about two (head, pair) elements per thread; rows are plentiful in a prefill, so fewer slices there
+    // about two (head, pair) elements per thread for the few rows of a decode step; a prefill has
+    // rows enough to fill the chip with one block each (measured faster there)
     const int n_rot = (a.Hq + a.Hkv) * (a.hd / 2);
-    int slices = (n_rot + 511) / 512;
-    if (a.T >= 1024 && slices > 2) slices = 2;
+    int slices = a.T >= 1024 ? 1 : (n_rot + 511) / 512;
     if (slices < 1) slices = 1;
     const dim3 grid((unsigned)a.T, (unsigned)slices);
     if (dtype == PD_F32) rope_kv_kernel<float><<<grid, 256, 0, s>>>(a);
