@@ -164,47 +164,8 @@ __global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a, i
     const float sl2e = a.scale * 1.4426950408889634f * (FP8 ? a.k_scale : 1.f);
     const float o_scale = FP8 ? a.v_scale : 1.f;
 
-    for (int k = key0; k < key1; k += 64) {
-        bf16x8 kf[4][4], vf[2][8];
-        if (FP8) {
-            u32x4 kr[4][2], vr[8];
-            const uint8_t *kb_ptr = Kp8 + (size_t)(k >> 4) * 2048;
-            const uint8_t *vb_ptr = Vp8 + (size_t)(k >> 6) * 8192;
-#pragma unroll
-            for (int kb = 0; kb < 4; ++kb)
-#pragma unroll
-                for (int t = 0; t < 2; ++t) kr[kb][t] = *(const u32x4 *)(kb_ptr + kb * 2048 + t * 1024);
-#pragma unroll
-            for (int db = 0; db < 8; ++db) vr[db] = *(const u32x4 *)(vb_ptr + db * 1024);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int kb = 0; kb < 4; ++kb)
-#pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    kf[kb][2 * t] = fp8x8_to_bf16(kr[kb][t][0], kr[kb][t][1]);
-                    kf[kb][2 * t + 1] = fp8x8_to_bf16(kr[kb][t][2], kr[kb][t][3]);
-                }
-#pragma unroll
-            for (int db = 0; db < 8; ++db) {
-                vf[0][db] = fp8x8_to_bf16(vr[db][0], vr[db][1]);
-                vf[1][db] = fp8x8_to_bf16(vr[db][2], vr[db][3]);
-            }
-        } else {
-        const uint16_t *kb_ptr = Kp + (size_t)(k >> 4) * 2048;
-        const uint16_t *vb_ptr = Vp + (size_t)(k >> 5) * 4096;
-#pragma unroll
-        for (int kb = 0; kb < 4; ++kb)
-#pragma unroll
-            for (int s = 0; s < 4; ++s) kf[kb][s] = *(const bf16x8 *)(kb_ptr + kb * 2048 + s * 512);
-#pragma unroll
-        for (int vb = 0; vb < 2; ++vb)
-#pragma unroll
-            for (int db = 0; db < 8; ++db) vf[vb][db] = *(const bf16x8 *)(vb_ptr + vb * 4096 + db * 512);
-        }
-        // all 32 loads (32 KB per wave) are issued before anything consumes them: bytes in flight,
-        // not instruction count, is what this kernel lives on
-        __builtin_amdgcn_sched_barrier(0);
-
+    // one 64-key step on operands handed in by get_k(key block, k-step) / get_v(key half, channel block)
+    auto process = [&](int k, auto get_k, auto get_v) {
         // scores: lane (qi, kg), block kb, register j  <->  key k + 16*kb + 4*kg + j
         f32x4 sacc[4];
 #pragma unroll
@@ -212,7 +173,7 @@ __global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a, i
             sacc[kb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int s = 0; s < 4; ++s)
-                sacc[kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kb][s], qf[s], sacc[kb], 0, 0, 0);
+                sacc[kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(get_k(kb, s), qf[s], sacc[kb], 0, 0, 0);
         }
         const int last = MULTI ? min(key1, limit) : key1;    // first key this column must not see
         const bool tail = k + 64 > (MULTI ? min(key1, limit_min) : key1);
@@ -260,7 +221,60 @@ __global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a, i
         for (int db = 0; db < 8; ++db)
 #pragma unroll
             for (int vb = 0; vb < 2; ++vb)
-                oacc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[vb][db], pf[vb], oacc[db], 0, 0, 0);
+                oacc[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(get_v(vb, db), pf[vb], oacc[db], 0, 0, 0);
+    };
+
+    if (FP8) {
+        // 16 loads of 16 bytes per lane per step: [0..7] keys (block kb, half t -> 2 kb + t), [8..15]
+        // values (channel block db).  Two register sets: the loads of the next step are issued before
+        // the current one is computed, so a wave always has a step's worth of bytes in flight (the
+        // codes are widened operand by operand right before their MFMA, so both sets fit).
+        u32x4 ra[16], rb[16];
+        auto issue = [&](int k, u32x4 (&r)[16]) {
+            const uint8_t *kb_ptr = Kp8 + (size_t)(k >> 4) * 2048;
+            const uint8_t *vb_ptr = Vp8 + (size_t)(k >> 6) * 8192;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) r[i] = *(const u32x4 *)(kb_ptr + i * 1024);
+#pragma unroll
+            for (int db = 0; db < 8; ++db) r[8 + db] = *(const u32x4 *)(vb_ptr + db * 1024);
+        };
+        auto run = [&](int k, u32x4 (&r)[16]) {
+            process(
+                k,
+                [&](int kb, int s) { return fp8x8_to_bf16(r[2 * kb + (s >> 1)][2 * (s & 1)], r[2 * kb + (s >> 1)][2 * (s & 1) + 1]); },
+                [&](int vb, int db) { return fp8x8_to_bf16(r[8 + db][2 * vb], r[8 + db][2 * vb + 1]); });
+        };
+        int k = key0;
+        if (k < key1) issue(k, ra);
+        while (k < key1) {
+            if (k + 64 < key1) issue(k + 64, rb);
+            __builtin_amdgcn_sched_barrier(0);
+            run(k, ra);
+            k += 64;
+            if (k >= key1) break;
+            if (k + 64 < key1) issue(k + 64, ra);
+            __builtin_amdgcn_sched_barrier(0);
+            run(k, rb);
+            k += 64;
+        }
+    } else {
+        for (int k = key0; k < key1; k += 64) {
+            bf16x8 kf[4][4], vf[2][8];
+            const uint16_t *kb_ptr = Kp + (size_t)(k >> 4) * 2048;
+            const uint16_t *vb_ptr = Vp + (size_t)(k >> 5) * 4096;
+#pragma unroll
+            for (int kb = 0; kb < 4; ++kb)
+#pragma unroll
+                for (int s = 0; s < 4; ++s) kf[kb][s] = *(const bf16x8 *)(kb_ptr + kb * 2048 + s * 512);
+#pragma unroll
+            for (int vb = 0; vb < 2; ++vb)
+#pragma unroll
+                for (int db = 0; db < 8; ++db) vf[vb][db] = *(const bf16x8 *)(vb_ptr + vb * 4096 + db * 512);
+            // all 32 loads (32 KB per wave) are issued before anything consumes them: bytes in flight,
+            // not instruction count, is what this kernel lives on
+            __builtin_amdgcn_sched_barrier(0);
+            process(k, [&](int kb, int s) { return kf[kb][s]; }, [&](int vb, int db) { return vf[vb][db]; });
+        }
     }
 
     float l_tot = l_run + __shfl_xor(l_run, 16, 64);
