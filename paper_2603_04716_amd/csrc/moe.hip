@@ -38,10 +38,8 @@ hipError_t launch_router_logits(int dtype, const void *y, const void *w_router, 
 
 // p = softmax(logits) over all experts; the top_k largest p (ties: lower index); weights
 // renormalised to sum 1.  The selection compares probabilities in double.
-__global__ void moe_topk_kernel(MoeRouteArgs a)
+__device__ __forceinline__ void moe_topk_token(const MoeRouteArgs &a, int t, int *chosen = nullptr)
 {
-    int t = blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= a.T) return;
     const float *r = a.logits + (size_t)t * a.E;
     double mx = -INFINITY;
     for (int e = 0; e < a.E; ++e) mx = fmax(mx, (double)r[e]);
@@ -70,6 +68,39 @@ __global__ void moe_topk_kernel(MoeRouteArgs a)
     for (int k = 0; k < a.top_k; ++k) {
         a.expert_idx[(size_t)t * a.top_k + k] = ik[k];
         a.expert_w[(size_t)t * a.top_k + k] = (float)(pk[k] / sum);
+        if (chosen) chosen[t * a.top_k + k] = ik[k];
+    }
+}
+
+__global__ void moe_topk_kernel(MoeRouteArgs a)
+{
+    int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < a.T) moe_topk_token(a, t);
+}
+
+// Decode-sized routing, at most 64 (token, expert) pairs: one wavefront selects the experts and
+// sorts the pairs in a single launch.  Lane i owns pair i; for every expert a ballot gives the
+// lanes that chose it, so a pair's place is the expert's base plus the number of lower lanes with
+// the same expert: the same stable order as the general kernel.
+__global__ __launch_bounds__(64) void moe_route_small_kernel(MoeRouteArgs a)
+{
+    __shared__ int chosen[64];
+    const int lane = threadIdx.x;
+    const int P = a.T * a.top_k;
+    if (lane < a.T) moe_topk_token(a, lane, chosen);
+    __syncthreads();
+    const int e = lane < P ? chosen[lane] : -1;
+    int base = 0;
+    if (lane == 0) a.offsets[0] = 0;
+    for (int ex = 0; ex < a.E; ++ex) {
+        const unsigned long long mask = __ballot(e == ex);
+        if (e == ex) {
+            const int pos = base + __popcll(mask & ((1ull << lane) - 1ull));
+            a.sorted_token[pos] = lane / a.top_k;
+            a.pair_pos[lane] = pos;
+        }
+        base += __popcll(mask);
+        if (lane == 0) a.offsets[ex + 1] = base;
     }
 }
 
@@ -124,6 +155,10 @@ __global__ __launch_bounds__(1024) void moe_sort_kernel(MoeRouteArgs a)
 hipError_t launch_moe_route(const MoeRouteArgs &a, hipStream_t s)
 {
     if (a.T <= 0) return hipSuccess;
+    if (a.T * a.top_k <= 64) {
+        moe_route_small_kernel<<<1, 64, 0, s>>>(a);
+        return hipGetLastError();
+    }
     moe_topk_kernel<<<(a.T + 255) / 256, 256, 0, s>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -139,13 +174,21 @@ __global__ __launch_bounds__(256) void moe_combine_kernel(const T *__restrict__ 
                                                           const float *__restrict__ w,
                                                           T *__restrict__ out, int d, int top_k)
 {
+    // blockIdx.x = token, the gridDim.y blocks of a token share its channels round-robin; the
+    // (at most 8) pair positions and weights are read once, not once per channel
     const int t = blockIdx.x;
-    for (int i = threadIdx.x; i < d; i += 256) {
+    int pp[8];
+    float ww[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        pp[k] = k < top_k ? pair_pos[(size_t)t * top_k + k] : 0;
+        ww[k] = k < top_k ? w[(size_t)t * top_k + k] : 0.f;
+    }
+    for (int i = blockIdx.y * 256 + threadIdx.x; i < d; i += gridDim.y * 256) {
         float acc = 0.f;
-        for (int k = 0; k < top_k; ++k) {
-            int p = pair_pos[(size_t)t * top_k + k];
-            acc = fmaf(w[(size_t)t * top_k + k], Elem<T>::ld(eo + (size_t)p * d + i), acc);
-        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            if (k < top_k) acc = fmaf(ww[k], Elem<T>::ld(eo + (size_t)pp[k] * d + i), acc);
         Elem<T>::st(out + (size_t)t * d + i, Elem<T>::ld(h + (size_t)t * d + i) + acc);
     }
 }
@@ -155,10 +198,13 @@ hipError_t launch_moe_combine(int dtype, const void *h, const void *expert_out,
                               int d, int top_k, hipStream_t s)
 {
     if (T <= 0) return hipSuccess;
+    // few tokens: spread a row over several blocks so that no thread chains many memory round trips
+    const int slices = T >= 512 ? 1 : (d + 511) / 512;
+    const dim3 grid((unsigned)T, (unsigned)(slices < 1 ? 1 : slices));
     if (dtype == PD_F32)
-        moe_combine_kernel<float><<<T, 256, 0, s>>>((const float *)h, (const float *)expert_out, pair_pos, expert_w, (float *)out, d, top_k);
+        moe_combine_kernel<float><<<grid, 256, 0, s>>>((const float *)h, (const float *)expert_out, pair_pos, expert_w, (float *)out, d, top_k);
     else
-        moe_combine_kernel<bf16_t><<<T, 256, 0, s>>>((const bf16_t *)h, (const bf16_t *)expert_out, pair_pos, expert_w, (bf16_t *)out, d, top_k);
+        moe_combine_kernel<bf16_t><<<grid, 256, 0, s>>>((const bf16_t *)h, (const bf16_t *)expert_out, pair_pos, expert_w, (bf16_t *)out, d, top_k);
     return hipGetLastError();
 }
 
