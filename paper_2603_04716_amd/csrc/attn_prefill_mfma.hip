@@ -84,13 +84,20 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_mfma_kernel(AttnArgs a,
                                                                    const int32_t *__restrict__ pad_cu)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    const int seq = blockIdx.z, head = blockIdx.y;
+    // Workgroups are dispatched in index order and a query block's work grows with its position in
+    // the sequence (causal), so the index runs over the query blocks from the last one down, and
+    // inside one block position over all (sequence, head) pairs: the longest workgroups start first
+    // and the chip drains on the shortest ones.  Heads of a group are neighbours and share K / V in
+    // the L2.
+    const int per_qb = a.Hq * a.n_seqs;
+    const int rank = blockIdx.x / per_qb, rest = blockIdx.x - rank * per_qb;
+    const int seq = rest / a.Hq, head = rest - seq * a.Hq;
     const int s0 = a.d_cu[seq], L = a.d_cu[seq + 1] - s0;
     const int P = a.prefix ? a.prefix[seq] : 0;    // keys ahead of the first query (chunked prefill)
     const int Lk = P + L;                          // keys of the sequence
     const int nqb = (L + BQ - 1) / BQ;
-    if ((int)blockIdx.x >= nqb) return;
-    const int qb = nqb - 1 - blockIdx.x;           // longest rows first
+    const int qb = (int)(gridDim.x / per_qb) - 1 - rank;   // block position, counted from the longest sequence's last
+    if (qb >= nqb) return;
     const int q0 = qb * BQ;
     const int g = head / (a.Hq / a.Hkv);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -386,7 +393,7 @@ hipError_t launch_attn_prefill_mfma(const AttnArgs &a, uint16_t *vt, int vt_ld, 
         attr_set = true;
     }
     const int nqb = (a.max_seq_len + BQ - 1) / BQ;
-    attn_prefill_mfma_kernel<<<dim3(nqb, a.Hq, a.n_seqs), 256, smem, s>>>(a, vt, vt_ld, pad_cu);
+    attn_prefill_mfma_kernel<<<dim3((unsigned)(nqb * a.Hq * a.n_seqs)), 256, smem, s>>>(a, vt, vt_ld, pad_cu);
     return hipGetLastError();
 }
 
@@ -416,7 +423,7 @@ hipError_t launch_attn_chunk_mfma(const AttnArgs &a_in, const int32_t *d_slots, 
         attr_set = true;
     }
     const int nqb = (a.max_seq_len + BQ - 1) / BQ;
-    attn_prefill_mfma_kernel<<<dim3(nqb, a.Hq, a.n_seqs), 256, smem, s>>>(a, vt, vt_ld, pad_cu);
+    attn_prefill_mfma_kernel<<<dim3((unsigned)(nqb * a.Hq * a.n_seqs)), 256, smem, s>>>(a, vt, vt_ld, pad_cu);
     return hipGetLastError();
 }
 
