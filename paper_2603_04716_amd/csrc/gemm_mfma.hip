@@ -30,6 +30,7 @@ namespace pd {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BK = 64;  // k per tile: 8 chunks of 16 bytes per row
 
@@ -253,6 +254,51 @@ __global__ __launch_bounds__(64 * WAVES_M *WAVES_N) void gemm_mfma_kernel(GemmAr
     }
     uint16_t *C = (uint16_t *)a.C;
     const uint16_t *R = (const uint16_t *)a.R;
+    // Row-contiguous stores: the accumulators hold one column per lane, which would make every store
+    // (and residual load) a 2-byte access.  Each wave instead passes its 32-row blocks through a
+    // private 8 KB of the (now idle) operand stages as fp32 and reads them back with 4 consecutive
+    // columns per lane, so a wave instruction moves whole 128-byte row segments; the residual is
+    // added in fp32 before the one rounding to bf16.
+    constexpr bool kStage = WN == 64 && NB == 2;
+    if (kStage && a.N % 4 == 0 && a.ldc % 4 == 0 && (EPI != EPI_RESIDUAL || a.ldr % 4 == 0)) {
+        constexpr int OC = EPI == EPI_SWIGLU ? 32 : 64;   // output columns of a staged block
+        constexpr int LPR = OC / 4, RPI = 64 / LPR;      // lanes per row, rows per wave instruction
+        __syncthreads();                                  // every wave is done with the operand stages
+        float *stg = (float *)smem + wave * 2048;
+        const int out_col0 = EPI == EPI_SWIGLU ? ((col0 + wn * WN) >> 6) * 32 : col0 + wn * WN;
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = 8 * (r >> 2) + 4 * fhalf + (r & 3);
+                if (EPI == EPI_SWIGLU) {
+                    stg[row * OC + frow] = silu_fast(acc[i][0][r]) * acc[i][1][r];
+                } else {
+                    stg[row * OC + frow] = acc[i][0][r];
+                    stg[row * OC + 32 + frow] = acc[i][1][r];
+                }
+            }
+#pragma unroll
+            for (int it = 0; it < 32 / RPI; ++it) {
+                const int row = it * RPI + lane / LPR, cg = (lane % LPR) * 4;
+                const f32x4 v = *(const f32x4 *)(stg + row * OC + cg);
+                const int m = row0 + wm * WM + i * 32 + row, n = out_col0 + cg;
+                if (m < row_end && n < a.N) {
+                    float o0 = v[0], o1 = v[1], o2 = v[2], o3 = v[3];
+                    if (EPI == EPI_RESIDUAL) {
+                        const uint2 rr = *(const uint2 *)(R + (size_t)m * a.ldr + n);
+                        o0 += bfbits2f(rr.x & 0xffffu); o1 += bfbits2f(rr.x >> 16);
+                        o2 += bfbits2f(rr.y & 0xffffu); o3 += bfbits2f(rr.y >> 16);
+                    }
+                    uint2 o;
+                    o.x = pack2bf(o0, o1);
+                    o.y = pack2bf(o2, o3);
+                    *(uint2 *)(C + (size_t)m * a.ldc + n) = o;
+                }
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < MB; ++i) {
 #pragma unroll
