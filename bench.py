@@ -30,7 +30,7 @@ DECODE_REPS = 3                    # decode steps per batch size per step; media
 # the FETCH_SIZE / WRITE_SIZE counters scaled by a plain copy (paper_2603_04716_amd/traffic_probe.py).
 # Valid only for the kernel source the counters were taken on.
 TRAFFIC = {"source": os.path.join("paper_2603_04716_amd", "csrc", "gemm_mfma.hip"),
-           "sha256": "cc77504d529ca0108747937a039102e0b204da152b9f4881f48ee14faec0d22d",
+           "sha256": "7aba27822d127b9c8127a0866e6fc41c3798cb2554aafb01b2c96eb464a7d8fd",
            "bytes_per_launch": 3053.6e6}
 
 
