@@ -30,7 +30,7 @@ DECODE_REPS = 3                    # decode steps per batch size per step; media
 # the FETCH_SIZE / WRITE_SIZE counters scaled by a plain copy (paper_2603_04716_amd/traffic_probe.py).
 # Valid only for the kernel source the counters were taken on.
 TRAFFIC = {"source": os.path.join("paper_2603_04716_amd", "csrc", "gemm_mfma.hip"),
-           "sha256": "7aba27822d127b9c8127a0866e6fc41c3798cb2554aafb01b2c96eb464a7d8fd",
+           "sha256": "6c1dc43d31f26f7c7bb4573d0033c7a3e0a825db7554562edbf354acf6770b85",
            "bytes_per_launch": 3053.6e6}
 
 

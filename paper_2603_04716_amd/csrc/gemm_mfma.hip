@@ -370,6 +370,13 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmArgs a, int spli
     *(uint2 *)((uint16_t *)a.C + (size_t)m * a.ldc + n) = o;
 }
 
+hipError_t launch_splitk_reduce(const GemmArgs &a, int splits, hipStream_t s)
+{
+    const size_t n_out = (size_t)a.M * (a.N / 4);
+    splitk_reduce_kernel<<<(unsigned)((n_out + 255) / 256), 256, 0, s>>>(a, splits);
+    return hipGetLastError();
+}
+
 bool gemm_mfma_supported(const GemmArgs &a)
 {
     if (a.K % BK != 0 || a.K <= 0 || a.M <= 0) return false;
@@ -414,9 +421,7 @@ static hipError_t launch_cfg(const GemmArgs &a, hipStream_t s, int splits = 1)
         LAUNCH(EPI_PARTIAL);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        const size_t n_out = (size_t)a.M * (a.N / 4);
-        splitk_reduce_kernel<<<(unsigned)((n_out + 255) / 256), 256, 0, s>>>(a, splits);
-        return hipGetLastError();
+        return launch_splitk_reduce(a, splits, s);
     }
     switch (a.epilogue) {
     case EPI_NONE: LAUNCH(EPI_NONE); break;

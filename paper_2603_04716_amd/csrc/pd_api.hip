@@ -652,13 +652,14 @@ static hipError_t run_gemm(const pd_layer *L, GemmArgs g, hipStream_t s)
     if (L->packed) {
         // packed weights are only understood by the matrix-core kernels
         if (L->w8) {
-            // the skinny kernel streams the 8-bit twin of the matrix; the tiled kernels take the bf16 pack
+            // decode-sized products stream the 8-bit twin of the matrix; the tiled kernels take the bf16 pack
             if (g.B == L->w_qkv) { g.B8 = L->q_qkv; g.b_scale = L->s_qkv; }
             else if (g.B == L->w_o) { g.B8 = L->q_o; g.b_scale = L->s_o; }
             else if (g.B == L->w_gate) { g.B8 = L->q_gate; g.b_scale = L->s_gate; }
             else if (g.B == L->w_down) { g.B8 = L->q_down; g.b_scale = L->s_down; }
         }
         if (gemv_mfma_supported(g)) return launch_gemv_mfma(g, s);
+        if (wgemm8_mfma_supported(g)) return launch_wgemm8_mfma(g, s);
         if (gemm_mfma_supported(g)) return launch_gemm_mfma(g, s);
         return hipErrorInvalidValue;
     }

@@ -153,7 +153,7 @@ struct GemmArgs {
     int32_t packed;                // B is in the MFMA block layout below (matrix-core kernels only)
     float *splitk_ws;              // optional scratch for split-K partials (decode-sized M)
     size_t splitk_ws_elems;
-    // 8-bit twin of the packed weights (skinny kernel only; null = none): E4M3 codes in the layout
+    // 8-bit twin of the packed weights (skinny and wide decode kernels only; null = none): E4M3 codes in the layout
     // of w8pack_off, and one power-of-two scale per packed weight row; weight = scale * value(code).
     // Groups are b_group_stride codes and (2N for SwiGLU, else N) scales apart.
     const void *B8;
@@ -166,6 +166,10 @@ hipError_t launch_rmsnorm(int dtype, const void *x, const void *g, void *y, int 
 hipError_t launch_gemm_generic(int dtype, const GemmArgs &a, hipStream_t s);
 bool gemm_mfma_supported(const GemmArgs &a);
 hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t s);   // bf16 only
+// sums the fp32 partials [splits][M][N or 2N packed] in a.splitk_ws in a fixed order and applies a.epilogue
+hipError_t launch_splitk_reduce(const GemmArgs &a, int splits, hipStream_t s);
+bool wgemm8_mfma_supported(const GemmArgs &a);                    // 8-bit weights, 16 < M <= 128
+hipError_t launch_wgemm8_mfma(const GemmArgs &a, hipStream_t s);
 bool gemv_mfma_supported(const GemmArgs &a);                      // bf16, M <= 16
 hipError_t launch_gemv_mfma(const GemmArgs &a, hipStream_t s);
 // per token row: its sequence, its position inside it and (if d_slots) its cache slot

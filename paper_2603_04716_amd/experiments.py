@@ -462,18 +462,19 @@ def run_fp8kv():
 
 
 def run_w8():
-    """Small-batch decode with the projection weights as 8-bit codes beside bf16 weights (both with the
+    """Decode up to batch 128 with the projection weights as 8-bit codes beside bf16 weights (both with the
     bf16 cache and, for the 8-bit weights, also the 8-bit cache), KV 2048, with per-step timings."""
     cfg = I.CONFIGS["llama8b"]
     hkv, hd, d = cfg["n_kv_heads"], cfg["head_dim"], cfg["d_model"]
-    S, bmax = 2048, 32
-    batches = (1, 2, 4, 8, 16, 32)
+    S, bmax = 2048, 128
+    batches = (1, 2, 4, 8, 16, 32, 64, 96, 128)
     host_w = I.layer_weights(cfg)
     xall = H._dev(I.hidden(bmax, d, seed=12, dtype="bf16"), "bf16")
     k, v = I.kv_fill(hkv, S, hd, seed=11, dtype="bf16")
     kd, vd = H._dev(k, "bf16"), H._dev(v, "bf16")
     attn_p, ffn_p = H.layer_params(cfg)
-    out = {"experiment": "decode with 8-bit projection weights (skinny kernel, <= 16 rows)", "kv_len": S, "cases": []}
+    out = {"experiment": "decode with 8-bit projection weights (skinny kernel <= 16 rows, wide kernel <= 128)",
+           "kv_len": S, "cases": []}
     for w8, fp8kv in ((False, False), (True, False), (True, True)):
         layer = H.Layer(cfg, host_w, w8=w8)
         cache = layer.new_cache(bmax, S + 8, fp8_scales=(0.5, 0.125) if fp8kv else None)
@@ -482,7 +483,7 @@ def run_w8():
         for B in batches:
             run = layer.make_decode_step(cache, xall[:B].contiguous(), [S] * B)
             ms = H.median([run() for _ in range(9)])
-            wbytes = (attn_p + ffn_p) * (1 if (w8 and B <= 16) else 2)
+            wbytes = (attn_p + ffn_p) * (1 if (w8 and B <= 128) else 2)
             kvbytes = 2.0 * hkv * hd * (1 if fp8kv else 2) * (S + 1) * B
             curve.append({"batch": B, "ms_per_layer": round(ms, 4), "tpot_ms": round(N_LAYERS * ms, 3),
                           "tok_s": round(B / (N_LAYERS * ms * 1e-3), 1),

@@ -23,8 +23,9 @@ def small(hq=4, hkv=2, d=256, F=512, **kw):
 
 @pytest.mark.parametrize("B", [1, 2, 7, 16, 17, 40, 130])
 def test_decode_batches_on_both_sides_of_the_skinny_kernel(B):
-    """Up to 16 rows stream the 8-bit codes, above that the bf16 copy of the same quantised weights
-    runs the tiled kernels: one oracle for both."""
+    """Up to 16 rows stream the 8-bit codes through the skinny kernel; above that the wide kernel does
+    where K is a multiple of 512 (here the O and down projections) and the bf16 copy of the same
+    quantised weights runs the tiled kernels elsewhere: one oracle for all."""
     cfg = small()
     ol, gl = both(cfg)
     rng = np.random.default_rng(B)
@@ -66,6 +67,32 @@ def test_shapes_long_and_short_k_prefill_then_decode(d, F, hq, hkv):
     gl.close()
 
 
+@pytest.mark.parametrize("d,F,hq,hkv", [(512, 1024, 4, 2), (1024, 512, 8, 8), (2048, 512, 16, 4), (576, 512, 4, 1)])
+@pytest.mark.parametrize("B", [17, 32, 33, 64, 65, 96, 97, 128])
+def test_wide_kernel_batches_17_to_128(B, d, F, hq, hkv):
+    """Every row-block count of the wide 8-bit kernel (2, 4, 6, 8 blocks of 16 rows, full and ragged),
+    with all four projections on it (every K a multiple of 512), K split over workgroups for the plain,
+    residual and SwiGLU epilogues (second shape; the third has K = 2048, which the 16-deep ring of the
+    smaller batches splits as well) and a last workgroup with weight blocks past the end (last shape: 576 output columns of the O and down projections; its other two products have
+    K = 576 and stay on the tiled kernels)."""
+    cfg = small(hq, hkv, d, F)
+    ol, gl = both(cfg, std=0.04, seed=B)
+    rng = np.random.default_rng(1000 + B)
+    lens = rng.integers(1, 90, B)
+    oc, gc = O.KVCache(ol, B, 96), gl.cache(B, 96)
+    for i, n in enumerate(lens):
+        k, v = I.kv_fill(hkv, int(n), 128, seed=4000 + i, dtype="bf16")
+        oc.set(i, k, v)
+        pd.pd_kv_cache_set(gc, i, to_dev(k, "bf16"), to_dev(v, "bf16"))
+    slots = list(range(B))
+    xn = I.hidden(B, d, seed=52, dtype="bf16")
+    ref = O.decode_step(ol, xn, slots, oc)
+    got = gl.decode(xn, slots, gc)
+    assert relmax(got, ref) <= TOL["bf16"]
+    assert max(relmax(got[i], ref[i]) for i in range(B)) <= 2 * TOL["bf16"]
+    gl.close()
+
+
 @pytest.mark.parametrize("B", [1, 6, 40])
 def test_moe_layer_with_8bit_expert_weights(B):
     cfg = small(4, 2, n_experts=4, top_k=2)
@@ -94,8 +121,8 @@ def test_w8_needs_a_matrix_core_layer():
 
 
 def test_llama8b_shape_w8_decode_sampled_rows_with_fp8_cache():
-    """8B-shaped layer, 8-bit weights and 8-bit cache together, batch 8 (skinny kernels) and 48
-    (tiled kernels); the oracle recomputes sampled rows."""
+    """8B-shaped layer, 8-bit weights and 8-bit cache together, batch 8 (skinny kernels), 48 and 128
+    (wide kernel, 4 and 8 row blocks); the oracle recomputes sampled rows."""
     cfg = I.CONFIGS["llama8b"]
     w = I.layer_weights(cfg)
     ol, gl = O.Layer(cfg, O.quantise_layer_weights(w)), GpuLayer(cfg, w, w8=True)
@@ -103,7 +130,7 @@ def test_llama8b_shape_w8_decode_sampled_rows_with_fp8_cache():
     S = 700
     k, v = I.kv_fill(cfg["n_kv_heads"], S, 128, seed=43, dtype="bf16")
     kd, vd = to_dev(k, "bf16"), to_dev(v, "bf16")
-    for B, rows in ((8, [0, 7]), (48, [3, 47])):
+    for B, rows in ((8, [0, 7]), (48, [3, 47]), (128, [0, 127])):
         gc = gl.cache(B, S + 8, fp8_scales=scales)
         for i in range(B):
             pd.pd_kv_cache_set(gc, i, kd[:, :S - i].contiguous(), vd[:, :S - i].contiguous())
