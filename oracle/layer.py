@@ -17,7 +17,7 @@ _lib = None
 class _Cfg(C.Structure):
     _fields_ = [("d_model", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("d_ff", C.c_int32), ("n_experts", C.c_int32),
-                ("top_k", C.c_int32), ("rms_eps", C.c_double), ("rope_base", C.c_double)]
+                ("top_k", C.c_int32), ("act8", C.c_int32), ("rms_eps", C.c_double), ("rope_base", C.c_double)]
 
 
 _WNAMES = ["g_attn", "w_q", "w_k", "w_v", "w_o", "g_ffn", "w_gate", "w_up", "w_down", "w_router"]
@@ -53,10 +53,12 @@ def _i32(a):
 class Layer:
     """One decoder layer: configuration + fp32 weights (dict of numpy arrays)."""
 
-    def __init__(self, cfg: dict, weights: dict):
+    def __init__(self, cfg: dict, weights: dict, act8: bool = False):
+        """act8: in calls of more than ACT8_ROWS rows every projection sees its input rows rounded to
+        bf16 and quantised like act_quantise_rows (pass weights from quantise_layer_weights with it)."""
         self.cfg = dict(cfg)
         self.c = _Cfg(cfg["d_model"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"],
-                      cfg["d_ff"], cfg.get("n_experts", 0), cfg.get("top_k", 0),
+                      cfg["d_ff"], cfg.get("n_experts", 0), cfg.get("top_k", 0), int(bool(act8)),
                       float(cfg.get("rms_eps", 1e-6)), float(cfg.get("rope_base", 10000.0)))
         self.w = {}
         self.cw = _Wts()
@@ -213,6 +215,22 @@ def quantise_rows(W):
     scales = np.empty(n_rows, np.float32)
     lib().orc_quantise_rows(_p(W), C.c_int(n_rows), C.c_int(K), _p(scales))
     return W, scales.reshape(W.shape[:-1])
+
+
+ACT8_ROWS = 256   # calls with more rows than this quantise their activations in an act8 layer
+
+
+def act_quantise_rows(x):
+    """(x', scales, codes) for activation rows: x rounded to bf16, then quantised like a weight row;
+    codes are the E4M3 bytes of x / scale."""
+    x = _f32(x).copy()
+    K = x.shape[-1]
+    n_rows = x.size // K
+    scales = np.empty(n_rows, np.float32)
+    lib().orc_act_quantise_rows(_p(x), C.c_int(n_rows), C.c_int(K), _p(scales))
+    sc = scales.reshape(x.shape[:-1])
+    codes = fp8_e4m3_encode(x / sc[..., None])
+    return x, sc, codes
 
 
 def quantise_layer_weights(weights):

@@ -39,8 +39,11 @@ typedef struct {
     int32_t d_model, n_q_heads, n_kv_heads, head_dim, d_ff;
     int32_t n_experts; /* 0 = dense FFN */
     int32_t top_k;
+    int32_t act8;      /* 8-bit activations in calls of more than ORC_ACT8_ROWS rows (see act_quantise_row) */
     double rms_eps, rope_base;
 } orc_config;
+
+#define ORC_ACT8_ROWS 256
 
 typedef struct {
     const float *g_attn;   /* [d] */
@@ -136,6 +139,32 @@ void orc_quantise_rows(float *W, int n_rows, int K, float *scales)
         if (scales) scales[n] = (float)s;
     }
 }
+
+/*
+ * 8-bit activations: in a call of more than ORC_ACT8_ROWS rows every projection (q/k/v, output, gate/up,
+ * down) sees its input row replaced by s * fp8(v / s), s as for a weight row.  The input rows are
+ * bf16 tensors in the layer this oracle checks, and a code is an integer decided by floating point,
+ * so the row is first rounded to bf16 (nearest even): the decision is taken in the precision the
+ * kernel takes it in.
+ */
+static float round_bf16(float x)
+{
+    uint32_t u;
+    memcpy(&u, &x, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return x; /* NaN */
+    u += 0x7fffu + ((u >> 16) & 1u);
+    u &= 0xffff0000u;
+    memcpy(&x, &u, 4);
+    return x;
+}
+
+void orc_act_quantise_rows(float *v, int n_rows, int n, float *scales)
+{
+    for (size_t i = 0; i < (size_t)n_rows * (size_t)n; ++i) v[i] = round_bf16(v[i]);
+    orc_quantise_rows(v, n_rows, n, scales);
+}
+
+static void act_quantise_row(float *v, int n) { orc_act_quantise_rows(v, 1, n, NULL); }
 
 void orc_rmsnorm_row(const float *x, const float *g, int d, double eps, float *y)
 {
@@ -258,7 +287,7 @@ static double silu(double z) { return z / (1.0 + exp(-z)); }
 
 /* out[d] += scale * Wd (silu(Wg y) * (Wu y)) for one token and one FFN. */
 static void ffn_row_accumulate(const float *y, const float *Wg, const float *Wu, const float *Wd,
-                               int d, int F, double scale, double *out_acc, float *act)
+                               int d, int F, double scale, double *out_acc, float *act, int q8)
 {
     for (int f = 0; f < F; ++f) {
         const float *wg = Wg + (size_t)f * d, *wu = Wu + (size_t)f * d;
@@ -270,6 +299,7 @@ static void ffn_row_accumulate(const float *y, const float *Wg, const float *Wu,
         }
         act[f] = (float)(silu(a) * b);
     }
+    if (q8) act_quantise_row(act, F);
     for (int o = 0; o < d; ++o) {
         const float *wd = Wd + (size_t)o * F;
         double acc = 0.0;
@@ -314,7 +344,7 @@ void orc_route_row(const float *logits, int E, int top_k, int32_t *idx, double *
 
 /* Second half of the layer for one token: out = h + FFN(rmsnorm(h)). */
 static void ffn_block_row(const orc_config *c, const orc_weights *w, const float *h,
-                          const float *router_logits_row, float *out, int32_t *expert_idx_out)
+                          const float *router_logits_row, float *out, int32_t *expert_idx_out, int q8)
 {
     int d = c->d_model, F = c->d_ff;
     float *y2 = (float *)malloc(sizeof(float) * (size_t)d);
@@ -322,7 +352,8 @@ static void ffn_block_row(const orc_config *c, const orc_weights *w, const float
     double *acc = (double *)calloc((size_t)d, sizeof(double));
     orc_rmsnorm_row(h, w->g_ffn, d, c->rms_eps, y2);
     if (c->n_experts <= 0) {
-        ffn_row_accumulate(y2, w->w_gate, w->w_up, w->w_down, d, F, 1.0, acc, act);
+        if (q8) act_quantise_row(y2, d);
+        ffn_row_accumulate(y2, w->w_gate, w->w_up, w->w_down, d, F, 1.0, acc, act, q8);
     } else {
         int E = c->n_experts, K = c->top_k;
         float *logits = (float *)malloc(sizeof(float) * (size_t)E);
@@ -337,7 +368,7 @@ static void ffn_block_row(const orc_config *c, const orc_weights *w, const float
         for (int k = 0; k < K; ++k) {
             size_t e = (size_t)idx[k];
             ffn_row_accumulate(y2, w->w_gate + e * (size_t)F * d, w->w_up + e * (size_t)F * d,
-                               w->w_down + e * (size_t)d * F, d, F, wgt[k], acc, act);
+                               w->w_down + e * (size_t)d * F, d, F, wgt[k], acc, act, 0);
             if (expert_idx_out) expert_idx_out[k] = idx[k];
         }
         free(logits);
@@ -372,6 +403,7 @@ int orc_prefill(const orc_config *c, const orc_weights *w, const float *x, int T
                 double v_scale)
 {
     int d = c->d_model, Hq = c->n_q_heads, Hkv = c->n_kv_heads, hd = c->head_dim;
+    const int q8 = c->act8 && T > ORC_ACT8_ROWS;   /* 8-bit activations in this call */
     if (Hkv <= 0 || Hq % Hkv != 0 || hd % 2 != 0) return -1;
     if (cu_seqlens[0] != 0 || cu_seqlens[n_seqs] != T) return -1;
     if (slots && rows) return -1;
@@ -411,6 +443,7 @@ int orc_prefill(const orc_config *c, const orc_weights *w, const float *x, int T
         if (!need_kv[t]) continue;
         float *y = (float *)malloc(sizeof(float) * (size_t)d);
         orc_rmsnorm_row(x + (size_t)t * d, w->g_attn, d, c->rms_eps, y);
+        if (q8) act_quantise_row(y, d);
         orc_linear_row(y, w->w_k, d, (int)dkv, kbuf + (size_t)t * dkv);
         orc_linear_row(y, w->w_v, d, (int)dkv, vbuf + (size_t)t * dkv);
         orc_rope_row(kbuf + (size_t)t * dkv, Hkv, hd, t - cu_seqlens[seq_of[t]], c->rope_base);
@@ -447,15 +480,17 @@ int orc_prefill(const orc_config *c, const orc_weights *w, const float *x, int T
         float *o = (float *)malloc(sizeof(float) * dq);
         float *h = (float *)malloc(sizeof(float) * (size_t)d);
         orc_rmsnorm_row(x + (size_t)t * d, w->g_attn, d, c->rms_eps, y);
+        if (q8) act_quantise_row(y, d);
         orc_linear_row(y, w->w_q, d, (int)dq, q);
         orc_rope_row(q, Hq, hd, t - s0, c->rope_base);
         orc_attend_row(q, kbuf + (size_t)s0 * dkv, vbuf + (size_t)s0 * dkv, dkv, (size_t)hd,
                        t - s0 + 1, Hq, Hkv, hd, o);
+        if (q8) act_quantise_row(o, (int)dq);
         orc_linear_row(o, w->w_o, (int)dq, d, h);
         for (int i = 0; i < d; ++i) h[i] = (float)((double)x[(size_t)t * d + i] + (double)h[i]);
         size_t r = (size_t)out_slot[t];
         ffn_block_row(c, w, h, router_logits ? router_logits + (size_t)t * c->n_experts : NULL,
-                      out + r * d, expert_idx ? expert_idx + r * (size_t)c->top_k : NULL);
+                      out + r * d, expert_idx ? expert_idx + r * (size_t)c->top_k : NULL, q8);
         free(y);
         free(q);
         free(o);
@@ -484,6 +519,7 @@ int orc_decode_step(const orc_config *c, const orc_weights *w, const float *x, i
                     int kv_fp8, double k_scale, double v_scale)
 {
     int d = c->d_model, Hq = c->n_q_heads, Hkv = c->n_kv_heads, hd = c->head_dim;
+    const int q8 = c->act8 && B > ORC_ACT8_ROWS;   /* 8-bit activations in this call */
     if (Hkv <= 0 || Hq % Hkv != 0 || hd % 2 != 0) return -1;
     size_t dq = (size_t)Hq * hd, dkv = (size_t)Hkv * hd;
     for (int b = 0; b < B; ++b)
@@ -498,6 +534,7 @@ int orc_decode_step(const orc_config *c, const orc_weights *w, const float *x, i
         float *o = (float *)malloc(sizeof(float) * dq);
         float *h = (float *)malloc(sizeof(float) * (size_t)d);
         orc_rmsnorm_row(x + (size_t)b * d, w->g_attn, d, c->rms_eps, y);
+        if (q8) act_quantise_row(y, d);
         orc_linear_row(y, w->w_q, d, (int)dq, q);
         orc_linear_row(y, w->w_k, d, (int)dkv, k);
         orc_linear_row(y, w->w_v, d, (int)dkv, v);
@@ -510,10 +547,11 @@ int orc_decode_step(const orc_config *c, const orc_weights *w, const float *x, i
         }
         orc_attend_row(q, k_cache + base, v_cache + base, (size_t)hd, (size_t)max_len * hd, p + 1,
                        Hq, Hkv, hd, o);
+        if (q8) act_quantise_row(o, (int)dq);
         orc_linear_row(o, w->w_o, (int)dq, d, h);
         for (int i = 0; i < d; ++i) h[i] = (float)((double)x[(size_t)b * d + i] + (double)h[i]);
         ffn_block_row(c, w, h, router_logits ? router_logits + (size_t)b * c->n_experts : NULL,
-                      out + (size_t)b * d, expert_idx ? expert_idx + (size_t)b * c->top_k : NULL);
+                      out + (size_t)b * d, expert_idx ? expert_idx + (size_t)b * c->top_k : NULL, q8);
         free(y);
         free(q);
         free(k);
@@ -548,6 +586,7 @@ int orc_prefill_chunk(const orc_config *c, const orc_weights *w, const float *x,
                       int32_t *expert_idx, int kv_fp8, double k_scale, double v_scale)
 {
     int d = c->d_model, Hq = c->n_q_heads, Hkv = c->n_kv_heads, hd = c->head_dim;
+    const int q8 = c->act8 && T > ORC_ACT8_ROWS;   /* 8-bit activations in this call */
     if (Hkv <= 0 || Hq % Hkv != 0 || hd % 2 != 0) return -1;
     if (!slots || cu_seqlens[0] != 0 || cu_seqlens[n_seqs] != T) return -1;
     size_t dq = (size_t)Hq * hd, dkv = (size_t)Hkv * hd;
@@ -572,6 +611,7 @@ int orc_prefill_chunk(const orc_config *c, const orc_weights *w, const float *x,
         float *k = (float *)malloc(sizeof(float) * dkv);
         float *v = (float *)malloc(sizeof(float) * dkv);
         orc_rmsnorm_row(x + (size_t)t * d, w->g_attn, d, c->rms_eps, y);
+        if (q8) act_quantise_row(y, d);
         orc_linear_row(y, w->w_k, d, (int)dkv, k);
         orc_linear_row(y, w->w_v, d, (int)dkv, v);
         orc_rope_row(k, Hkv, hd, pos, c->rope_base);
@@ -595,15 +635,17 @@ int orc_prefill_chunk(const orc_config *c, const orc_weights *w, const float *x,
         float *o = (float *)malloc(sizeof(float) * dq);
         float *h = (float *)malloc(sizeof(float) * (size_t)d);
         orc_rmsnorm_row(x + (size_t)t * d, w->g_attn, d, c->rms_eps, y);
+        if (q8) act_quantise_row(y, d);
         orc_linear_row(y, w->w_q, d, (int)dq, q);
         orc_rope_row(q, Hq, hd, pos, c->rope_base);
         size_t base = (size_t)slot * Hkv * (size_t)max_len * hd;
         orc_attend_row(q, k_cache + base, v_cache + base, (size_t)hd, (size_t)max_len * hd, pos + 1,
                        Hq, Hkv, hd, o);
+        if (q8) act_quantise_row(o, (int)dq);
         orc_linear_row(o, w->w_o, (int)dq, d, h);
         for (int i = 0; i < d; ++i) h[i] = (float)((double)x[(size_t)t * d + i] + (double)h[i]);
         ffn_block_row(c, w, h, router_logits ? router_logits + (size_t)t * c->n_experts : NULL,
-                      out + (size_t)t * d, expert_idx ? expert_idx + (size_t)t * c->top_k : NULL);
+                      out + (size_t)t * d, expert_idx ? expert_idx + (size_t)t * c->top_k : NULL, q8);
         free(y);
         free(q);
         free(o);
@@ -643,5 +685,6 @@ void orc_ffn_block(const orc_config *c, const orc_weights *w, const float *h, in
         ffn_block_row(c, w, h + (size_t)t * c->d_model,
                       router_logits ? router_logits + (size_t)t * c->n_experts : NULL,
                       out + (size_t)t * c->d_model,
-                      expert_idx ? expert_idx + (size_t)t * c->top_k : NULL);
+                      expert_idx ? expert_idx + (size_t)t * c->top_k : NULL,
+                      c->act8 && T > ORC_ACT8_ROWS);
 }

@@ -11,8 +11,18 @@ from oracle import layer as O
 
 # ---- independent float64 composition of library routines ----------------------------------------
 
-def torch_layer(cfg, w, x, cu, router_logits=None):
+def torch_act_q(z):
+    """Library form of the 8-bit activation rule: rows rounded to bf16, power-of-two scale that keeps
+    the row inside +-448, the library's float8_e4m3fn conversion of z / s."""
+    zb = z.to(torch.float32).to(torch.bfloat16).to(torch.float64)
+    m = zb.abs().amax(dim=-1, keepdim=True)
+    s = torch.where(m > 0, 2.0 ** torch.ceil(torch.log2(m / 448.0)), torch.ones_like(m))
+    return (zb / s).to(torch.float32).to(torch.float8_e4m3fn).to(torch.float64) * s
+
+
+def torch_layer(cfg, w, x, cu, router_logits=None, act_q=None):
     f64 = torch.float64
+    aq = act_q if act_q is not None else (lambda z: z)
     W = {k: torch.from_numpy(np.asarray(v)).to(f64) for k, v in w.items()}
     x = torch.from_numpy(x).to(f64)
     d, hq, hkv, hd = cfg["d_model"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"]
@@ -28,7 +38,7 @@ def torch_layer(cfg, w, x, cu, router_logits=None):
         a1, a2 = a[..., :half], a[..., half:]
         return torch.cat([a1 * c - a2 * s, a2 * c + a1 * s], dim=-1)
 
-    y = norm(x, W["g_attn"])
+    y = aq(norm(x, W["g_attn"]))
     q = (y @ W["w_q"].T).view(-1, hq, hd)
     k = (y @ W["w_k"].T).view(-1, hkv, hd)
     v = (y @ W["w_v"].T).view(-1, hkv, hd)
@@ -43,11 +53,13 @@ def torch_layer(cfg, w, x, cu, router_logits=None):
         vs = v[a:b].transpose(0, 1)[None].repeat_interleave(hq // hkv, dim=1)
         os_ = torch.nn.functional.scaled_dot_product_attention(qs, ks, vs, is_causal=True)
         o[a:b] = os_[0].transpose(0, 1)
-    h = x + o.reshape(-1, hq * hd) @ W["w_o"].T
+    h = x + aq(o.reshape(-1, hq * hd)) @ W["w_o"].T
     y2 = norm(h, W["g_ffn"])
+    if cfg.get("n_experts", 0) == 0:
+        y2 = aq(y2)
 
     def ffn(z, wg, wu, wd):
-        return (torch.nn.functional.silu(z @ wg.T) * (z @ wu.T)) @ wd.T
+        return aq(torch.nn.functional.silu(z @ wg.T) * (z @ wu.T)) @ wd.T
 
     if cfg.get("n_experts", 0) == 0:
         out = h + ffn(y2, W["w_gate"], W["w_up"], W["w_down"])
@@ -527,3 +539,67 @@ def test_layer_with_quantised_weights_is_the_layer_on_the_replaced_weights():
     # the quantised layer is close to, and different from, the exact one (3 mantissa bits per weight)
     err = np.max(np.abs(a - b)) / np.max(np.abs(b))
     assert 1e-4 < err < 0.1
+
+
+def test_activation_row_quantisation_against_library_conversions():
+    """act_quantise_rows = round to bf16, then the weight-row rule: against torch's bfloat16 and
+    float8_e4m3fn conversions (values, scales and code bytes), with planted boundary cases."""
+    rng = np.random.default_rng(31)
+    x = (rng.standard_normal((23, 136)) * np.exp(rng.uniform(-6, 4, (23, 1)))).astype(np.float32)
+    x[3] = 0.0                                     # zero row: scale 1
+    x[4, :] = 0.0
+    x[4, 9] = 448.0 * 4.0                          # maximum exactly 448 * 2^2
+    x[5, 2] = np.float32(448.0 * 4.0) * np.float32(1 + 2.0 ** -7)   # one bf16 step above: next scale
+    x[6, 5] = 1.0 + 2.0 ** -9                      # rounds to 1.0 in bf16 before anything else
+    xq, s, codes = O.act_quantise_rows(x)
+    xb = torch.from_numpy(x).to(torch.bfloat16).float().numpy()
+    assert s[3] == 1.0 and s[4] == 4.0 and s[5] == 8.0
+    m = np.max(np.abs(xb), axis=1)
+    live = m > 0
+    assert np.all(np.log2(s[live]) == np.round(np.log2(s[live])))
+    assert np.all(m[live] / s[live] <= 448.0) and np.all(m[live] / (s[live] / 2) > 448.0)
+    t8 = torch.from_numpy(xb / s[:, None]).to(torch.float8_e4m3fn)
+    assert np.array_equal(xq, t8.float().numpy() * s[:, None])
+    assert np.array_equal(codes, t8.view(torch.uint8).numpy())
+    # the bf16 rounding comes first: quantising the rounded rows as weights gives the same thing
+    assert np.array_equal(xq, O.quantise_rows(xb)[0])
+    assert xq[6, 5] == O.quantise_rows(np.where(np.arange(136) == 5, 1.0, xb[6]).astype(np.float32)[None])[0][0, 5]
+
+
+def test_act8_layer_matches_library_composition_above_the_row_threshold():
+    """8-bit activations: the four projections of a call with more than ACT8_ROWS rows see quantised
+    input rows; against the float64 library composition with the library's conversions in the same
+    four places."""
+    cfg = I.small_config(d_model=64, n_q_heads=4, n_kv_heads=2, head_dim=16, d_ff=96)
+    w = O.quantise_layer_weights(I.layer_weights(cfg, std=0.08))
+    T = O.ACT8_ROWS + 4
+    cu = np.array([0, 100, 101, T], np.int32)
+    x = I.hidden(T, cfg["d_model"], seed=6)
+    got = O.prefill(O.Layer(cfg, w, act8=True), x, cu)
+    ref = torch_layer(cfg, w, x, cu, act_q=torch_act_q)
+    assert relmax(got, ref) < 2e-6
+    plain = O.prefill(O.Layer(cfg, w), x, cu)
+    assert 1e-4 < relmax(got, plain) < 0.2       # and it is not the layer without them
+
+
+def test_act8_layer_is_unchanged_up_to_the_row_threshold():
+    cfg = I.small_config()
+    w = I.layer_weights(cfg, std=0.08)
+    la, lp = O.Layer(cfg, w, act8=True), O.Layer(cfg, w)
+    T = O.ACT8_ROWS
+    cu = np.array([0, 200, T], np.int32)
+    x = I.hidden(T + 1, cfg["d_model"], seed=7)
+    assert np.array_equal(O.prefill(la, x[:T], cu), O.prefill(lp, x[:T], cu))
+    cu1 = np.array([0, 200, T + 1], np.int32)
+    assert not np.array_equal(O.prefill(la, x, cu1), O.prefill(lp, x, cu1))
+    # decode and chunked prefill follow the same rule on their own row counts
+    ca, cp = O.KVCache(la, 2, 16), O.KVCache(lp, 2, 16)
+    xs = I.hidden(2, cfg["d_model"], seed=8)
+    assert np.array_equal(O.decode_step(la, xs, [0, 1], ca), O.decode_step(lp, xs, [0, 1], cp))
+    B = T + 1
+    ca, cp = O.KVCache(la, B, 4), O.KVCache(lp, B, 4)
+    xs = I.hidden(B, cfg["d_model"], seed=9)
+    assert not np.array_equal(O.decode_step(la, xs, list(range(B)), ca), O.decode_step(lp, xs, list(range(B)), cp))
+    ca, cp = O.KVCache(la, 1, T + 8), O.KVCache(lp, 1, T + 8)
+    cuc = np.array([0, T + 1], np.int32)
+    assert not np.array_equal(O.prefill_chunk(la, x, cuc, [0], ca), O.prefill_chunk(lp, x, cuc, [0], cp))
