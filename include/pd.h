@@ -96,15 +96,49 @@ pd_status pd_layer_create(const pd_layer_config *cfg, const pd_layer_weights *w,
  * not the norm gains, not the router) is held as OCP E4M3 codes with one scale per output row,
  * the smallest power of two s with max|w_row| / s <= 448 (1 for a row of zeros); the layer then
  * computes with w' = s * value(code) everywhere (activations stay bf16).  Decode is bound by
- * reading the weights (Section 2.1), so calls of up to 16 rows stream the codes (half the bytes)
- * through the skinny kernel and widen them in registers; larger calls use a bf16 copy of w' and
- * give the same results as a layer created from w' with pd_layer_create.  All other calls take
- * such a layer unchanged.
+ * reading the weights (Section 2.1), so dense calls of up to 128 rows stream the codes (half the
+ * bytes) and widen them in registers; larger calls use a bf16 copy of w' and give the same results
+ * as a layer created from w' with pd_layer_create.  All other calls take such a layer unchanged.
  * Errors: as pd_layer_create, plus PD_ERR_DTYPE if the layer is not bf16 with d_model, d_ff and the
  * head dimensions multiples of 64.
  */
 pd_status pd_layer_create_w8(const pd_layer_config *cfg, const pd_layer_weights *w, pd_layer **out);
+
+/*
+ * 8-bit weights as above and, where the layer is bound by the matrix cores (Section 2.1: prefill),
+ * 8-bit activations too: in every call of more than 256 rows (T of a prefill call, B of a decode
+ * call) each of the four projections first quantises its bf16 input rows (the normalised hidden
+ * state, the attention output, the SwiGLU output) like pd_quantize_rows_e4m3 and multiplies codes
+ * by codes in E4M3 on the matrix cores with fp32 accumulation; the sums are multiplied by the two
+ * scales.  Calls of up to 256 rows behave as in a pd_layer_create_w8 layer.
+ * Errors: as pd_layer_create_w8, plus PD_ERR_DTYPE for a mixture-of-experts layer or when d_model,
+ * d_ff or n_q_heads * head_dim is not a multiple of 128.
+ */
+pd_status pd_layer_create_w8a8(const pd_layer_config *cfg, const pd_layer_weights *w, pd_layer **out);
 void pd_layer_destroy(pd_layer *layer);
+
+/*
+ * Row-wise 8-bit quantisation as used for activations by a pd_layer_create_w8a8 layer:
+ * x [n_rows, n_cols] bf16 (device, row-major, n_cols a multiple of 8) -> codes [n_rows, n_cols]
+ * bytes (device) and scales [n_rows] fp32 (device); scale = the smallest power of two s with
+ * max|x_row| / s <= 448 (1 for a row of zeros or one holding an infinity), code = OCP E4M3 of
+ * x / s, rounded to nearest even, saturating at +-448.  Asynchronous on stream.
+ * Errors: PD_ERR_INVALID_ARG (NULL pointer, negative n_rows, n_cols not a positive multiple of 8).
+ */
+pd_status pd_quantize_rows_e4m3(const void *x, int32_t n_rows, int32_t n_cols, void *codes,
+                                float *scales, void *stream);
+
+/*
+ * The product a pd_layer_create_w8a8 layer computes in its projections, on its own:
+ *   c[m, n] = a_scales[m] * b_scales[n] * sum_k value(a_codes[m, k]) * value(b_codes[n, k])
+ * a_codes [M, K] and b_codes [N, K] are row-major OCP E4M3 bytes (device), the scales fp32 (device),
+ * c [M, N] bf16 (device); products and sums in fp32 on the matrix cores, one rounding to bf16.
+ * Allocates temporary device memory and returns after the work on stream has finished.
+ * Errors: PD_ERR_INVALID_ARG (NULL pointer), PD_ERR_SHAPE (M < 1, N not a multiple of 16, K not a
+ * multiple of 128, an operand of 4 GiB or more), PD_ERR_DEVICE.
+ */
+pd_status pd_gemm_e4m3(const void *a_codes, const float *a_scales, const void *b_codes,
+                       const float *b_scales, int32_t M, int32_t N, int32_t K, void *c, void *stream);
 
 /* Pre-sizes the layer's workspace for calls of up to max_tokens rows (prefill T or decode B). */
 pd_status pd_layer_reserve(pd_layer *layer, int32_t max_tokens);

@@ -227,10 +227,18 @@ def act_quantise_rows(x):
     K = x.shape[-1]
     n_rows = x.size // K
     scales = np.empty(n_rows, np.float32)
-    lib().orc_act_quantise_rows(_p(x), C.c_int(n_rows), C.c_int(K), _p(scales))
-    sc = scales.reshape(x.shape[:-1])
-    codes = fp8_e4m3_encode(x / sc[..., None])
-    return x, sc, codes
+    codes = np.empty(x.shape, np.uint8)
+    lib().orc_act_quantise_rows(_p(x), C.c_int(n_rows), C.c_int(K), _p(scales), codes.ctypes.data_as(C.c_void_p))
+    return x, scales.reshape(x.shape[:-1]), codes
+
+
+def gemm_e4m3(a_codes, a_scales, b_codes, b_scales):
+    """c[m, n] = a_scales[m] b_scales[n] sum_k value(a_codes[m, k]) value(b_codes[n, k]) in float64:
+    the product of two row-quantised matrices, written out."""
+    table = fp8_e4m3_decode(np.arange(256, dtype=np.uint8))
+    A = table[np.asarray(a_codes, np.uint8)] * np.asarray(a_scales, np.float64)[:, None]
+    B = table[np.asarray(b_codes, np.uint8)] * np.asarray(b_scales, np.float64)[:, None]
+    return A @ B.T
 
 
 def quantise_layer_weights(weights):

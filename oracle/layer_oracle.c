@@ -122,19 +122,25 @@ void orc_cache_quantise(float *x, size_t n, double scale)
  * scale s, the smallest power of two with max|w_row| / s <= 448 (1 for a row of zeros).  The layer
  * then runs unchanged on the replaced weights.
  */
+static double row_scale(const float *w, int K)
+{
+    double m = 0.0;
+    for (int k = 0; k < K; ++k)
+        if (fabs((double)w[k]) > m) m = fabs((double)w[k]);
+    double s = 1.0;
+    if (m > 0.0 && isfinite(m)) {
+        int e;
+        double f = frexp(m / 448.0, &e);          /* m / 448 = f * 2^e, f in [0.5, 1) */
+        s = ldexp(1.0, f == 0.5 ? e - 1 : e);     /* smallest power of two >= m / 448 */
+    }
+    return s;
+}
+
 void orc_quantise_rows(float *W, int n_rows, int K, float *scales)
 {
     for (int n = 0; n < n_rows; ++n) {
         float *w = W + (size_t)n * K;
-        double m = 0.0;
-        for (int k = 0; k < K; ++k)
-            if (fabs((double)w[k]) > m) m = fabs((double)w[k]);
-        double s = 1.0;
-        if (m > 0.0 && isfinite(m)) {
-            int e;
-            double f = frexp(m / 448.0, &e);          /* m / 448 = f * 2^e, f in [0.5, 1) */
-            s = ldexp(1.0, f == 0.5 ? e - 1 : e);     /* smallest power of two >= m / 448 */
-        }
+        double s = row_scale(w, K);
         for (int k = 0; k < K; ++k) w[k] = cache_value(w[k], 1, s);
         if (scales) scales[n] = (float)s;
     }
@@ -158,13 +164,23 @@ static float round_bf16(float x)
     return x;
 }
 
-void orc_act_quantise_rows(float *v, int n_rows, int n, float *scales)
+/* rows of v replaced in place; scales [n_rows] and codes [n_rows, n] (the E4M3 bytes) are optional outputs */
+void orc_act_quantise_rows(float *v, int n_rows, int n, float *scales, uint8_t *codes)
 {
-    for (size_t i = 0; i < (size_t)n_rows * (size_t)n; ++i) v[i] = round_bf16(v[i]);
-    orc_quantise_rows(v, n_rows, n, scales);
+    for (int r = 0; r < n_rows; ++r) {
+        float *row = v + (size_t)r * n;
+        for (int i = 0; i < n; ++i) row[i] = round_bf16(row[i]);
+        double s = row_scale(row, n);
+        for (int i = 0; i < n; ++i) {
+            uint8_t c = orc_fp8_e4m3_encode((double)row[i] / s);
+            if (codes) codes[(size_t)r * n + i] = c;
+            row[i] = (float)(s * orc_fp8_e4m3_decode(c));
+        }
+        if (scales) scales[r] = (float)s;
+    }
 }
 
-static void act_quantise_row(float *v, int n) { orc_act_quantise_rows(v, 1, n, NULL); }
+static void act_quantise_row(float *v, int n) { orc_act_quantise_rows(v, 1, n, NULL, NULL); }
 
 void orc_rmsnorm_row(const float *x, const float *g, int d, double eps, float *y)
 {

@@ -21,7 +21,7 @@ PD_ERR_KV_CAPACITY, PD_ERR_TTFT_INFEASIBLE, PD_ERR_TPOT_INFEASIBLE = 6, 7, 8
 PD_F32, PD_BF16 = 0, 1
 
 EXPORTS = [
-    "pd_layer_create", "pd_layer_create_w8", "pd_layer_destroy", "pd_layer_reserve", "pd_kv_cache_create", "pd_kv_cache_create_fp8",
+    "pd_layer_create", "pd_layer_create_w8", "pd_layer_create_w8a8", "pd_quantize_rows_e4m3", "pd_gemm_e4m3", "pd_layer_destroy", "pd_layer_reserve", "pd_kv_cache_create", "pd_kv_cache_create_fp8",
     "pd_kv_cache_destroy", "pd_kv_cache_set", "pd_kv_cache_set_len", "pd_kv_cache_len",
     "pd_kv_cache_set_lens", "pd_kv_cache_get", "pd_profile_enable", "pd_profile_read", "pd_stream_copy", "pd_head_create", "pd_head_destroy", "pd_embed", "pd_lm_head", "pd_prefill", "pd_prefill_chunk", "pd_decode_step", "pd_last_expert_choice", "pd_allocate",
     "pd_fifo_replay", "pd_mm1_sojourn", "pd_fifo_replay_batched", "pd_prefill_throughput_dp", "pd_mg1_sojourn", "pd_kv_transfer_overhead", "pd_allocate_stages", "pd_status_string", "pd_last_error",
@@ -120,22 +120,38 @@ def make_config(cfg: dict) -> pd_layer_config:
 
 # ---- device entry points ---------------------------------------------------------------------------
 
-def pd_layer_create(cfg: dict, weights: dict, w8=False):
+def pd_layer_create(cfg: dict, weights: dict, w8=False, a8=False):
     """weights: name -> contiguous device torch tensor in the layer's dtype; w8: hold the projection
-    matrices as 8-bit codes with per-row power-of-two scales (pd_layer_create_w8)."""
+    matrices as 8-bit codes with per-row power-of-two scales (pd_layer_create_w8); a8: also quantise
+    the activations of calls with more than 256 rows (pd_layer_create_w8a8)."""
     w = pd_layer_weights()
     for n in _WNAMES:
         t = weights.get(n)
         setattr(w, n, None if t is None else t.data_ptr())
     h = C.c_void_p()
     c = make_config(cfg)
-    create = lib.pd_layer_create_w8 if w8 else lib.pd_layer_create
+    create = lib.pd_layer_create_w8a8 if a8 else lib.pd_layer_create_w8 if w8 else lib.pd_layer_create
     _check(create(C.byref(c), C.byref(w), C.byref(h)))
     return h
 
 
 def pd_layer_destroy(layer):
     lib.pd_layer_destroy(layer)
+
+
+def pd_quantize_rows_e4m3(x, codes, scales):
+    """x [n_rows, n_cols] bf16 -> codes [n_rows, n_cols] uint8, scales [n_rows] fp32 (device tensors)."""
+    _check(lib.pd_quantize_rows_e4m3(_ptr(x), C.c_int32(x.shape[0]), C.c_int32(x.shape[1]), _ptr(codes),
+                                     C.cast(scales.data_ptr(), C.POINTER(C.c_float)), _stream()))
+
+
+def pd_gemm_e4m3(a_codes, a_scales, b_codes, b_scales, out):
+    """out [M, N] bf16 = (a_scales * value(a_codes [M, K])) (b_scales * value(b_codes [N, K]))^T (device tensors)."""
+    M, K = a_codes.shape
+    N = b_codes.shape[0]
+    fp = C.POINTER(C.c_float)
+    _check(lib.pd_gemm_e4m3(_ptr(a_codes), C.cast(a_scales.data_ptr(), fp), _ptr(b_codes), C.cast(b_scales.data_ptr(), fp),
+                            C.c_int32(M), C.c_int32(N), C.c_int32(K), _ptr(out), _stream()))
 
 
 def pd_layer_reserve(layer, max_tokens):

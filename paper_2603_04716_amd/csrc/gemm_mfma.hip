@@ -31,6 +31,14 @@ namespace pd {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ i32x8 cat32(bf16x8 lo, bf16x8 hi)
+{
+    const i32x4 l = __builtin_bit_cast(i32x4, lo), h = __builtin_bit_cast(i32x4, hi);
+    return i32x8{l[0], l[1], l[2], l[3], h[0], h[1], h[2], h[3]};
+}
 
 constexpr int BK = 64;  // k per tile: 8 chunks of 16 bytes per row
 
@@ -38,7 +46,13 @@ __device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >>
 
 __device__ __forceinline__ float silu_fast(float z) { return z / (1.0f + __expf(-z)); }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int NS>
+// F8: both operands are E4M3 codes and the caller passes them as if two codes were one bf16 element
+// (K, lda, ldb halved; the weight pack is the bf16 pack of that view), so every byte moves exactly as
+// above.  Two consecutive 16-byte fragments of a lane form the 32-byte operand of
+// v_mfma_f32_32x32x64_f8f6f4: which of the 64 k of the step a byte stands for does not matter as long
+// as both operands are assembled the same way, and they are.  The fp32 sums are multiplied by the
+// scale of their activation row and of their weight row before any epilogue.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, int NS, bool F8 = false>
 __global__ __launch_bounds__(64 * WAVES_M *WAVES_N) void gemm_mfma_kernel(GemmArgs a, int tiles_m,
                                                                           int tiles_n, int kt_per_split)
 {
@@ -204,6 +218,25 @@ __global__ __launch_bounds__(64 * WAVES_M *WAVES_N) void gemm_mfma_kernel(GemmAr
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
     };
     auto compute = [&](const unsigned char *st) {
+        if (F8) {
+#pragma unroll
+            for (int kk = 0; kk < BK / 16; kk += 2) {
+                bf16x8 fa[2][MB], fb[2][NB];
+                load_frags(st, kk, fa[0], fb[0]);
+                load_frags(st, kk + 1, fa[1], fb[1]);
+                i32x8 pb[NB];
+#pragma unroll
+                for (int j = 0; j < NB; ++j) pb[j] = cat32(fb[0][j], fb[1][j]);
+#pragma unroll
+                for (int i = 0; i < MB; ++i) {
+                    const i32x8 pa = cat32(fa[0][i], fa[1][i]);
+#pragma unroll
+                    for (int j = 0; j < NB; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(pa, pb[j], acc[i][j], 0, 0, 0, 0, 0, 0);
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
             bf16x8 fa[MB], fb[NB];
@@ -236,6 +269,20 @@ __global__ __launch_bounds__(64 * WAVES_M *WAVES_N) void gemm_mfma_kernel(GemmAr
 
     // ---- epilogue: lane holds column (lane % 32) of each block; register r is row
     //      8*(r/4) + 4*(lane/32) + r%4 ----------------------------------------------------------------
+    if (F8) {
+        float sb[NB];
+#pragma unroll
+        for (int j = 0; j < NB; ++j) sb[j] = a.b_scale[min(col0 + wn * WN + j * 32 + frow, n_cols - 1)];
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = row0 + wm * WM + i * 32 + 8 * (r >> 2) + 4 * fhalf + (r & 3);
+                const float sa = a.a_scale[min(m, row_end - 1)];
+#pragma unroll
+                for (int j = 0; j < NB; ++j) acc[i][j][r] *= sa * sb[j];
+            }
+    }
     if (EPI == EPI_PARTIAL) {
         float *P = a.splitk_ws + (size_t)blockIdx.y * a.M * n_cols;
 #pragma unroll
@@ -391,7 +438,7 @@ bool gemm_mfma_supported(const GemmArgs &a)
     return true;
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int NS = 2>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int NS = 2, bool F8 = false>
 static hipError_t launch_cfg(const GemmArgs &a, hipStream_t s, int splits = 1)
 {
     const int n_cols = a.epilogue == EPI_SWIGLU ? 2 * a.N : a.N;
@@ -405,7 +452,7 @@ static hipError_t launch_cfg(const GemmArgs &a, hipStream_t s, int splits = 1)
     const dim3 block(64 * WAVES_M * WAVES_N);
 #define LAUNCH(EPI)                                                                              \
     do {                                                                                         \
-        auto kern = gemm_mfma_kernel<BM, BN, WAVES_M, WAVES_N, EPI, NS>;                             \
+        auto kern = gemm_mfma_kernel<BM, BN, WAVES_M, WAVES_N, EPI, NS, F8>;                         \
         static bool attr_set = false;                                                            \
         if (!attr_set) {                                                                         \
             hipError_t e = hipFuncSetAttribute((const void *)kern,                               \
@@ -470,6 +517,18 @@ static int choose_splits_mid(const GemmArgs &a)
     if (splits > nk / 8) splits = nk / 8;
     while (splits > 1 && (size_t)splits * a.M * n_cols > a.splitk_ws_elems) --splits;
     return splits < 1 ? 1 : splits;
+}
+
+// 8-bit operands (see the kernel): a.A are E4M3 codes [M, 2 K] with a.a_scale per row, a.B the codes in
+// the pack of the halved view with a.b_scale per packed row; a.K, a.lda, a.ldb count code pairs.
+bool gemm_mfma_f8_supported(const GemmArgs &a)
+{
+    return gemm_mfma_supported(a) && a.a_scale && a.b_scale && !a.group_offsets && !a.a_gather;
+}
+
+hipError_t launch_gemm_mfma_f8(const GemmArgs &a, hipStream_t s)
+{
+    return launch_cfg<256, 256, 2, 4, 2, true>(a, s, choose_splits_mid(a));
 }
 
 hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t s)

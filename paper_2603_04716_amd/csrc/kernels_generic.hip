@@ -620,6 +620,114 @@ hipError_t launch_embed_rows(void *out, const void *table, const int32_t *ids, i
     return hipGetLastError();
 }
 
+// ---- 8-bit activations: per-row power-of-two scale and E4M3 codes -----------------------------------
+// One workgroup per row of x [T, K] (bf16).  The scale is the smallest power of two s with
+// max|x_row| / s <= 448 (1 for a row of zeros or with an infinity); x / s is exact, the hardware
+// conversion rounds to nearest even and is given only values inside +-448, so the codes are those of
+// a saturating round-to-nearest-even encoder.
+__global__ __launch_bounds__(256) void quant_rows_e4m3_kernel(const uint16_t *__restrict__ x, int ldx, int K,
+                                                              uint8_t *__restrict__ codes, float *__restrict__ scales)
+{
+    __shared__ float red[4];
+    __shared__ float inv_s;
+    const int row = blockIdx.x, tid = threadIdx.x;
+    const uint4 *p = (const uint4 *)(x + (size_t)row * ldx);
+    const int n8 = K >> 3;
+    float m = 0.f;
+    for (int i = tid; i < n8; i += 256) {
+        const uint4 v = p[i];
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            m = fmaxf(m, fabsf(bfbits2f(w[j] & 0xffffu)));
+            m = fmaxf(m, fabsf(bfbits2f(w[j] >> 16)));
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+    if ((tid & 63) == 0) red[tid >> 6] = m;
+    __syncthreads();
+    if (tid == 0) {
+        m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        float s = 1.f;
+        if (m > 0.f && m < INFINITY) {
+            int e;
+            const double f = frexp((double)m / 448.0, &e);    // m / 448 = f * 2^e, f in [0.5, 1)
+            s = (float)ldexp(1.0, f == 0.5 ? e - 1 : e);
+        }
+        scales[row] = s;
+        inv_s = 1.0f / s;
+    }
+    __syncthreads();
+    const float inv = inv_s;
+    uint2 *q = (uint2 *)(codes + (size_t)row * K);
+    for (int i = tid; i < n8; i += 256) {
+        const uint4 v = p[i];
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        float f[8];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            f[2 * j] = bfbits2f(w[j] & 0xffffu) * inv;
+            f[2 * j + 1] = bfbits2f(w[j] >> 16) * inv;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (f[j] == f[j]) f[j] = fminf(fmaxf(f[j], -448.f), 448.f);
+        int lo = __builtin_amdgcn_cvt_pk_fp8_f32(f[0], f[1], 0, false);
+        lo = __builtin_amdgcn_cvt_pk_fp8_f32(f[2], f[3], lo, true);
+        int hi = __builtin_amdgcn_cvt_pk_fp8_f32(f[4], f[5], 0, false);
+        hi = __builtin_amdgcn_cvt_pk_fp8_f32(f[6], f[7], hi, true);
+        q[i] = make_uint2((uint32_t)lo, (uint32_t)hi);
+    }
+}
+
+hipError_t launch_quant_rows_e4m3(const void *x, int ldx, int T, int K, void *codes, float *scales, hipStream_t s)
+{
+    if (T <= 0) return hipSuccess;
+    if (K % 8 != 0 || ldx % 8 != 0) return hipErrorInvalidValue;
+    quant_rows_e4m3_kernel<<<T, 256, 0, s>>>((const uint16_t *)x, ldx, K, (uint8_t *)codes, scales);
+    return hipGetLastError();
+}
+
+// 8-bit weight codes from the skinny kernels' layout into the tiled kernel's: the matrix seen as
+// [n_rows, K / 2] two-byte elements in the block pack of wpack_off; 16 codes per thread step.
+__global__ __launch_bounds__(256) void repack_w8_tiles_kernel(const uint8_t *__restrict__ src, uint8_t *__restrict__ dst,
+                                                              int n_rows, int K)
+{
+    const size_t n_items = (size_t)n_rows * (K >> 4);
+    for (size_t it = (size_t)blockIdx.x * 256 + threadIdx.x; it < n_items; it += (size_t)gridDim.x * 256) {
+        const int n = (int)(it / (K >> 4)), k = (int)(it % (K >> 4)) << 4;
+        const uint2 a = *(const uint2 *)(src + w8pack_off(n, k, K));
+        const uint2 b = *(const uint2 *)(src + w8pack_off(n, k + 8, K));
+        *(uint4 *)(dst + 2 * wpack_off(n, k >> 1, K >> 1)) = make_uint4(a.x, a.y, b.x, b.y);
+    }
+}
+
+// the same from plain row-major codes [n_rows, K]
+__global__ __launch_bounds__(256) void pack_rows_e4m3_tiles_kernel(const uint8_t *__restrict__ src, uint8_t *__restrict__ dst,
+                                                                   int n_rows, int K)
+{
+    const size_t n_items = (size_t)n_rows * (K >> 4);
+    for (size_t it = (size_t)blockIdx.x * 256 + threadIdx.x; it < n_items; it += (size_t)gridDim.x * 256) {
+        const int n = (int)(it / (K >> 4)), k = (int)(it % (K >> 4)) << 4;
+        *(uint4 *)(dst + 2 * wpack_off(n, k >> 1, K >> 1)) = *(const uint4 *)(src + (size_t)n * K + k);
+    }
+}
+
+hipError_t launch_pack_rows_e4m3_tiles(const void *src, void *dst, int n_rows, int K, hipStream_t s)
+{
+    if (K % 64 != 0 || n_rows % 16 != 0) return hipErrorInvalidValue;
+    pack_rows_e4m3_tiles_kernel<<<2048, 256, 0, s>>>((const uint8_t *)src, (uint8_t *)dst, n_rows, K);
+    return hipGetLastError();
+}
+
+hipError_t launch_repack_w8_tiles(const void *src8, void *dst, int n_rows, int K, hipStream_t s)
+{
+    if (K % 64 != 0 || n_rows % 16 != 0) return hipErrorInvalidValue;
+    repack_w8_tiles_kernel<<<2048, 256, 0, s>>>((const uint8_t *)src8, (uint8_t *)dst, n_rows, K);
+    return hipGetLastError();
+}
+
 // ---- plain copy (traffic-counter calibration) -----------------------------------------------------
 __global__ __launch_bounds__(256) void stream_copy_kernel(uint4 *__restrict__ dst, const uint4 *__restrict__ src,
                                                           size_t n)

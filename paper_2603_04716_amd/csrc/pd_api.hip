@@ -25,6 +25,12 @@ struct pd_layer {
     bool w8;
     void *q_qkv, *q_o, *q_gate, *q_down;
     float *s_qkv, *s_o, *s_gate, *s_down;
+    // 8-bit activations on top of 8-bit weights: projections called with more than 256 rows quantise
+    // their input rows and multiply codes by codes; t_* are the weight codes in the tiled kernel's pack
+    bool a8;
+    void *t_qkv, *t_o, *t_gate, *t_down;
+    uint8_t *a8_codes;        // [ws_tokens][max K] activation codes (inside ws)
+    float *a8_scales;         // [ws_tokens]
     double *inv_freq;
     float2 *rope_table;       // (cos, sin) for positions < kRopeTableLen
     int32_t *d_cu, *d_slots, *d_pad_cu, *d_prefix;  // [4097] each
@@ -59,6 +65,8 @@ struct pd_kv_cache {
 };
 
 static const int kMaxSeqs = 4096;
+// a layer with 8-bit activations quantises the input of a projection when the call has more rows than this
+static const int kA8Rows = 256;
 // Work split of the decode attention: a sequence of n keys is cut into ceil(n / chunk_keys) equal
 // chunks, one wavefront-sized worker per (chunk, kv head).  Two measured effects set chunk_keys
 // (8B shape, 2048 .. 16384 keys, batch 4 .. 256, both cache formats):
@@ -250,6 +258,7 @@ static void free_layer(pd_layer *L)
 {
     if (!L) return;
     void *ptrs[] = {L->q_qkv, L->q_o, L->q_gate, L->q_down, L->s_qkv, L->s_o, L->s_gate, L->s_down,
+                    L->t_qkv, L->t_o, L->t_gate, L->t_down,
                     L->g_attn, L->g_ffn, L->w_qkv, L->w_o, L->w_gate, L->w_up, L->w_down,
                     L->w_router, L->inv_freq, L->rope_table, L->d_cu, L->d_slots, L->d_pad_cu, L->d_prefix, L->vt, L->ws};
     for (void *p : ptrs)
@@ -258,21 +267,29 @@ static void free_layer(pd_layer *L)
     delete L;
 }
 
-static pd_status layer_create(const pd_layer_config *cfg, const pd_layer_weights *w, bool w8, pd_layer **out);
+static pd_status layer_create(const pd_layer_config *cfg, const pd_layer_weights *w, bool w8, bool a8,
+                              pd_layer **out);
 
 extern "C" pd_status pd_layer_create(const pd_layer_config *cfg, const pd_layer_weights *w,
                                      pd_layer **out)
 {
-    return layer_create(cfg, w, false, out);
+    return layer_create(cfg, w, false, false, out);
 }
 
 extern "C" pd_status pd_layer_create_w8(const pd_layer_config *cfg, const pd_layer_weights *w,
                                         pd_layer **out)
 {
-    return layer_create(cfg, w, true, out);
+    return layer_create(cfg, w, true, false, out);
 }
 
-static pd_status layer_create(const pd_layer_config *cfg, const pd_layer_weights *w, bool w8, pd_layer **out)
+extern "C" pd_status pd_layer_create_w8a8(const pd_layer_config *cfg, const pd_layer_weights *w,
+                                          pd_layer **out)
+{
+    return layer_create(cfg, w, true, true, out);
+}
+
+static pd_status layer_create(const pd_layer_config *cfg, const pd_layer_weights *w, bool w8, bool a8,
+                              pd_layer **out)
 {
     if (!cfg || !w || !out) {
         set_error("pd_layer_create: NULL argument");
@@ -306,8 +323,14 @@ static pd_status layer_create(const pd_layer_config *cfg, const pd_layer_weights
                   L->Nkv % 64 == 0;
     L->packed = L->use_mfma;
     L->w8 = w8;
+    L->a8 = a8;
     if (w8 && !L->use_mfma) {
         set_error("pd_layer_create_w8: needs a bf16 layer whose dimensions are multiples of 64");
+        delete L;
+        return PD_ERR_DTYPE;
+    }
+    if (a8 && (d % 128 != 0 || F % 128 != 0 || L->Nq % 128 != 0 || E > 0)) {
+        set_error("pd_layer_create_w8a8: needs a dense layer whose dimensions are multiples of 128");
         delete L;
         return PD_ERR_DTYPE;
     }
@@ -390,6 +413,16 @@ static pd_status layer_create(const pd_layer_config *cfg, const pd_layer_weights
                             w8 ? (char *)L->q_down + (size_t)g * d * F : nullptr,
                             w8 ? L->s_down + (size_t)g * d : nullptr));
         }
+        if (a8) {
+            CREATE_TRY(hipMalloc(&L->t_qkv, (size_t)L->Nqkv * d));
+            CREATE_TRY(hipMalloc(&L->t_o, (size_t)d * L->Nq));
+            CREATE_TRY(hipMalloc(&L->t_gate, (size_t)2 * F * d));
+            CREATE_TRY(hipMalloc(&L->t_down, (size_t)d * F));
+            CREATE_TRY(launch_repack_w8_tiles(L->q_qkv, L->t_qkv, L->Nqkv, d, nullptr));
+            CREATE_TRY(launch_repack_w8_tiles(L->q_o, L->t_o, d, L->Nq, nullptr));
+            CREATE_TRY(launch_repack_w8_tiles(L->q_gate, L->t_gate, 2 * F, d, nullptr));
+            CREATE_TRY(launch_repack_w8_tiles(L->q_down, L->t_down, d, F, nullptr));
+        }
     } else {
         CREATE_TRY(hipMemcpy(L->w_qkv, w->w_q, (size_t)L->Nq * d * esz, hipMemcpyDeviceToDevice));
         CREATE_TRY(hipMemcpy((char *)L->w_qkv + (size_t)L->Nq * d * esz, w->w_k,
@@ -436,6 +469,52 @@ static size_t decode_chunk_bound(const pd_layer *L, int batch)
     return (size_t)(8192 / L->cfg.n_kv_heads + 1) + (size_t)batch;
 }
 
+extern "C" pd_status pd_quantize_rows_e4m3(const void *x, int32_t n_rows, int32_t n_cols, void *codes,
+                                           float *scales, void *stream)
+{
+    if (!x || !codes || !scales || n_rows < 0 || n_cols <= 0 || n_cols % 8 != 0) {
+        set_error("pd_quantize_rows_e4m3: NULL argument, negative row count or a column count that is not a multiple of 8");
+        return PD_ERR_INVALID_ARG;
+    }
+    HIP_TRY(launch_quant_rows_e4m3(x, n_cols, n_rows, n_cols, codes, scales, (hipStream_t)stream), PD_ERR_DEVICE);
+    return PD_OK;
+}
+
+extern "C" pd_status pd_gemm_e4m3(const void *a_codes, const float *a_scales, const void *b_codes,
+                                  const float *b_scales, int32_t M, int32_t N, int32_t K, void *c, void *stream)
+{
+    if (!a_codes || !a_scales || !b_codes || !b_scales || !c) {
+        set_error("pd_gemm_e4m3: NULL argument");
+        return PD_ERR_INVALID_ARG;
+    }
+    if (M < 1 || N < 16 || N % 16 != 0 || K < 128 || K % 128 != 0 || (int64_t)N * K >= (1ll << 32) ||
+        (int64_t)M * K >= (1ll << 32)) {
+        set_error("pd_gemm_e4m3: needs M >= 1, N a multiple of 16, K a multiple of 128 and operands below 4 GiB (M=%d N=%d K=%d)",
+                  M, N, K);
+        return PD_ERR_SHAPE;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    void *tiles = nullptr;
+    float *ws = nullptr;
+    const size_t ws_elems = (size_t)8 * 256 * N + (size_t)M * N;   // a few splits of mid-sized problems
+    HIP_TRY(hipMalloc(&tiles, (size_t)N * K), PD_ERR_DEVICE);
+    hipError_t e = hipMalloc((void **)&ws, ws_elems * sizeof(float));
+    if (e == hipSuccess) e = launch_pack_rows_e4m3_tiles(b_codes, tiles, N, K, s);
+    if (e == hipSuccess) {
+        GemmArgs g;
+        memset(&g, 0, sizeof(g));
+        g.A = a_codes; g.B = tiles; g.C = c; g.M = M; g.N = N; g.K = K / 2; g.lda = K / 2; g.ldb = K / 2; g.ldc = N;
+        g.epilogue = EPI_NONE; g.packed = 1; g.n_groups = 1; g.a_scale = a_scales; g.b_scale = b_scales;
+        g.splitk_ws = ws; g.splitk_ws_elems = ws_elems;
+        e = gemm_mfma_f8_supported(g) ? launch_gemm_mfma_f8(g, s) : hipErrorInvalidValue;
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    (void)hipFree(tiles);
+    (void)hipFree(ws);
+    HIP_TRY(e, PD_ERR_DEVICE);
+    return PD_OK;
+}
+
 extern "C" pd_status pd_layer_reserve(pd_layer *L, int32_t max_tokens)
 {
     if (!L || max_tokens < 0) {
@@ -465,6 +544,9 @@ extern "C" pd_status pd_layer_reserve(pd_layer *L, int32_t max_tokens)
     if ((size_t)d > maxn) maxn = (size_t)d;
     const size_t sk_elems = L->use_mfma ? (size_t)256 * (640 * 128 + 2 * maxn) : 0;
     size_t o_sk = carve(sk_elems * sizeof(float));
+    size_t maxk = (size_t)d > (size_t)L->Nq ? (size_t)d : (size_t)L->Nq;
+    if ((size_t)F > maxk) maxk = (size_t)F;
+    size_t o_a8c = carve(L->a8 ? T * maxk : 0), o_a8s = carve(L->a8 ? T * sizeof(float) : 0);
     HIP_TRY(hipDeviceSynchronize(), PD_ERR_DEVICE);
     char *nw = nullptr;
     hipError_t e = hipMalloc((void **)&nw, off);
@@ -495,6 +577,8 @@ extern "C" pd_status pd_layer_reserve(pd_layer *L, int32_t max_tokens)
     L->dec_part = (float *)(nw + o_part);
     L->splitk = sk_elems ? (float *)(nw + o_sk) : nullptr;
     L->splitk_elems = sk_elems;
+    L->a8_codes = L->a8 ? (uint8_t *)(nw + o_a8c) : nullptr;
+    L->a8_scales = L->a8 ? (float *)(nw + o_a8s) : nullptr;
     return PD_OK;
 }
 
@@ -653,10 +737,26 @@ static hipError_t run_gemm(const pd_layer *L, GemmArgs g, hipStream_t s)
         // packed weights are only understood by the matrix-core kernels
         if (L->w8) {
             // decode-sized products stream the 8-bit twin of the matrix; the tiled kernels take the bf16 pack
-            if (g.B == L->w_qkv) { g.B8 = L->q_qkv; g.b_scale = L->s_qkv; }
-            else if (g.B == L->w_o) { g.B8 = L->q_o; g.b_scale = L->s_o; }
-            else if (g.B == L->w_gate) { g.B8 = L->q_gate; g.b_scale = L->s_gate; }
-            else if (g.B == L->w_down) { g.B8 = L->q_down; g.b_scale = L->s_down; }
+            const void *tiles = nullptr;
+            if (g.B == L->w_qkv) { g.B8 = L->q_qkv; g.b_scale = L->s_qkv; tiles = L->t_qkv; }
+            else if (g.B == L->w_o) { g.B8 = L->q_o; g.b_scale = L->s_o; tiles = L->t_o; }
+            else if (g.B == L->w_gate) { g.B8 = L->q_gate; g.b_scale = L->s_gate; tiles = L->t_gate; }
+            else if (g.B == L->w_down) { g.B8 = L->q_down; g.b_scale = L->s_down; tiles = L->t_down; }
+            if (L->a8 && g.M > kA8Rows && tiles) {
+                // 8-bit activations: quantise the input rows, then codes x codes on the matrix cores
+                hipError_t e = launch_quant_rows_e4m3(g.A, g.lda, g.M, g.K, L->a8_codes, L->a8_scales, s);
+                if (e != hipSuccess) return e;
+                GemmArgs f = g;
+                f.A = L->a8_codes;
+                f.B = tiles;
+                f.B8 = nullptr;
+                f.a_scale = L->a8_scales;
+                f.K = g.K / 2;
+                f.lda = g.K / 2;
+                f.ldb = g.K / 2;
+                if (!gemm_mfma_f8_supported(f)) return hipErrorInvalidValue;
+                return launch_gemm_mfma_f8(f, s);
+            }
         }
         if (gemv_mfma_supported(g)) return launch_gemv_mfma(g, s);
         if (wgemm8_mfma_supported(g)) return launch_wgemm8_mfma(g, s);

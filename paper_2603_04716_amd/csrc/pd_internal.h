@@ -158,6 +158,8 @@ struct GemmArgs {
     // Groups are b_group_stride codes and (2N for SwiGLU, else N) scales apart.
     const void *B8;
     const float *b_scale;
+    // 8-bit activations (tiled kernel, F8 form): one scale per row of A; A and B then hold E4M3 codes
+    const float *a_scale;
 };
 
 // ---- launchers (each returns hipGetLastError() after the launch) ------------------------------
@@ -166,6 +168,14 @@ hipError_t launch_rmsnorm(int dtype, const void *x, const void *g, void *y, int 
 hipError_t launch_gemm_generic(int dtype, const GemmArgs &a, hipStream_t s);
 bool gemm_mfma_supported(const GemmArgs &a);
 hipError_t launch_gemm_mfma(const GemmArgs &a, hipStream_t s);   // bf16 only
+bool gemm_mfma_f8_supported(const GemmArgs &a);                   // E4M3 x E4M3, dense
+hipError_t launch_gemm_mfma_f8(const GemmArgs &a, hipStream_t s);
+// per row of x [T, K] (bf16, row stride ldx): scale = smallest power of two with max|x| / scale <= 448
+// (1 for a zero row), codes = E4M3(x / scale), round to nearest even, saturating; codes [T, K] bytes
+hipError_t launch_quant_rows_e4m3(const void *x, int ldx, int T, int K, void *codes, float *scales, hipStream_t s);
+// codes in the layout of w8pack_off -> the bf16 block pack of the same matrix seen as [n_rows, K / 2] code pairs
+hipError_t launch_repack_w8_tiles(const void *src8, void *dst, int n_rows, int K, hipStream_t s);
+hipError_t launch_pack_rows_e4m3_tiles(const void *src, void *dst, int n_rows, int K, hipStream_t s);   // from row-major codes
 // sums the fp32 partials [splits][M][N or 2N packed] in a.splitk_ws in a fixed order and applies a.epilogue
 hipError_t launch_splitk_reduce(const GemmArgs &a, int splits, hipStream_t s);
 bool wgemm8_mfma_supported(const GemmArgs &a);                    // 8-bit weights, 16 < M <= 128

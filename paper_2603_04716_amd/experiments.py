@@ -508,6 +508,46 @@ def run_w8():
     return out
 
 
+def run_a8():
+    """Prefill with 8-bit weights and 8-bit activations (codes x codes on the matrix cores for calls of
+    more than 256 rows) beside the bf16 layer: 8192 tokens at three input lengths, per-step timings at
+    4 x 2048, and the mid-sized calls of a chunked prefill."""
+    cfg = I.CONFIGS["llama8b"]
+    host_w = I.layer_weights(cfg)
+    T = 8192
+    x = H._dev(I.hidden(T, cfg["d_model"], seed=10, dtype="bf16"), "bf16")
+    out = {"experiment": "prefill with 8-bit weights and activations (E4M3 x E4M3, fp32 accumulation)", "cases": []}
+    for a8 in (False, True):
+        layer = H.Layer(cfg, host_w, a8=a8)
+        pts = []
+        for l_in in (1024, 2048, 4096):
+            cu = I.uniform_cu_seqlens(T // l_in, l_in)
+            ms = layer.time_prefill(x, cu, iters=10, warmup=3)
+            fl = H.prefill_flops(cfg, [l_in] * (T // l_in))
+            pts.append({"l_in": l_in, "ms_per_layer": round(ms, 4), "tok_s_model": round(T / (N_LAYERS * ms * 1e-3), 1),
+                        "tflops": round(fl / (ms * 1e-3) / 1e12, 1)})
+        mid = []
+        for rows in (512, 1024, 2048):
+            cu = I.uniform_cu_seqlens(1, rows)
+            ms = layer.time_prefill(x[:rows].contiguous(), cu, iters=10, warmup=3)
+            mid.append({"tokens": rows, "ms_per_layer": round(ms, 4), "tok_s_model": round(rows / (N_LAYERS * ms * 1e-3), 1)})
+        cu = I.uniform_cu_seqlens(4, 2048)
+        pd.pd_profile_enable(layer.h, True)
+        o = torch.empty_like(x)
+        acc = {}
+        for it in range(5):
+            pd.pd_prefill(layer.h, x, cu, o)
+            torch.cuda.synchronize()
+            if it >= 2:
+                for n, t in pd.pd_profile_read(layer.h):
+                    acc.setdefault(n, []).append(t)
+        pd.pd_profile_enable(layer.h, False)
+        out["cases"].append({"layer": "e4m3 weights and activations" if a8 else "bf16", "points": pts, "single_sequence": mid,
+                             "steps_ms_4x2048": {n: round(H.median(t), 4) for n, t in acc.items()}})
+        layer.close()
+    return out
+
+
 def run_kvxfer():
     """The KV hand-off from a prefill to a decode instance as far as one GPU shows it: reading a
     sequence's keys and values out of the (blocked) cache into one contiguous buffer and writing
@@ -562,7 +602,7 @@ def run_kvxfer():
 def main():
     which = sys.argv[1] if len(sys.argv) > 1 else "prefill"
     fn = {"prefill": run_prefill, "longctx": run_longctx, "queue": run_queue, "moe": run_moe,
-          "chunk": run_chunk, "stack": run_stack, "queue_fixed": run_queue_fixed, "fp8kv": run_fp8kv, "kvxfer": run_kvxfer, "w8": run_w8}[which]
+          "chunk": run_chunk, "stack": run_stack, "queue_fixed": run_queue_fixed, "fp8kv": run_fp8kv, "kvxfer": run_kvxfer, "w8": run_w8, "a8": run_a8}[which]
     print(json.dumps(fn()))
 
 

@@ -54,12 +54,12 @@ def _dev(a, dtype):
 class Layer:
     """Device copy of one seeded layer plus timing helpers."""
 
-    def __init__(self, cfg, weights, w8=False):
+    def __init__(self, cfg, weights, w8=False, a8=False):
         self.cfg = cfg
         self.dtype = cfg["dtype"]
         self.tdtype = torch.bfloat16 if self.dtype == "bf16" else torch.float32
         dev_w = {k: _dev(v, self.dtype) for k, v in weights.items()}
-        self.h = pd.pd_layer_create(cfg, dev_w, w8=w8)
+        self.h = pd.pd_layer_create(cfg, dev_w, w8=w8 or a8, a8=a8)
         del dev_w
         torch.cuda.empty_cache()
         self.caches = []

@@ -24,11 +24,11 @@ def relmax(got, ref):
 
 
 class GpuLayer:
-    def __init__(self, cfg, weights, w8=False):
+    def __init__(self, cfg, weights, w8=False, a8=False):
         self.cfg = cfg
         self.dtype = cfg["dtype"]
         self.dev_w = {k: to_dev(v, self.dtype) for k, v in weights.items()}
-        self.h = pd.pd_layer_create(cfg, self.dev_w, w8=w8)
+        self.h = pd.pd_layer_create(cfg, self.dev_w, w8=w8 or a8, a8=a8)
         self.caches = []
 
     def cache(self, n_slots, max_len, fp8_scales=None):

@@ -603,3 +603,23 @@ def test_act8_layer_is_unchanged_up_to_the_row_threshold():
     ca, cp = O.KVCache(la, 1, T + 8), O.KVCache(lp, 1, T + 8)
     cuc = np.array([0, T + 1], np.int32)
     assert not np.array_equal(O.prefill_chunk(la, x, cuc, [0], ca), O.prefill_chunk(lp, x, cuc, [0], cp))
+
+
+def test_gemm_e4m3_is_the_product_of_the_decoded_matrices():
+    """Against the library's own reading of the bytes (float8_e4m3fn view) and a float64 matmul."""
+    rng = np.random.default_rng(41)
+    a = rng.integers(0, 256, (9, 64), dtype=np.uint8)
+    b = rng.integers(0, 256, (5, 64), dtype=np.uint8)
+    a[(a & 0x7f) == 0x7f] = 0x30                      # no NaN codes
+    b[(b & 0x7f) == 0x7f] = 0xB1
+    sa = 2.0 ** rng.integers(-6, 6, 9).astype(np.float32)
+    sb = 2.0 ** rng.integers(-6, 6, 5).astype(np.float32)
+    A = torch.from_numpy(a).view(torch.float8_e4m3fn).to(torch.float64) * torch.from_numpy(sa).to(torch.float64)[:, None]
+    B = torch.from_numpy(b).view(torch.float8_e4m3fn).to(torch.float64) * torch.from_numpy(sb).to(torch.float64)[:, None]
+    ref = (A @ B.T).numpy()
+    got = O.gemm_e4m3(a, sa, b, sb)
+    assert np.allclose(got, ref, rtol=1e-13, atol=0)
+    # one-hot rows pick single products
+    a1 = np.zeros((1, 64), np.uint8)
+    a1[0, 7] = 0x38                                  # 1.0
+    assert np.array_equal(O.gemm_e4m3(a1, np.ones(1), b, np.ones(5))[0], O.fp8_e4m3_decode(b[:, 7]))
