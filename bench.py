@@ -30,7 +30,7 @@ DECODE_REPS = 3                    # decode steps per batch size per step; media
 # the FETCH_SIZE / WRITE_SIZE counters scaled by a plain copy (paper_2603_04716_amd/traffic_probe.py).
 # Valid only for the kernel source the counters were taken on.
 TRAFFIC = {"source": os.path.join("paper_2603_04716_amd", "csrc", "gemm_mfma.hip"),
-           "sha256": "6c1dc43d31f26f7c7bb4573d0033c7a3e0a825db7554562edbf354acf6770b85",
+           "sha256": "47831b5b205e0e40b30a54f209b60abe256a3a19c51c6aaca2625f8f039ad5d8",
            "bytes_per_launch": 3053.6e6}
 
 
@@ -62,6 +62,44 @@ def cpu_baseline(cfg, weights):
             "kind": "oracle", "sample": f"prefill of 2x{n // 2} tokens through the full 8B-shaped layer, {dt:.1f} s"}
 
 
+def fp8_section(cfg, weights, x, cu, kd, vd):
+    """The same layer with 8-bit (E4M3) weights, activations (calls of more than 256 rows) and KV cache:
+    prefill rate, decode curve and the allocation they give.  Reported beside the bf16 figures, never
+    as `value`."""
+    import torch
+    import pd_inputs as I
+    import paper_2603_04716_amd as pd
+    from paper_2603_04716_amd import harness as H
+    layer = H.Layer(cfg, weights, a8=True)
+    T = x.shape[0]
+    t_pre = layer.time_prefill(x, cu, iters=6, warmup=3)
+    batches = [b for b in BATCHES] + [320, 384, 448]
+    bmax = max(batches)
+    cache = layer.new_cache(bmax, KV_LEN + 8, fp8_scales=(0.5, 0.125))
+    layer.fill_cache(cache, [KV_LEN] * bmax, kd, vd)
+    xdec = H._dev(I.hidden(bmax, cfg["d_model"], seed=12, dtype="bf16"), "bf16")
+    curve, tpot = [], []
+    for B in batches:
+        run = layer.make_decode_step(cache, xdec[:B].contiguous(), [KV_LEN] * B)
+        ms = H.median([run() for _ in range(7)])
+        tpot.append(N_LAYERS * ms * 1e-3)
+        curve.append({"batch": B, "ms_per_layer": round(ms, 4), "tpot_ms": round(N_LAYERS * ms, 3),
+                      "tok_s": round(B / (N_LAYERS * ms * 1e-3), 1)})
+    tp_hat = T / (N_LAYERS * t_pre * 1e-3)
+    alloc = pd.pd_allocate(5e6 / 60.0, float(L_IN), L_OUT, TTFT_SLO, TPOT_SLO, tp_hat, batches, tpot)
+    star = next(c for c in curve if c["batch"] == alloc["decode_batch"])
+    fl = H.prefill_flops(cfg, [L_IN] * N_SEQ)
+    layer.close()
+    return {"what": "E4M3 weights (power-of-two row scales), E4M3 activations in calls of more than 256 rows, "
+                    "E4M3 KV cache (static scales); fp32 accumulation",
+            "prefill": {"ms_per_layer": round(t_pre, 4), "tok_s_model": round(tp_hat, 1),
+                        "tflops": round(fl / (t_pre * 1e-3) / 1e12, 1),
+                        "mfma_frac_of_8bit_peak": round(fl / (t_pre * 1e-3) / 1e12 / 5000.0, 4)},
+            "decode": {"max_feasible_batch": alloc["decode_batch"], "tpot_ms": star["tpot_ms"], "tok_s": star["tok_s"],
+                       "curve": curve},
+            "allocation": {k2: alloc[k2] for k2 in ("n_prefill", "n_decode", "ratio_pd", "tp_prefill_eff", "tp_decode_eff")}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -69,6 +107,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--no-fp8", action="store_true", help="skip the 8-bit section reported beside the bf16 figures")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the path uses no second device and no collectives; "
@@ -232,9 +271,11 @@ def main():
                      "algorithmic_bytes": 2.0 * (T * d + 2 * f * d + T * f), "avg_launch_ms": round(gu_ms, 4)},
         "kernels": kernels,
     }
+    layer.close()
+    if not args.no_fp8:
+        line["fp8"] = fp8_section(cfg, weights, x, cu, kd, vd)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(cfg, weights)
-    layer.close()
     print(json.dumps(line))
 
 

@@ -151,6 +151,25 @@ def test_prefill_with_8bit_activations(T, cu, d, F, hq, hkv):
     gl.close()
 
 
+def test_decode_step_of_more_than_256_rows_quantises_too():
+    """The rule counts the rows of the call, whichever entry point: a decode batch of 300."""
+    cfg = small()
+    ol, gl = both(cfg, std=0.04, seed=3)
+    B = 300
+    rng = np.random.default_rng(9)
+    lens = rng.integers(1, 40, B)
+    oc, gc = O.KVCache(ol, B, 48), gl.cache(B, 48)
+    for i, n in enumerate(lens):
+        k, v = I.kv_fill(2, int(n), 128, seed=6000 + i, dtype="bf16")
+        oc.set(i, k, v)
+        pd.pd_kv_cache_set(gc, i, to_dev(k, "bf16"), to_dev(v, "bf16"))
+    xn = I.hidden(B, cfg["d_model"], seed=53, dtype="bf16")
+    ref = O.decode_step(ol, xn, list(range(B)), oc)
+    got = gl.decode(xn, list(range(B)), gc)
+    assert relmax(got, ref) <= TOL_A8
+    gl.close()
+
+
 def test_calls_of_up_to_256_rows_are_those_of_the_8bit_weight_layer():
     cfg = small()
     w = I.layer_weights(cfg, std=0.05)
