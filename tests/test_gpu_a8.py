@@ -170,6 +170,28 @@ def test_decode_step_of_more_than_256_rows_quantises_too():
     gl.close()
 
 
+@pytest.mark.parametrize("fp8_cache", [False, True])
+def test_chunked_prefill_counts_the_rows_of_each_call(fp8_cache):
+    """A 40-token first chunk (bf16 activations), then one of 300 tokens against that prefix (8-bit
+    activations), then a decode step; with the bf16 and with the 8-bit cache."""
+    cfg = small()
+    ol, gl = both(cfg, std=0.04, seed=11)
+    scales = (0.5, 0.125) if fp8_cache else None
+    oc, gc = O.KVCache(ol, 2, 352, fp8_scales=scales), gl.cache(2, 352, fp8_scales=scales)
+    d = cfg["d_model"]
+    for step, (n0, n1) in enumerate(((25, 15), (180, 120))):
+        cu = np.array([0, n0, n0 + n1], np.int32)
+        x = I.hidden(n0 + n1, d, seed=70 + step, dtype="bf16")
+        ref = O.prefill_chunk(ol, x, cu, [0, 1], oc)
+        got = gl.prefill_chunk(x, cu, [0, 1], gc)
+        assert relmax(got, ref) <= (TOL["bf16"] if step == 0 else TOL_A8), step
+    xn = I.hidden(2, d, seed=75, dtype="bf16")
+    ref = O.decode_step(ol, xn, [0, 1], oc)
+    got = gl.decode(xn, [0, 1], gc)
+    assert relmax(got, ref) <= TOL_A8       # the cached keys and values of the second chunk carry its code differences
+    gl.close()
+
+
 def test_calls_of_up_to_256_rows_are_those_of_the_8bit_weight_layer():
     cfg = small()
     w = I.layer_weights(cfg, std=0.05)
