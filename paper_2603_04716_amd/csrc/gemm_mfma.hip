@@ -528,6 +528,8 @@ bool gemm_mfma_f8_supported(const GemmArgs &a)
 
 hipError_t launch_gemm_mfma_f8(const GemmArgs &a, hipStream_t s)
 {
+    // as for bf16: 16 waves for the short-K products (a.K counts code pairs)
+    if (a.K <= 2048 && a.epilogue != EPI_SWIGLU) return launch_cfg<256, 256, 4, 4, 2, true>(a, s, choose_splits_mid(a));
     return launch_cfg<256, 256, 2, 4, 2, true>(a, s, choose_splits_mid(a));
 }
 

@@ -681,6 +681,100 @@ __global__ __launch_bounds__(256) void quant_rows_e4m3_kernel(const uint16_t *__
     }
 }
 
+// RMSNorm and row quantisation in one pass for rows of up to 8192 bf16 elements: the normalised row is
+// rounded to bf16 exactly as rmsnorm_bf16_vec_kernel rounds it, kept in registers, and encoded like
+// quant_rows_e4m3_kernel encodes a stored row; the bf16 row itself is not written.
+__global__ __launch_bounds__(256) void rmsnorm_quant_e4m3_kernel(const uint4 *__restrict__ x, const uint4 *__restrict__ g,
+                                                                 int d8, float d_inv, float eps,
+                                                                 uint8_t *__restrict__ codes, float *__restrict__ scales)
+{
+    __shared__ float red[4], redm[4];
+    __shared__ float inv_s;
+    const int tid = threadIdx.x;
+    const uint4 *xr = x + (size_t)blockIdx.x * d8;
+    uint4 xv[4];
+    float ss = 0.f;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int i = tid + u * 256;
+        xv[u] = i < d8 ? xr[i] : make_uint4(0u, 0u, 0u, 0u);
+        const uint32_t w[4] = {xv[u].x, xv[u].y, xv[u].z, xv[u].w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float a = bfbits2f(w[j] & 0xffffu), b = bfbits2f(w[j] >> 16);
+            ss += a * a + b * b;
+        }
+    }
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0) red[tid >> 6] = ss;
+    __syncthreads();
+    const float inv = rsqrtf((red[0] + red[1] + red[2] + red[3]) * d_inv + eps);
+    uint32_t y[4][4];
+    float m = 0.f;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int i = tid + u * 256;
+        const uint4 gg = i < d8 ? g[i] : make_uint4(0u, 0u, 0u, 0u);
+        const uint32_t w[4] = {xv[u].x, xv[u].y, xv[u].z, xv[u].w}, gw[4] = {gg.x, gg.y, gg.z, gg.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float a = bfbits2f(w[j] & 0xffffu) * inv * bfbits2f(gw[j] & 0xffffu);
+            float b = bfbits2f(w[j] >> 16) * inv * bfbits2f(gw[j] >> 16);
+            y[u][j] = pack2bf(a, b);
+            m = fmaxf(m, fmaxf(fabsf(bfbits2f(y[u][j] & 0xffffu)), fabsf(bfbits2f(y[u][j] >> 16))));
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+    if ((tid & 63) == 0) redm[tid >> 6] = m;
+    __syncthreads();
+    if (tid == 0) {
+        m = fmaxf(fmaxf(redm[0], redm[1]), fmaxf(redm[2], redm[3]));
+        float s = 1.f;
+        if (m > 0.f && m < INFINITY) {
+            int e;
+            const double f = frexp((double)m / 448.0, &e);
+            s = (float)ldexp(1.0, f == 0.5 ? e - 1 : e);
+        }
+        scales[blockIdx.x] = s;
+        inv_s = 1.0f / s;
+    }
+    __syncthreads();
+    const float is = inv_s;
+    uint2 *q = (uint2 *)(codes + (size_t)blockIdx.x * d8 * 8);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int i = tid + u * 256;
+        if (i >= d8) continue;
+        float f[8];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            f[2 * j] = bfbits2f(y[u][j] & 0xffffu) * is;
+            f[2 * j + 1] = bfbits2f(y[u][j] >> 16) * is;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (f[j] == f[j]) f[j] = fminf(fmaxf(f[j], -448.f), 448.f);
+        int lo = __builtin_amdgcn_cvt_pk_fp8_f32(f[0], f[1], 0, false);
+        lo = __builtin_amdgcn_cvt_pk_fp8_f32(f[2], f[3], lo, true);
+        int hi = __builtin_amdgcn_cvt_pk_fp8_f32(f[4], f[5], 0, false);
+        hi = __builtin_amdgcn_cvt_pk_fp8_f32(f[6], f[7], hi, true);
+        q[i] = make_uint2((uint32_t)lo, (uint32_t)hi);
+    }
+}
+
+bool rmsnorm_quant_supported(int d) { return d % 8 == 0 && d <= 8192; }
+
+hipError_t launch_rmsnorm_quant_e4m3(const void *x, const void *g, int T, int d, float eps, void *codes,
+                                     float *scales, hipStream_t s)
+{
+    if (T <= 0) return hipSuccess;
+    if (!rmsnorm_quant_supported(d)) return hipErrorInvalidValue;
+    rmsnorm_quant_e4m3_kernel<<<T, 256, 0, s>>>((const uint4 *)x, (const uint4 *)g, d / 8, 1.0f / (float)d, eps,
+                                                (uint8_t *)codes, scales);
+    return hipGetLastError();
+}
+
 hipError_t launch_quant_rows_e4m3(const void *x, int ldx, int T, int K, void *codes, float *scales, hipStream_t s)
 {
     if (T <= 0) return hipSuccess;

@@ -31,6 +31,8 @@ struct pd_layer {
     void *t_qkv, *t_o, *t_gate, *t_down;
     uint8_t *a8_codes;        // [ws_tokens][max K] activation codes (inside ws)
     float *a8_scales;         // [ws_tokens]
+    mutable const void *a8_src;   // the buffer whose (unwritten) rows a8_codes already encode: set by a fused
+                                  // norm + quantisation, consumed by the projection that follows
     double *inv_freq;
     float2 *rope_table;       // (cos, sin) for positions < kRopeTableLen
     int32_t *d_cu, *d_slots, *d_pad_cu, *d_prefix;  // [4097] each
@@ -743,9 +745,13 @@ static hipError_t run_gemm(const pd_layer *L, GemmArgs g, hipStream_t s)
             else if (g.B == L->w_gate) { g.B8 = L->q_gate; g.b_scale = L->s_gate; tiles = L->t_gate; }
             else if (g.B == L->w_down) { g.B8 = L->q_down; g.b_scale = L->s_down; tiles = L->t_down; }
             if (L->a8 && g.M > kA8Rows && tiles) {
-                // 8-bit activations: quantise the input rows, then codes x codes on the matrix cores
-                hipError_t e = launch_quant_rows_e4m3(g.A, g.lda, g.M, g.K, L->a8_codes, L->a8_scales, s);
-                if (e != hipSuccess) return e;
+                // 8-bit activations: quantise the input rows (unless the norm before already did), then
+                // codes x codes on the matrix cores
+                if (L->a8_src != g.A) {
+                    hipError_t e = launch_quant_rows_e4m3(g.A, g.lda, g.M, g.K, L->a8_codes, L->a8_scales, s);
+                    if (e != hipSuccess) return e;
+                }
+                L->a8_src = nullptr;
                 GemmArgs f = g;
                 f.A = L->a8_codes;
                 f.B = tiles;
@@ -764,6 +770,20 @@ static hipError_t run_gemm(const pd_layer *L, GemmArgs g, hipStream_t s)
         return hipErrorInvalidValue;
     }
     return launch_gemm_generic(L->cfg.dtype, g, s);
+}
+
+// RMSNorm in front of a projection: where that projection will multiply codes, the normalised rows go
+// straight to codes (y is then not written; nothing else reads it in a dense layer).
+static hipError_t norm_for_gemm(const pd_layer *L, const void *x, const void *g, void *y, int T, hipStream_t s)
+{
+    const pd_layer_config &c = L->cfg;
+    L->a8_src = nullptr;
+    if (L->a8 && T > kA8Rows && rmsnorm_quant_supported(c.d_model)) {
+        hipError_t e = launch_rmsnorm_quant_e4m3(x, g, T, c.d_model, c.rms_eps, L->a8_codes, L->a8_scales, s);
+        if (e == hipSuccess) L->a8_src = y;
+        return e;
+    }
+    return launch_rmsnorm(c.dtype, x, g, y, T, c.d_model, c.rms_eps, s);
 }
 
 static bool cache_matches(const pd_layer *L, const pd_kv_cache *c)
@@ -787,7 +807,7 @@ static pd_status run_tail(pd_layer *L, const void *x, int T, const void *router_
         memset(&g, 0, sizeof(g));
         g.A = L->h; g.lda = d; g.B = L->w_gate; g.B1 = L->w_up; g.ldb = d; g.C = L->act; g.ldc = F;
         g.M = T; g.N = F; g.K = d; g.epilogue = EPI_SWIGLU; g.n_groups = 1;
-        STEP("rmsnorm_ffn", launch_rmsnorm(c.dtype, L->h, L->g_ffn, L->y, T, d, c.rms_eps, s));
+        STEP("rmsnorm_ffn", norm_for_gemm(L, L->h, L->g_ffn, L->y, T, s));
         g.A = L->y;
         STEP("gate_up_swiglu", run_gemm(L, g, s));
         memset(&g, 0, sizeof(g));
@@ -908,7 +928,7 @@ static pd_status prefill_common(pd_layer *L, const pd_tokens *tk, pd_kv_cache *c
     HIP_TRY(launch_token_meta(L->d_cu, keep ? L->d_slots : nullptr, chunk ? L->d_prefix : nullptr, n, T,
                               L->tok_seq, L->tok_pos, L->tok_slot, s),
             PD_ERR_DEVICE);
-    STEP("rmsnorm_attn", launch_rmsnorm(c.dtype, tk->hidden, L->g_attn, L->y, T, c.d_model, c.rms_eps, s));
+    STEP("rmsnorm_attn", norm_for_gemm(L, tk->hidden, L->g_attn, L->y, T, s));
     GemmArgs g;
     memset(&g, 0, sizeof(g));
     g.A = L->y; g.lda = c.d_model; g.B = L->w_qkv; g.ldb = c.d_model; g.C = L->qkv; g.ldc = L->Nqkv;
@@ -1117,7 +1137,7 @@ extern "C" pd_status pd_decode_step(pd_layer *L, const pd_batch *bt, pd_kv_cache
     memset(&g, 0, sizeof(g));
     g.A = bt->hidden; g.lda = c.d_model; g.B = L->w_qkv; g.ldb = c.d_model; g.C = L->qkv; g.ldc = L->Nqkv;
     g.M = B; g.N = L->Nqkv; g.K = c.d_model; g.epilogue = EPI_NONE; g.n_groups = 1;
-    STEP("rmsnorm_attn", launch_rmsnorm(c.dtype, bt->hidden, L->g_attn, L->y, B, c.d_model, c.rms_eps, s));
+    STEP("rmsnorm_attn", norm_for_gemm(L, bt->hidden, L->g_attn, L->y, B, s));
     g.A = L->y;
     STEP("qkv_proj", run_gemm(L, g, s));
     RopeArgs r;

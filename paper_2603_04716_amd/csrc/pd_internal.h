@@ -173,6 +173,10 @@ hipError_t launch_gemm_mfma_f8(const GemmArgs &a, hipStream_t s);
 // per row of x [T, K] (bf16, row stride ldx): scale = smallest power of two with max|x| / scale <= 448
 // (1 for a zero row), codes = E4M3(x / scale), round to nearest even, saturating; codes [T, K] bytes
 hipError_t launch_quant_rows_e4m3(const void *x, int ldx, int T, int K, void *codes, float *scales, hipStream_t s);
+// the two in one pass for bf16 rows of up to 8192 elements (the normalised bf16 row is not stored)
+bool rmsnorm_quant_supported(int d);
+hipError_t launch_rmsnorm_quant_e4m3(const void *x, const void *g, int T, int d, float eps, void *codes,
+                                     float *scales, hipStream_t s);
 // codes in the layout of w8pack_off -> the bf16 block pack of the same matrix seen as [n_rows, K / 2] code pairs
 hipError_t launch_repack_w8_tiles(const void *src8, void *dst, int n_rows, int K, hipStream_t s);
 hipError_t launch_pack_rows_e4m3_tiles(const void *src, void *dst, int n_rows, int K, hipStream_t s);   // from row-major codes
