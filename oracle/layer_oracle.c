@@ -381,10 +381,11 @@ static void ffn_block_row(const orc_config *c, const orc_weights *w, const float
             orc_linear_row(y2, w->w_router, d, E, logits);
         }
         orc_route_row(logits, E, K, idx, wgt);
+        if (q8) act_quantise_row(y2, d);   /* after routing: the router reads the unquantised row */
         for (int k = 0; k < K; ++k) {
             size_t e = (size_t)idx[k];
             ffn_row_accumulate(y2, w->w_gate + e * (size_t)F * d, w->w_up + e * (size_t)F * d,
-                               w->w_down + e * (size_t)d * F, d, F, wgt[k], acc, act, 0);
+                               w->w_down + e * (size_t)d * F, d, F, wgt[k], acc, act, q8);
             if (expert_idx_out) expert_idx_out[k] = idx[k];
         }
         free(logits);

@@ -55,8 +55,8 @@ def torch_layer(cfg, w, x, cu, router_logits=None, act_q=None):
         o[a:b] = os_[0].transpose(0, 1)
     h = x + aq(o.reshape(-1, hq * hd)) @ W["w_o"].T
     y2 = norm(h, W["g_ffn"])
-    if cfg.get("n_experts", 0) == 0:
-        y2 = aq(y2)
+    y2r = y2                  # the router reads the unquantised row
+    y2 = aq(y2)
 
     def ffn(z, wg, wu, wd):
         return aq(torch.nn.functional.silu(z @ wg.T) * (z @ wu.T)) @ wd.T
@@ -64,7 +64,7 @@ def torch_layer(cfg, w, x, cu, router_logits=None, act_q=None):
     if cfg.get("n_experts", 0) == 0:
         out = h + ffn(y2, W["w_gate"], W["w_up"], W["w_down"])
     else:
-        r = torch.from_numpy(router_logits).to(f64) if router_logits is not None else y2 @ W["w_router"].T
+        r = torch.from_numpy(router_logits).to(f64) if router_logits is not None else y2r @ W["w_router"].T
         p = torch.softmax(r, dim=-1)
         tv, ti = torch.topk(p, cfg["top_k"], dim=-1)
         tv = tv / tv.sum(-1, keepdim=True)
@@ -580,6 +580,21 @@ def test_act8_layer_matches_library_composition_above_the_row_threshold():
     assert relmax(got, ref) < 2e-6
     plain = O.prefill(O.Layer(cfg, w), x, cu)
     assert 1e-4 < relmax(got, plain) < 0.2       # and it is not the layer without them
+
+
+def test_act8_moe_layer_matches_library_composition():
+    """Mixture of experts: the normalised row is quantised once per token after routing (the router
+    reads it unquantised), the SwiGLU row once per (token, expert) pair."""
+    cfg = I.small_config(d_model=64, n_q_heads=4, n_kv_heads=2, head_dim=16, d_ff=48, n_experts=4, top_k=2)
+    w = O.quantise_layer_weights(I.layer_weights(cfg, std=0.08, with_router=True))
+    T = O.ACT8_ROWS + 3
+    cu = np.array([0, 150, T], np.int32)
+    x = I.hidden(T, cfg["d_model"], seed=16)
+    for rl in (None, I.router_logits(T, 4, seed=17)):
+        got = O.prefill(O.Layer(cfg, w, act8=True), x, cu, router_logits=rl)
+        ref = torch_layer(cfg, w, x, cu, router_logits=rl, act_q=torch_act_q)
+        assert relmax(got, ref) < 2e-6
+        assert relmax(got, O.prefill(O.Layer(cfg, w), x, cu, router_logits=rl)) > 1e-4
 
 
 def test_act8_layer_is_unchanged_up_to_the_row_threshold():
