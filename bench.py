@@ -30,7 +30,7 @@ DECODE_REPS = 3                    # decode steps per batch size per step; media
 # the FETCH_SIZE / WRITE_SIZE counters scaled by a plain copy (paper_2603_04716_amd/traffic_probe.py).
 # Valid only for the kernel source the counters were taken on.
 TRAFFIC = {"source": os.path.join("paper_2603_04716_amd", "csrc", "gemm_mfma.hip"),
-           "sha256": "47831b5b205e0e40b30a54f209b60abe256a3a19c51c6aaca2625f8f039ad5d8",
+           "sha256": "961847c1938b313bc249be0ee8113a91fa32d85d60510dea1294aa22c2f664e3",
            "bytes_per_launch": 3053.6e6}
 
 

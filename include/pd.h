@@ -110,9 +110,11 @@ pd_status pd_layer_create_w8(const pd_layer_config *cfg, const pd_layer_weights 
  * call) each of the four projections first quantises its bf16 input rows (the normalised hidden
  * state, the attention output, the SwiGLU output) like pd_quantize_rows_e4m3 and multiplies codes
  * by codes in E4M3 on the matrix cores with fp32 accumulation; the sums are multiplied by the two
- * scales.  Calls of up to 256 rows behave as in a pd_layer_create_w8 layer.
- * Errors: as pd_layer_create_w8, plus PD_ERR_DTYPE for a mixture-of-experts layer or when d_model,
- * d_ff or n_q_heads * head_dim is not a multiple of 128.
+ * scales.  In a mixture-of-experts layer the normalised row is quantised once per token (the router
+ * reads it unquantised) and the SwiGLU row once per (token, expert) pair.  Calls of up to 256 rows
+ * behave as in a pd_layer_create_w8 layer.
+ * Errors: as pd_layer_create_w8, plus PD_ERR_DTYPE when d_model, d_ff or n_q_heads * head_dim is not
+ * a multiple of 128.
  */
 pd_status pd_layer_create_w8a8(const pd_layer_config *cfg, const pd_layer_weights *w, pd_layer **out);
 void pd_layer_destroy(pd_layer *layer);

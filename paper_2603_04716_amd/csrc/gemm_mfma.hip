@@ -272,13 +272,16 @@ __global__ __launch_bounds__(64 * WAVES_M *WAVES_N) void gemm_mfma_kernel(GemmAr
     if (F8) {
         float sb[NB];
 #pragma unroll
-        for (int j = 0; j < NB; ++j) sb[j] = a.b_scale[min(col0 + wn * WN + j * 32 + frow, n_cols - 1)];
+        for (int j = 0; j < NB; ++j)
+            sb[j] = a.b_scale[(size_t)group * n_cols + min(col0 + wn * WN + j * 32 + frow, n_cols - 1)];
 #pragma unroll
         for (int i = 0; i < MB; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int m = row0 + wm * WM + i * 32 + 8 * (r >> 2) + 4 * fhalf + (r & 3);
-                const float sa = a.a_scale[min(m, row_end - 1)];
+                int mr = min(m, row_end - 1);
+                if (a.a_gather) mr = a.a_gather[mr];        // the scale belongs to the row the codes came from
+                const float sa = a.a_scale[mr];
 #pragma unroll
                 for (int j = 0; j < NB; ++j) acc[i][j][r] *= sa * sb[j];
             }
@@ -523,13 +526,14 @@ static int choose_splits_mid(const GemmArgs &a)
 // the pack of the halved view with a.b_scale per packed row; a.K, a.lda, a.ldb count code pairs.
 bool gemm_mfma_f8_supported(const GemmArgs &a)
 {
-    return gemm_mfma_supported(a) && a.a_scale && a.b_scale && !a.group_offsets && !a.a_gather;
+    return gemm_mfma_supported(a) && a.a_scale && a.b_scale;
 }
 
 hipError_t launch_gemm_mfma_f8(const GemmArgs &a, hipStream_t s)
 {
     // as for bf16: 16 waves for the short-K products (a.K counts code pairs)
-    if (a.K <= 2048 && a.epilogue != EPI_SWIGLU) return launch_cfg<256, 256, 4, 4, 2, true>(a, s, choose_splits_mid(a));
+    if (a.K <= 2048 && a.epilogue != EPI_SWIGLU && !a.group_offsets)
+        return launch_cfg<256, 256, 4, 4, 2, true>(a, s, choose_splits_mid(a));
     return launch_cfg<256, 256, 2, 4, 2, true>(a, s, choose_splits_mid(a));
 }
 

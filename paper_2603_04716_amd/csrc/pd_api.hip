@@ -29,8 +29,8 @@ struct pd_layer {
     // their input rows and multiply codes by codes; t_* are the weight codes in the tiled kernel's pack
     bool a8;
     void *t_qkv, *t_o, *t_gate, *t_down;
-    uint8_t *a8_codes;        // [ws_tokens][max K] activation codes (inside ws)
-    float *a8_scales;         // [ws_tokens]
+    uint8_t *a8_codes;        // [ws_tokens * top_k][max K] activation codes (inside ws)
+    float *a8_scales;         // [ws_tokens * top_k]
     mutable const void *a8_src;   // the buffer whose (unwritten) rows a8_codes already encode: set by a fused
                                   // norm + quantisation, consumed by the projection that follows
     double *inv_freq;
@@ -49,6 +49,7 @@ struct pd_layer {
     int32_t *tok_seq, *tok_pos, *tok_slot, *eidx, *sorted_token, *pair_pos, *offsets, *chunk_cu;
     float *logits, *ew;
     int last_rows;
+    int call_rows;            // rows of the call in progress (T of a prefill, B of a decode step)
     // optional per-kernel timing of the last call
     bool prof_on;
     std::vector<hipEvent_t> prof_ev;          // pairs (start, stop)
@@ -331,8 +332,8 @@ static pd_status layer_create(const pd_layer_config *cfg, const pd_layer_weights
         delete L;
         return PD_ERR_DTYPE;
     }
-    if (a8 && (d % 128 != 0 || F % 128 != 0 || L->Nq % 128 != 0 || E > 0)) {
-        set_error("pd_layer_create_w8a8: needs a dense layer whose dimensions are multiples of 128");
+    if (a8 && (d % 128 != 0 || F % 128 != 0 || L->Nq % 128 != 0)) {
+        set_error("pd_layer_create_w8a8: needs a layer whose dimensions are multiples of 128");
         delete L;
         return PD_ERR_DTYPE;
     }
@@ -418,12 +419,16 @@ static pd_status layer_create(const pd_layer_config *cfg, const pd_layer_weights
         if (a8) {
             CREATE_TRY(hipMalloc(&L->t_qkv, (size_t)L->Nqkv * d));
             CREATE_TRY(hipMalloc(&L->t_o, (size_t)d * L->Nq));
-            CREATE_TRY(hipMalloc(&L->t_gate, (size_t)2 * F * d));
-            CREATE_TRY(hipMalloc(&L->t_down, (size_t)d * F));
+            CREATE_TRY(hipMalloc(&L->t_gate, (size_t)G * 2 * F * d));
+            CREATE_TRY(hipMalloc(&L->t_down, (size_t)G * d * F));
             CREATE_TRY(launch_repack_w8_tiles(L->q_qkv, L->t_qkv, L->Nqkv, d, nullptr));
             CREATE_TRY(launch_repack_w8_tiles(L->q_o, L->t_o, d, L->Nq, nullptr));
-            CREATE_TRY(launch_repack_w8_tiles(L->q_gate, L->t_gate, 2 * F, d, nullptr));
-            CREATE_TRY(launch_repack_w8_tiles(L->q_down, L->t_down, d, F, nullptr));
+            for (int g = 0; g < G; ++g) {
+                CREATE_TRY(launch_repack_w8_tiles((const char *)L->q_gate + (size_t)g * 2 * F * d,
+                                                  (char *)L->t_gate + (size_t)g * 2 * F * d, 2 * F, d, nullptr));
+                CREATE_TRY(launch_repack_w8_tiles((const char *)L->q_down + (size_t)g * d * F,
+                                                  (char *)L->t_down + (size_t)g * d * F, d, F, nullptr));
+            }
         }
     } else {
         CREATE_TRY(hipMemcpy(L->w_qkv, w->w_q, (size_t)L->Nq * d * esz, hipMemcpyDeviceToDevice));
@@ -548,7 +553,7 @@ extern "C" pd_status pd_layer_reserve(pd_layer *L, int32_t max_tokens)
     size_t o_sk = carve(sk_elems * sizeof(float));
     size_t maxk = (size_t)d > (size_t)L->Nq ? (size_t)d : (size_t)L->Nq;
     if ((size_t)F > maxk) maxk = (size_t)F;
-    size_t o_a8c = carve(L->a8 ? T * maxk : 0), o_a8s = carve(L->a8 ? T * sizeof(float) : 0);
+    size_t o_a8c = carve(L->a8 ? T * K * maxk : 0), o_a8s = carve(L->a8 ? T * K * sizeof(float) : 0);
     HIP_TRY(hipDeviceSynchronize(), PD_ERR_DEVICE);
     char *nw = nullptr;
     hipError_t e = hipMalloc((void **)&nw, off);
@@ -744,11 +749,13 @@ static hipError_t run_gemm(const pd_layer *L, GemmArgs g, hipStream_t s)
             else if (g.B == L->w_o) { g.B8 = L->q_o; g.b_scale = L->s_o; tiles = L->t_o; }
             else if (g.B == L->w_gate) { g.B8 = L->q_gate; g.b_scale = L->s_gate; tiles = L->t_gate; }
             else if (g.B == L->w_down) { g.B8 = L->q_down; g.b_scale = L->s_down; tiles = L->t_down; }
-            if (L->a8 && g.M > kA8Rows && tiles) {
-                // 8-bit activations: quantise the input rows (unless the norm before already did), then
-                // codes x codes on the matrix cores
+            if (L->a8 && L->call_rows > kA8Rows && tiles) {
+                // 8-bit activations: quantise the input rows (unless the norm before already did; a
+                // gathered operand is quantised where it lies, once per token), then codes x codes on the
+                // matrix cores
                 if (L->a8_src != g.A) {
-                    hipError_t e = launch_quant_rows_e4m3(g.A, g.lda, g.M, g.K, L->a8_codes, L->a8_scales, s);
+                    const int src_rows = g.a_gather ? L->call_rows : g.M;
+                    hipError_t e = launch_quant_rows_e4m3(g.A, g.lda, src_rows, g.K, L->a8_codes, L->a8_scales, s);
                     if (e != hipSuccess) return e;
                 }
                 L->a8_src = nullptr;
@@ -760,6 +767,7 @@ static hipError_t run_gemm(const pd_layer *L, GemmArgs g, hipStream_t s)
                 f.K = g.K / 2;
                 f.lda = g.K / 2;
                 f.ldb = g.K / 2;
+                f.b_group_stride = g.b_group_stride / 2;
                 if (!gemm_mfma_f8_supported(f)) return hipErrorInvalidValue;
                 return launch_gemm_mfma_f8(f, s);
             }
@@ -778,7 +786,7 @@ static hipError_t norm_for_gemm(const pd_layer *L, const void *x, const void *g,
 {
     const pd_layer_config &c = L->cfg;
     L->a8_src = nullptr;
-    if (L->a8 && T > kA8Rows && rmsnorm_quant_supported(c.d_model)) {
+    if (L->a8 && c.n_experts == 0 && T > kA8Rows && rmsnorm_quant_supported(c.d_model)) {
         hipError_t e = launch_rmsnorm_quant_e4m3(x, g, T, c.d_model, c.rms_eps, L->a8_codes, L->a8_scales, s);
         if (e == hipSuccess) L->a8_src = y;
         return e;
@@ -917,6 +925,7 @@ static pd_status prefill_common(pd_layer *L, const pd_tokens *tk, pd_kv_cache *c
         set_error("pd_prefill: MoE layer needs router_logits or w_router");
         return PD_ERR_INVALID_ARG;
     }
+    L->call_rows = T;
     pd_status st = pd_layer_reserve(L, T);
     if (st != PD_OK) return st;
     hipStream_t s = (hipStream_t)stream;
@@ -1102,6 +1111,7 @@ extern "C" pd_status pd_decode_step(pd_layer *L, const pd_batch *bt, pd_kv_cache
                 return PD_ERR_KV_CAPACITY;
             }
     }
+    L->call_rows = B;
     pd_status st = pd_layer_reserve(L, B);
     if (st != PD_OK) return st;
     hipStream_t s = (hipStream_t)stream;

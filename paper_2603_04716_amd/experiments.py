@@ -545,6 +545,25 @@ def run_a8():
         out["cases"].append({"layer": "e4m3 weights and activations" if a8 else "bf16", "points": pts, "single_sequence": mid,
                              "steps_ms_4x2048": {n: round(H.median(t), 4) for n, t in acc.items()}})
         layer.close()
+    # the mixture-of-experts layer (8 experts, top-2), 4 x 2048 tokens, given router logits
+    mcfg = I.CONFIGS["moe"]
+    mw = I.layer_weights(mcfg)
+    rl = torch.from_numpy(I.router_logits(T, mcfg["n_experts"], seed=13)).cuda()
+    cu = I.uniform_cu_seqlens(4, 2048)
+    fl = H.prefill_flops(mcfg, [2048] * 4)
+    out["moe"] = []
+    for a8 in (False, True):
+        layer = H.Layer(mcfg, mw, a8=a8)
+        ms = layer.time_prefill(x, cu, iters=8, warmup=3, router_logits=rl)
+        pd.pd_profile_enable(layer.h, True)
+        o = torch.empty_like(x)
+        pd.pd_prefill(layer.h, x, cu, o, router_logits=rl)
+        steps = pd.pd_profile_read(layer.h)
+        pd.pd_profile_enable(layer.h, False)
+        out["moe"].append({"layer": "e4m3 weights and activations" if a8 else "bf16", "ms_per_layer": round(ms, 4),
+                           "tok_s_model": round(T / (N_LAYERS * ms * 1e-3), 1), "tflops": round(fl / (ms * 1e-3) / 1e12, 1),
+                           "steps_ms": {n: round(t, 4) for n, t in steps}})
+        layer.close()
     return out
 
 

@@ -206,8 +206,32 @@ def test_calls_of_up_to_256_rows_are_those_of_the_8bit_weight_layer():
     gw.close()
 
 
-def test_w8a8_needs_a_dense_layer_with_dimensions_in_multiples_of_128():
-    for cfg in (small(d=320, F=512), small(F=576), small(n_experts=4, top_k=2)):
+@pytest.mark.parametrize("T,given_logits", [(300, True), (700, False)])
+def test_moe_prefill_with_8bit_activations(T, given_logits):
+    """Grouped products on codes: the gathered operand is quantised once per token where it lies, its
+    scale follows the gather, every expert has its own weight scales; expert choices are compared
+    as integers."""
+    cfg = small(4, 2, 256, 384, n_experts=4, top_k=2)
+    w = I.layer_weights(cfg, std=0.04, with_router=True, seed=T)
+    ol, gl = O.Layer(cfg, O.quantise_layer_weights(w), act8=True), GpuLayer(cfg, w, a8=True)
+    cu = np.array([0, 120, T], np.int32)
+    x = I.hidden(T, cfg["d_model"], seed=18, dtype="bf16")
+    rl = I.router_logits(T, 4, seed=19) if given_logits else None
+    ref, eref = O.prefill(ol, x, cu, router_logits=rl, return_experts=True)
+    got = gl.prefill(x, cu, router_logits=rl)
+    if given_logits:
+        assert np.array_equal(np.sort(gl.experts(T), axis=1), np.sort(eref, axis=1))
+        assert relmax(got, ref) <= TOL_A8
+    else:
+        # own router logits come from different roundings: compare the tokens that chose the same experts
+        same = np.all(np.sort(gl.experts(T), axis=1) == np.sort(eref, axis=1), axis=1)
+        assert same.mean() > 0.97
+        assert relmax(got[same], ref[same]) <= TOL_A8
+    gl.close()
+
+
+def test_w8a8_needs_dimensions_in_multiples_of_128():
+    for cfg in (small(d=320, F=512), small(F=576)):
         w = I.layer_weights(cfg, with_router=cfg.get("n_experts", 0) > 0)
         dev = {k: to_dev(v, cfg["dtype"]) for k, v in w.items()}
         with pytest.raises(pd.PdError) as e:
