@@ -73,7 +73,7 @@ def fp8_section(cfg, weights, x, cu, kd, vd):
     layer = H.Layer(cfg, weights, a8=True)
     T = x.shape[0]
     t_pre = layer.time_prefill(x, cu, iters=6, warmup=3)
-    batches = [b for b in BATCHES] + [320, 384, 448]
+    batches = [b for b in BATCHES] + [320, 384, 448, 512, 576]
     bmax = max(batches)
     cache = layer.new_cache(bmax, KV_LEN + 8, fp8_scales=(0.5, 0.125))
     layer.fill_cache(cache, [KV_LEN] * bmax, kd, vd)

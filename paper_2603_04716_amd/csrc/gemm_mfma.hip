@@ -531,6 +531,12 @@ bool gemm_mfma_f8_supported(const GemmArgs &a)
 
 hipError_t launch_gemm_mfma_f8(const GemmArgs &a, hipStream_t s)
 {
+    // a decode batch of a few hundred rows is bound by the weight stream, not by the matrix pipe: for the
+    // products with few columns narrow column tiles and K split over workgroups, as for bf16 (measured
+    // at 448 rows: QKV 44 -> 26 us, O 46 -> 34, down 68 -> 57; the wide gate / up product is faster on
+    // the large tiles, 65 against 74 us)
+    if (a.M <= 512 && !a.group_offsets && (a.epilogue == EPI_SWIGLU ? 2 * a.N : a.N) < 16384)
+        return launch_cfg<256, 64, 8, 1, 3, true>(a, s, choose_splits(a, 256, 64));
     // as for bf16: 16 waves for the short-K products (a.K counts code pairs)
     if (a.K <= 2048 && a.epilogue != EPI_SWIGLU && !a.group_offsets)
         return launch_cfg<256, 256, 4, 4, 2, true>(a, s, choose_splits_mid(a));
