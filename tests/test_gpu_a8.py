@@ -85,10 +85,13 @@ def test_quantiser_argument_errors():
     assert e.value.status == pd.PD_ERR_INVALID_ARG
 
 
-@pytest.mark.parametrize("M,N,K", [(1, 16, 128), (257, 512, 256), (300, 528, 1152), (1100, 1024, 4096), (2048, 6144, 4096)])
+@pytest.mark.parametrize("M,N,K", [(1, 16, 128), (257, 512, 256), (300, 528, 1152), (300, 512, 8192), (448, 4096, 14336),
+                                   (1100, 1024, 4096), (2048, 6144, 4096)])
 def test_gemm_e4m3_same_codes_on_both_sides(M, N, K):
     """The matrix-core product on given codes and scales against the oracle on the same bytes: only
-    the fp32 summation order and the one rounding to bf16 differ (2^-8 of the largest output)."""
+    the fp32 summation order and the one rounding to bf16 differ (2^-8 of the largest output).  Sizes
+    on both sides of 512 rows (decode-style narrow tiles with K split over workgroups below, large
+    tiles above), one row, ragged row and column tiles."""
     rng = np.random.default_rng(M + N)
     a = rng.integers(0, 256, (M, K), dtype=np.uint8)
     b = rng.integers(0, 256, (N, K), dtype=np.uint8)
