@@ -262,14 +262,16 @@ def run_queue_fixed(n_req=2000):
     return out
 
 
-def run_stack(n_layers=32, n_weight_sets=4, batches=(1, 8, 64, 256), kv_len=2048):
+def run_stack(n_layers=32, n_weight_sets=4, batches=(1, 8, 64, 256), kv_len=2048, fp8=False):
     """A real stack of n_layers resident layers (distinct device copies of a few seeded weight
     sets, one KV cache per layer), each layer's output feeding the next: measured prefill time and
-    TPOT of the whole stack beside n_layers x the single-layer time that the sweeps scale up."""
+    TPOT of the whole stack beside n_layers x the single-layer time that the sweeps scale up.
+    fp8: the layers hold 8-bit weights, quantise activations in calls of more than 256 rows, and
+    the caches hold 8-bit codes (the stack's ends stay bf16)."""
     cfg = I.CONFIGS["llama8b"]
     d = cfg["d_model"]
     host_sets = [I.layer_weights(cfg, seed=s0) for s0 in range(n_weight_sets)]
-    layers = [H.Layer(cfg, host_sets[i % n_weight_sets]) for i in range(n_layers)]
+    layers = [H.Layer(cfg, host_sets[i % n_weight_sets], a8=fp8) for i in range(n_layers)]
     del host_sets
     T, l_in = 8192, 2048
     cu = I.uniform_cu_seqlens(T // l_in, l_in)
@@ -316,7 +318,8 @@ def run_stack(n_layers=32, n_weight_sets=4, batches=(1, 8, 64, 256), kv_len=2048
     prefill_stack(True)
     ms_model = timed(lambda: prefill_stack(True), 5)
     ms_one = layers[0].time_prefill(x, cu, iters=10, warmup=3)
-    res = {"experiment": "resident layer stack vs single layer scaled up", "n_layers": n_layers,
+    res = {"experiment": "resident layer stack vs single layer scaled up" + (" (8-bit weights, activations, cache)" if fp8 else ""),
+           "n_layers": n_layers,
            "prefill": {"tokens": T, "l_in": l_in, "stack_ms": round(ms_stack, 3),
                        "single_layer_ms_x_layers": round(ms_one * n_layers, 3),
                        "with_embedding_and_lm_head_ms": round(ms_model, 3),
@@ -328,7 +331,7 @@ def run_stack(n_layers=32, n_weight_sets=4, batches=(1, 8, 64, 256), kv_len=2048
     bmax = max(batches)
     k, v = I.kv_fill(cfg["n_kv_heads"], kv_len, cfg["head_dim"], seed=11, dtype="bf16")
     kd, vd = H._dev(k, "bf16"), H._dev(v, "bf16")
-    caches = [L.new_cache(bmax, kv_len + 8) for L in layers]
+    caches = [L.new_cache(bmax, kv_len + 8, fp8_scales=(0.5, 0.125) if fp8 else None) for L in layers]
     for L, c in zip(layers, caches):
         L.fill_cache(c, [kv_len] * bmax, kd, vd)
     xdec = H._dev(I.hidden(bmax, d, seed=12, dtype="bf16"), "bf16")
@@ -392,7 +395,8 @@ def run_stack(n_layers=32, n_weight_sets=4, batches=(1, 8, 64, 256), kv_len=2048
         ends_ms = timed(ends_only, 15)
         one = layers[0].make_decode_step(caches[0], xb, lens)
         ms_one_d = H.median([one() for _ in range(7)])
-        by = H.decode_bytes(cfg, lens) * n_layers
+        # 8-bit mode: one byte per cached element; one byte per weight where the codes are streamed (up to 128 rows)
+        by = H.decode_bytes(cfg, lens, esz=1 if (fp8 and B <= 128) else 2, kv_esz=1 if fp8 else None) * n_layers
         res["decode"].append({"batch": B, "tpot_ms_stack": round(tpot, 3),
                               "tpot_ms_scaled": round(ms_one_d * n_layers, 3),
                               "tpot_ms_with_embedding_and_lm_head": round(tpot_model, 3),
@@ -621,7 +625,8 @@ def run_kvxfer():
 def main():
     which = sys.argv[1] if len(sys.argv) > 1 else "prefill"
     fn = {"prefill": run_prefill, "longctx": run_longctx, "queue": run_queue, "moe": run_moe,
-          "chunk": run_chunk, "stack": run_stack, "queue_fixed": run_queue_fixed, "fp8kv": run_fp8kv, "kvxfer": run_kvxfer, "w8": run_w8, "a8": run_a8}[which]
+          "chunk": run_chunk, "stack": run_stack, "queue_fixed": run_queue_fixed, "fp8kv": run_fp8kv, "kvxfer": run_kvxfer, "w8": run_w8, "a8": run_a8,
+          "stack_fp8": lambda: run_stack(batches=(1, 8, 64, 256, 448), fp8=True)}[which]
     print(json.dumps(fn()))
 
 
