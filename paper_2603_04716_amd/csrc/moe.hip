@@ -37,7 +37,11 @@ hipError_t launch_router_logits(int dtype, const void *y, const void *w_router, 
 }
 
 // p = softmax(logits) over all experts; the top_k largest p (ties: lower index); weights
-// renormalised to sum 1.  The selection compares probabilities in double.
+// renormalised to sum 1.  The probabilities are exp(r - max) / denom in double with one denom per
+// token, a non-decreasing function of the logit, so a clearly larger logit is a larger probability
+// and the selection compares logits; logits closer than 1e-6 (where rounding could make two
+// probabilities equal, which the lower index then wins) are decided on the probabilities
+// themselves.  Only those and the chosen experts' weights need exponentials.
 __device__ __forceinline__ void moe_topk_token(const MoeRouteArgs &a, int t, int *chosen = nullptr)
 {
     const float *r = a.logits + (size_t)t * a.E;
@@ -51,19 +55,21 @@ __device__ __forceinline__ void moe_topk_token(const MoeRouteArgs &a, int t, int
     int ik[8];
     for (int k = 0; k < a.top_k; ++k) {
         int best = -1;
-        double pbest = -1.0;
+        float rbest = 0.f;
         for (int e = 0; e < a.E; ++e) {
             if ((taken >> e) & 1ull) continue;
-            double p = exp((double)r[e] - mx) / denom;
-            if (best < 0 || p > pbest) {
+            bool better = best < 0 || r[e] > rbest;      // strict: the lower index wins a tie
+            if (better && best >= 0 && (double)r[e] - (double)rbest < 1e-6)
+                better = exp((double)r[e] - mx) / denom > exp((double)rbest - mx) / denom;   // nearly equal: decide on the probabilities themselves
+            if (better) {
                 best = e;
-                pbest = p;
+                rbest = r[e];
             }
         }
         taken |= 1ull << best;
-        pk[k] = pbest;
+        pk[k] = exp((double)rbest - mx) / denom;
         ik[k] = best;
-        sum += pbest;
+        sum += pk[k];
     }
     for (int k = 0; k < a.top_k; ++k) {
         a.expert_idx[(size_t)t * a.top_k + k] = ik[k];
@@ -152,6 +158,65 @@ __global__ __launch_bounds__(1024) void moe_sort_kernel(MoeRouteArgs a)
     }
 }
 
+// The same order from many blocks of 256 pairs.  First kernel: how many pairs of each expert a block
+// holds.  Second kernel: a pair's place is the expert's first place, plus the pairs of that expert
+// in earlier blocks, in earlier waves of its block and in lower lanes of its wave (ballots).
+__global__ __launch_bounds__(256) void moe_block_hist_kernel(MoeRouteArgs a)
+{
+    __shared__ int wcnt[64][4];
+    const int P = a.T * a.top_k, i = blockIdx.x * 256 + threadIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int e = i < P ? a.expert_idx[i] : -1;
+    for (int ex = 0; ex < a.E; ++ex) {
+        const unsigned long long mask = __ballot(e == ex);
+        if (lane == 0) wcnt[ex][wave] = __popcll(mask);
+    }
+    __syncthreads();
+    if (threadIdx.x < a.E)
+        a.block_hist[(size_t)blockIdx.x * a.E + threadIdx.x] =
+            wcnt[threadIdx.x][0] + wcnt[threadIdx.x][1] + wcnt[threadIdx.x][2] + wcnt[threadIdx.x][3];
+}
+
+__global__ __launch_bounds__(256) void moe_block_scatter_kernel(MoeRouteArgs a, int n_blocks)
+{
+    __shared__ int wcnt[64][4];
+    __shared__ int before[64], total[64], first[65];
+    const int P = a.T * a.top_k, i = blockIdx.x * 256 + threadIdx.x, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int e = i < P ? a.expert_idx[i] : -1;
+    int rank = 0;
+    for (int ex = 0; ex < a.E; ++ex) {
+        const unsigned long long mask = __ballot(e == ex);
+        if (e == ex) rank = __popcll(mask & ((1ull << lane) - 1ull));
+        if (lane == 0) wcnt[ex][wave] = __popcll(mask);
+    }
+    if (threadIdx.x < a.E) {
+        int b = 0, t = 0;
+        for (int j = 0; j < n_blocks; ++j) {
+            const int c = a.block_hist[(size_t)j * a.E + threadIdx.x];
+            if (j < (int)blockIdx.x) b += c;
+            t += c;
+        }
+        before[threadIdx.x] = b;
+        total[threadIdx.x] = t;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int acc = 0;
+        for (int ex = 0; ex < a.E; ++ex) {
+            first[ex] = acc;
+            acc += total[ex];
+        }
+        first[a.E] = acc;
+    }
+    __syncthreads();
+    if (blockIdx.x == 0 && threadIdx.x <= a.E) a.offsets[threadIdx.x] = first[threadIdx.x];
+    if (e >= 0) {
+        int pos = first[e] + before[e] + rank;
+        for (int w = 0; w < wave; ++w) pos += wcnt[e][w];
+        a.sorted_token[pos] = i / a.top_k;
+        a.pair_pos[i] = pos;
+    }
+}
+
 hipError_t launch_moe_route(const MoeRouteArgs &a, hipStream_t s)
 {
     if (a.T <= 0) return hipSuccess;
@@ -162,6 +227,14 @@ hipError_t launch_moe_route(const MoeRouteArgs &a, hipStream_t s)
     moe_topk_kernel<<<(a.T + 255) / 256, 256, 0, s>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    if (a.block_hist) {
+        const int nb = (a.T * a.top_k + 255) / 256;
+        moe_block_hist_kernel<<<nb, 256, 0, s>>>(a);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        moe_block_scatter_kernel<<<nb, 256, 0, s>>>(a, nb);
+        return hipGetLastError();
+    }
     moe_sort_kernel<<<1, 1024, 0, s>>>(a);
     return hipGetLastError();
 }
@@ -193,6 +266,43 @@ __global__ __launch_bounds__(256) void moe_combine_kernel(const T *__restrict__ 
     }
 }
 
+// bf16 rows with d % 8 == 0: 8 channels (16 bytes) per thread step
+__global__ __launch_bounds__(256) void moe_combine_bf16_vec_kernel(const uint4 *__restrict__ h, const uint4 *__restrict__ eo,
+                                                                   const int32_t *__restrict__ pair_pos,
+                                                                   const float *__restrict__ w, uint4 *__restrict__ out,
+                                                                   int d8, int top_k)
+{
+    const int t = blockIdx.x;
+    int pp[8];
+    float ww[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        pp[k] = k < top_k ? pair_pos[(size_t)t * top_k + k] : 0;
+        ww[k] = k < top_k ? w[(size_t)t * top_k + k] : 0.f;
+    }
+    for (int i = blockIdx.y * 256 + threadIdx.x; i < d8; i += gridDim.y * 256) {
+        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            if (k < top_k) {
+                const uint4 v = eo[(size_t)pp[k] * d8 + i];
+                const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    acc[2 * j] = fmaf(ww[k], bfbits2f(u[j] & 0xffffu), acc[2 * j]);
+                    acc[2 * j + 1] = fmaf(ww[k], bfbits2f(u[j] >> 16), acc[2 * j + 1]);
+                }
+            }
+        const uint4 hv = h[(size_t)t * d8 + i];
+        const uint32_t u[4] = {hv.x, hv.y, hv.z, hv.w};
+        uint32_t o[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            o[j] = pack2bf(bfbits2f(u[j] & 0xffffu) + acc[2 * j], bfbits2f(u[j] >> 16) + acc[2 * j + 1]);
+        out[(size_t)t * d8 + i] = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+}
+
 hipError_t launch_moe_combine(int dtype, const void *h, const void *expert_out,
                               const int32_t *pair_pos, const float *expert_w, void *out, int T,
                               int d, int top_k, hipStream_t s)
@@ -203,6 +313,8 @@ hipError_t launch_moe_combine(int dtype, const void *h, const void *expert_out,
     const dim3 grid((unsigned)T, (unsigned)(slices < 1 ? 1 : slices));
     if (dtype == PD_F32)
         moe_combine_kernel<float><<<grid, 256, 0, s>>>((const float *)h, (const float *)expert_out, pair_pos, expert_w, (float *)out, d, top_k);
+    else if (d % 8 == 0 && T >= 512)
+        moe_combine_bf16_vec_kernel<<<dim3((unsigned)T, 1), 256, 0, s>>>((const uint4 *)h, (const uint4 *)expert_out, pair_pos, expert_w, (uint4 *)out, d / 8, top_k);
     else
         moe_combine_kernel<bf16_t><<<grid, 256, 0, s>>>((const bf16_t *)h, (const bf16_t *)expert_out, pair_pos, expert_w, (bf16_t *)out, d, top_k);
     return hipGetLastError();

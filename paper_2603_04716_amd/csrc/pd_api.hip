@@ -46,7 +46,7 @@ struct pd_layer {
     int ws_tokens;
     char *ws;
     void *y, *qkv, *o, *h, *act, *eo;
-    int32_t *tok_seq, *tok_pos, *tok_slot, *eidx, *sorted_token, *pair_pos, *offsets, *chunk_cu;
+    int32_t *tok_seq, *tok_pos, *tok_slot, *eidx, *sorted_token, *pair_pos, *offsets, *chunk_cu, *block_hist;
     float *logits, *ew;
     int last_rows;
     int call_rows;            // rows of the call in progress (T of a prefill, B of a decode step)
@@ -542,7 +542,7 @@ extern "C" pd_status pd_layer_reserve(pd_layer *L, int32_t max_tokens)
            o_h = carve(T * d * esz), o_act = carve(T * K * F * esz),
            o_eo = carve(E > 0 ? T * K * d * esz : 0), o_seq = carve(T * 4), o_pos = carve(T * 4),
            o_slot = carve(T * 4), o_eidx = carve(T * K * 4), o_sorted = carve(T * K * 4),
-           o_pp = carve(T * K * 4), o_off = carve(65 * 4 + 4), o_log = carve(T * (E > 0 ? E : 1) * 4),
+           o_pp = carve(T * K * 4), o_off = carve(65 * 4 + 4), o_bh = carve(E > 0 ? (T * K / 256 + 1) * (size_t)E * 4 : 0), o_log = carve(T * (E > 0 ? E : 1) * 4),
            o_ew = carve(T * K * 4), o_ccu = carve((T + 1) * 4), o_units = carve(4 * T * 4),
            o_part = carve(decode_chunk_bound(L, max_tokens) * L->cfg.n_q_heads * 130 * sizeof(float));
     // split-K scratch: splits * columns never exceeds 640 tiles * 128 columns + one row of tiles
@@ -576,6 +576,7 @@ extern "C" pd_status pd_layer_reserve(pd_layer *L, int32_t max_tokens)
     L->eidx = (int32_t *)(nw + o_eidx);
     L->sorted_token = (int32_t *)(nw + o_sorted);
     L->pair_pos = (int32_t *)(nw + o_pp);
+    L->block_hist = E > 0 ? (int32_t *)(nw + o_bh) : nullptr;
     L->offsets = (int32_t *)(nw + o_off);
     L->logits = (float *)(nw + o_log);
     L->ew = (float *)(nw + o_ew);
@@ -832,7 +833,7 @@ static pd_status run_tail(pd_layer *L, const void *x, int T, const void *router_
     }
     MoeRouteArgs r;
     r.logits = logits; r.T = T; r.E = E; r.top_k = c.top_k; r.expert_idx = L->eidx; r.expert_w = L->ew;
-    r.sorted_token = L->sorted_token; r.pair_pos = L->pair_pos; r.offsets = L->offsets;
+    r.sorted_token = L->sorted_token; r.pair_pos = L->pair_pos; r.offsets = L->offsets; r.block_hist = L->block_hist;
     STEP("moe_route_sort", launch_moe_route(r, s));
     const int P = T * c.top_k;
     memset(&g, 0, sizeof(g));

@@ -315,6 +315,7 @@ struct MoeRouteArgs {
     int32_t *sorted_token; // [T*top_k] token of each (token, expert) pair, ordered by expert
     int32_t *pair_pos;     // [T, top_k] position of each pair in the sorted order
     int32_t *offsets;      // [E+1]
+    int32_t *block_hist;   // scratch [ceil(T*top_k / 256)][E], or nullptr (then one block sorts alone)
 };
 hipError_t launch_moe_route(const MoeRouteArgs &a, hipStream_t s);
 hipError_t launch_router_logits(int dtype, const void *y, const void *w_router, float *logits,

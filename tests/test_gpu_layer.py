@@ -106,7 +106,10 @@ def test_moe_small(dtype):
     r = I.router_logits(150, 8, seed=9)
     r[3] = 0.25                                  # all-equal logits: ties resolve to experts 0, 1
     r[4, 5] = r[4, 2] = 3.0                      # two-way tie at the top
+    r[5] = -5.0                                  # different logits whose probabilities round to the same double:
+    r[5, 3], r[5, 1], r[5, 6] = 1.0, 1e-30, 2e-30        # a tie for the second place, the lower index wins
     ref, eref = O.prefill(ol, x, cu, router_logits=r, return_experts=True)
+    assert list(eref[5]) == [3, 1]
     got = gl.prefill(x, cu, router_logits=r)
     assert np.array_equal(gl.experts(150), eref)            # integer decisions: bit-exact
     assert relmax(got, ref) <= tol
