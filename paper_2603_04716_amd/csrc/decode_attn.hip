@@ -225,10 +225,14 @@ __global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a, i
     };
 
     if (FP8) {
+        // Two register sets: the loads of the next 64-key step are issued before the current one is
+        // computed, so a wave always has a step's worth of bytes in flight.  The issue is unconditional
+        // - past the end of the chunk the last step is requested again (a cache hit, never used) -
+        // because after a conditional issue the compiler no longer knows which loads are the older
+        // ones and waits for the prefetched step before it starts on the current one.
+        const int k_last = key0 + ((key1 - key0 - 1) >> 6 << 6);     // first key of the last step (key1 > key0)
         // 16 loads of 16 bytes per lane per step: [0..7] keys (block kb, half t -> 2 kb + t), [8..15]
-        // values (channel block db).  Two register sets: the loads of the next step are issued before
-        // the current one is computed, so a wave always has a step's worth of bytes in flight (the
-        // codes are widened operand by operand right before their MFMA, so both sets fit).
+        // values (channel block db); the codes are widened operand by operand right before their MFMA
         u32x4 ra[16], rb[16];
         auto issue = [&](int k, u32x4 (&r)[16]) {
             const uint8_t *kb_ptr = Kp8 + (size_t)(k >> 4) * 2048;
@@ -244,20 +248,24 @@ __global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a, i
                 [&](int kb, int s) { return fp8x8_to_bf16(r[2 * kb + (s >> 1)][2 * (s & 1)], r[2 * kb + (s >> 1)][2 * (s & 1) + 1]); },
                 [&](int vb, int db) { return fp8x8_to_bf16(r[8 + db][2 * vb], r[8 + db][2 * vb + 1]); });
         };
-        int k = key0;
-        if (k < key1) issue(k, ra);
-        while (k < key1) {
-            if (k + 64 < key1) issue(k + 64, rb);
-            __builtin_amdgcn_sched_barrier(0);
-            run(k, ra);
-            k += 64;
-            if (k >= key1) break;
-            if (k + 64 < key1) issue(k + 64, ra);
-            __builtin_amdgcn_sched_barrier(0);
-            run(k, rb);
-            k += 64;
+        if (key0 < key1) {
+            issue(key0, ra);
+            for (int k = key0;; k += 128) {
+                issue(min(k + 64, k_last), rb);
+                __builtin_amdgcn_sched_barrier(0);
+                run(k, ra);
+                if (k + 64 >= key1) break;
+                issue(min(k + 128, k_last), ra);
+                __builtin_amdgcn_sched_barrier(0);
+                run(k + 64, rb);
+                if (k + 128 >= key1) break;
+            }
         }
     } else {
+        // 32 loads of 16 bytes per lane per step.  All of them (32 KB per wave) are issued before
+        // anything consumes them: bytes in flight, not instruction count, is what this kernel lives
+        // on.  (A second register set for the next step does not fit beside the accumulators at two
+        // workgroups per CU, and with 2048 resident waves the memory system is saturated anyway.)
         for (int k = key0; k < key1; k += 64) {
             bf16x8 kf[4][4], vf[2][8];
             const uint16_t *kb_ptr = Kp + (size_t)(k >> 4) * 2048;
@@ -270,8 +278,6 @@ __global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a, i
             for (int vb = 0; vb < 2; ++vb)
 #pragma unroll
                 for (int db = 0; db < 8; ++db) vf[vb][db] = *(const bf16x8 *)(vb_ptr + vb * 4096 + db * 512);
-            // all 32 loads (32 KB per wave) are issued before anything consumes them: bytes in flight,
-            // not instruction count, is what this kernel lives on
             __builtin_amdgcn_sched_barrier(0);
             process(k, [&](int kb, int s) { return kf[kb][s]; }, [&](int vb, int db) { return vf[vb][db]; });
         }
