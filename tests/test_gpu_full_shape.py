@@ -158,3 +158,55 @@ def test_moe_8_experts_full_shape_sampled_rows():
     refd = O.decode_step(ol, xn[sample], [0, 1], oc, router_logits=rn[sample])
     assert relmax(to_np(run.out)[sample], refd) <= TOL["bf16"]
     layer.close()
+
+
+def test_llama8b_8bit_layer_at_the_bench_shapes_sampled_rows():
+    """The 8-bit section of bench.py: 8-bit weights and (above 256 rows) activations, prefill of 4 x 2048
+    tokens, then a decode step of batch 448 over an 8-bit cache at KV 2048 through a replayed graph;
+    the oracle recomputes sampled rows with the same rule.  Bounds: those of the 8-bit-activation
+    layer (6e-2 of the largest output)."""
+    tol = 6e-2
+    cfg = I.CONFIGS["llama8b"]
+    w = I.layer_weights(cfg)
+    layer = H.Layer(cfg, w, a8=True)
+    ol = O.Layer(cfg, O.quantise_layer_weights(w), act8=True)
+    T, l_in = 8192, 2048
+    x = I.hidden(T, cfg["d_model"], seed=10, dtype="bf16")
+    cu = I.uniform_cu_seqlens(T // l_in, l_in)
+    xd = H._dev(x, "bf16")
+    out = torch.empty_like(xd)
+    pd.pd_prefill(layer.h, xd, cu, out)
+    torch.cuda.synchronize()
+    got = to_np(out)
+    assert np.isfinite(got).all()
+    rows = [0, 1, 1500, 3 * l_in + 7, 3 * l_in + 2047]
+    ref = O.prefill(ol, x, cu, rows=rows)
+    for i, r in enumerate(rows):
+        assert relmax(got[r], ref[i]) <= tol, r
+    # decode: batch 448 (8-bit activations too), 8-bit cache
+    B, S = 448, 2048
+    scales = (0.5, 0.125)
+    hkv, hd = cfg["n_kv_heads"], cfg["head_dim"]
+    cache = layer.new_cache(B, S + 8, fp8_scales=scales)
+    sets = [I.kv_fill(hkv, S, hd, seed=40 + j, dtype="bf16") for j in range(4)]
+    dev_sets = [(H._dev(k, "bf16"), H._dev(v, "bf16")) for k, v in sets]
+    for s in range(B):
+        pd.pd_kv_cache_set(cache, s, *dev_sets[s % 4])
+    xb = I.hidden(B, cfg["d_model"], seed=41, dtype="bf16")
+    run = layer.make_decode_step(cache, H._dev(xb, "bf16"), [S] * B, use_graph=True)
+    run()
+    run()
+    torch.cuda.synchronize()
+    gotd = to_np(run.out)
+    rows = [0, 255, 256, 447]
+    # the rule counts the rows of the call, and rows are independent of each other: the oracle
+    # evaluates the sampled rows inside a call of 257 rows (padded with copies of the first)
+    pad = 257 - len(rows)
+    xs = np.concatenate([xb[rows], np.repeat(xb[rows[:1]], pad, axis=0)])
+    ocp = O.KVCache(ol, 257, S + 8, fp8_scales=scales)
+    for j in range(257):
+        ocp.set(j, *sets[(rows[j] if j < len(rows) else rows[0]) % 4])
+    refd = O.decode_step(ol, xs, list(range(257)), ocp)[:len(rows)]
+    for j, r in enumerate(rows):
+        assert relmax(gotd[r], refd[j]) <= tol, r
+    layer.close()
