@@ -774,7 +774,7 @@ static hipError_t run_gemm(const pd_layer *L, GemmArgs g, hipStream_t s)
             }
         }
         if (gemv_mfma_supported(g)) return launch_gemv_mfma(g, s);
-        if (wgemm8_mfma_supported(g)) return launch_wgemm8_mfma(g, s);
+        if (wgemm_mfma_supported(g)) return launch_wgemm_mfma(g, s);
         if (gemm_mfma_supported(g)) return launch_gemm_mfma(g, s);
         return hipErrorInvalidValue;
     }

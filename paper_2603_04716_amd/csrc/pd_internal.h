@@ -182,8 +182,8 @@ hipError_t launch_repack_w8_tiles(const void *src8, void *dst, int n_rows, int K
 hipError_t launch_pack_rows_e4m3_tiles(const void *src, void *dst, int n_rows, int K, hipStream_t s);   // from row-major codes
 // sums the fp32 partials [splits][M][N or 2N packed] in a.splitk_ws in a fixed order and applies a.epilogue
 hipError_t launch_splitk_reduce(const GemmArgs &a, int splits, hipStream_t s);
-bool wgemm8_mfma_supported(const GemmArgs &a);                    // 8-bit weights, 16 < M <= 128
-hipError_t launch_wgemm8_mfma(const GemmArgs &a, hipStream_t s);
+bool wgemm_mfma_supported(const GemmArgs &a);                    // 16 < M <= 128 (8-bit weights) or 32 (bf16)
+hipError_t launch_wgemm_mfma(const GemmArgs &a, hipStream_t s);
 bool gemv_mfma_supported(const GemmArgs &a);                      // bf16, M <= 16
 hipError_t launch_gemv_mfma(const GemmArgs &a, hipStream_t s);
 // per token row: its sequence, its position inside it and (if d_slots) its cache slot

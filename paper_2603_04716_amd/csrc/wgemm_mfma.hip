@@ -1,4 +1,4 @@
-// GEMM over 8-bit weights for a decode batch of 17 .. 128 rows:
+// GEMM for a decode batch of 17 .. 128 rows over 8-bit weights (and of 17 .. 32 rows over bf16 weights):
 //   C[M, N] = epilogue(A[M, K] * (scale[n] * value(code[n, k]))^T), bf16 activations, fp32 accumulation.
 //
 // At these sizes the bf16 GEMM is bound by the weight stream (the gate / up projection at 64 rows
@@ -63,8 +63,10 @@ __device__ __forceinline__ bf16x8 wg_widen(unsigned w0, unsigned w1)
 // conditional request it waits for everything outstanding).  Requests past the end of the split
 // repeat its last chunk: they hit in cache, land in a stage or register set nobody reads again, and
 // keep the number of requests per step constant.
-template <int EPI, int MT, int WM>
-__global__ __launch_bounds__(256 * WM) void wgemm8_kernel(GemmArgs a, int chunks_per_split)
+// W8 = false: the same with bf16 weights from the block pack of wpack_off (two 1 KB blocks per row block
+// and chunk, no widening, no scales).
+template <int EPI, int MT, int WM, bool W8>
+__global__ __launch_bounds__(256 * WM) void wgemm_kernel(GemmArgs a, int chunks_per_split)
 {
     constexpr int NW = 4 * WM;                         // waves: 4 along the weight rows x WM along the batch
     constexpr int MTW = MT / WM;                       // row blocks of 16 batch rows per wave
@@ -72,7 +74,8 @@ __global__ __launch_bounds__(256 * WM) void wgemm8_kernel(GemmArgs a, int chunks
     constexpr int A_BYTES = ROWS * WG_KC * 2;          // one stage
     static_assert(MT % (2 * WM) == 0, "a stage is loaded 8 rows per wave at a time");
     constexpr int A_LD = ROWS / 8 / NW;                // direct-to-LDS instructions per wave per stage
-    constexpr int LPC = A_LD + 2;                      // vector-memory instructions per wave per chunk
+    constexpr int WL = W8 ? 2 : 4;                     // weight loads per wave per chunk (16 bytes per lane each)
+    constexpr int LPC = A_LD + WL;                     // vector-memory instructions per wave per chunk
     static_assert(WG_AHEAD * LPC <= 63, "vector-memory counter range");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
@@ -94,9 +97,11 @@ __global__ __launch_bounds__(256 * WM) void wgemm8_kernel(GemmArgs a, int chunks
     const int n_cols = swiglu ? 2 * a.N : a.N;
     const int last_blk = (n_cols >> 4) - 1;
     const bool blk_ok0 = rowblk[0] <= last_blk, blk_ok1 = rowblk[1] <= last_blk;
-    const size_t blk_bytes = (size_t)(a.K >> 6) * 1024;
-    const uint8_t *wp0 = (const uint8_t *)a.B8 + (size_t)min(rowblk[0], last_blk) * blk_bytes + lane * 16;
-    const uint8_t *wp1 = (const uint8_t *)a.B8 + (size_t)min(rowblk[1], last_blk) * blk_bytes + lane * 16;
+    const size_t chunk_bytes = W8 ? 1024 : 2048;       // one row block's weights of a 64-k chunk
+    const size_t blk_bytes = (size_t)(a.K >> 6) * chunk_bytes;
+    const uint8_t *wbase = (const uint8_t *)(W8 ? a.B8 : a.B);
+    const uint8_t *wp0 = wbase + (size_t)min(rowblk[0], last_blk) * blk_bytes + lane * 16;
+    const uint8_t *wp1 = wbase + (size_t)min(rowblk[1], last_blk) * blk_bytes + lane * 16;
 
     // activation loader: instruction i of wave w moves rows 8 * (NW i + w) .. + 7; lane l owns LDS slot
     // (row, l % 8) and fetches chunk (l % 8) ^ swizzle(row) of that row (MT is even: ROWS / 8 is a
@@ -115,7 +120,7 @@ __global__ __launch_bounds__(256 * WM) void wgemm8_kernel(GemmArgs a, int chunks
     // on that channel.  So the workgroups of an XCD (every 8th one) start at evenly spread chunks and
     // wrap around; the order of the fp32 sums differs per workgroup and is fixed for a given launch shape.
     const int rot = (int)(((blockIdx.x >> 3) * (unsigned)n_chunks) / ((gridDim.x + 7) >> 3));
-    auto issue = [&](int c, int set, u32x4 (&w)[2]) {  // chunk c (relative to c_begin) into stage / register set `set`
+    auto issue = [&](int c, int set, u32x4 (&w)[WL]) { // chunk c (relative to c_begin) into stage / register set `set`
         int cr = min(c, n_chunks - 1) + rot;
         if (cr >= n_chunks) cr -= n_chunks;
         const int cc = c_begin + cr;
@@ -124,8 +129,15 @@ __global__ __launch_bounds__(256 * WM) void wgemm8_kernel(GemmArgs a, int chunks
 #pragma unroll
         for (int i = 0; i < A_LD; ++i)
             __builtin_amdgcn_global_load_lds((gptr_t)(ab + a_off[i]), (lptr_t)(st + (i * NW + wave) * 1024), 16, 0, 0);
-        w[0] = *(const u32x4 *)(wp0 + (size_t)cc * 1024);
-        w[1] = *(const u32x4 *)(wp1 + (size_t)cc * 1024);
+        if (W8) {                                      // one load = both k-steps of a row block
+            w[0] = *(const u32x4 *)(wp0 + (size_t)cc * 1024);
+            w[1] = *(const u32x4 *)(wp1 + (size_t)cc * 1024);
+        } else {                                       // [row block][k-step]
+            w[0] = *(const u32x4 *)(wp0 + (size_t)cc * 2048);
+            w[1] = *(const u32x4 *)(wp0 + (size_t)cc * 2048 + 1024);
+            w[WL - 2] = *(const u32x4 *)(wp1 + (size_t)cc * 2048);
+            w[WL - 1] = *(const u32x4 *)(wp1 + (size_t)cc * 2048 + 1024);
+        }
     };
 
     f32x4 acc[2][MTW];                               // [weight row block][batch row block of this wave]
@@ -140,11 +152,12 @@ __global__ __launch_bounds__(256 * WM) void wgemm8_kernel(GemmArgs a, int chunks
         return *(const bf16x8 *)(smem + set * A_BYTES + r * 128 + wg_swz(r, 4 * ks + kg) * 16);
     };
     // piece p of widening one chunk's weights: [row block p / 2][k-step p % 2]
-    auto widen = [&](const u32x4 (&w)[2], bf16x8 (&o)[2][2], int p) {
-        o[p >> 1][p & 1] = wg_widen(w[p >> 1][2 * (p & 1)], w[p >> 1][2 * (p & 1) + 1]);
+    auto widen = [&](const u32x4 (&w)[WL], bf16x8 (&o)[2][2], int p) {
+        if (W8) o[p >> 1][p & 1] = wg_widen(w[p >> 1][2 * (p & 1)], w[p >> 1][2 * (p & 1) + 1]);
+        else o[p >> 1][p & 1] = __builtin_bit_cast(bf16x8, w[W8 ? 0 : p]);
     };
 
-    u32x4 w[WG_SETS][2];
+    u32x4 w[WG_SETS][WL];
     bf16x8 x0[MTW], x1[MTW];                             // fragments of k-step 0 and 1
     bf16x8 wf[2][2][2];                                // widened weights of this and the next chunk: [c % 2][row block][k-step]
     // start-up: requests in the order of the steady state (the waits below count on it); then chunk 0's
@@ -207,7 +220,7 @@ __global__ __launch_bounds__(256 * WM) void wgemm8_kernel(GemmArgs a, int chunks
 #pragma unroll
             for (int mb = 0; mb < MTW; ++mb) {          // one LDS read, a share of the 32 conversions, two MFMAs, ...
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, (32 + MTW - 1) / MTW, 0);
+                if (W8) __builtin_amdgcn_sched_group_barrier(0x002, (32 + MTW - 1) / MTW, 0);
                 __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -215,12 +228,14 @@ __global__ __launch_bounds__(256 * WM) void wgemm8_kernel(GemmArgs a, int chunks
     }
 
     // ---- epilogue: lane (batch row 16 mb + n16, kg) holds packed weight rows 4 kg + j of each block --
-    const f32x4 sc0 = *(const f32x4 *)(a.b_scale + min(rowblk[0], last_blk) * 16 + 4 * kg);
-    const f32x4 sc1 = *(const f32x4 *)(a.b_scale + min(rowblk[1], last_blk) * 16 + 4 * kg);
+    if (W8) {
+        const f32x4 sc0 = *(const f32x4 *)(a.b_scale + min(rowblk[0], last_blk) * 16 + 4 * kg);
+        const f32x4 sc1 = *(const f32x4 *)(a.b_scale + min(rowblk[1], last_blk) * 16 + 4 * kg);
 #pragma unroll
-    for (int mb = 0; mb < MTW; ++mb) {
-        acc[0][mb] *= sc0;
-        acc[1][mb] *= sc1;
+        for (int mb = 0; mb < MTW; ++mb) {
+            acc[0][mb] *= sc0;
+            acc[1][mb] *= sc1;
+        }
     }
     if (EPI == EPI_PARTIAL) {
         float *P = a.splitk_ws + (size_t)blockIdx.y * a.M * n_cols;
@@ -266,10 +281,13 @@ __global__ __launch_bounds__(256 * WM) void wgemm8_kernel(GemmArgs a, int chunks
     }
 }
 
-bool wgemm8_mfma_supported(const GemmArgs &a)
+bool wgemm_mfma_supported(const GemmArgs &a)
 {
-    if (!a.B8 || !a.b_scale || a.group_offsets || a.a_gather || !a.packed) return false;
-    if (a.M <= 16 || a.M > 128) return false;
+    if ((a.B8 && !a.b_scale) || (!a.B8 && !a.B) || a.group_offsets || a.a_gather || !a.packed) return false;
+    // bf16 weights: only up to 32 rows does this beat the tiled kernels (decode step 0.189 -> 0.184 ms at
+    // 32 rows, but 0.246 -> 0.269 at 64 and 0.367 -> 0.392 at 128: twice the bytes per weight make the
+    // waves wait where the tiled kernel's LDS ring does not)
+    if (a.M <= 16 || a.M > (a.B8 ? 128 : 32)) return false;
     const int64_t n_cols = a.epilogue == EPI_SWIGLU ? 2 * (int64_t)a.N : a.N;
     // whole register-set rounds of chunks; whole 16-row weight blocks; 8-byte stores
     if (a.K % (WG_KC * 8) != 0 || n_cols % 16 != 0 || a.ldb != a.K) return false;
@@ -279,8 +297,8 @@ bool wgemm8_mfma_supported(const GemmArgs &a)
     return true;
 }
 
-template <int MT, int WM>
-static hipError_t launch_wgemm8_t(const GemmArgs &a, hipStream_t s)
+template <int MT, int WM, bool W8>
+static hipError_t launch_wgemm_t(const GemmArgs &a, hipStream_t s)
 {
     const int n_cols = a.epilogue == EPI_SWIGLU ? 2 * a.N : a.N;
     const int wgs = (n_cols + 127) / 128;
@@ -298,7 +316,7 @@ static hipError_t launch_wgemm8_t(const GemmArgs &a, hipStream_t s)
     const dim3 grid((unsigned)wgs, (unsigned)splits);
 #define PD_WG_LAUNCH(EPI)                                                                                    \
     do {                                                                                                     \
-        auto kern = wgemm8_kernel<EPI, MT, WM>;                                                              \
+        auto kern = wgemm_kernel<EPI, MT, WM, W8>;                                                           \
         static bool attr_set = false;                                                                        \
         if (!attr_set) {                                                                                     \
             hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, \
@@ -323,14 +341,15 @@ static hipError_t launch_wgemm8_t(const GemmArgs &a, hipStream_t s)
     return hipGetLastError();
 }
 
-hipError_t launch_wgemm8_mfma(const GemmArgs &a, hipStream_t s)
+hipError_t launch_wgemm_mfma(const GemmArgs &a, hipStream_t s)
 {
+    if (!a.B8) return launch_wgemm_t<2, 1, false>(a, s);    // bf16 weights: up to 32 rows only
     // 4 waves, or 8 with the batch rows split between two waves per SIMD (fewer registers each; the
     // measured times are the same)
-    if (a.M <= 32) return launch_wgemm8_t<2, 1>(a, s);
-    if (a.M <= 64) return launch_wgemm8_t<4, 2>(a, s);
-    if (a.M <= 96) return launch_wgemm8_t<6, 1>(a, s);
-    return launch_wgemm8_t<8, 2>(a, s);
+    if (a.M <= 32) return launch_wgemm_t<2, 1, true>(a, s);
+    if (a.M <= 64) return launch_wgemm_t<4, 2, true>(a, s);
+    if (a.M <= 96) return launch_wgemm_t<6, 1, true>(a, s);
+    return launch_wgemm_t<8, 2, true>(a, s);
 }
 
 }  // namespace pd
