@@ -287,6 +287,18 @@ typedef struct pd_head pd_head; /* opaque */
 pd_status pd_head_create(int32_t d_model, int32_t vocab, float rms_eps, pd_dtype dtype,
                          const void *g_final, const void *w_embed, const void *w_lm,
                          int32_t max_rows, pd_head **out);
+
+/*
+ * The same head with the vocabulary projection held as 8-bit weights exactly like a layer's
+ * projections in pd_layer_create_w8 (E4M3 codes, one power-of-two scale per vocabulary row;
+ * pd_lm_head streams the codes for calls of up to 128 rows and uses a bf16 copy of the quantised
+ * weights above that); the embedding table is kept as given.
+ * Errors: as pd_head_create, plus PD_ERR_DTYPE unless dtype is bf16, d_model a multiple of 64 and
+ * vocab a multiple of 16.
+ */
+pd_status pd_head_create_w8(int32_t d_model, int32_t vocab, float rms_eps, pd_dtype dtype,
+                         const void *g_final, const void *w_embed, const void *w_lm,
+                         int32_t max_rows, pd_head **out);
 void pd_head_destroy(pd_head *head);
 pd_status pd_embed(pd_head *head, const int32_t *token_ids, int32_t T, void *hidden, void *stream);
 pd_status pd_lm_head(pd_head *head, const void *hidden, int32_t T, void *logits, void *stream);

@@ -23,7 +23,7 @@ PD_F32, PD_BF16 = 0, 1
 EXPORTS = [
     "pd_layer_create", "pd_layer_create_w8", "pd_layer_create_w8a8", "pd_quantize_rows_e4m3", "pd_gemm_e4m3", "pd_layer_destroy", "pd_layer_reserve", "pd_kv_cache_create", "pd_kv_cache_create_fp8",
     "pd_kv_cache_destroy", "pd_kv_cache_set", "pd_kv_cache_set_len", "pd_kv_cache_len",
-    "pd_kv_cache_set_lens", "pd_kv_cache_get", "pd_profile_enable", "pd_profile_read", "pd_stream_copy", "pd_head_create", "pd_head_destroy", "pd_embed", "pd_lm_head", "pd_prefill", "pd_prefill_chunk", "pd_decode_step", "pd_last_expert_choice", "pd_allocate",
+    "pd_kv_cache_set_lens", "pd_kv_cache_get", "pd_profile_enable", "pd_profile_read", "pd_stream_copy", "pd_head_create", "pd_head_create_w8", "pd_head_destroy", "pd_embed", "pd_lm_head", "pd_prefill", "pd_prefill_chunk", "pd_decode_step", "pd_last_expert_choice", "pd_allocate",
     "pd_fifo_replay", "pd_mm1_sojourn", "pd_fifo_replay_batched", "pd_prefill_throughput_dp", "pd_mg1_sojourn", "pd_kv_transfer_overhead", "pd_allocate_stages", "pd_status_string", "pd_last_error",
 ]
 
@@ -201,10 +201,12 @@ def pd_profile_read(layer, max_entries=64):
     return [(names[i].decode(), float(ms[i])) for i in range(n.value)]
 
 
-def pd_head_create(d_model, vocab, rms_eps, dtype, g_final, w_lm, w_embed=None, max_rows=256):
-    """dtype: "f32" / "bf16"; tensors are device tensors of that dtype."""
+def pd_head_create(d_model, vocab, rms_eps, dtype, g_final, w_lm, w_embed=None, max_rows=256, w8=False):
+    """dtype: "f32" / "bf16"; tensors are device tensors of that dtype; w8: hold w_lm as 8-bit codes with
+    per-row power-of-two scales (pd_head_create_w8)."""
     h = C.c_void_p()
-    _check(lib.pd_head_create(C.c_int32(d_model), C.c_int32(vocab), C.c_float(rms_eps),
+    create = lib.pd_head_create_w8 if w8 else lib.pd_head_create
+    _check(create(C.c_int32(d_model), C.c_int32(vocab), C.c_float(rms_eps),
                               C.c_int(PD_BF16 if dtype == "bf16" else PD_F32), _ptr(g_final),
                               None if w_embed is None else _ptr(w_embed), _ptr(w_lm), C.c_int32(max_rows), C.byref(h)))
     return h

@@ -1247,21 +1247,41 @@ struct pd_head {
     float eps;
     size_t esz;
     bool packed;        // bf16 with shapes the matrix-core kernels take: w_lm is in the block layout
-    void *g, *w_lm, *w_embed, *y;
+    bool w8;            // w_lm also held as E4M3 codes with one power-of-two scale per vocabulary row
+    void *g, *w_lm, *w_embed, *y, *q_lm;
+    float *s_lm;
 };
 
 static void free_head(pd_head *h)
 {
     if (!h) return;
-    void *ptrs[] = {h->g, h->w_lm, h->w_embed, h->y};
+    void *ptrs[] = {h->g, h->w_lm, h->w_embed, h->y, h->q_lm, h->s_lm};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     delete h;
 }
 
+static pd_status head_create(int32_t d_model, int32_t vocab, float rms_eps, pd_dtype dtype,
+                             const void *g_final, const void *w_embed, const void *w_lm,
+                             int32_t max_rows, bool w8, pd_head **out);
+
 extern "C" pd_status pd_head_create(int32_t d_model, int32_t vocab, float rms_eps, pd_dtype dtype,
                                     const void *g_final, const void *w_embed, const void *w_lm,
                                     int32_t max_rows, pd_head **out)
+{
+    return head_create(d_model, vocab, rms_eps, dtype, g_final, w_embed, w_lm, max_rows, false, out);
+}
+
+extern "C" pd_status pd_head_create_w8(int32_t d_model, int32_t vocab, float rms_eps, pd_dtype dtype,
+                                       const void *g_final, const void *w_embed, const void *w_lm,
+                                       int32_t max_rows, pd_head **out)
+{
+    return head_create(d_model, vocab, rms_eps, dtype, g_final, w_embed, w_lm, max_rows, true, out);
+}
+
+static pd_status head_create(int32_t d_model, int32_t vocab, float rms_eps, pd_dtype dtype,
+                             const void *g_final, const void *w_embed, const void *w_lm,
+                             int32_t max_rows, bool w8, pd_head **out)
 {
     if (!g_final || !w_lm || !out || max_rows <= 0) {
         set_error("pd_head_create: NULL argument or max_rows <= 0");
@@ -1280,6 +1300,12 @@ extern "C" pd_status pd_head_create(int32_t d_model, int32_t vocab, float rms_ep
     h->esz = dtype == PD_F32 ? 4 : 2;
     h->packed = dtype == PD_BF16 && d_model % 64 == 0 && vocab % 16 == 0 &&
                 (int64_t)d_model * 2 * vocab < (1ll << 32);
+    h->w8 = w8;
+    if (w8 && !h->packed) {
+        set_error("pd_head_create_w8: needs a bf16 head with d_model a multiple of 64 and vocab a multiple of 16");
+        delete h;
+        return PD_ERR_DTYPE;
+    }
     const size_t wbytes = (size_t)vocab * d_model * h->esz;
 #define HEAD_TRY(expr)                                                                 \
     do {                                                                               \
@@ -1295,7 +1321,15 @@ extern "C" pd_status pd_head_create(int32_t d_model, int32_t vocab, float rms_ep
     HEAD_TRY(hipMalloc(&h->w_lm, wbytes));
     HEAD_TRY(hipMalloc(&h->y, (size_t)max_rows * d_model * h->esz));
     HEAD_TRY(hipMemcpy(h->g, g_final, d_model * h->esz, hipMemcpyDeviceToDevice));
-    if (h->packed) {
+    if (h->w8) {
+        HEAD_TRY(hipMalloc(&h->q_lm, (size_t)vocab * d_model));
+        HEAD_TRY(hipMalloc((void **)&h->s_lm, sizeof(float) * (size_t)vocab));
+        w8_row_scale_kernel<<<(vocab + 3) / 4, 256>>>(h->s_lm, (const uint16_t *)w_lm, nullptr, vocab, d_model);
+        HEAD_TRY(hipGetLastError());
+        pack_weight_w8_kernel<<<2048, 256>>>((uint4 *)h->w_lm, (uint8_t *)h->q_lm, (const uint4 *)w_lm, nullptr,
+                                             h->s_lm, vocab, d_model);
+        HEAD_TRY(hipGetLastError());
+    } else if (h->packed) {
         pack_weight_kernel<<<2048, 256>>>((uint4 *)h->w_lm, (const uint4 *)w_lm, nullptr, vocab, d_model);
         HEAD_TRY(hipGetLastError());
     } else {
@@ -1352,9 +1386,14 @@ extern "C" pd_status pd_lm_head(pd_head *h, const void *hidden, int32_t T, void 
     g.A = h->y; g.lda = h->d; g.B = h->w_lm; g.ldb = h->d; g.C = logits; g.ldc = h->vocab;
     g.M = T; g.N = h->vocab; g.K = h->d; g.epilogue = EPI_NONE; g.n_groups = 1;
     g.packed = h->packed ? 1 : 0;
+    if (h->w8) {
+        g.B8 = h->q_lm;
+        g.b_scale = h->s_lm;
+    }
     if (h->packed) {
         // packed weights are only understood by the matrix-core kernels
         if (gemv_mfma_supported(g)) HIP_TRY(launch_gemv_mfma(g, s), PD_ERR_DEVICE);
+        else if (wgemm_mfma_supported(g)) HIP_TRY(launch_wgemm_mfma(g, s), PD_ERR_DEVICE);
         else if (gemm_mfma_supported(g)) HIP_TRY(launch_gemm_mfma(g, s), PD_ERR_DEVICE);
         else {
             set_error("pd_lm_head: shape not covered by the matrix-core kernels");

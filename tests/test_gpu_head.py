@@ -37,6 +37,40 @@ def test_lm_head_rows_and_shapes(dtype, d, V, T):
     pd.pd_head_destroy(h)
 
 
+@pytest.mark.parametrize("d,V", [(256, 1040), (512, 4112)])
+@pytest.mark.parametrize("T", [1, 16, 17, 64, 100, 128, 130])
+def test_lm_head_with_8bit_weights(d, V, T):
+    """pd_head_create_w8: the oracle is the head on the row-quantised vocabulary matrix; the codes are
+    streamed up to 128 rows (skinny kernel to 16 rows, the wide one above where d is a multiple of
+    512), the bf16 copy of the same weights serves the rest.  The embedding is not quantised."""
+    hw = I.head_weights(d, V, seed=d + V + 1, dtype="bf16", std=0.05)
+    dev = {k: to_dev(v, "bf16") for k, v in hw.items()}
+    h = pd.pd_head_create(d, V, 1e-6, "bf16", dev["g_final"], dev["w_lm"], dev["w_embed"], 256, w8=True)
+    x = I.hidden(T, d, seed=T + 3, dtype="bf16")
+    ref = O.lm_head(x, hw["g_final"], O.quantise_rows(hw["w_lm"])[0])
+    logits = torch.empty((T, V), dtype=torch.bfloat16, device="cuda")
+    pd.pd_lm_head(h, to_dev(x, "bf16"), logits)
+    torch.cuda.synchronize()
+    got = to_np(logits)
+    assert relmax(got, ref) <= TOL["bf16"]
+    assert max(relmax(got[t], ref[t]) for t in range(T)) <= 2 * TOL["bf16"]
+    ids = torch.tensor([0, V - 1, 7], dtype=torch.int32, device="cuda")
+    out = torch.empty((3, d), dtype=torch.bfloat16, device="cuda")
+    pd.pd_embed(h, ids, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(out), hw["w_embed"][[0, V - 1, 7]])
+    pd.pd_head_destroy(h)
+
+
+def test_8bit_head_needs_bf16_matrix_core_shapes():
+    for dtype, d, V in (("f32", 256, 1024), ("bf16", 100, 320), ("bf16", 256, 1001)):
+        hw = I.head_weights(d, V, seed=1, dtype=dtype)
+        dev = {k: to_dev(v, dtype) for k, v in hw.items()}
+        with pytest.raises(pd.PdError) as e:
+            pd.pd_head_create(d, V, 1e-6, dtype, dev["g_final"], dev["w_lm"], None, 16, w8=True)
+        assert e.value.status == pd.PD_ERR_DTYPE
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_embedding_bit_exact_and_out_of_range_ids_give_zero_rows(dtype):
     d, V = 192, 777
