@@ -233,6 +233,24 @@ def test_moe_prefill_with_8bit_activations(T, given_logits):
     gl.close()
 
 
+def test_moe_with_8bit_activations_and_empty_experts():
+    """All tokens on experts 1 and 2 (the others get no rows), one expert with fewer rows than a row tile."""
+    cfg = small(4, 2, 256, 384, n_experts=4, top_k=2)
+    w = I.layer_weights(cfg, std=0.04, with_router=True, seed=5)
+    ol, gl = O.Layer(cfg, O.quantise_layer_weights(w), act8=True), GpuLayer(cfg, w, a8=True)
+    T = 400
+    cu = np.array([0, T], np.int32)
+    x = I.hidden(T, cfg["d_model"], seed=28, dtype="bf16")
+    rl = np.full((T, 4), -20.0, np.float32)
+    rl[:, 1], rl[:, 2] = 3.0, 2.0
+    rl[:7, 3] = 5.0                                 # seven tokens also pick expert 3 (instead of 2)
+    ref, eref = O.prefill(ol, x, cu, router_logits=rl, return_experts=True)
+    got = gl.prefill(x, cu, router_logits=rl)
+    assert np.array_equal(gl.experts(T), eref)
+    assert relmax(got, ref) <= TOL_A8
+    gl.close()
+
+
 def test_w8a8_needs_dimensions_in_multiples_of_128():
     for cfg in (small(d=320, F=512), small(F=576)):
         w = I.layer_weights(cfg, with_router=cfg.get("n_experts", 0) > 0)
