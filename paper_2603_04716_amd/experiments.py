@@ -187,13 +187,15 @@ def run_prefill_on(layer, cfg):
         "steps_ms": {n: round(t, 4) for n, t in steps}}}
 
 
-def run_chunk(l_in=8192, chunks=(256, 512, 1024, 2048, 4096, 8192), reps=5):
+def run_chunk(l_in=8192, chunks=(256, 512, 1024, 2048, 4096, 8192), reps=5, fp8=False):
     """Prefill of one l_in-token prompt chunk by chunk (pd_prefill_chunk against the growing cached
-    prefix): throughput against the chunk size."""
-    cfg, layer = _layer("llama8b")
+    prefix): throughput against the chunk size.  fp8: 8-bit weights, 8-bit activations in chunks of
+    more than 256 tokens, 8-bit cache."""
+    cfg = I.CONFIGS["llama8b"]
+    layer = H.Layer(cfg, I.layer_weights(cfg), a8=fp8)
     x = H._dev(I.hidden(l_in, cfg["d_model"], seed=10, dtype="bf16"), "bf16")
     out = torch.empty_like(x)
-    cache = layer.new_cache(1, l_in)
+    cache = layer.new_cache(1, l_in, fp8_scales=(0.5, 0.125) if fp8 else None)
     pd.pd_layer_reserve(layer.h, l_in)
     fl = H.prefill_flops(cfg, [l_in])
     pts = []
@@ -221,7 +223,8 @@ def run_chunk(l_in=8192, chunks=(256, 512, 1024, 2048, 4096, 8192), reps=5):
     # the same prompt in one unchunked call, for reference
     ms_full = layer.time_prefill(x, [0, l_in], iters=5, warmup=2)
     layer.close()
-    return {"experiment": "chunked prefill: throughput vs chunk size", "l_in": l_in, "points": pts,
+    return {"experiment": "chunked prefill: throughput vs chunk size" + (" (8-bit weights, activations, cache)" if fp8 else ""),
+            "l_in": l_in, "points": pts,
             "unchunked_ms_per_layer": round(ms_full, 4)}
 
 
@@ -626,7 +629,8 @@ def main():
     which = sys.argv[1] if len(sys.argv) > 1 else "prefill"
     fn = {"prefill": run_prefill, "longctx": run_longctx, "queue": run_queue, "moe": run_moe,
           "chunk": run_chunk, "stack": run_stack, "queue_fixed": run_queue_fixed, "fp8kv": run_fp8kv, "kvxfer": run_kvxfer, "w8": run_w8, "a8": run_a8,
-          "stack_fp8": lambda: run_stack(batches=(1, 8, 64, 256, 448), fp8=True)}[which]
+          "stack_fp8": lambda: run_stack(batches=(1, 8, 64, 256, 448), fp8=True),
+          "chunk_fp8": lambda: run_chunk(fp8=True)}[which]
     print(json.dumps(fn()))
 
 
