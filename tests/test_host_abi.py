@@ -157,3 +157,31 @@ def test_stage_allocation_bit_exact_against_oracle():
             tuple(A.allocate_stages(tp, l_in, l_out, work, tps, rounding))
     with pytest.raises(pd.PdError):
         pd.pd_allocate_stages(1e5, 100.0, 10.0, [1.0, -2.0], [5.0, 5.0])
+
+
+def test_device_entry_points_reject_bad_arguments_before_touching_a_device():
+    """Argument checks come first, so they hold on a machine without a GPU: NULL handles and pointers,
+    impossible shapes (the non-NULL pointers below are never dereferenced)."""
+    import ctypes as C
+    lib = pd.lib
+    fake = C.c_void_p(0x1000)
+    ffake = C.cast(fake, C.POINTER(C.c_float))
+    h = C.c_void_p()
+    assert lib.pd_layer_create(None, None, C.byref(h)) == pd.PD_ERR_INVALID_ARG
+    assert lib.pd_layer_create_w8(None, None, C.byref(h)) == pd.PD_ERR_INVALID_ARG
+    assert lib.pd_layer_create_w8a8(None, None, C.byref(h)) == pd.PD_ERR_INVALID_ARG
+    assert lib.pd_quantize_rows_e4m3(None, C.c_int32(4), C.c_int32(8), fake, ffake, None) == pd.PD_ERR_INVALID_ARG
+    assert lib.pd_quantize_rows_e4m3(fake, C.c_int32(4), C.c_int32(12), fake, ffake, None) == pd.PD_ERR_INVALID_ARG
+    assert lib.pd_quantize_rows_e4m3(fake, C.c_int32(-1), C.c_int32(8), fake, ffake, None) == pd.PD_ERR_INVALID_ARG
+    args = lambda M, N, K: (fake, ffake, fake, ffake, C.c_int32(M), C.c_int32(N), C.c_int32(K), fake, None)
+    assert lib.pd_gemm_e4m3(None, ffake, fake, ffake, C.c_int32(4), C.c_int32(16), C.c_int32(128), fake, None) == pd.PD_ERR_INVALID_ARG
+    for M, N, K in ((0, 16, 128), (4, 24, 128), (4, 16, 192), (4, 16, 64)):
+        assert lib.pd_gemm_e4m3(*args(M, N, K)) == pd.PD_ERR_SHAPE
+    assert b"multiple of 128" in lib.pd_last_error()
+    for create in (lib.pd_head_create, lib.pd_head_create_w8):
+        assert create(C.c_int32(64), C.c_int32(32), C.c_float(1e-6), C.c_int(pd.PD_BF16), None, None, fake,
+                      C.c_int32(4), C.byref(h)) == pd.PD_ERR_INVALID_ARG
+        assert create(C.c_int32(0), C.c_int32(32), C.c_float(1e-6), C.c_int(pd.PD_BF16), fake, None, fake,
+                      C.c_int32(4), C.byref(h)) == pd.PD_ERR_SHAPE
+    assert lib.pd_lm_head(None, fake, C.c_int32(1), fake, None) == pd.PD_ERR_INVALID_ARG
+    assert lib.pd_embed(None, fake, C.c_int32(1), fake, None) == pd.PD_ERR_INVALID_ARG
