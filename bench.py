@@ -83,8 +83,11 @@ def fp8_section(cfg, weights, x, cu, kd, vd):
         run = layer.make_decode_step(cache, xdec[:B].contiguous(), [KV_LEN] * B)
         ms = H.median([run() for _ in range(7)])
         tpot.append(N_LAYERS * ms * 1e-3)
+        # bytes a step must read: codes of the weights (the bf16 copy for 129 .. 256 rows), 8-bit cache
+        by = H.decode_bytes(cfg, [KV_LEN] * B, esz=2 if 128 < B <= 256 else 1, kv_esz=1)
         curve.append({"batch": B, "ms_per_layer": round(ms, 4), "tpot_ms": round(N_LAYERS * ms, 3),
-                      "tok_s": round(B / (N_LAYERS * ms * 1e-3), 1)})
+                      "tok_s": round(B / (N_LAYERS * ms * 1e-3), 1),
+                      "hbm_frac": round(by / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)})
     tp_hat = T / (N_LAYERS * t_pre * 1e-3)
     alloc = pd.pd_allocate(5e6 / 60.0, float(L_IN), L_OUT, TTFT_SLO, TPOT_SLO, tp_hat, batches, tpot)
     star = next(c for c in curve if c["batch"] == alloc["decode_batch"])
