@@ -1026,7 +1026,13 @@ static pd_status prefill_common(pd_layer *L, const pd_tokens *tk, pd_kv_cache *c
                                  (prefix[(size_t)q] + tk->cu_seqlens[q + 1] - tk->cu_seqlens[q] + 63) / 64 * 64;
         const int vt_ld = pad[(size_t)n];
         const size_t vt_bytes = (size_t)c.n_kv_heads * c.head_dim * vt_ld * 2;
-        const size_t need = chunk ? 2 * vt_bytes : vt_bytes;
+        int n_split = 1, max_keys = 0;
+        if (chunk) {
+            for (int q = 0; q < n; ++q)
+                max_keys = std::max(max_keys, prefix[(size_t)q] + tk->cu_seqlens[q + 1] - tk->cu_seqlens[q]);
+            n_split = attn_chunk_splits(a, max_keys);
+        }
+        const size_t need = chunk ? 2 * vt_bytes + attn_chunk_split_bytes(a, n_split) : vt_bytes;
         if (need > L->vt_cap) {
             HIP_TRY(hipDeviceSynchronize(), PD_ERR_DEVICE);
             if (L->vt) (void)hipFree(L->vt);
@@ -1045,7 +1051,7 @@ static pd_status prefill_common(pd_layer *L, const pd_tokens *tk, pd_kv_cache *c
             a.kv_fp8 = cache->fp8; a.k_scale = (float)cache->k_scale; a.v_scale = (float)cache->v_scale;
             STEP("prefill_attention",
                  launch_attn_chunk_mfma(a, L->d_slots, (uint16_t *)((char *)L->vt + vt_bytes), (uint16_t *)L->vt,
-                                        vt_ld, L->d_pad_cu, s));
+                                        vt_ld, L->d_pad_cu, n_split, (float *)((char *)L->vt + 2 * vt_bytes), s));
         } else {
             STEP("prefill_attention", launch_attn_prefill_mfma(a, (uint16_t *)L->vt, vt_ld, L->d_pad_cu, s));
         }

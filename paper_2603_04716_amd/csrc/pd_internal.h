@@ -257,8 +257,13 @@ hipError_t launch_attn_prefill_mfma(const AttnArgs &a, uint16_t *vt, int vt_ld, 
 // and the values (transposed, vt[g][d][pad_cu[s] + pos], zero past the end) of positions
 // 0 .. prefix[s] + L_s - 1 of every sequence's slot out of the cache, then runs the prefill kernel
 // with the prefix offsets.  pad_cu: padded key-row starts (multiples of 64) of the sequences.
+// n_split >= 2 divides every query block's keys over that many workgroups (fp32 partial results in
+// part, attn_chunk_split_bytes(a, n_split) bytes, merged by a second kernel); attn_chunk_splits
+// picks the count for the call's grid and its longest key range.
 hipError_t launch_attn_chunk_mfma(const AttnArgs &a, const int32_t *d_slots, uint16_t *kx, uint16_t *vt,
-                                  int vt_ld, const int32_t *pad_cu, hipStream_t s);
+                                  int vt_ld, const int32_t *pad_cu, int n_split, float *part, hipStream_t s);
+int attn_chunk_splits(const AttnArgs &a, int max_keys);
+size_t attn_chunk_split_bytes(const AttnArgs &a, int n_split);
 
 hipError_t launch_stream_copy(void *dst, const void *src, size_t n_vec16, hipStream_t s);
 // out[t, :] = table[ids[t], :] (rows of row_bytes bytes, a multiple of 4); ids outside 0 .. n_rows-1 give zeros

@@ -79,6 +79,19 @@ def test_bf16_chunked_prefill_matrix_core_path(hq, hkv):
     gl.close()
 
 
+@pytest.mark.parametrize("hq,hkv", [(4, 1), (8, 4), (6, 2)])
+def test_bf16_chunked_prefill_long_prefix_splits_the_keys(hq, hkv):
+    """Few query blocks behind a long prefix: the key tiles of a query block are divided over
+    several workgroups and merged by a second kernel.  The second and third calls split four ways
+    (2100 and 2300 keys at most); the short sequences leave some splits with one tile or none.
+    Groups of 4 and 2 heads run two heads per workgroup, the group of 3 one."""
+    cfg = I.small_config(dtype="bf16", d_model=256, n_q_heads=hq, n_kv_heads=hkv, head_dim=128, d_ff=256)
+    lens = [2300, 1100, 150]
+    plan = [[1200, 500, 0], [900, 77, 50], [200, 523, 100]]
+    ol, gl, oc, gc, xs = run_plan(cfg, lens, plan, [1, 2, 0], cap=2304)
+    gl.close()
+
+
 def test_bf16_chunked_prefill_moe():
     cfg = I.small_config(dtype="bf16", d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=128, d_ff=256,
                          n_experts=4, top_k=2)
