@@ -155,6 +155,34 @@ def test_llama8b_chunk_against_cached_prefix_sampled_rows():
     layer.close()
 
 
+def test_llama8b_small_chunk_behind_a_long_prefix_sampled_rows():
+    """Full shape, the launch the chunk sweep times: one 512-token chunk behind 3584 cached tokens
+    (64 eight-wave workgroups unsplit, so the keys are split four ways).  Reference rows as in the
+    test above: sampled rows of the oracle's prefill of the whole sequence."""
+    cfg = I.CONFIGS["llama8b"]
+    w = I.layer_weights(cfg)
+    layer = H.Layer(cfg, w)
+    pre, chk = 3584, 512
+    xs = I.hidden(pre + chk, cfg["d_model"], seed=75, dtype="bf16")
+    cache = layer.new_cache(1, 4096)
+    xp = H._dev(xs[:pre], "bf16")
+    pd.pd_prefill(layer.h, xp, [0, pre], torch.empty_like(xp), cache, [0])
+    xc = H._dev(xs[pre:], "bf16")
+    out_c = torch.empty_like(xc)
+    pd.pd_prefill_chunk(layer.h, xc, [0, chk], [0], cache, out_c)
+    torch.cuda.synchronize()
+    got = to_np(out_c)
+    assert np.isfinite(got).all()
+    assert pd.pd_kv_cache_len(cache, 0) == 4096
+    rows_in_chunk = [0, 31, 127, 128, 300, 511]
+    ref = O.prefill(O.Layer(cfg, w), xs, np.array([0, pre + chk], np.int32), rows=[pre + r for r in rows_in_chunk])
+    mine = got[rows_in_chunk]
+    assert relmax(mine, ref) <= TOL["bf16"]
+    for j in range(len(rows_in_chunk)):
+        assert relmax(mine[j], ref[j]) <= 2 * TOL["bf16"], rows_in_chunk[j]
+    layer.close()
+
+
 @pytest.mark.parametrize("hq,hkv", [(4, 1), (8, 2), (2, 2), (8, 1), (16, 1)])
 def test_bf16_multi_token_decode_steps(hq, hkv):
     """Chunks of at most 8 tokens over a blocked cache take the decode attention kernel with units
