@@ -248,6 +248,42 @@ hipError_t launch_write_ints(int32_t *dst, const int32_t *host_src, int n, hipSt
     return hipSuccess;
 }
 
+// Up to four short arrays in one launch: array k takes c.v[start[k] .. start[k + 1]).
+__global__ void write_ints4_kernel(IntDst4 d, IntChunk c)
+{
+    const int i = threadIdx.x;
+    if (i >= d.start[4]) return;
+    const int k = (i >= d.start[1]) + (i >= d.start[2]) + (i >= d.start[3]);
+    d.dst[k][i - d.start[k]] = c.v[i];
+}
+
+hipError_t launch_write_ints4(int32_t *const dst[4], const int32_t *const host_src[4], const int n[4],
+                              hipStream_t s)
+{
+    const int total = n[0] + n[1] + n[2] + n[3];
+    if (total > 256) {                             // too long for one launch: one array at a time
+        for (int k = 0; k < 4; ++k) {
+            if (n[k] == 0) continue;
+            hipError_t e = launch_write_ints(dst[k], host_src[k], n[k], s);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    }
+    if (total == 0) return hipSuccess;
+    IntDst4 d;
+    IntChunk c;
+    int at = 0;
+    for (int k = 0; k < 4; ++k) {
+        d.dst[k] = dst[k];
+        d.start[k] = at;
+        for (int i = 0; i < n[k]; ++i) c.v[at + i] = host_src[k][i];
+        at += n[k];
+    }
+    d.start[4] = at;
+    write_ints4_kernel<<<1, 256, 0, s>>>(d, c);
+    return hipGetLastError();
+}
+
 __global__ void scatter_ints_kernel(int32_t *dst, IntChunk c, int n)
 {
     int i = threadIdx.x;

@@ -932,9 +932,19 @@ static pd_status prefill_common(pd_layer *L, const pd_tokens *tk, pd_kv_cache *c
     hipStream_t s = (hipStream_t)stream;
     L->prof_names.clear();
 
-    HIP_TRY(launch_write_ints(L->d_cu, tk->cu_seqlens, n + 1, s), PD_ERR_DEVICE);
-    if (keep) HIP_TRY(launch_write_ints(L->d_slots, tk->slots, n, s), PD_ERR_DEVICE);
-    if (chunk) HIP_TRY(launch_write_ints(L->d_prefix, prefix.data(), n, s), PD_ERR_DEVICE);
+    // padded key-row starts of the sequences (multiples of 64) for the matrix-core attention's
+    // transposed-V scratch (and, chunked, the gathered key rows)
+    std::vector<int32_t> pad((size_t)n + 1);
+    pad[0] = 0;
+    for (int q = 0; q < n; ++q)
+        pad[(size_t)q + 1] = pad[(size_t)q] +
+                             (prefix[(size_t)q] + tk->cu_seqlens[q + 1] - tk->cu_seqlens[q] + 63) / 64 * 64;
+    {
+        int32_t *const dst[4] = {L->d_cu, L->d_pad_cu, L->d_slots, L->d_prefix};
+        const int32_t *const src[4] = {tk->cu_seqlens, pad.data(), tk->slots, prefix.data()};
+        const int cnt[4] = {n + 1, n + 1, keep ? n : 0, chunk ? n : 0};
+        HIP_TRY(launch_write_ints4(dst, src, cnt, s), PD_ERR_DEVICE);
+    }
     HIP_TRY(launch_token_meta(L->d_cu, keep ? L->d_slots : nullptr, chunk ? L->d_prefix : nullptr, n, T,
                               L->tok_seq, L->tok_pos, L->tok_slot, s),
             PD_ERR_DEVICE);
@@ -1017,13 +1027,6 @@ static pd_status prefill_common(pd_layer *L, const pd_tokens *tk, pd_kv_cache *c
             set_error("pd_prefill_chunk: blocked cache without the matrix-core attention path");
             return PD_ERR_SHAPE;
         }
-        // padded key-row starts of the sequences (multiples of 64) for the transposed-V scratch
-        // (and, chunked, the gathered key rows)
-        std::vector<int32_t> pad((size_t)n + 1);
-        pad[0] = 0;
-        for (int q = 0; q < n; ++q)
-            pad[(size_t)q + 1] = pad[(size_t)q] +
-                                 (prefix[(size_t)q] + tk->cu_seqlens[q + 1] - tk->cu_seqlens[q] + 63) / 64 * 64;
         const int vt_ld = pad[(size_t)n];
         const size_t vt_bytes = (size_t)c.n_kv_heads * c.head_dim * vt_ld * 2;
         int n_split = 1, max_keys = 0;
@@ -1045,7 +1048,6 @@ static pd_status prefill_common(pd_layer *L, const pd_tokens *tk, pd_kv_cache *c
             }
             L->vt_cap = need;
         }
-        HIP_TRY(launch_write_ints(L->d_pad_cu, pad.data(), n + 1, s), PD_ERR_DEVICE);
         if (chunk) {
             a.prefix = L->d_prefix; a.k_cache = cache->k; a.v_cache = cache->v; a.max_len = cache->plane_len;
             a.kv_fp8 = cache->fp8; a.k_scale = (float)cache->k_scale; a.v_scale = (float)cache->v_scale;

@@ -131,6 +131,10 @@ constexpr int kMetaChunk = 255;  // ints carried by value per meta-kernel launch
 struct IntChunk {
     int32_t v[256];
 };
+struct IntDst4 {
+    int32_t *dst[4];
+    int32_t start[5];   // array k is v[start[k] .. start[k + 1])
+};
 
 enum Epilogue { EPI_NONE = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2, EPI_PARTIAL = 3 /* internal: fp32 split-K partials */ };
 
@@ -192,6 +196,9 @@ hipError_t launch_token_meta(const int32_t *d_cu, const int32_t *d_slots, const 
                              int n_seqs, int T, int32_t *tok_seq, int32_t *tok_pos, int32_t *tok_slot,
                              hipStream_t s);
 hipError_t launch_write_ints(int32_t *dst, const int32_t *host_src, int n, hipStream_t s);
+// Up to four arrays (n[k] may be 0) in one launch when they hold 256 ints or fewer together.
+hipError_t launch_write_ints4(int32_t *const dst[4], const int32_t *const host_src[4], const int n[4],
+                              hipStream_t s);
 // dst[idx[i]] = val[i] for i < n (host arrays, carried by value in the kernel arguments)
 hipError_t launch_scatter_ints(int32_t *dst, const int32_t *host_idx, const int32_t *host_val, int n,
                                hipStream_t s);
