@@ -334,6 +334,58 @@ hipError_t launch_token_meta(const int32_t *d_cu, const int32_t *d_slots, const 
     return hipGetLastError();
 }
 
+// The sequence arrays of a prefill call and the per-token metadata in one launch: block 0 stores
+// the arrays like write_ints4_kernel (0 = sequence starts, 1 = padded starts, 2 = slots or empty,
+// 3 = prefixes or empty), and every thread derives its token's entries from the copy of the arrays in
+// the kernel arguments, so nothing waits for those stores.
+__global__ void prefill_meta_kernel(IntDst4 d, IntChunk c, int n_seqs, int T, int32_t *__restrict__ tok_seq,
+                                    int32_t *__restrict__ tok_pos, int32_t *__restrict__ tok_slot)
+{
+    if (blockIdx.x == 0) {
+        const int i = threadIdx.x;
+        if (i < d.start[4]) {
+            const int k = (i >= d.start[1]) + (i >= d.start[2]) + (i >= d.start[3]);
+            d.dst[k][i - d.start[k]] = c.v[i];
+        }
+    }
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= T) return;
+    int lo = 0, hi = n_seqs;  // largest s with cu[s] <= t; cu = c.v[0 .. n_seqs]
+    while (hi - lo > 1) {
+        int mid = (lo + hi) >> 1;
+        if (c.v[mid] <= t) lo = mid; else hi = mid;
+    }
+    const bool has_slots = d.start[3] > d.start[2], has_prefix = d.start[4] > d.start[3];
+    tok_seq[t] = lo;
+    tok_pos[t] = t - c.v[lo] + (has_prefix ? c.v[d.start[3] + lo] : 0);
+    if (has_slots) tok_slot[t] = c.v[d.start[2] + lo];
+}
+
+hipError_t launch_prefill_meta(int32_t *const dst[4], const int32_t *const host_src[4], const int n[4],
+                               int n_seqs, int T, int32_t *tok_seq, int32_t *tok_pos, int32_t *tok_slot,
+                               hipStream_t s)
+{
+    const int total = n[0] + n[1] + n[2] + n[3];
+    if (total > 256 || T <= 0) {                   // too many sequences for the kernel arguments: separate launches
+        hipError_t e = launch_write_ints4(dst, host_src, n, s);
+        if (e != hipSuccess) return e;
+        return launch_token_meta(dst[0], n[2] ? dst[2] : nullptr, n[3] ? dst[3] : nullptr, n_seqs, T, tok_seq,
+                                 tok_pos, tok_slot, s);
+    }
+    IntDst4 d;
+    IntChunk c;
+    int at = 0;
+    for (int k = 0; k < 4; ++k) {
+        d.dst[k] = dst[k];
+        d.start[k] = at;
+        for (int i = 0; i < n[k]; ++i) c.v[at + i] = host_src[k][i];
+        at += n[k];
+    }
+    d.start[4] = at;
+    prefill_meta_kernel<<<(T + 255) / 256, 256, 0, s>>>(d, c, n_seqs, T, tok_seq, tok_pos, tok_slot);
+    return hipGetLastError();
+}
+
 __global__ void decode_meta_kernel(const int32_t *__restrict__ slots, int B, int32_t *len,
                                    int32_t *pos)
 {

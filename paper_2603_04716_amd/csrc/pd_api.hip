@@ -943,11 +943,8 @@ static pd_status prefill_common(pd_layer *L, const pd_tokens *tk, pd_kv_cache *c
         int32_t *const dst[4] = {L->d_cu, L->d_pad_cu, L->d_slots, L->d_prefix};
         const int32_t *const src[4] = {tk->cu_seqlens, pad.data(), tk->slots, prefix.data()};
         const int cnt[4] = {n + 1, n + 1, keep ? n : 0, chunk ? n : 0};
-        HIP_TRY(launch_write_ints4(dst, src, cnt, s), PD_ERR_DEVICE);
+        HIP_TRY(launch_prefill_meta(dst, src, cnt, n, T, L->tok_seq, L->tok_pos, L->tok_slot, s), PD_ERR_DEVICE);
     }
-    HIP_TRY(launch_token_meta(L->d_cu, keep ? L->d_slots : nullptr, chunk ? L->d_prefix : nullptr, n, T,
-                              L->tok_seq, L->tok_pos, L->tok_slot, s),
-            PD_ERR_DEVICE);
     STEP("rmsnorm_attn", norm_for_gemm(L, tk->hidden, L->g_attn, L->y, T, s));
     GemmArgs g;
     memset(&g, 0, sizeof(g));

@@ -199,6 +199,11 @@ hipError_t launch_write_ints(int32_t *dst, const int32_t *host_src, int n, hipSt
 // Up to four arrays (n[k] may be 0) in one launch when they hold 256 ints or fewer together.
 hipError_t launch_write_ints4(int32_t *const dst[4], const int32_t *const host_src[4], const int n[4],
                               hipStream_t s);
+// The same four arrays of a prefill call (0 = sequence starts [n_seqs + 1], 1 = padded starts, 2 = slots
+// or none, 3 = prefixes or none) together with the per-token sequence index / position / slot.
+hipError_t launch_prefill_meta(int32_t *const dst[4], const int32_t *const host_src[4], const int n[4],
+                               int n_seqs, int T, int32_t *tok_seq, int32_t *tok_pos, int32_t *tok_slot,
+                               hipStream_t s);
 // dst[idx[i]] = val[i] for i < n (host arrays, carried by value in the kernel arguments)
 hipError_t launch_scatter_ints(int32_t *dst, const int32_t *host_idx, const int32_t *host_val, int n,
                                hipStream_t s);
