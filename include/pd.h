@@ -87,8 +87,8 @@ typedef struct pd_kv_cache pd_kv_cache; /* opaque */
  * Creates a layer on the current device.  The weights are copied (and repacked) into memory the
  * layer owns; the caller's buffers may be released once the call returns (the call synchronises).
  * Errors: PD_ERR_INVALID_ARG (NULL), PD_ERR_SHAPE (non-positive sizes, odd head_dim, n_q_heads not
- * a multiple of n_kv_heads, top_k > n_experts, n_experts > 64, head_dim > 256), PD_ERR_DTYPE,
- * PD_ERR_OOM, PD_ERR_DEVICE.
+ * a multiple of n_kv_heads, top_k > n_experts, top_k > 8, n_experts > 64, head_dim > 256),
+ * PD_ERR_DTYPE, PD_ERR_OOM, PD_ERR_DEVICE.
  */
 pd_status pd_layer_create(const pd_layer_config *cfg, const pd_layer_weights *w, pd_layer **out);
 /*
@@ -96,8 +96,9 @@ pd_status pd_layer_create(const pd_layer_config *cfg, const pd_layer_weights *w,
  * not the norm gains, not the router) is held as OCP E4M3 codes with one scale per output row,
  * the smallest power of two s with max|w_row| / s <= 448 (1 for a row of zeros); the layer then
  * computes with w' = s * value(code) everywhere (activations stay bf16).  Decode is bound by
- * reading the weights (Section 2.1), so dense calls of up to 128 rows stream the codes (half the
- * bytes) and widen them in registers; larger calls use a bf16 copy of w' and give the same results
+ * reading the weights (Introduction: decode is bound by memory bandwidth), so dense calls of up
+ * to 128 rows stream the codes (half the bytes) and widen them in registers; larger calls use a
+ * bf16 copy of w' and give the same results
  * as a layer created from w' with pd_layer_create.  All other calls take such a layer unchanged.
  * Errors: as pd_layer_create, plus PD_ERR_DTYPE if the layer is not bf16 with d_model, d_ff and the
  * head dimensions multiples of 64.
@@ -105,8 +106,8 @@ pd_status pd_layer_create(const pd_layer_config *cfg, const pd_layer_weights *w,
 pd_status pd_layer_create_w8(const pd_layer_config *cfg, const pd_layer_weights *w, pd_layer **out);
 
 /*
- * 8-bit weights as above and, where the layer is bound by the matrix cores (Section 2.1: prefill),
- * 8-bit activations too: in every call of more than 256 rows (T of a prefill call, B of a decode
+ * 8-bit weights as above and, where the layer is bound by the matrix cores (Introduction: prefill
+ * is compute-bound), 8-bit activations too: in every call of more than 256 rows (T of a prefill call, B of a decode
  * call) each of the four projections first quantises its bf16 input rows (the normalised hidden
  * state, the attention output, the SwiGLU output) like pd_quantize_rows_e4m3 and multiplies codes
  * by codes in E4M3 on the matrix cores with fp32 accumulation; the sums are multiplied by the two
@@ -135,14 +136,22 @@ pd_status pd_quantize_rows_e4m3(const void *x, int32_t n_rows, int32_t n_cols, v
  *   c[m, n] = a_scales[m] * b_scales[n] * sum_k value(a_codes[m, k]) * value(b_codes[n, k])
  * a_codes [M, K] and b_codes [N, K] are row-major OCP E4M3 bytes (device), the scales fp32 (device),
  * c [M, N] bf16 (device); products and sums in fp32 on the matrix cores, one rounding to bf16.
- * Allocates temporary device memory and returns after the work on stream has finished.
+ * A synchronous helper for tests and tools, unlike every other call that takes a stream: it
+ * allocates temporary device memory, returns after the work on stream has finished, and must not
+ * be called while the stream is being captured into a graph.
  * Errors: PD_ERR_INVALID_ARG (NULL pointer), PD_ERR_SHAPE (M < 1, N not a multiple of 16, K not a
  * multiple of 128, an operand of 4 GiB or more), PD_ERR_DEVICE.
  */
 pd_status pd_gemm_e4m3(const void *a_codes, const float *a_scales, const void *b_codes,
                        const float *b_scales, int32_t M, int32_t N, int32_t K, void *c, void *stream);
 
-/* Pre-sizes the layer's workspace for calls of up to max_tokens rows (prefill T or decode B). */
+/*
+ * Pre-sizes the layer's workspace for calls of up to max_tokens rows (prefill T or decode B).
+ * A call with more rows than reserved so far (and a prefill whose attention scratch has to grow)
+ * synchronises the device, frees the old workspace and allocates a larger one: a HIP graph
+ * captured over this layer before that holds the freed addresses and must not be replayed again.
+ * Reserve for the largest call first, then capture.
+ */
 pd_status pd_layer_reserve(pd_layer *layer, int32_t max_tokens);
 
 /*
@@ -156,7 +165,8 @@ pd_status pd_kv_cache_create(const pd_layer *layer, int32_t max_seqs, int32_t ma
  * bits, no infinities, largest finite value 448) with one static scale for keys and one for
  * values: an element x is held as the code nearest to x / scale (ties to the even mantissa,
  * saturating at +-448) and read as scale * value(code).  Decode is bound by reading the cache
- * (Section 2.1's memory-bound decode stage), so halving its bytes halves that part of a step.
+ * (the memory-bandwidth-bound decode stage of the Introduction), so halving its bytes halves that
+ * part of a step.
  * Everything attention reads from such a cache (pd_decode_step, pd_prefill_chunk, pd_kv_cache_get)
  * is the quantised value; pd_prefill's own attention works on the fresh keys and values and only
  * its stores quantise.  pd_kv_cache_set / _get still take and return tensors in the layer's dtype.

@@ -53,12 +53,10 @@ def _i32(a):
 class Layer:
     """One decoder layer: configuration + fp32 weights (dict of numpy arrays)."""
 
-    def __init__(self, cfg: dict, weights: dict, act8: bool = False):
-        """act8: in calls of more than ACT8_ROWS rows every projection sees its input rows rounded to
-        bf16 and quantised like act_quantise_rows (pass weights from quantise_layer_weights with it)."""
+    def __init__(self, cfg: dict, weights: dict):
         self.cfg = dict(cfg)
         self.c = _Cfg(cfg["d_model"], cfg["n_q_heads"], cfg["n_kv_heads"], cfg["head_dim"],
-                      cfg["d_ff"], cfg.get("n_experts", 0), cfg.get("top_k", 0), int(bool(act8)),
+                      cfg["d_ff"], cfg.get("n_experts", 0), cfg.get("top_k", 0), 0,
                       float(cfg.get("rms_eps", 1e-6)), float(cfg.get("rope_base", 10000.0)))
         self.w = {}
         self.cw = _Wts()
@@ -73,6 +71,14 @@ class Layer:
     @property
     def d(self):
         return self.c.d_model
+
+    def call_cfg(self, act8: bool):
+        """The configuration of one call.  act8 is the caller's statement that THIS call quantises the
+        input rows of its four projections (rounded to bf16, then like act_quantise_rows); pass weights
+        from quantise_layer_weights with it.  Which calls of a layer quantise is for the caller to say."""
+        c = _Cfg.from_buffer_copy(self.c)
+        c.act8 = int(bool(act8))
+        return c
 
 
 class KVCache:
@@ -105,7 +111,7 @@ class KVCache:
 
 
 def prefill(layer: Layer, x, cu_seqlens, router_logits=None, rows=None, cache: KVCache = None,
-            slots=None, return_experts=False):
+            slots=None, return_experts=False, act8=False):
     x = _f32(x)
     T, d = x.shape
     cu = _i32(cu_seqlens)
@@ -117,7 +123,7 @@ def prefill(layer: Layer, x, cu_seqlens, router_logits=None, rows=None, cache: K
     k = max(layer.c.top_k, 1)
     eidx = np.full((n_out, k), -1, np.int32)
     sl = None if slots is None else _i32(slots)
-    rc = lib().orc_prefill(C.byref(layer.c), C.byref(layer.cw), _p(x), C.c_int(T), C.c_int(n_seqs),
+    rc = lib().orc_prefill(C.byref(layer.call_cfg(act8)), C.byref(layer.cw), _p(x), C.c_int(T), C.c_int(n_seqs),
                            _p(cu), _p(rl), _p(rows_a), C.c_int(n_out), _p(sl),
                            _p(cache.k) if cache is not None and sl is not None else None,
                            _p(cache.v) if cache is not None and sl is not None else None,
@@ -129,7 +135,7 @@ def prefill(layer: Layer, x, cu_seqlens, router_logits=None, rows=None, cache: K
     return (out, eidx) if return_experts else out
 
 
-def decode_step(layer: Layer, x, slots, cache: KVCache, router_logits=None, return_experts=False):
+def decode_step(layer: Layer, x, slots, cache: KVCache, router_logits=None, return_experts=False, act8=False):
     x = _f32(x)
     B, d = x.shape
     sl = _i32(slots)
@@ -137,7 +143,7 @@ def decode_step(layer: Layer, x, slots, cache: KVCache, router_logits=None, retu
     out = np.zeros((B, d), np.float32)
     k = max(layer.c.top_k, 1)
     eidx = np.full((B, k), -1, np.int32)
-    rc = lib().orc_decode_step(C.byref(layer.c), C.byref(layer.cw), _p(x), C.c_int(B), _p(sl),
+    rc = lib().orc_decode_step(C.byref(layer.call_cfg(act8)), C.byref(layer.cw), _p(x), C.c_int(B), _p(sl),
                                _p(cache.k), _p(cache.v), _p(cache.lens), C.c_int(cache.max_len),
                                _p(rl), _p(out), _p(eidx), *cache.q())
     if rc == -2:
@@ -148,7 +154,7 @@ def decode_step(layer: Layer, x, slots, cache: KVCache, router_logits=None, retu
 
 
 def prefill_chunk(layer: Layer, x, cu_seqlens, slots, cache: KVCache, router_logits=None,
-                  return_experts=False):
+                  return_experts=False, act8=False):
     """Chunked prefill: sequence s continues cache slot slots[s]; its rows take the positions
     behind the cached prefix, are appended to the cache and attend over prefix + chunk."""
     x = _f32(x)
@@ -160,7 +166,7 @@ def prefill_chunk(layer: Layer, x, cu_seqlens, slots, cache: KVCache, router_log
     out = np.zeros((T, d), np.float32)
     k = max(layer.c.top_k, 1)
     eidx = np.full((T, k), -1, np.int32)
-    rc = lib().orc_prefill_chunk(C.byref(layer.c), C.byref(layer.cw), _p(x), C.c_int(T), C.c_int(n_seqs),
+    rc = lib().orc_prefill_chunk(C.byref(layer.call_cfg(act8)), C.byref(layer.cw), _p(x), C.c_int(T), C.c_int(n_seqs),
                                  _p(cu), _p(rl), _p(sl), _p(cache.k), _p(cache.v), _p(cache.lens),
                                  C.c_int(cache.max_len), _p(out), _p(eidx), *cache.q())
     if rc == -2:
@@ -215,9 +221,6 @@ def quantise_rows(W):
     scales = np.empty(n_rows, np.float32)
     lib().orc_quantise_rows(_p(W), C.c_int(n_rows), C.c_int(K), _p(scales))
     return W, scales.reshape(W.shape[:-1])
-
-
-ACT8_ROWS = 256   # calls with more rows than this quantise their activations in an act8 layer
 
 
 def act_quantise_rows(x):
@@ -297,10 +300,10 @@ def route(logits, top_k):
     return idx, wgt
 
 
-def ffn_block(layer: Layer, h, router_logits=None):
+def ffn_block(layer: Layer, h, router_logits=None, act8=False):
     h = _f32(h)
     rl = None if router_logits is None else _f32(router_logits)
     out = np.empty_like(h)
-    lib().orc_ffn_block(C.byref(layer.c), C.byref(layer.cw), _p(h), C.c_int(h.shape[0]), _p(rl),
+    lib().orc_ffn_block(C.byref(layer.call_cfg(act8)), C.byref(layer.cw), _p(h), C.c_int(h.shape[0]), _p(rl),
                         _p(out), None)
     return out

@@ -39,11 +39,9 @@ typedef struct {
     int32_t d_model, n_q_heads, n_kv_heads, head_dim, d_ff;
     int32_t n_experts; /* 0 = dense FFN */
     int32_t top_k;
-    int32_t act8;      /* 8-bit activations in calls of more than ORC_ACT8_ROWS rows (see act_quantise_row) */
+    int32_t act8;      /* != 0: this call quantises the input rows of its projections (see act_quantise_row) */
     double rms_eps, rope_base;
 } orc_config;
-
-#define ORC_ACT8_ROWS 256
 
 typedef struct {
     const float *g_attn;   /* [d] */
@@ -147,11 +145,11 @@ void orc_quantise_rows(float *W, int n_rows, int K, float *scales)
 }
 
 /*
- * 8-bit activations: in a call of more than ORC_ACT8_ROWS rows every projection (q/k/v, output, gate/up,
- * down) sees its input row replaced by s * fp8(v / s), s as for a weight row.  The input rows are
- * bf16 tensors in the layer this oracle checks, and a code is an integer decided by floating point,
- * so the row is first rounded to bf16 (nearest even): the decision is taken in the precision the
- * kernel takes it in.
+ * 8-bit activations: a call whose configuration has act8 set gives every projection (q/k/v, output,
+ * gate/up, down) its input row replaced by s * fp8(v / s), s as for a weight row.  Whether a call
+ * quantises is the caller's statement, call by call; nothing here decides it.  The tensor being
+ * quantised is a bf16 tensor (bf16 is the storage precision of the activations of an 8-bit layer),
+ * so the row is first rounded to bf16 (nearest even) and the codes are those of the stored values.
  */
 static float round_bf16(float x)
 {
@@ -420,7 +418,7 @@ int orc_prefill(const orc_config *c, const orc_weights *w, const float *x, int T
                 double v_scale)
 {
     int d = c->d_model, Hq = c->n_q_heads, Hkv = c->n_kv_heads, hd = c->head_dim;
-    const int q8 = c->act8 && T > ORC_ACT8_ROWS;   /* 8-bit activations in this call */
+    const int q8 = c->act8 != 0;   /* 8-bit activations in this call */
     if (Hkv <= 0 || Hq % Hkv != 0 || hd % 2 != 0) return -1;
     if (cu_seqlens[0] != 0 || cu_seqlens[n_seqs] != T) return -1;
     if (slots && rows) return -1;
@@ -536,7 +534,7 @@ int orc_decode_step(const orc_config *c, const orc_weights *w, const float *x, i
                     int kv_fp8, double k_scale, double v_scale)
 {
     int d = c->d_model, Hq = c->n_q_heads, Hkv = c->n_kv_heads, hd = c->head_dim;
-    const int q8 = c->act8 && B > ORC_ACT8_ROWS;   /* 8-bit activations in this call */
+    const int q8 = c->act8 != 0;   /* 8-bit activations in this call */
     if (Hkv <= 0 || Hq % Hkv != 0 || hd % 2 != 0) return -1;
     size_t dq = (size_t)Hq * hd, dkv = (size_t)Hkv * hd;
     for (int b = 0; b < B; ++b)
@@ -603,7 +601,7 @@ int orc_prefill_chunk(const orc_config *c, const orc_weights *w, const float *x,
                       int32_t *expert_idx, int kv_fp8, double k_scale, double v_scale)
 {
     int d = c->d_model, Hq = c->n_q_heads, Hkv = c->n_kv_heads, hd = c->head_dim;
-    const int q8 = c->act8 && T > ORC_ACT8_ROWS;   /* 8-bit activations in this call */
+    const int q8 = c->act8 != 0;   /* 8-bit activations in this call */
     if (Hkv <= 0 || Hq % Hkv != 0 || hd % 2 != 0) return -1;
     if (!slots || cu_seqlens[0] != 0 || cu_seqlens[n_seqs] != T) return -1;
     size_t dq = (size_t)Hq * hd, dkv = (size_t)Hkv * hd;
@@ -703,5 +701,5 @@ void orc_ffn_block(const orc_config *c, const orc_weights *w, const float *h, in
                       router_logits ? router_logits + (size_t)t * c->n_experts : NULL,
                       out + (size_t)t * c->d_model,
                       expert_idx ? expert_idx + (size_t)t * c->top_k : NULL,
-                      c->act8 && T > ORC_ACT8_ROWS);
+                      c->act8 != 0);
 }

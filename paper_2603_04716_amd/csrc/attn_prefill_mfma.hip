@@ -494,15 +494,16 @@ static bool attn_two_heads(const AttnArgs &a) { return (a.Hq / a.Hkv) % 2 == 0; 
 
 static hipError_t attn_kernel_attrs()
 {
-    static bool attr_set = false;
-    if (attr_set) return hipSuccess;
+    static OncePerDevice attr;
+    int dev;
+    if (!attr.need(&dev)) return hipSuccess;
     const void *fns[4] = {(const void *)attn_prefill_mfma_kernel<false, 4>, (const void *)attn_prefill_mfma_kernel<true, 4>,
                           (const void *)attn_prefill_mfma_kernel<false, 8>, (const void *)attn_prefill_mfma_kernel<true, 8>};
     for (const void *f : fns) {
         hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * ASTAGE);
         if (e != hipSuccess) return e;
     }
-    attr_set = true;
+    attr.mark(dev);
     return hipSuccess;
 }
 

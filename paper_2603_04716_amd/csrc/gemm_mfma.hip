@@ -456,12 +456,13 @@ static hipError_t launch_cfg(const GemmArgs &a, hipStream_t s, int splits = 1)
 #define LAUNCH(EPI)                                                                              \
     do {                                                                                         \
         auto kern = gemm_mfma_kernel<BM, BN, WAVES_M, WAVES_N, EPI, NS, F8>;                         \
-        static bool attr_set = false;                                                            \
-        if (!attr_set) {                                                                         \
+        static OncePerDevice attr;                                                               \
+        int dev;                                                                                 \
+        if (attr.need(&dev)) {                                                                   \
             hipError_t e = hipFuncSetAttribute((const void *)kern,                               \
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem); \
             if (e != hipSuccess) return e;                                                       \
-            attr_set = true;                                                                     \
+            attr.mark(dev);                                                                      \
         }                                                                                        \
         kern<<<grid, block, smem, s>>>(a, tiles_m, tiles_n, kt_per);                             \
     } while (0)

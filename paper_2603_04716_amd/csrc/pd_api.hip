@@ -989,18 +989,41 @@ static pd_status prefill_common(pd_layer *L, const pd_tokens *tk, pd_kv_cache *c
             }
         }
         const int nu = (int)u_slot.size();
-        // partial rows are [chunk][kv head][16 columns]; the reserved buffer is counted in [chunk][q head] rows
-        const int chunk_keys = pick_chunk_keys(u_keys, c.n_kv_heads,
-                                               decode_chunk_bound(L, T) * c.n_q_heads / ((size_t)c.n_kv_heads * 16));
+        // Partial results are rows of 130 floats, [chunk][kv head][16 columns]; the workspace part holds
+        // what a one-token decode step of ws_tokens rows needs.  Every unit needs at least one chunk, so a
+        // call of many short sequences can need more than that: the rest comes from the attention scratch
+        // buffer (unused on this path), grown on demand like for an ordinary prefill.
+        const size_t rows_per_chunk = (size_t)c.n_kv_heads * 16;
+        const size_t ws_rows = decode_chunk_bound(L, L->ws_tokens) * c.n_q_heads;
+        size_t max_chunks = ws_rows / rows_per_chunk;
+        const size_t floor_chunks = (size_t)nu + (size_t)(8192 / c.n_kv_heads + 1);
+        if (max_chunks < floor_chunks) max_chunks = floor_chunks;
+        const int chunk_keys = pick_chunk_keys(u_keys, c.n_kv_heads, max_chunks);
         std::vector<int32_t> ccu((size_t)nu + 1);
         ccu[0] = 0;
         for (int u = 0; u < nu; ++u)
             ccu[(size_t)u + 1] = ccu[(size_t)u] + (u_pos[(size_t)u] + u_cnt[(size_t)u] + chunk_keys - 1) / chunk_keys;
         const int total_chunks = ccu[(size_t)nu];
-        // partial rows: [chunk][kv head][16 columns]; the reserved buffer is counted in [chunk][q head] rows
-        if ((size_t)total_chunks * c.n_kv_heads * 16 > decode_chunk_bound(L, T) * c.n_q_heads) {
+        if ((size_t)total_chunks > max_chunks) {
             set_error("pd_prefill_chunk: internal chunk bound exceeded (%d chunks)", total_chunks);
             return PD_ERR_DEVICE;
+        }
+        float *part = L->dec_part;
+        if ((size_t)total_chunks * rows_per_chunk > ws_rows) {
+            const size_t need = (size_t)total_chunks * rows_per_chunk * 130 * sizeof(float);
+            if (need > L->vt_cap) {
+                HIP_TRY(hipDeviceSynchronize(), PD_ERR_DEVICE);
+                if (L->vt) (void)hipFree(L->vt);
+                L->vt = nullptr;
+                L->vt_cap = 0;
+                hipError_t e = hipMalloc(&L->vt, need);
+                if (e != hipSuccess) {
+                    set_error("pd_prefill_chunk: cannot allocate %zu bytes of attention scratch", need);
+                    return PD_ERR_OOM;
+                }
+                L->vt_cap = need;
+            }
+            part = (float *)L->vt;
         }
         const size_t ws_t = (size_t)L->ws_tokens;
         HIP_TRY(launch_write_ints(L->chunk_cu, ccu.data(), nu + 1, s), PD_ERR_DEVICE);
@@ -1016,8 +1039,8 @@ static pd_status prefill_common(pd_layer *L, const pd_tokens *tk, pd_kv_cache *c
         da.chunk_cu = L->chunk_cu; da.chunk_keys = chunk_keys; da.total_chunks = total_chunks;
         da.k_cache = cache->k; da.v_cache = cache->v; da.max_len_pad = cache->plane_len;
         da.fp8 = cache->fp8; da.k_scale = (float)cache->k_scale; da.v_scale = (float)cache->v_scale;
-        da.part_o = L->dec_part;
-        da.part_ml = L->dec_part + (size_t)total_chunks * c.n_kv_heads * 16 * 128;
+        da.part_o = part;
+        da.part_ml = part + (size_t)total_chunks * c.n_kv_heads * 16 * 128;
         STEP("prefill_attention", launch_decode_attn_mfma(da, s));
     } else if (chunk || (L->use_mfma && attn_prefill_mfma_supported(a))) {
         if (chunk && !attn_prefill_mfma_supported(a)) {

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "pd.h"
 
 namespace pd {
@@ -342,5 +344,23 @@ hipError_t launch_moe_combine(int dtype, const void *h, const void *expert_out,
                               int d, int top_k, hipStream_t s);
 
 void set_error(const char *fmt, ...);
+
+// "Done once per device" flag for per-kernel attributes (hipFuncSetAttribute applies to the current
+// device only).  Threads that race on the first call of a device both do the work, which is harmless.
+struct OncePerDevice {
+    std::atomic<uint64_t> done{0};
+    // true if the caller has to do the work for the current device (devices beyond 63: every time)
+    bool need(int *dev_out)
+    {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess) dev = 64;
+        *dev_out = dev;
+        return dev >= 64 || !((done.load(std::memory_order_acquire) >> dev) & 1u);
+    }
+    void mark(int dev)
+    {
+        if (dev < 64) done.fetch_or(1ull << dev, std::memory_order_release);
+    }
+};
 
 }  // namespace pd

@@ -317,12 +317,13 @@ static hipError_t launch_wgemm_t(const GemmArgs &a, hipStream_t s)
 #define PD_WG_LAUNCH(EPI)                                                                                    \
     do {                                                                                                     \
         auto kern = wgemm_kernel<EPI, MT, WM, W8>;                                                           \
-        static bool attr_set = false;                                                                        \
-        if (!attr_set) {                                                                                     \
+        static OncePerDevice attr;                                                                           \
+        int dev;                                                                                             \
+        if (attr.need(&dev)) {                                                                               \
             hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, \
                                                (int)smem);                                                   \
             if (e != hipSuccess) return e;                                                                   \
-            attr_set = true;                                                                                 \
+            attr.mark(dev);                                                                                  \
         }                                                                                                    \
         kern<<<grid, 256 * WM, smem, s>>>(a, per * WG_SETS);                                                 \
     } while (0)

@@ -1,6 +1,7 @@
 """GPU parity of 8-bit activations (pd_layer_create_w8a8, pd_quantize_rows_e4m3, pd_gemm_e4m3): the row
 quantiser is compared byte for byte with the oracle's, the product on given codes to the bf16 rounding
-of its output, and the layer against the oracle with the same rule.  In the layer the two sides do
+of its output, and the layer against the oracle, each oracle call being told whether the library's
+call quantises (the library's rule: calls of more than 256 rows).  In the layer the two sides do
 not quantise the same numbers: what they quantise (attention output, normalised hidden state, SwiGLU
 output) already differs by the bf16 bound, a code has 3 mantissa bits, so a few per cent of the
 activations land one code apart; TOL_A8 is the bound derived for that."""
@@ -20,6 +21,10 @@ pytestmark = pytest.mark.gpu
 # element), i.e. sqrt(p) * 0.09 ~ 0.027 of a projection's output, through two projections in a row
 # (attention output -> h -> FFN) and relative to the largest output: 6e-2.
 TOL_A8 = 6e-2
+# The library's rule (pd.h, pd_layer_create_w8a8): a call of more than this many rows quantises the
+# inputs of its projections.  The oracle knows no such rule; every oracle call below is told whether
+# its call quantises.
+A8_ROWS = 256
 
 
 def small(hq=4, hkv=2, d=256, F=512, **kw):
@@ -127,7 +132,7 @@ def test_gemm_e4m3_argument_errors():
 
 def both(cfg, std=0.05, seed=None):
     w = I.layer_weights(cfg, seed=seed, std=std)
-    return O.Layer(cfg, O.quantise_layer_weights(w), act8=True), GpuLayer(cfg, w, a8=True)
+    return O.Layer(cfg, O.quantise_layer_weights(w)), GpuLayer(cfg, w, a8=True)
 
 
 @pytest.mark.parametrize("T,cu", [(257, [0, 257]), (300, [0, 130, 131, 300]), (700, [0, 5, 400, 700]), (1100, [0, 1100])])
@@ -142,13 +147,13 @@ def test_prefill_with_8bit_activations(T, cu, d, F, hq, hkv):
     n = len(cu) - 1
     x = I.hidden(T, d, seed=8, dtype="bf16")
     oc, gc = O.KVCache(ol, n, 1104), gl.cache(n, 1104)
-    ref = O.prefill(ol, x, cu, cache=oc, slots=list(range(n)))
+    ref = O.prefill(ol, x, cu, cache=oc, slots=list(range(n)), act8=T > A8_ROWS)
     got = gl.prefill(x, cu, cache=gc, slots=list(range(n)))
     assert relmax(got, ref) <= TOL_A8
     rms = float(np.sqrt(np.mean((got - ref) ** 2)) / np.sqrt(np.mean(ref ** 2)))
     assert rms <= TOL_A8 / 3
     xn = I.hidden(n, d, seed=81, dtype="bf16")
-    ref = O.decode_step(ol, xn, list(range(n)), oc)
+    ref = O.decode_step(ol, xn, list(range(n)), oc, act8=n > A8_ROWS)
     got = gl.decode(xn, list(range(n)), gc)
     assert relmax(got, ref) <= TOL["bf16"]         # keys and values come from a projection of exact inputs
     gl.close()
@@ -167,7 +172,7 @@ def test_decode_step_of_more_than_256_rows_quantises_too():
         oc.set(i, k, v)
         pd.pd_kv_cache_set(gc, i, to_dev(k, "bf16"), to_dev(v, "bf16"))
     xn = I.hidden(B, cfg["d_model"], seed=53, dtype="bf16")
-    ref = O.decode_step(ol, xn, list(range(B)), oc)
+    ref = O.decode_step(ol, xn, list(range(B)), oc, act8=B > A8_ROWS)
     got = gl.decode(xn, list(range(B)), gc)
     assert relmax(got, ref) <= TOL_A8
     gl.close()
@@ -185,11 +190,11 @@ def test_chunked_prefill_counts_the_rows_of_each_call(fp8_cache):
     for step, (n0, n1) in enumerate(((25, 15), (180, 120))):
         cu = np.array([0, n0, n0 + n1], np.int32)
         x = I.hidden(n0 + n1, d, seed=70 + step, dtype="bf16")
-        ref = O.prefill_chunk(ol, x, cu, [0, 1], oc)
+        ref = O.prefill_chunk(ol, x, cu, [0, 1], oc, act8=n0 + n1 > A8_ROWS)
         got = gl.prefill_chunk(x, cu, [0, 1], gc)
         assert relmax(got, ref) <= (TOL["bf16"] if step == 0 else TOL_A8), step
     xn = I.hidden(2, d, seed=75, dtype="bf16")
-    ref = O.decode_step(ol, xn, [0, 1], oc)
+    ref = O.decode_step(ol, xn, [0, 1], oc, act8=2 > A8_ROWS)
     got = gl.decode(xn, [0, 1], gc)
     assert relmax(got, ref) <= TOL_A8       # the cached keys and values of the second chunk carry its code differences
     gl.close()
@@ -216,11 +221,11 @@ def test_moe_prefill_with_8bit_activations(T, given_logits):
     as integers."""
     cfg = small(4, 2, 256, 384, n_experts=4, top_k=2)
     w = I.layer_weights(cfg, std=0.04, with_router=True, seed=T)
-    ol, gl = O.Layer(cfg, O.quantise_layer_weights(w), act8=True), GpuLayer(cfg, w, a8=True)
+    ol, gl = O.Layer(cfg, O.quantise_layer_weights(w)), GpuLayer(cfg, w, a8=True)
     cu = np.array([0, 120, T], np.int32)
     x = I.hidden(T, cfg["d_model"], seed=18, dtype="bf16")
     rl = I.router_logits(T, 4, seed=19) if given_logits else None
-    ref, eref = O.prefill(ol, x, cu, router_logits=rl, return_experts=True)
+    ref, eref = O.prefill(ol, x, cu, router_logits=rl, return_experts=True, act8=T > A8_ROWS)
     got = gl.prefill(x, cu, router_logits=rl)
     if given_logits:
         assert np.array_equal(np.sort(gl.experts(T), axis=1), np.sort(eref, axis=1))
@@ -237,14 +242,14 @@ def test_moe_with_8bit_activations_and_empty_experts():
     """All tokens on experts 1 and 2 (the others get no rows), one expert with fewer rows than a row tile."""
     cfg = small(4, 2, 256, 384, n_experts=4, top_k=2)
     w = I.layer_weights(cfg, std=0.04, with_router=True, seed=5)
-    ol, gl = O.Layer(cfg, O.quantise_layer_weights(w), act8=True), GpuLayer(cfg, w, a8=True)
+    ol, gl = O.Layer(cfg, O.quantise_layer_weights(w)), GpuLayer(cfg, w, a8=True)
     T = 400
     cu = np.array([0, T], np.int32)
     x = I.hidden(T, cfg["d_model"], seed=28, dtype="bf16")
     rl = np.full((T, 4), -20.0, np.float32)
     rl[:, 1], rl[:, 2] = 3.0, 2.0
     rl[:7, 3] = 5.0                                 # seven tokens also pick expert 3 (instead of 2)
-    ref, eref = O.prefill(ol, x, cu, router_logits=rl, return_experts=True)
+    ref, eref = O.prefill(ol, x, cu, router_logits=rl, return_experts=True, act8=T > A8_ROWS)
     got = gl.prefill(x, cu, router_logits=rl)
     assert np.array_equal(gl.experts(T), eref)
     assert relmax(got, ref) <= TOL_A8
@@ -264,13 +269,13 @@ def test_llama8b_shape_prefill_sampled_rows():
     """8B-shaped layer, 2 x 1024 tokens; the oracle recomputes sampled rows of the same call."""
     cfg = I.CONFIGS["llama8b"]
     w = I.layer_weights(cfg)
-    ol, gl = O.Layer(cfg, O.quantise_layer_weights(w), act8=True), GpuLayer(cfg, w, a8=True)
+    ol, gl = O.Layer(cfg, O.quantise_layer_weights(w)), GpuLayer(cfg, w, a8=True)
     T = 2048
     cu = np.array([0, 1024, 2048], np.int32)
     x = I.hidden(T, cfg["d_model"], seed=10, dtype="bf16")
     got = gl.prefill(x, cu)
     rows = np.array([0, 511, 1023, 1024, 2047], np.int32)
-    ref = O.prefill(ol, x, cu, rows=rows)
+    ref = O.prefill(ol, x, cu, rows=rows, act8=T > A8_ROWS)
     for j, r in enumerate(rows):
         assert relmax(got[r], ref[j]) <= TOL_A8, r
     gl.close()

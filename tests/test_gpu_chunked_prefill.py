@@ -198,3 +198,40 @@ def test_bf16_multi_token_decode_steps(hq, hkv):
     got = gl.decode(xn, [1, 2, 0], gc)
     assert relmax(got, ref) <= TOL["bf16"]
     gl.close()
+
+
+@pytest.mark.parametrize("n_seqs,q", [(512, 1), (1024, 2), (700, 3)])
+def test_bf16_multi_token_decode_of_many_sequences(n_seqs, q):
+    """A multi-token decode step over hundreds of sequences (what a decode batch of several hundred
+    with multi-token prediction issues): 512 slots x 1 token, 1024 slots x 2 tokens, 700 x 3.  Every
+    unit of tokens needs at least one partial-result chunk, more than a one-token decode step of the
+    same row count does at the 8B head layout (32 query heads over 8 kv heads)."""
+    cfg = I.small_config(dtype="bf16", d_model=256, n_q_heads=32, n_kv_heads=8, head_dim=128, d_ff=512)
+    w = I.layer_weights(cfg, std=0.05)
+    ol, gl = O.Layer(cfg, w), GpuLayer(cfg, w)
+    rng = np.random.default_rng(n_seqs)
+    prefix = rng.integers(0, 90, n_seqs)
+    prefix[:3] = [0, 1, 89]
+    cap = 96
+    oc, gc = O.KVCache(ol, n_seqs, cap), gl.cache(n_seqs, cap)
+    k, v = I.kv_fill(8, 89, 128, seed=5, dtype="bf16")
+    kd, vd = to_dev(k, "bf16"), to_dev(v, "bf16")
+    for s_ in range(n_seqs):
+        n = int(prefix[s_])
+        oc.set(s_, k[:, :n], v[:, :n])
+        pd.pd_kv_cache_set(gc, s_, kd[:, :n].contiguous(), vd[:, :n].contiguous())
+    slots = list(rng.permutation(n_seqs).astype(int))
+    cu = (np.arange(n_seqs + 1) * q).astype(np.int32)
+    x = I.hidden(n_seqs * q, cfg["d_model"], seed=6, dtype="bf16")
+    ref = O.prefill_chunk(ol, x, cu, slots, oc)
+    got = gl.prefill_chunk(x, cu, slots, gc)
+    assert relmax(got, ref) <= TOL["bf16"]
+    for i in (0, 1, 2, n_seqs // 2, n_seqs - 1):
+        assert relmax(got[cu[i]:cu[i + 1]], ref[cu[i]:cu[i + 1]]) <= 2 * TOL["bf16"], i
+    assert all(pd.pd_kv_cache_len(gc, s_) == int(oc.lens[s_]) for s_ in (slots[0], slots[-1]))
+    # and the plain decode step that follows reads what the multi-token step appended
+    xn = I.hidden(n_seqs, cfg["d_model"], seed=7, dtype="bf16")
+    ref = O.decode_step(ol, xn, slots, oc)
+    got = gl.decode(xn, slots, gc)
+    assert relmax(got, ref) <= TOL["bf16"]
+    gl.close()

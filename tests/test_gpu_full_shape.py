@@ -24,6 +24,17 @@ def llama():
     layer.close()
 
 
+def tile_rows(T, l_in, seed, tile=256):
+    """One seeded row inside every `tile`-row band of the call (the row tiles of the large GEMM kernels
+    and two query blocks of the attention kernel each), plus the first and the last row of every
+    sequence: a mapping error confined to one band of the tile grid, or to one sequence, shows."""
+    rng = np.random.default_rng(seed)
+    rows = {int(t0 + rng.integers(0, min(tile, T - t0))) for t0 in range(0, T, tile)}
+    for s0 in range(0, T, l_in):
+        rows |= {s0, min(s0 + l_in, T) - 1}
+    return sorted(rows)
+
+
 @pytest.mark.parametrize("l_in", [2048, 4096, 1024])
 def test_llama8b_prefill_8192_tokens_sampled_rows(llama, l_in):
     cfg, w, layer = llama
@@ -37,8 +48,7 @@ def test_llama8b_prefill_8192_tokens_sampled_rows(llama, l_in):
     torch.cuda.synchronize()
     got = to_np(out)
     assert np.isfinite(got).all()
-    last = (n_seq - 1) * l_in
-    rows = [0, 1, 130, min(l_in, 1500) - 1, last + 7, last + 640]     # first and last sequence
+    rows = tile_rows(T, l_in, seed=l_in)                # every 256-row tile, every sequence's ends
     ref = O.prefill(O.Layer(cfg, w), x, cu, rows=rows)
     assert relmax(got[rows], ref) <= TOL["bf16"]
     for i, r in enumerate(rows):
@@ -70,7 +80,9 @@ def test_llama8b_decode_kv2048_sampled_rows_graph_replay(llama, B):
     torch.cuda.synchronize()
     got = to_np(run.out)
     assert np.isfinite(got).all()
-    sample = sorted(set([0, B // 3, B - 1]))
+    # one seeded row in every band of 32 rows (two 16-row matrix-core blocks each) and both ends
+    rng = np.random.default_rng(B)
+    sample = sorted({0, B - 1} | {int(b0 + rng.integers(0, min(32, B - b0))) for b0 in range(0, B, 32)})
     ol = O.Layer(cfg, w)
     oc = O.KVCache(ol, len(sample), S + 8)
     for i, b in enumerate(sample):
@@ -117,6 +129,56 @@ def test_llama8b_decode_ragged_long_context_sampled_rows(llama):
     layer.free_cache(cache)
 
 
+@pytest.mark.parametrize("ragged", [False, True])
+def test_llama8b_decode_kv16384_128_slots_sampled_rows(llama, ragged):
+    """The long-context configuration at its largest size: 128 slots of capacity 16384, so the cache
+    planes of the upper slots lie beyond 4 GiB (128 x 8 x 16384 x 128 x 2 B = 4.3 GB each for keys
+    and values).  Uniform lengths (every slot full but for the new token) and one ragged batch
+    (log-normal prompt + partial generation, with a full slot and the shortest slot sampled)."""
+    cfg, w, layer = llama
+    B, cap = 128, 16384
+    hkv, hd = cfg["n_kv_heads"], cfg["head_dim"]
+    if ragged:
+        lens = I.ragged_kv_lengths(B, cap - 1, seed=3)
+        lens[127] = cap - 1
+        lens[1] = 17
+    else:
+        lens = np.full(B, cap - 1, np.int32)
+    cache = layer.new_cache(B, cap)
+    sets = [I.kv_fill(hkv, cap - 1, hd, seed=70 + j, dtype="bf16") for j in range(2)]
+    dev_sets = [(H._dev(k, "bf16"), H._dev(v, "bf16")) for k, v in sets]
+    for s in range(B):
+        kd, vd = dev_sets[s % 2]
+        pd.pd_kv_cache_set(cache, s, kd[:, :int(lens[s])].contiguous(), vd[:, :int(lens[s])].contiguous())
+    x = I.hidden(B, cfg["d_model"], seed=71, dtype="bf16")
+    run = layer.make_decode_step(cache, H._dev(x, "bf16"), lens, use_graph=True)
+    run()
+    run()
+    torch.cuda.synchronize()
+    got = to_np(run.out)
+    assert np.isfinite(got).all()
+    sample = sorted({0, 1, 62, 63, 64, 126, 127, int(np.argmax(lens)), int(np.argmin(lens))})
+    ol = O.Layer(cfg, w)
+    oc = O.KVCache(ol, len(sample), cap)
+    for i, b in enumerate(sample):
+        k, v = sets[b % 2]
+        oc.set(i, k[:, :lens[b]], v[:, :lens[b]])
+    ref = O.decode_step(ol, x[sample], list(range(len(sample))), oc)
+    for i, b in enumerate(sample):
+        assert relmax(got[b], ref[i]) <= TOL["bf16"], (b, int(lens[b]))
+    # the appended key / value of the last slot (plane offset beyond 4 GiB) equal the oracle's
+    n = int(lens[127]) + 1
+    k = torch.empty((hkv, n, hd), dtype=torch.bfloat16, device="cuda")
+    v = torch.empty_like(k)
+    pd.pd_kv_cache_get(cache, 127, k, v)
+    torch.cuda.synchronize()
+    j = sample.index(127)
+    assert relmax(to_np(k)[:, n - 1], oc.k[j, :, n - 1]) <= TOL["bf16"]
+    assert relmax(to_np(v)[:, n - 1], oc.v[j, :, n - 1]) <= TOL["bf16"]
+    assert np.array_equal(to_np(k)[:, :n - 1], sets[127 % 2][0][:, :n - 1])
+    layer.free_cache(cache)
+
+
 def test_moe_8_experts_full_shape_sampled_rows():
     cfg = I.CONFIGS["moe"]
     w = I.layer_weights(cfg)
@@ -133,13 +195,15 @@ def test_moe_8_experts_full_shape_sampled_rows():
     e = torch.empty((T, 2), dtype=torch.int32, device="cuda")
     pd.pd_last_expert_choice(layer.h, T, e)
     torch.cuda.synchronize()
-    rows = [0, 3, 700, 6144 + 11]
+    rows = tile_rows(T, l_in, seed=5, tile=512)         # 16 bands + the ends of the four sequences
     ol = O.Layer(cfg, w)
     ref, eref = O.prefill(ol, x, cu, router_logits=r, rows=rows, return_experts=True)
     assert np.array_equal(e.cpu().numpy()[rows], eref)
     # every token's experts: the two largest logits (no ties in continuous draws)
     assert np.array_equal(np.sort(e.cpu().numpy(), 1), np.sort(np.argsort(-r, 1, kind="stable")[:, :2], 1))
     assert relmax(got[rows], ref) <= TOL["bf16"]
+    for i, r_ in enumerate(rows):
+        assert relmax(got[r_], ref[i]) <= 2 * TOL["bf16"], r_
     # decode step over a filled cache, batch 16
     B, S = 16, 512
     cache = layer.new_cache(B, S + 8)
@@ -163,13 +227,13 @@ def test_moe_8_experts_full_shape_sampled_rows():
 def test_llama8b_8bit_layer_at_the_bench_shapes_sampled_rows():
     """The 8-bit section of bench.py: 8-bit weights and (above 256 rows) activations, prefill of 4 x 2048
     tokens, then a decode step of batch 448 over an 8-bit cache at KV 2048 through a replayed graph;
-    the oracle recomputes sampled rows with the same rule.  Bounds: those of the 8-bit-activation
+    the oracle recomputes sampled rows, told that these calls quantise.  Bounds: those of the 8-bit-activation
     layer (6e-2 of the largest output)."""
     tol = 6e-2
     cfg = I.CONFIGS["llama8b"]
     w = I.layer_weights(cfg)
     layer = H.Layer(cfg, w, a8=True)
-    ol = O.Layer(cfg, O.quantise_layer_weights(w), act8=True)
+    ol = O.Layer(cfg, O.quantise_layer_weights(w))
     T, l_in = 8192, 2048
     x = I.hidden(T, cfg["d_model"], seed=10, dtype="bf16")
     cu = I.uniform_cu_seqlens(T // l_in, l_in)
@@ -179,8 +243,8 @@ def test_llama8b_8bit_layer_at_the_bench_shapes_sampled_rows():
     torch.cuda.synchronize()
     got = to_np(out)
     assert np.isfinite(got).all()
-    rows = [0, 1, 1500, 3 * l_in + 7, 3 * l_in + 2047]
-    ref = O.prefill(ol, x, cu, rows=rows)
+    rows = tile_rows(T, l_in, seed=6, tile=512)
+    ref = O.prefill(ol, x, cu, rows=rows, act8=True)    # 8192 rows: the library's call quantises
     for i, r in enumerate(rows):
         assert relmax(got[r], ref[i]) <= tol, r
     # decode: batch 448 (8-bit activations too), 8-bit cache
@@ -198,15 +262,13 @@ def test_llama8b_8bit_layer_at_the_bench_shapes_sampled_rows():
     run()
     torch.cuda.synchronize()
     gotd = to_np(run.out)
-    rows = [0, 255, 256, 447]
-    # the rule counts the rows of the call, and rows are independent of each other: the oracle
-    # evaluates the sampled rows inside a call of 257 rows (padded with copies of the first)
-    pad = 257 - len(rows)
-    xs = np.concatenate([xb[rows], np.repeat(xb[rows[:1]], pad, axis=0)])
-    ocp = O.KVCache(ol, 257, S + 8, fp8_scales=scales)
-    for j in range(257):
-        ocp.set(j, *sets[(rows[j] if j < len(rows) else rows[0]) % 4])
-    refd = O.decode_step(ol, xs, list(range(257)), ocp)[:len(rows)]
+    rows = sorted({0, 255, 256, 447} | {int(r_) for r_ in np.random.default_rng(7).integers(0, B, 12)})
+    # a call of 448 rows quantises in the library; rows are independent of each other, so the oracle
+    # evaluates the sampled rows alone and is told that the call quantises
+    ocp = O.KVCache(ol, len(rows), S + 8, fp8_scales=scales)
+    for j, r_ in enumerate(rows):
+        ocp.set(j, *sets[r_ % 4])
+    refd = O.decode_step(ol, xb[rows], list(range(len(rows))), ocp, act8=True)
     for j, r in enumerate(rows):
         assert relmax(gotd[r], refd[j]) <= tol, r
     layer.close()

@@ -566,58 +566,67 @@ def test_activation_row_quantisation_against_library_conversions():
     assert xq[6, 5] == O.quantise_rows(np.where(np.arange(136) == 5, 1.0, xb[6]).astype(np.float32)[None])[0][0, 5]
 
 
-def test_act8_layer_matches_library_composition_above_the_row_threshold():
-    """8-bit activations: the four projections of a call with more than ACT8_ROWS rows see quantised
-    input rows; against the float64 library composition with the library's conversions in the same
-    four places."""
+def test_act8_call_matches_library_composition():
+    """8-bit activations: in a call that says so the four projections see quantised input rows;
+    against the float64 library composition with the library's conversions in the same four places."""
     cfg = I.small_config(d_model=64, n_q_heads=4, n_kv_heads=2, head_dim=16, d_ff=96)
     w = O.quantise_layer_weights(I.layer_weights(cfg, std=0.08))
-    T = O.ACT8_ROWS + 4
-    cu = np.array([0, 100, 101, T], np.int32)
+    T = 70
+    cu = np.array([0, 30, 31, T], np.int32)
     x = I.hidden(T, cfg["d_model"], seed=6)
-    got = O.prefill(O.Layer(cfg, w, act8=True), x, cu)
+    ol = O.Layer(cfg, w)
+    got = O.prefill(ol, x, cu, act8=True)
     ref = torch_layer(cfg, w, x, cu, act_q=torch_act_q)
     assert relmax(got, ref) < 2e-6
-    plain = O.prefill(O.Layer(cfg, w), x, cu)
+    plain = O.prefill(ol, x, cu)
     assert 1e-4 < relmax(got, plain) < 0.2       # and it is not the layer without them
+    assert np.array_equal(plain, O.prefill(ol, x, cu, act8=False))
 
 
-def test_act8_moe_layer_matches_library_composition():
+def test_act8_moe_call_matches_library_composition():
     """Mixture of experts: the normalised row is quantised once per token after routing (the router
     reads it unquantised), the SwiGLU row once per (token, expert) pair."""
     cfg = I.small_config(d_model=64, n_q_heads=4, n_kv_heads=2, head_dim=16, d_ff=48, n_experts=4, top_k=2)
     w = O.quantise_layer_weights(I.layer_weights(cfg, std=0.08, with_router=True))
-    T = O.ACT8_ROWS + 3
-    cu = np.array([0, 150, T], np.int32)
+    T = 45
+    cu = np.array([0, 20, T], np.int32)
     x = I.hidden(T, cfg["d_model"], seed=16)
+    ol = O.Layer(cfg, w)
     for rl in (None, I.router_logits(T, 4, seed=17)):
-        got = O.prefill(O.Layer(cfg, w, act8=True), x, cu, router_logits=rl)
+        got = O.prefill(ol, x, cu, router_logits=rl, act8=True)
         ref = torch_layer(cfg, w, x, cu, router_logits=rl, act_q=torch_act_q)
         assert relmax(got, ref) < 2e-6
-        assert relmax(got, O.prefill(O.Layer(cfg, w), x, cu, router_logits=rl)) > 1e-4
+        assert relmax(got, O.prefill(ol, x, cu, router_logits=rl)) > 1e-4
 
 
-def test_act8_layer_is_unchanged_up_to_the_row_threshold():
+def test_act8_is_a_statement_of_the_call_at_any_row_count():
+    """Nothing inside the oracle decides which calls quantise: one row or many, prefill, decode and
+    chunked prefill all follow the flag of the call; the flag changes nothing else (cache contents of
+    a call without it stay exact)."""
     cfg = I.small_config()
     w = I.layer_weights(cfg, std=0.08)
-    la, lp = O.Layer(cfg, w, act8=True), O.Layer(cfg, w)
-    T = O.ACT8_ROWS
-    cu = np.array([0, 200, T], np.int32)
-    x = I.hidden(T + 1, cfg["d_model"], seed=7)
-    assert np.array_equal(O.prefill(la, x[:T], cu), O.prefill(lp, x[:T], cu))
-    cu1 = np.array([0, 200, T + 1], np.int32)
-    assert not np.array_equal(O.prefill(la, x, cu1), O.prefill(lp, x, cu1))
-    # decode and chunked prefill follow the same rule on their own row counts
-    ca, cp = O.KVCache(la, 2, 16), O.KVCache(lp, 2, 16)
-    xs = I.hidden(2, cfg["d_model"], seed=8)
-    assert np.array_equal(O.decode_step(la, xs, [0, 1], ca), O.decode_step(lp, xs, [0, 1], cp))
-    B = T + 1
-    ca, cp = O.KVCache(la, B, 4), O.KVCache(lp, B, 4)
-    xs = I.hidden(B, cfg["d_model"], seed=9)
-    assert not np.array_equal(O.decode_step(la, xs, list(range(B)), ca), O.decode_step(lp, xs, list(range(B)), cp))
-    ca, cp = O.KVCache(la, 1, T + 8), O.KVCache(lp, 1, T + 8)
-    cuc = np.array([0, T + 1], np.int32)
-    assert not np.array_equal(O.prefill_chunk(la, x, cuc, [0], ca), O.prefill_chunk(lp, x, cuc, [0], cp))
+    ol = O.Layer(cfg, w)
+    for T in (1, 2, 40):
+        cu = np.array([0, T], np.int32)
+        x = I.hidden(T, cfg["d_model"], seed=7)
+        assert not np.array_equal(O.prefill(ol, x, cu, act8=True), O.prefill(ol, x, cu))
+    for B in (1, 3):
+        ca, cp = O.KVCache(ol, B, 16), O.KVCache(ol, B, 16)
+        xs = I.hidden(B, cfg["d_model"], seed=8)
+        a = O.decode_step(ol, xs, list(range(B)), ca, act8=True)
+        p = O.decode_step(ol, xs, list(range(B)), cp)
+        assert not np.array_equal(a, p)
+        # decode with the flag == prefill with the flag of the same one-token sequences
+        cu = np.arange(B + 1, dtype=np.int32)
+        assert relmax(a, O.prefill(ol, xs, cu, act8=True)) < 1e-6
+    ca, cp = O.KVCache(ol, 1, 48), O.KVCache(ol, 1, 48)
+    x = I.hidden(40, cfg["d_model"], seed=9)
+    cuc = np.array([0, 40], np.int32)
+    a = O.prefill_chunk(ol, x, cuc, [0], ca, act8=True)
+    assert not np.array_equal(a, O.prefill_chunk(ol, x, cuc, [0], cp))
+    assert relmax(a, O.prefill(ol, x, cuc, act8=True)) < 1e-6
+    h = I.hidden(5, cfg["d_model"], seed=10)
+    assert not np.array_equal(O.ffn_block(ol, h, act8=True), O.ffn_block(ol, h))
 
 
 def test_gemm_e4m3_is_the_product_of_the_decoded_matrices():
