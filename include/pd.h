@@ -253,6 +253,26 @@ typedef struct {
 pd_status pd_decode_step(pd_layer *layer, const pd_batch *batch, pd_kv_cache *cache,
                          void *out_hidden, void *stream);
 
+/*
+ * pd_decode_step for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  The same step with the same kernels, but
+ * every intermediate buffer (normalised rows, projections, attention partial results, split-K
+ * partial sums, routing tables) lies in one 64 MiB array of static device memory that every GPU
+ * the library runs on holds until the process ends, instead of the layer's own workspace.  The call
+ * makes no hipMalloc / hipFree (nor any allocating library call) and needs no pd_layer_reserve;
+ * the layer's workspace, if it has one, is left as it was.
+ * Limits: the step's scratch need grows with the batch and the layer's widths; a call that needs
+ * more than the 64 MiB returns PD_ERR_SHAPE and enqueues nothing (the 8B-shaped dense bf16 layer
+ * fits up to batch 256).  The layer's device must be the current device.  No per-kernel events are
+ * recorded.  Every call on one GPU shares that GPU's array: nothing in it has to start at zero
+ * (each region is written before it is read within a step), but two such calls that overlap in
+ * time on one GPU (different streams or threads) race, and so does a call that overlaps a replay of
+ * a graph captured from one.
+ * Arguments, state changes and all other errors as pd_decode_step.
+ */
+pd_status pd_decode_step_noalloc(pd_layer *layer, const pd_batch *batch, pd_kv_cache *cache,
+                                 void *out_hidden, void *stream);
+
 /* MoE only: device-to-device copy of the experts chosen by the last call on this layer, int32
  * [rows, top_k], into `expert_idx` (device).  Enqueued on `stream`. */
 pd_status pd_last_expert_choice(const pd_layer *layer, int32_t rows, void *expert_idx, void *stream);

@@ -23,7 +23,7 @@ PD_F32, PD_BF16 = 0, 1
 EXPORTS = [
     "pd_layer_create", "pd_layer_create_w8", "pd_layer_create_w8a8", "pd_quantize_rows_e4m3", "pd_gemm_e4m3", "pd_layer_destroy", "pd_layer_reserve", "pd_kv_cache_create", "pd_kv_cache_create_fp8",
     "pd_kv_cache_destroy", "pd_kv_cache_set", "pd_kv_cache_set_len", "pd_kv_cache_len",
-    "pd_kv_cache_set_lens", "pd_kv_cache_get", "pd_profile_enable", "pd_profile_read", "pd_stream_copy", "pd_head_create", "pd_head_create_w8", "pd_head_destroy", "pd_embed", "pd_lm_head", "pd_prefill", "pd_prefill_chunk", "pd_decode_step", "pd_last_expert_choice", "pd_allocate",
+    "pd_kv_cache_set_lens", "pd_kv_cache_get", "pd_profile_enable", "pd_profile_read", "pd_stream_copy", "pd_head_create", "pd_head_create_w8", "pd_head_destroy", "pd_embed", "pd_lm_head", "pd_prefill", "pd_prefill_chunk", "pd_decode_step", "pd_decode_step_noalloc", "pd_last_expert_choice", "pd_allocate",
     "pd_fifo_replay", "pd_mm1_sojourn", "pd_fifo_replay_batched", "pd_prefill_throughput_dp", "pd_mg1_sojourn", "pd_kv_transfer_overhead", "pd_allocate_stages", "pd_status_string", "pd_last_error",
 ]
 
@@ -267,6 +267,14 @@ def pd_decode_step(layer, hidden, slots, cache, out, router_logits=None):
     bt = pd_batch(hidden.data_ptr(), len(slots), sl,
                   None if router_logits is None else router_logits.data_ptr())
     _check(lib.pd_decode_step(layer, C.byref(bt), cache, _ptr(out), _stream()))
+    return out
+
+
+def pd_decode_step_noalloc(layer, hidden, slots, cache, out, router_logits=None):
+    sl = _i32_array(slots)
+    bt = pd_batch(hidden.data_ptr(), len(slots), sl,
+                  None if router_logits is None else router_logits.data_ptr())
+    _check(lib.pd_decode_step_noalloc(layer, C.byref(bt), cache, _ptr(out), _stream()))
     return out
 
 

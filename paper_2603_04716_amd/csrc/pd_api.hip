@@ -6,6 +6,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <atomic>
 #include <vector>
 
 #include "pd_internal.h"
@@ -40,6 +41,7 @@ struct pd_layer {
     void *vt;                 // transposed-V scratch for the MFMA attention, vt_cap bytes
     size_t vt_cap;
     float *dec_part;          // partial outputs of the decode attention chunks (inside ws)
+    int chunk_slack_workers;  // the partial-output part holds batch + this many workers' chunks (see decode_chunk_bound)
     float *splitk;            // split-K partials of the decode-sized GEMMs (inside ws)
     size_t splitk_elems;
     // workspace, sized for ws_tokens rows
@@ -84,6 +86,10 @@ static const int kA8Rows = 256;
 // max_chunks: what the partial-output workspace holds; the chunk size is raised until the step fits
 // (one chunk per sequence always does).
 static const int kDecodeWorkers = 768;
+// Workers (chunk x kv head) beyond one per sequence that the partial-output buffer of a layer's own
+// workspace leaves room for, and what the static scratch of pd_decode_step_noalloc leaves room for
+// (the work split asks for at most about 1536 workers beyond one chunk per sequence).
+static const int kChunkSlackWorkers = 8192, kChunkSlackWorkersStatic = 2048;
 
 static int pick_chunk_keys(const std::vector<int32_t> &keys, int n_kv_heads, size_t max_chunks)
 {
@@ -327,6 +333,7 @@ static pd_status layer_create(const pd_layer_config *cfg, const pd_layer_weights
     L->packed = L->use_mfma;
     L->w8 = w8;
     L->a8 = a8;
+    L->chunk_slack_workers = kChunkSlackWorkers;
     if (w8 && !L->use_mfma) {
         set_error("pd_layer_create_w8: needs a bf16 layer whose dimensions are multiples of 64");
         delete L;
@@ -473,7 +480,7 @@ extern "C" void pd_layer_destroy(pd_layer *layer)
 // is chosen so that a step fits), so a decode step never allocates.
 static size_t decode_chunk_bound(const pd_layer *L, int batch)
 {
-    return (size_t)(8192 / L->cfg.n_kv_heads + 1) + (size_t)batch;
+    return (size_t)(L->chunk_slack_workers / L->cfg.n_kv_heads + 1) + (size_t)batch;
 }
 
 extern "C" pd_status pd_quantize_rows_e4m3(const void *x, int32_t n_rows, int32_t n_cols, void *codes,
@@ -522,6 +529,80 @@ extern "C" pd_status pd_gemm_e4m3(const void *a_codes, const float *a_scales, co
     return PD_OK;
 }
 
+// Offsets of the parts of a workspace for calls of up to max_tokens rows, and its size.
+struct WsLayout {
+    size_t y, qkv, o, h, act, eo, seq, pos, slot, eidx, sorted, pp, off, bh, log, ew, ccu, units, part, sk, a8c, a8s;
+    size_t sk_elems;
+    size_t total;
+};
+
+// sk_rows: rows the split-K scratch is sized for (a launcher whose partials would not fit takes fewer splits)
+static WsLayout ws_layout(const pd_layer *L, int max_tokens, size_t sk_rows = 256, size_t sk_per_row = 0)
+{
+    const size_t T = (size_t)max_tokens, esz = L->esz;
+    const int d = L->cfg.d_model, F = L->cfg.d_ff, E = L->cfg.n_experts;
+    const size_t K = E > 0 ? (size_t)L->cfg.top_k : 1;
+    WsLayout w;
+    size_t off = 0;
+    auto carve = [&](size_t bytes) {
+        size_t o = off;
+        off += align256(bytes);
+        return o;
+    };
+    w.y = carve(T * d * esz); w.qkv = carve(T * L->Nqkv * esz); w.o = carve(T * L->Nq * esz);
+    w.h = carve(T * d * esz); w.act = carve(T * K * F * esz);
+    w.eo = carve(E > 0 ? T * K * d * esz : 0); w.seq = carve(T * 4); w.pos = carve(T * 4);
+    w.slot = carve(T * 4); w.eidx = carve(T * K * 4); w.sorted = carve(T * K * 4);
+    w.pp = carve(T * K * 4); w.off = carve(65 * 4 + 4); w.bh = carve(E > 0 ? (T * K / 256 + 1) * (size_t)E * 4 : 0);
+    w.log = carve(T * (E > 0 ? E : 1) * 4);
+    w.ew = carve(T * K * 4); w.ccu = carve((T + 1) * 4); w.units = carve(4 * T * 4);
+    w.part = carve(decode_chunk_bound(L, max_tokens) * L->cfg.n_q_heads * 130 * sizeof(float));
+    // split-K scratch: splits * columns never exceeds 640 tiles * 128 columns + one row of tiles (a
+    // launcher that would need more takes fewer splits)
+    size_t maxn = (size_t)L->Nqkv;
+    if ((size_t)2 * F > maxn) maxn = (size_t)2 * F;
+    if ((size_t)d > maxn) maxn = (size_t)d;
+    if (sk_per_row == 0) sk_per_row = 640 * 128 + 2 * maxn;
+    w.sk_elems = L->use_mfma ? sk_rows * sk_per_row : 0;
+    w.sk = carve(w.sk_elems * sizeof(float));
+    size_t maxk = (size_t)d > (size_t)L->Nq ? (size_t)d : (size_t)L->Nq;
+    if ((size_t)F > maxk) maxk = (size_t)F;
+    w.a8c = carve(L->a8 ? T * K * maxk : 0);
+    w.a8s = carve(L->a8 ? T * K * sizeof(float) : 0);
+    w.total = off;
+    return w;
+}
+
+// Points the layer's workspace members into base (a buffer of w.total bytes laid out for max_tokens rows).
+static void ws_bind(pd_layer *L, char *nw, const WsLayout &w, int max_tokens)
+{
+    const int E = L->cfg.n_experts;
+    L->ws_tokens = max_tokens;
+    L->y = nw + w.y;
+    L->qkv = nw + w.qkv;
+    L->o = nw + w.o;
+    L->h = nw + w.h;
+    L->act = nw + w.act;
+    L->eo = nw + w.eo;
+    L->tok_seq = (int32_t *)(nw + w.seq);
+    L->tok_pos = (int32_t *)(nw + w.pos);
+    L->tok_slot = (int32_t *)(nw + w.slot);
+    L->eidx = (int32_t *)(nw + w.eidx);
+    L->sorted_token = (int32_t *)(nw + w.sorted);
+    L->pair_pos = (int32_t *)(nw + w.pp);
+    L->block_hist = E > 0 ? (int32_t *)(nw + w.bh) : nullptr;
+    L->offsets = (int32_t *)(nw + w.off);
+    L->logits = (float *)(nw + w.log);
+    L->ew = (float *)(nw + w.ew);
+    L->chunk_cu = (int32_t *)(nw + w.ccu);
+    L->units = (int32_t *)(nw + w.units);
+    L->dec_part = (float *)(nw + w.part);
+    L->splitk = w.sk_elems ? (float *)(nw + w.sk) : nullptr;
+    L->splitk_elems = w.sk_elems;
+    L->a8_codes = L->a8 ? (uint8_t *)(nw + w.a8c) : nullptr;
+    L->a8_scales = L->a8 ? (float *)(nw + w.a8s) : nullptr;
+}
+
 extern "C" pd_status pd_layer_reserve(pd_layer *L, int32_t max_tokens)
 {
     if (!L || max_tokens < 0) {
@@ -529,64 +610,17 @@ extern "C" pd_status pd_layer_reserve(pd_layer *L, int32_t max_tokens)
         return PD_ERR_INVALID_ARG;
     }
     if (max_tokens <= L->ws_tokens) return PD_OK;
-    const size_t T = (size_t)max_tokens, esz = L->esz;
-    const int d = L->cfg.d_model, F = L->cfg.d_ff, E = L->cfg.n_experts;
-    const size_t K = E > 0 ? (size_t)L->cfg.top_k : 1;
-    size_t off = 0;
-    auto carve = [&](size_t bytes) {
-        size_t o = off;
-        off += align256(bytes);
-        return o;
-    };
-    size_t o_y = carve(T * d * esz), o_qkv = carve(T * L->Nqkv * esz), o_o = carve(T * L->Nq * esz),
-           o_h = carve(T * d * esz), o_act = carve(T * K * F * esz),
-           o_eo = carve(E > 0 ? T * K * d * esz : 0), o_seq = carve(T * 4), o_pos = carve(T * 4),
-           o_slot = carve(T * 4), o_eidx = carve(T * K * 4), o_sorted = carve(T * K * 4),
-           o_pp = carve(T * K * 4), o_off = carve(65 * 4 + 4), o_bh = carve(E > 0 ? (T * K / 256 + 1) * (size_t)E * 4 : 0), o_log = carve(T * (E > 0 ? E : 1) * 4),
-           o_ew = carve(T * K * 4), o_ccu = carve((T + 1) * 4), o_units = carve(4 * T * 4),
-           o_part = carve(decode_chunk_bound(L, max_tokens) * L->cfg.n_q_heads * 130 * sizeof(float));
-    // split-K scratch: splits * columns never exceeds 640 tiles * 128 columns + one row of tiles
-    size_t maxn = (size_t)L->Nqkv;
-    if ((size_t)2 * F > maxn) maxn = (size_t)2 * F;
-    if ((size_t)d > maxn) maxn = (size_t)d;
-    const size_t sk_elems = L->use_mfma ? (size_t)256 * (640 * 128 + 2 * maxn) : 0;
-    size_t o_sk = carve(sk_elems * sizeof(float));
-    size_t maxk = (size_t)d > (size_t)L->Nq ? (size_t)d : (size_t)L->Nq;
-    if ((size_t)F > maxk) maxk = (size_t)F;
-    size_t o_a8c = carve(L->a8 ? T * K * maxk : 0), o_a8s = carve(L->a8 ? T * K * sizeof(float) : 0);
+    const WsLayout w = ws_layout(L, max_tokens);
     HIP_TRY(hipDeviceSynchronize(), PD_ERR_DEVICE);
     char *nw = nullptr;
-    hipError_t e = hipMalloc((void **)&nw, off);
+    hipError_t e = hipMalloc((void **)&nw, w.total);
     if (e != hipSuccess) {
-        set_error("pd_layer_reserve: cannot allocate %zu bytes of workspace: %s", off, hipGetErrorString(e));
+        set_error("pd_layer_reserve: cannot allocate %zu bytes of workspace: %s", w.total, hipGetErrorString(e));
         return PD_ERR_OOM;
     }
     if (L->ws) (void)hipFree(L->ws);
     L->ws = nw;
-    L->ws_tokens = max_tokens;
-    L->y = nw + o_y;
-    L->qkv = nw + o_qkv;
-    L->o = nw + o_o;
-    L->h = nw + o_h;
-    L->act = nw + o_act;
-    L->eo = nw + o_eo;
-    L->tok_seq = (int32_t *)(nw + o_seq);
-    L->tok_pos = (int32_t *)(nw + o_pos);
-    L->tok_slot = (int32_t *)(nw + o_slot);
-    L->eidx = (int32_t *)(nw + o_eidx);
-    L->sorted_token = (int32_t *)(nw + o_sorted);
-    L->pair_pos = (int32_t *)(nw + o_pp);
-    L->block_hist = E > 0 ? (int32_t *)(nw + o_bh) : nullptr;
-    L->offsets = (int32_t *)(nw + o_off);
-    L->logits = (float *)(nw + o_log);
-    L->ew = (float *)(nw + o_ew);
-    L->chunk_cu = (int32_t *)(nw + o_ccu);
-    L->units = (int32_t *)(nw + o_units);
-    L->dec_part = (float *)(nw + o_part);
-    L->splitk = sk_elems ? (float *)(nw + o_sk) : nullptr;
-    L->splitk_elems = sk_elems;
-    L->a8_codes = L->a8 ? (uint8_t *)(nw + o_a8c) : nullptr;
-    L->a8_scales = L->a8 ? (float *)(nw + o_a8s) : nullptr;
+    ws_bind(L, nw, w, max_tokens);
     return PD_OK;
 }
 
@@ -1103,8 +1137,67 @@ extern "C" pd_status pd_prefill_chunk(pd_layer *L, const pd_tokens *tk, pd_kv_ca
     return prefill_common(L, tk, cache, out, stream, true);
 }
 
+// ---- static scratch for the entry point that allocates nothing --------------------------------------
+// One array per GPU, held from the moment the library's code is loaded on it until the process ends.
+// Host code never uses the array's name as an address: the device address of the current device's
+// copy comes from hipGetSymbolAddress, once per device.
+static const size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+static pd_status static_scratch_ptr(const pd_layer *L, char **ptr)
+{
+    static std::atomic<void *> ptrs[64];
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev), PD_ERR_DEVICE);
+    if (dev != L->device || dev < 0 || dev >= 64) {
+        set_error("pd_decode_step_noalloc: the layer's device %d must be the current device (it is %d)", L->device, dev);
+        return PD_ERR_INVALID_ARG;
+    }
+    void *p = ptrs[dev].load(std::memory_order_acquire);
+    if (!p) {
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), PD_ERR_DEVICE);
+        if (!p) {
+            set_error("pd_decode_step_noalloc: no address for the static scratch array");
+            return PD_ERR_DEVICE;
+        }
+        ptrs[dev].store(p, std::memory_order_release);
+    }
+    *ptr = (char *)p;
+    return PD_OK;
+}
+
+static pd_status decode_step_impl(pd_layer *L, const pd_batch *bt, pd_kv_cache *cache, void *out, void *stream,
+                                  bool static_ws);
+
 extern "C" pd_status pd_decode_step(pd_layer *L, const pd_batch *bt, pd_kv_cache *cache, void *out,
                                     void *stream)
+{
+    return decode_step_impl(L, bt, cache, out, stream, false);
+}
+
+extern "C" pd_status pd_decode_step_noalloc(pd_layer *L, const pd_batch *bt, pd_kv_cache *cache, void *out,
+                                            void *stream)
+{
+    if (!L) {
+        set_error("pd_decode_step_noalloc: NULL layer");
+        return PD_ERR_INVALID_ARG;
+    }
+    // the step runs on the static array instead of the layer's workspace; the layer's own workspace (if
+    // any) is bound again afterwards, untouched
+    const int own_tokens = L->ws_tokens;
+    const bool prof = L->prof_on;
+    L->prof_on = false;                      // per-kernel events would have to be created
+    L->chunk_slack_workers = kChunkSlackWorkersStatic;
+    const pd_status st = decode_step_impl(L, bt, cache, out, stream, true);
+    L->chunk_slack_workers = kChunkSlackWorkers;
+    L->prof_on = prof;
+    L->ws_tokens = 0;
+    if (L->ws) ws_bind(L, L->ws, ws_layout(L, own_tokens), own_tokens);
+    return st;
+}
+
+static pd_status decode_step_impl(pd_layer *L, const pd_batch *bt, pd_kv_cache *cache, void *out, void *stream,
+                                  bool static_ws)
 {
     if (!L || !bt || !cache || !bt->slots || !bt->hidden || !out) {
         set_error("pd_decode_step: NULL argument");
@@ -1141,8 +1234,24 @@ extern "C" pd_status pd_decode_step(pd_layer *L, const pd_batch *bt, pd_kv_cache
             }
     }
     L->call_rows = B;
-    pd_status st = pd_layer_reserve(L, B);
-    if (st != PD_OK) return st;
+    pd_status st = PD_OK;
+    if (static_ws) {
+        const size_t rows = (size_t)B * (c.n_experts > 0 ? c.top_k : 1);
+        // split-K partials: a launcher's splits x columns stay within 256 workgroups x 128 columns per row
+        const WsLayout w = ws_layout(L, B, rows < 256 ? rows : 256, 256 * 128);
+        if (w.total > kStaticScratchBytes) {
+            set_error("pd_decode_step_noalloc: a batch of %d rows of this layer needs %zu bytes of scratch, the static "
+                      "array holds %zu", B, w.total, kStaticScratchBytes);
+            return PD_ERR_SHAPE;
+        }
+        char *base = nullptr;
+        st = static_scratch_ptr(L, &base);
+        if (st != PD_OK) return st;
+        ws_bind(L, base, w, B);
+    } else {
+        st = pd_layer_reserve(L, B);
+        if (st != PD_OK) return st;
+    }
     hipStream_t s = (hipStream_t)stream;
     L->prof_names.clear();
 

@@ -1,0 +1,134 @@
+"""pd_decode_step_noalloc (the decode step on the library's static scratch array, for callers that
+cannot allocate device memory) against pd_decode_step on the same inputs: two calls in a row, the
+second with a smaller batch, then the limit and the state the call must leave alone.  Bound as for
+the other layer tests: max |a - b| / max |b| <= 2e-2 (bf16), 1e-5 (fp32); cache lengths and the
+appended keys / values are compared too.  Collected last on purpose."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2603_04716_amd as pd
+import pd_inputs as I
+from oracle import layer as O
+from gpu_util import GpuLayer, TOL, relmax, to_dev, to_np
+
+pytestmark = pytest.mark.gpu
+
+
+def filled_pair(gl, n_slots, cap, lens, hkv, hd, dtype, seed):
+    """Two caches with identical contents."""
+    ca, cb = gl.cache(n_slots, cap), gl.cache(n_slots, cap)
+    k, v = I.kv_fill(hkv, max(lens), hd, seed=seed, dtype=dtype)
+    kd, vd = to_dev(k, dtype), to_dev(v, dtype)
+    for s, n in enumerate(lens):
+        for c in (ca, cb):
+            pd.pd_kv_cache_set(c, s, kd[:, :n].contiguous(), vd[:, :n].contiguous())
+    return ca, cb, k, v
+
+
+def step_both(gl, ca, cb, x, slots, router_logits=None):
+    xd = to_dev(x, gl.dtype)
+    rl = None if router_logits is None else torch.from_numpy(router_logits).cuda().contiguous()
+    ref, got = torch.empty_like(xd), torch.empty_like(xd)
+    pd.pd_decode_step(gl.h, xd, slots, ca, ref, rl)
+    pd.pd_decode_step_noalloc(gl.h, xd, slots, cb, got, rl)
+    torch.cuda.synchronize()
+    return to_np(got), to_np(ref)
+
+
+@pytest.mark.parametrize("shape", ["llama8b", "small_bf16", "tiny_f32", "moe_bf16"])
+def test_two_calls_in_a_row_the_second_smaller(shape):
+    if shape == "llama8b":
+        cfg, std, B1, B2, cap = I.CONFIGS["llama8b"], 0.02, 256, 5, 300
+    elif shape == "small_bf16":
+        cfg, std, B1, B2, cap = I.small_config(dtype="bf16", d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=128,
+                                               d_ff=512), 0.05, 300, 17, 200
+    elif shape == "moe_bf16":
+        cfg, std, B1, B2, cap = I.small_config(dtype="bf16", d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=128,
+                                               d_ff=384, n_experts=4, top_k=2), 0.05, 40, 3, 200
+    else:
+        cfg, std, B1, B2, cap = I.CONFIGS["tiny"], 0.02, 8, 2, 140
+    dt = cfg["dtype"]
+    w = I.layer_weights(cfg, std=std)
+    gl = GpuLayer(cfg, w)
+    rng = np.random.default_rng(3)
+    lens = [int(n) for n in rng.integers(1, cap - 4, B1)]
+    lens[0] = cap - 4
+    ca, cb, k, v = filled_pair(gl, B1, cap, lens, cfg["n_kv_heads"], cfg["head_dim"], dt, seed=4)
+    E = cfg.get("n_experts", 0)
+    # first call: the larger batch; second: fewer rows, other slots, on what the first call left behind
+    for call, B in enumerate((B1, B2)):
+        slots = list(range(B)) if call == 0 else [int(s) for s in rng.permutation(B1)[:B]]
+        x = I.hidden(B, cfg["d_model"], seed=10 + call, dtype=dt)
+        rl = I.router_logits(B, E, seed=20 + call) if E else None
+        got, ref = step_both(gl, ca, cb, x, slots, rl)
+        assert np.isfinite(got).all()
+        assert relmax(got, ref) <= TOL[dt], (shape, call)
+        for b in range(B):
+            assert relmax(got[b], ref[b]) <= 2 * TOL[dt], (shape, call, b)
+        for s in slots[:4]:
+            assert pd.pd_kv_cache_len(ca, s) == pd.pd_kv_cache_len(cb, s)
+    # what the two calls appended is the same in both caches, bit for bit (same kernels, same inputs)
+    s0 = 0
+    n = pd.pd_kv_cache_len(cb, s0)
+    tdt = torch.bfloat16 if dt == "bf16" else torch.float32
+    ka = torch.empty((cfg["n_kv_heads"], n, cfg["head_dim"]), dtype=tdt, device="cuda")
+    va, kb, vb = torch.empty_like(ka), torch.empty_like(ka), torch.empty_like(ka)
+    pd.pd_kv_cache_get(ca, s0, ka, va)
+    pd.pd_kv_cache_get(cb, s0, kb, vb)
+    torch.cuda.synchronize()
+    assert torch.equal(ka, kb) and torch.equal(va, vb)
+    # and against the oracle, as for every other path (first call's batch, one more step)
+    if shape != "llama8b":
+        ol = O.Layer(cfg, w)
+        oc = O.KVCache(ol, B1, cap + 4)
+        for s in range(B1):
+            m = pd.pd_kv_cache_len(cb, s)
+            kk = torch.empty((cfg["n_kv_heads"], m, cfg["head_dim"]), dtype=tdt, device="cuda")
+            vv = torch.empty_like(kk)
+            pd.pd_kv_cache_get(cb, s, kk, vv)
+            torch.cuda.synchronize()
+            oc.set(s, to_np(kk), to_np(vv))
+        rows = [s for s in range(B1) if pd.pd_kv_cache_len(cb, s) < cap][:6]
+        x = I.hidden(len(rows), cfg["d_model"], seed=30, dtype=dt)
+        rl = I.router_logits(len(rows), E, seed=31) if E else None
+        want = O.decode_step(ol, x, rows, oc, router_logits=rl)
+        xd = to_dev(x, dt)
+        out = torch.empty_like(xd)
+        pd.pd_decode_step_noalloc(gl.h, xd, rows, cb, out, None if rl is None else torch.from_numpy(rl).cuda())
+        torch.cuda.synchronize()
+        assert relmax(to_np(out), want) <= TOL[dt]
+    gl.close()
+
+
+def test_limit_and_untouched_workspace():
+    """A batch whose scratch need exceeds the static array is refused with a clear error and nothing
+    is enqueued; the layer's own (reserved) workspace keeps serving ordinary calls in between."""
+    cfg = I.CONFIGS["llama8b"]
+    w = I.layer_weights(cfg)
+    gl = GpuLayer(cfg, w)
+    B = 1024
+    ca, cb, k, v = filled_pair(gl, B, 8, [3] * B, cfg["n_kv_heads"], cfg["head_dim"], "bf16", seed=5)
+    x = I.hidden(B, cfg["d_model"], seed=6, dtype="bf16")
+    xd = to_dev(x, "bf16")
+    out = torch.empty_like(xd)
+    with pytest.raises(pd.PdError) as e:
+        pd.pd_decode_step_noalloc(gl.h, xd, list(range(B)), cb, out)
+    assert e.value.status == pd.PD_ERR_SHAPE and "scratch" in str(e.value)
+    assert pd.pd_kv_cache_len(cb, 0) == 3                     # refused before any state change
+    # batch 64 of this shape fits (so does 256, in the first test)
+    pd.pd_layer_reserve(gl.h, 128)
+    ref128 = torch.empty((128, cfg["d_model"]), dtype=torch.bfloat16, device="cuda")
+    pd.pd_decode_step(gl.h, xd[:128].contiguous(), list(range(128)), ca, ref128)       # ordinary call, own workspace
+    got64 = torch.empty((64, cfg["d_model"]), dtype=torch.bfloat16, device="cuda")
+    pd.pd_decode_step_noalloc(gl.h, xd[:64].contiguous(), list(range(64)), cb, got64)
+    # the ordinary call still works on its reserved workspace afterwards (slots 128..255, both caches)
+    a2, b2 = torch.empty_like(ref128), torch.empty_like(ref128)
+    pd.pd_decode_step(gl.h, xd[128:256].contiguous(), list(range(128, 256)), ca, a2)
+    pd.pd_decode_step(gl.h, xd[128:256].contiguous(), list(range(128, 256)), cb, b2)
+    torch.cuda.synchronize()
+    assert relmax(to_np(got64), to_np(ref128)[:64]) <= TOL["bf16"]
+    assert torch.equal(a2, b2)
+    with pytest.raises(pd.PdError):
+        pd.pd_decode_step_noalloc(gl.h, xd[:65].contiguous(), list(range(64)) + [64], None, out)   # NULL cache
+    gl.close()
