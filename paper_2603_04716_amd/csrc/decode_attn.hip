@@ -31,11 +31,11 @@ __device__ __forceinline__ float dexp2(float x) { return __builtin_amdgcn_exp2f(
 // slots arrive in the kernel arguments (B <= 256) and are also stored to slots_out for the kernels
 // that follow, which saves the separate upload launch of a small decode step.
 template <bool BYVAL>
-__global__ __launch_bounds__(1024) void decode_meta_chunks_kernel(const int32_t *__restrict__ slots, IntChunk sv,
-                                                                  int32_t *slots_out, int B, int32_t *len,
-                                                                  int32_t *pos, int32_t *chunk_cu, int chunk_keys)
+__device__ __forceinline__ void decode_meta_chunks_body(const int32_t *__restrict__ slots, const IntChunk &sv,
+                                                        int32_t *slots_out, int B, int32_t *len, int32_t *pos,
+                                                        int32_t *chunk_cu, int32_t *chunk_seq, int chunk_keys,
+                                                        int *wave_tot)
 {
-    __shared__ int wave_tot[16];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     int cnt[4], sum = 0;
 #pragma unroll
@@ -72,27 +72,70 @@ __global__ __launch_bounds__(1024) void decode_meta_chunks_kernel(const int32_t 
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         int b = tid * 4 + i;
+        // the attention workers find their sequence with one load instead of a bisection of chunk_cu
+        for (int c = run; c < run + cnt[i]; ++c) chunk_seq[c] = b;
         run += cnt[i];
         if (b < B) chunk_cu[b + 1] = run;
     }
 }
 
+template <bool BYVAL>
+__global__ __launch_bounds__(1024) void decode_meta_chunks_kernel(const int32_t *__restrict__ slots, IntChunk sv,
+                                                                  int32_t *slots_out, int B, int32_t *len,
+                                                                  int32_t *pos, int32_t *chunk_cu, int32_t *chunk_seq,
+                                                                  int chunk_keys)
+{
+    __shared__ int wave_tot[16];
+    decode_meta_chunks_body<BYVAL>(slots, sv, slots_out, B, len, pos, chunk_cu, chunk_seq, chunk_keys, wave_tot);
+}
+
+// The bookkeeping of a decode step of up to 256 rows (block B) and the RMSNorm of its rows (blocks
+// 0 .. B-1) in one launch: neither needs the other, and a launch of its own costs each of them more than
+// the work itself.
+__global__ __launch_bounds__(256) void decode_meta_norm_kernel(IntChunk sv, int32_t *slots_out, int B, int32_t *len,
+                                                               int32_t *pos, int32_t *chunk_cu, int32_t *chunk_seq,
+                                                               int chunk_keys,
+                                                               const uint4 *__restrict__ x, const uint4 *__restrict__ g,
+                                                               uint4 *__restrict__ y, int d8, float d_inv, float eps)
+{
+    __shared__ int wave_tot[16];
+    __shared__ float red[4];
+    if ((int)blockIdx.x == B) {
+        decode_meta_chunks_body<true>(nullptr, sv, slots_out, B, len, pos, chunk_cu, chunk_seq, chunk_keys, wave_tot);
+        return;
+    }
+    rmsnorm_bf16_row(x + (size_t)blockIdx.x * d8, g, y + (size_t)blockIdx.x * d8, d8, d_inv, eps, red);
+}
+
+hipError_t launch_decode_meta_norm(const int32_t *host_slots, int32_t *d_slots, int B, int32_t *d_len, int32_t *d_pos,
+                                   int32_t *chunk_cu, int32_t *chunk_seq, int chunk_keys, const void *x, const void *g,
+                                   void *y, int d, float eps, hipStream_t s)
+{
+    if (B > 256 || B < 1 || d % 8 != 0) return hipErrorInvalidValue;
+    IntChunk sv;
+    for (int i = 0; i < B; ++i) sv.v[i] = host_slots[i];
+    decode_meta_norm_kernel<<<B + 1, 256, 0, s>>>(sv, d_slots, B, d_len, d_pos, chunk_cu, chunk_seq, chunk_keys, (const uint4 *)x,
+                                                  (const uint4 *)g, (uint4 *)y, d / 8, 1.0f / (float)d, eps);
+    return hipGetLastError();
+}
+
 hipError_t launch_decode_meta_chunks(const int32_t *d_slots, int B, int32_t *d_len, int32_t *d_pos,
-                                     int32_t *chunk_cu, int chunk_keys, hipStream_t s)
+                                     int32_t *chunk_cu, int32_t *chunk_seq, int chunk_keys, hipStream_t s)
 {
     IntChunk none;
     none.v[0] = 0;
-    decode_meta_chunks_kernel<false><<<1, 1024, 0, s>>>(d_slots, none, nullptr, B, d_len, d_pos, chunk_cu, chunk_keys);
+    decode_meta_chunks_kernel<false><<<1, 1024, 0, s>>>(d_slots, none, nullptr, B, d_len, d_pos, chunk_cu, chunk_seq, chunk_keys);
     return hipGetLastError();
 }
 
 hipError_t launch_decode_meta_chunks_upload(const int32_t *host_slots, int32_t *d_slots, int B, int32_t *d_len,
-                                            int32_t *d_pos, int32_t *chunk_cu, int chunk_keys, hipStream_t s)
+                                            int32_t *d_pos, int32_t *chunk_cu, int32_t *chunk_seq, int chunk_keys,
+                                            hipStream_t s)
 {
     if (B > 256) return hipErrorInvalidValue;
     IntChunk sv;
     for (int i = 0; i < B; ++i) sv.v[i] = host_slots[i];
-    decode_meta_chunks_kernel<true><<<1, 256, 0, s>>>(nullptr, sv, d_slots, B, d_len, d_pos, chunk_cu, chunk_keys);
+    decode_meta_chunks_kernel<true><<<1, 256, 0, s>>>(nullptr, sv, d_slots, B, d_len, d_pos, chunk_cu, chunk_seq, chunk_keys);
     return hipGetLastError();
 }
 
@@ -110,17 +153,47 @@ __device__ __forceinline__ bf16x8 fp8x8_to_bf16(unsigned w0, unsigned w1)
 // FP8: the cache holds E4M3 codes in the 8-bit blocked layout (half the bytes per key); the codes are
 // widened to bf16 in registers, the key scale is folded into the score scale and the value scale
 // into the final normalisation.
-template <bool MULTI, bool FP8>
+// (cos, sin) of pos * inv_freq[i .. i + 3]: from the table, or in double beyond it (as the stand-alone
+// rotary kernel does)
+__device__ __forceinline__ void rope_factors4(const DecodeAttnArgs &a, int pos, int i, float (&c)[4], float (&s)[4])
+{
+    if (pos < a.rope_table_len) {
+        const float4 *t = (const float4 *)(a.rope_table + (size_t)pos * 64 + i);
+        const float4 t0 = t[0], t1 = t[1];
+        c[0] = t0.x; s[0] = t0.y; c[1] = t0.z; s[1] = t0.w;
+        c[2] = t1.x; s[2] = t1.y; c[3] = t1.z; s[3] = t1.w;
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            double sv, cv;
+            sincos((double)pos * a.inv_freq[i + e], &sv, &cv);
+            c[e] = (float)cv;
+            s[e] = (float)sv;
+        }
+    }
+}
+
+// ROPE (one-token step): q and the new key arrive unrotated and are rotated here; the new token is not
+// read from the cache but joins the softmax from registers (see DecodeAttnArgs).  Storing it into the
+// cache is left to a later launch of the step: the 2-byte stores into the transposed value blocks cost
+// this kernel 19 us at batch 256 when it issued them itself.
+template <bool MULTI, bool FP8, bool ROPE = false>
 __global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a, int n_workers)
 {
+    static_assert(!(MULTI && ROPE), "the fused rotary embedding serves the one-token step");
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int w = blockIdx.x * 4 + wave;
     if (w >= n_workers) return;
     const int g = w % a.Hkv, cid = w / a.Hkv;
-    int lo = 0, hi = a.B;   // largest b with chunk_cu[b] <= cid (every sequence has >= 1 chunk)
-    while (hi - lo > 1) {
-        int mid = (lo + hi) >> 1;
-        if (a.chunk_cu[mid] <= cid) lo = mid; else hi = mid;
+    int lo = 0;
+    if (a.chunk_seq) {
+        lo = a.chunk_seq[cid];
+    } else {
+        int hi = a.B;       // largest b with chunk_cu[b] <= cid (every sequence has >= 1 chunk)
+        while (hi - lo > 1) {
+            int mid = (lo + hi) >> 1;
+            if (a.chunk_cu[mid] <= cid) lo = mid; else hi = mid;
+        }
     }
     const int b = lo;
     const int ntok = MULTI ? a.u_ntok[b] : 1;
@@ -128,7 +201,10 @@ __global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a, i
     const int n_chunks = a.chunk_cu[b + 1] - a.chunk_cu[b];
     const int csz = ((n_keys + n_chunks - 1) / n_chunks + 63) & ~63;   // equal chunks, 64-key granules
     const int key0 = (cid - a.chunk_cu[b]) * csz;                       // < n_keys since csz <= chunk_keys
-    const int key1 = min(n_keys, key0 + csz);
+    // ROPE: the chunks cover the cached keys only; the new token (position pos, not yet in the cache)
+    // is added from registers by the worker of the last chunk
+    const int key1 = min(ROPE ? n_keys - 1 : n_keys, key0 + csz);
+    const bool own_new = ROPE && cid - a.chunk_cu[b] == n_chunks - 1;
     const int group = a.Hq / a.Hkv;
     const int qi = lane & 15, kg = lane >> 4;
     // MFMA column qi: head qh of the group (and, multi-token, token qt of the unit)
@@ -151,12 +227,35 @@ __global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a, i
             qf[s] = __builtin_bit_cast(bf16x8, z);
         }
     }
+    if (ROPE) {
+        // rotate-half pairs channel i with i + 64: fragment s (channels 32 s + 8 kg + e) with fragment s + 2
+        const int pos = a.pos[b];
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const u32x4 lo = __builtin_bit_cast(u32x4, qf[s]), hi = __builtin_bit_cast(u32x4, qf[s + 2]);
+            u32x4 nlo, nhi;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                float c[4], sn[4];
+                rope_factors4(a, pos, 32 * s + 8 * kg + 4 * h, c, sn);
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const unsigned wl = lo[2 * h + e], wh = hi[2 * h + e];
+                    const float x0a = bfbits2f(wl & 0xffffu), x0b = bfbits2f(wl >> 16);
+                    const float x1a = bfbits2f(wh & 0xffffu), x1b = bfbits2f(wh >> 16);
+                    nlo[2 * h + e] = pack2bf(x0a * c[2 * e] - x1a * sn[2 * e], x0b * c[2 * e + 1] - x1b * sn[2 * e + 1]);
+                    nhi[2 * h + e] = pack2bf(x1a * c[2 * e] + x0a * sn[2 * e], x1b * c[2 * e + 1] + x0b * sn[2 * e + 1]);
+                }
+            }
+            qf[s] = __builtin_bit_cast(bf16x8, nlo);
+            qf[s + 2] = __builtin_bit_cast(bf16x8, nhi);
+        }
+    }
     const size_t plane = ((size_t)a.slots[b] * a.Hkv + g) * (size_t)a.max_len_pad * 128;
     const uint16_t *Kp = (const uint16_t *)a.k_cache + plane + qi * 32 + kg * 8;
     const uint16_t *Vp = (const uint16_t *)a.v_cache + plane + qi * 32 + kg * 8;
     const uint8_t *Kp8 = (const uint8_t *)a.k_cache + plane + lane * 16;
     const uint8_t *Vp8 = (const uint8_t *)a.v_cache + plane + lane * 16;
-
     f32x4 oacc[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) oacc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -283,6 +382,56 @@ __global__ __launch_bounds__(256, 2) void decode_attn_kernel(DecodeAttnArgs a, i
         }
     }
 
+    if (own_new) {
+        // The new token as one more key, from registers: its rotated key exactly as the cache now holds it
+        // (rounded to bf16, or the value of its E4M3 code), the score on the lane's 32 channels summed over
+        // the four lanes of a column, then one step of the online softmax with p in fp32.
+        const int pos = a.pos[b];
+        const uint16_t *kr = (const uint16_t *)a.qkv + (size_t)b * a.ld + (size_t)(a.Hq + g) * 128 + kg * 8;
+        const uint16_t *vr = (const uint16_t *)a.qkv + (size_t)b * a.ld + (size_t)(a.Hq + a.Hkv + g) * 128;
+        float dot = 0.f;
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const u32x4 klo = *(const u32x4 *)(kr + 32 * s), khi = *(const u32x4 *)(kr + 32 * s + 64);
+            const u32x4 qlo = __builtin_bit_cast(u32x4, qf[s]), qhi = __builtin_bit_cast(u32x4, qf[s + 2]);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                float c[4], sn[4];
+                rope_factors4(a, pos, 32 * s + 8 * kg + 4 * h, c, sn);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int wi = 2 * h + (e >> 1), sh = 16 * (e & 1);
+                    const float x0 = bfbits2f((klo[wi] >> sh) & 0xffffu), x1 = bfbits2f((khi[wi] >> sh) & 0xffffu);
+                    float y0 = x0 * c[e] - x1 * sn[e], y1 = x1 * c[e] + x0 * sn[e];
+                    if (FP8) {
+                        y0 = e4m3_decode(e4m3_encode((double)y0 / a.k_scale_d));
+                        y1 = e4m3_decode(e4m3_encode((double)y1 / a.k_scale_d));
+                    } else {
+                        y0 = bf2f(f2bf(y0));
+                        y1 = bf2f(f2bf(y1));
+                    }
+                    dot += bfbits2f((qlo[wi] >> sh) & 0xffffu) * y0 + bfbits2f((qhi[wi] >> sh) & 0xffffu) * y1;
+                }
+            }
+        }
+        dot += __shfl_xor(dot, 16, 64);
+        dot += __shfl_xor(dot, 32, 64);
+        const float x = dot * sl2e;
+        const float m_new = fmaxf(m_run, x);
+        const float alpha = dexp2(m_run - m_new), pnew = dexp2(x - m_new);
+        m_run = m_new;
+        l_run = l_run * alpha + (kg == 0 ? pnew : 0.f);
+#pragma unroll
+        for (int db = 0; db < 8; ++db) {
+            const uint2 vv = *(const uint2 *)(vr + 16 * db + 4 * kg);     // channels 16 db + 4 kg + j
+            float v[4] = {bfbits2f(vv.x & 0xffffu), bfbits2f(vv.x >> 16), bfbits2f(vv.y & 0xffffu), bfbits2f(vv.y >> 16)};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (FP8) v[j] = e4m3_decode(e4m3_encode((double)v[j] / a.v_scale_d));
+                oacc[db][j] = oacc[db][j] * alpha + pnew * v[j];
+            }
+        }
+    }
     float l_tot = l_run + __shfl_xor(l_run, 16, 64);
     l_tot += __shfl_xor(l_tot, 32, 64);
     if (col_ok && n_chunks == 1) {
@@ -386,7 +535,8 @@ static hipError_t launch_decode_attn_t(const DecodeAttnArgs &a, int n_workers, h
         decode_attn_merge_kernel<true><<<dim3(a.B, a.Hkv * 16), 128, 0, s>>>(a);
         return hipGetLastError();
     }
-    decode_attn_kernel<false, FP8><<<(n_workers + 3) / 4, 256, 0, s>>>(a, n_workers);
+    if (a.rope_table) decode_attn_kernel<false, FP8, true><<<(n_workers + 3) / 4, 256, 0, s>>>(a, n_workers);
+    else decode_attn_kernel<false, FP8><<<(n_workers + 3) / 4, 256, 0, s>>>(a, n_workers);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     decode_attn_merge_kernel<false><<<dim3(a.B, a.Hq), 128, 0, s>>>(a);

@@ -44,40 +44,14 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const T *__restrict__ x,
         Elem<T>::st(yr + i, Elem<T>::ld(xr + i) * inv * Elem<T>::ld(g + i));
 }
 
-// bf16 rows with d % 8 == 0: 16-byte loads and stores.
+// bf16 rows with d % 8 == 0: 16-byte loads and stores (the row routine is rmsnorm_bf16_row of pd_internal.h).
 __global__ __launch_bounds__(256) void rmsnorm_bf16_vec_kernel(const uint4 *__restrict__ x,
                                                                const uint4 *__restrict__ g,
                                                                uint4 *__restrict__ y, int d8,
                                                                float d_inv, float eps)
 {
     __shared__ float red[4];
-    const uint4 *xr = x + (size_t)blockIdx.x * d8;
-    uint4 *yr = y + (size_t)blockIdx.x * d8;
-    float ss = 0.f;
-    for (int i = threadIdx.x; i < d8; i += 256) {
-        uint4 v = xr[i];
-        uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            float a = bfbits2f(w[j] & 0xffffu), b = bfbits2f(w[j] >> 16);
-            ss += a * a + b * b;
-        }
-    }
-    ss = wave_sum(ss);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
-    __syncthreads();
-    float inv = rsqrtf((red[0] + red[1] + red[2] + red[3]) * d_inv + eps);
-    for (int i = threadIdx.x; i < d8; i += 256) {
-        uint4 v = xr[i], gg = g[i];
-        uint32_t w[4] = {v.x, v.y, v.z, v.w}, gw[4] = {gg.x, gg.y, gg.z, gg.w}, o[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            float a = bfbits2f(w[j] & 0xffffu) * inv * bfbits2f(gw[j] & 0xffffu);
-            float b = bfbits2f(w[j] >> 16) * inv * bfbits2f(gw[j] >> 16);
-            o[j] = pack2bf(a, b);
-        }
-        yr[i] = make_uint4(o[0], o[1], o[2], o[3]);
-    }
+    rmsnorm_bf16_row(x + (size_t)blockIdx.x * d8, g, y + (size_t)blockIdx.x * d8, d8, d_inv, eps, red);
 }
 
 hipError_t launch_rmsnorm(int dtype, const void *x, const void *g, void *y, int T, int d, float eps,
@@ -504,6 +478,74 @@ hipError_t launch_rope_table(float2 *table, int table_len, int half, const doubl
 {
     size_t n = (size_t)table_len * half;
     rope_table_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(table, table_len, half, inv_freq);
+    return hipGetLastError();
+}
+
+// Blocks 0 .. n_rows-1: RMSNorm of one bf16 row each.  Blocks n_rows .. n_rows + a.T - 1: the cache append
+// of decode row t = block - n_rows (bf16, blocked or 8-bit cache): key rotated at tok_pos[t] in fp32 and
+// stored, value stored; the qkv buffer is only read.
+__global__ __launch_bounds__(256) void rmsnorm_append_kernel(RopeArgs a, const uint4 *__restrict__ x,
+                                                             const uint4 *__restrict__ g, uint4 *__restrict__ y,
+                                                             int n_rows, int d8, float d_inv, float eps)
+{
+    __shared__ float red[4];
+    __shared__ float cs[128], sn[128];
+    if ((int)blockIdx.x < n_rows) {
+        rmsnorm_bf16_row(x + (size_t)blockIdx.x * d8, g, y + (size_t)blockIdx.x * d8, d8, d_inv, eps, red);
+        return;
+    }
+    const int t = blockIdx.x - n_rows;
+    const int half = a.hd >> 1;
+    const int pos = a.tok_pos[t], slot = a.tok_slot[t];
+    for (int i = threadIdx.x; i < half; i += 256) {
+        if (pos < a.table_len) {
+            float2 f = a.table[(size_t)pos * half + i];
+            cs[i] = f.x;
+            sn[i] = f.y;
+        } else {
+            double sv, cv;
+            sincos((double)pos * a.inv_freq[i], &sv, &cv);
+            cs[i] = (float)cv;
+            sn[i] = (float)sv;
+        }
+    }
+    __syncthreads();
+    const uint16_t *row = (const uint16_t *)a.qkv + (size_t)t * a.ld;
+    const size_t plane_elems = (size_t)a.max_len * a.hd;
+    for (int idx = threadIdx.x; idx < a.Hkv * half; idx += 256) {
+        const int gk = idx / half, i = idx - gk * half;
+        const uint16_t *kv = row + (size_t)(a.Hq + gk) * a.hd;
+        const float x0 = bfbits2f(kv[i]), x1 = bfbits2f(kv[i + half]);
+        const float y0 = x0 * cs[i] - x1 * sn[i], y1 = x1 * cs[i] + x0 * sn[i];
+        const size_t plane = ((size_t)slot * a.Hkv + gk) * plane_elems;
+        if (a.fp8) {
+            uint8_t *p8 = (uint8_t *)a.k_cache + plane;
+            p8[kblk8_off(pos, i)] = (uint8_t)e4m3_encode((double)y0 / a.k_scale);
+            p8[kblk8_off(pos, i + half)] = (uint8_t)e4m3_encode((double)y1 / a.k_scale);
+        } else {
+            uint16_t *pk = (uint16_t *)a.k_cache + plane;
+            pk[kblk_off(pos, i)] = f2bf(y0).x;
+            pk[kblk_off(pos, i + half)] = f2bf(y1).x;
+        }
+    }
+    const uint16_t *vsrc = row + (size_t)(a.Hq + a.Hkv) * a.hd;
+    for (int idx = threadIdx.x; idx < a.Hkv * a.hd; idx += 256) {
+        const int gv = idx / a.hd, i = idx - gv * a.hd;
+        const size_t plane = ((size_t)slot * a.Hkv + gv) * plane_elems;
+        if (a.fp8)
+            ((uint8_t *)a.v_cache)[plane + vblk8_off(pos, i)] = (uint8_t)e4m3_encode((double)bfbits2f(vsrc[idx]) / a.v_scale);
+        else
+            ((uint16_t *)a.v_cache)[plane + vblk_off(pos, i)] = vsrc[idx];
+    }
+}
+
+hipError_t launch_rmsnorm_append(const RopeArgs &a, const void *x, const void *g, void *y, int n_rows, int d,
+                                 float eps, hipStream_t s)
+{
+    if (d % 8 != 0 || a.hd != 128 || !a.blocked || !a.tok_slot || n_rows < 0 || a.T < 0) return hipErrorInvalidValue;
+    if (n_rows + a.T == 0) return hipSuccess;
+    rmsnorm_append_kernel<<<n_rows + a.T, 256, 0, s>>>(a, (const uint4 *)x, (const uint4 *)g, (uint4 *)y, n_rows, d / 8,
+                                                       1.0f / (float)d, eps);
     return hipGetLastError();
 }
 

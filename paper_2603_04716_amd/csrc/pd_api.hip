@@ -48,7 +48,7 @@ struct pd_layer {
     int ws_tokens;
     char *ws;
     void *y, *qkv, *o, *h, *act, *eo;
-    int32_t *tok_seq, *tok_pos, *tok_slot, *eidx, *sorted_token, *pair_pos, *offsets, *chunk_cu, *block_hist;
+    int32_t *tok_seq, *tok_pos, *tok_slot, *eidx, *sorted_token, *pair_pos, *offsets, *chunk_cu, *chunk_seq, *block_hist;
     float *logits, *ew;
     int last_rows;
     int call_rows;            // rows of the call in progress (T of a prefill, B of a decode step)
@@ -531,7 +531,7 @@ extern "C" pd_status pd_gemm_e4m3(const void *a_codes, const float *a_scales, co
 
 // Offsets of the parts of a workspace for calls of up to max_tokens rows, and its size.
 struct WsLayout {
-    size_t y, qkv, o, h, act, eo, seq, pos, slot, eidx, sorted, pp, off, bh, log, ew, ccu, units, part, sk, a8c, a8s;
+    size_t y, qkv, o, h, act, eo, seq, pos, slot, eidx, sorted, pp, off, bh, log, ew, ccu, cseq, units, part, sk, a8c, a8s;
     size_t sk_elems;
     size_t total;
 };
@@ -555,7 +555,8 @@ static WsLayout ws_layout(const pd_layer *L, int max_tokens, size_t sk_rows = 25
     w.slot = carve(T * 4); w.eidx = carve(T * K * 4); w.sorted = carve(T * K * 4);
     w.pp = carve(T * K * 4); w.off = carve(65 * 4 + 4); w.bh = carve(E > 0 ? (T * K / 256 + 1) * (size_t)E * 4 : 0);
     w.log = carve(T * (E > 0 ? E : 1) * 4);
-    w.ew = carve(T * K * 4); w.ccu = carve((T + 1) * 4); w.units = carve(4 * T * 4);
+    w.ew = carve(T * K * 4); w.ccu = carve((T + 1) * 4); w.cseq = carve(decode_chunk_bound(L, max_tokens) * 4);
+    w.units = carve(4 * T * 4);
     w.part = carve(decode_chunk_bound(L, max_tokens) * L->cfg.n_q_heads * 130 * sizeof(float));
     // split-K scratch: splits * columns never exceeds 640 tiles * 128 columns + one row of tiles (a
     // launcher that would need more takes fewer splits)
@@ -595,6 +596,7 @@ static void ws_bind(pd_layer *L, char *nw, const WsLayout &w, int max_tokens)
     L->logits = (float *)(nw + w.log);
     L->ew = (float *)(nw + w.ew);
     L->chunk_cu = (int32_t *)(nw + w.ccu);
+    L->chunk_seq = (int32_t *)(nw + w.cseq);
     L->units = (int32_t *)(nw + w.units);
     L->dec_part = (float *)(nw + w.part);
     L->splitk = w.sk_elems ? (float *)(nw + w.sk) : nullptr;
@@ -835,8 +837,10 @@ static bool cache_matches(const pd_layer *L, const pd_kv_cache *c)
 }
 
 // Everything after the attention output: O projection + residual, RMSNorm, FFN or MoE.
+// append (decode step with the fused rotary embedding, bf16 layers): the step's cache append rides in the
+// launch of the second RMSNorm.
 static pd_status run_tail(pd_layer *L, const void *x, int T, const void *router_logits, void *out,
-                          hipStream_t s)
+                          hipStream_t s, const RopeArgs *append = nullptr)
 {
     const pd_layer_config &c = L->cfg;
     const int d = c.d_model, F = c.d_ff, E = c.n_experts;
@@ -850,7 +854,12 @@ static pd_status run_tail(pd_layer *L, const void *x, int T, const void *router_
         memset(&g, 0, sizeof(g));
         g.A = L->h; g.lda = d; g.B = L->w_gate; g.B1 = L->w_up; g.ldb = d; g.C = L->act; g.ldc = F;
         g.M = T; g.N = F; g.K = d; g.epilogue = EPI_SWIGLU; g.n_groups = 1;
-        STEP("rmsnorm_ffn", norm_for_gemm(L, L->h, L->g_ffn, L->y, T, s));
+        if (append) {
+            L->a8_src = nullptr;
+            STEP("rmsnorm_ffn", launch_rmsnorm_append(*append, L->h, L->g_ffn, L->y, T, d, c.rms_eps, s));
+        } else {
+            STEP("rmsnorm_ffn", norm_for_gemm(L, L->h, L->g_ffn, L->y, T, s));
+        }
         g.A = L->y;
         STEP("gate_up_swiglu", run_gemm(L, g, s));
         memset(&g, 0, sizeof(g));
@@ -859,7 +868,8 @@ static pd_status run_tail(pd_layer *L, const void *x, int T, const void *router_
         STEP("down_residual", run_gemm(L, g, s));
         return PD_OK;
     }
-    STEP("rmsnorm_ffn", launch_rmsnorm(c.dtype, L->h, L->g_ffn, L->y, T, d, c.rms_eps, s));
+    if (append) STEP("rmsnorm_ffn", launch_rmsnorm_append(*append, L->h, L->g_ffn, L->y, T, d, c.rms_eps, s));
+    else STEP("rmsnorm_ffn", launch_rmsnorm(c.dtype, L->h, L->g_ffn, L->y, T, d, c.rms_eps, s));
     const float *logits = (const float *)router_logits;
     if (!logits) {
         STEP("router_logits", launch_router_logits(c.dtype, L->y, L->w_router, L->logits, T, d, E, s));
@@ -1269,14 +1279,23 @@ static pd_status decode_step_impl(pd_layer *L, const pd_batch *bt, pd_kv_cache *
             return PD_ERR_DEVICE;
         }
     }
-    if (mfma_dec && B <= 256) {
+    // up to 256 rows of a bf16 layer: the step's bookkeeping rides in the launch of the first RMSNorm
+    const bool meta_in_norm = mfma_dec && B <= 256 && c.dtype == PD_BF16 && c.d_model % 8 == 0 &&
+                              !(L->a8 && B > kA8Rows);
+    if (meta_in_norm) {
+        L->a8_src = nullptr;
+        STEP("rmsnorm_attn", launch_decode_meta_norm(bt->slots, L->d_slots, B, cache->d_len, L->tok_pos, L->chunk_cu,
+                                                     L->chunk_seq, chunk_keys, bt->hidden, L->g_attn, L->y, c.d_model,
+                                                     c.rms_eps, s));
+    } else if (mfma_dec && B <= 256) {
         HIP_TRY(launch_decode_meta_chunks_upload(bt->slots, L->d_slots, B, cache->d_len, L->tok_pos, L->chunk_cu,
-                                                 chunk_keys, s),
+                                                 L->chunk_seq, chunk_keys, s),
                 PD_ERR_DEVICE);
     } else {
         HIP_TRY(launch_write_ints(L->d_slots, bt->slots, B, s), PD_ERR_DEVICE);
         if (mfma_dec)
-            HIP_TRY(launch_decode_meta_chunks(L->d_slots, B, cache->d_len, L->tok_pos, L->chunk_cu, chunk_keys, s),
+            HIP_TRY(launch_decode_meta_chunks(L->d_slots, B, cache->d_len, L->tok_pos, L->chunk_cu, L->chunk_seq,
+                                              chunk_keys, s),
                     PD_ERR_DEVICE);
         else
             HIP_TRY(launch_decode_meta(L->d_slots, B, cache->d_len, L->tok_pos, s), PD_ERR_DEVICE);
@@ -1285,7 +1304,7 @@ static pd_status decode_step_impl(pd_layer *L, const pd_batch *bt, pd_kv_cache *
     memset(&g, 0, sizeof(g));
     g.A = bt->hidden; g.lda = c.d_model; g.B = L->w_qkv; g.ldb = c.d_model; g.C = L->qkv; g.ldc = L->Nqkv;
     g.M = B; g.N = L->Nqkv; g.K = c.d_model; g.epilogue = EPI_NONE; g.n_groups = 1;
-    STEP("rmsnorm_attn", norm_for_gemm(L, bt->hidden, L->g_attn, L->y, B, s));
+    if (!meta_in_norm) STEP("rmsnorm_attn", norm_for_gemm(L, bt->hidden, L->g_attn, L->y, B, s));
     g.A = L->y;
     STEP("qkv_proj", run_gemm(L, g, s));
     RopeArgs r;
@@ -1294,13 +1313,22 @@ static pd_status decode_step_impl(pd_layer *L, const pd_batch *bt, pd_kv_cache *
     r.max_len = cache->plane_len; r.blocked = cache->blocked; r.inv_freq = L->inv_freq;
     r.fp8 = cache->fp8; r.k_scale = cache->k_scale; r.v_scale = cache->v_scale;
     r.table = L->rope_table; r.table_len = kRopeTableLen;
-    STEP("rope_kv_append", launch_rope_kv(c.dtype, r, s));
+    // Fused form (matrix-core attention over a blocked cache, no 8-bit activations in this call): the
+    // attention kernel rotates q and the new key itself and takes the new token from registers; the
+    // append to the cache rides in the launch of the second RMSNorm.  Otherwise a launch of its own
+    // rotates in place and appends first.
+    const bool fused_rope = mfma_dec && c.d_model % 8 == 0 && !(L->a8 && B > kA8Rows);
+    if (!fused_rope) STEP("rope_kv_append", launch_rope_kv(c.dtype, r, s));
     if (mfma_dec) {
         DecodeAttnArgs da;
         memset(&da, 0, sizeof(da));
+        if (fused_rope) {
+            da.rope_table = L->rope_table; da.rope_table_len = kRopeTableLen; da.inv_freq = L->inv_freq;
+            da.k_scale_d = cache->k_scale; da.v_scale_d = cache->v_scale;
+        }
         da.qkv = L->qkv; da.ld = L->Nqkv; da.o = L->o; da.B = B; da.Hq = c.n_q_heads; da.Hkv = c.n_kv_heads;
         da.scale = (float)(1.0 / sqrt((double)c.head_dim)); da.slots = L->d_slots; da.pos = L->tok_pos;
-        da.chunk_cu = L->chunk_cu; da.chunk_keys = chunk_keys; da.total_chunks = total_chunks;
+        da.chunk_cu = L->chunk_cu; da.chunk_seq = L->chunk_seq; da.chunk_keys = chunk_keys; da.total_chunks = total_chunks;
         da.k_cache = cache->k; da.v_cache = cache->v; da.max_len_pad = cache->plane_len;
         da.fp8 = cache->fp8; da.k_scale = (float)cache->k_scale; da.v_scale = (float)cache->v_scale;
         da.part_o = L->dec_part;
@@ -1315,7 +1343,7 @@ static pd_status decode_step_impl(pd_layer *L, const pd_batch *bt, pd_kv_cache *
         a.decode = 1;
         STEP("decode_attention", launch_attn_generic(c.dtype, a, s));
     }
-    st = run_tail(L, bt->hidden, B, bt->router_logits, out, s);
+    st = run_tail(L, bt->hidden, B, bt->router_logits, out, s, mfma_dec && fused_rope ? &r : nullptr);
     if (st != PD_OK) return st;
     for (int b = 0; b < B; ++b) cache->h_len[(size_t)bt->slots[b]] += 1;
     L->last_rows = B;

@@ -129,6 +129,39 @@ __host__ __device__ __forceinline__ size_t w8pack_off(int n, int k, int K)
            ((k >> 5) & 1) * 8 + (k & 7);
 }
 
+// RMSNorm of one bf16 row of 8 * d8 elements by one workgroup of 256 threads: 16-byte loads and stores,
+// statistics in fp32.  red: 4 floats of LDS.
+__device__ __forceinline__ void rmsnorm_bf16_row(const uint4 *__restrict__ xr, const uint4 *__restrict__ g,
+                                                 uint4 *__restrict__ yr, int d8, float d_inv, float eps, float *red)
+{
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < d8; i += 256) {
+        uint4 v = xr[i];
+        uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float a = bfbits2f(w[j] & 0xffffu), b = bfbits2f(w[j] >> 16);
+            ss += a * a + b * b;
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    float inv = rsqrtf((red[0] + red[1] + red[2] + red[3]) * d_inv + eps);
+    for (int i = threadIdx.x; i < d8; i += 256) {
+        uint4 v = xr[i], gg = g[i];
+        uint32_t w[4] = {v.x, v.y, v.z, v.w}, gw[4] = {gg.x, gg.y, gg.z, gg.w}, o[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float a = bfbits2f(w[j] & 0xffffu) * inv * bfbits2f(gw[j] & 0xffffu);
+            float b = bfbits2f(w[j] >> 16) * inv * bfbits2f(gw[j] >> 16);
+            o[j] = pack2bf(a, b);
+        }
+        yr[i] = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+}
+
 constexpr int kMetaChunk = 255;  // ints carried by value per meta-kernel launch (+1 for cu_seqlens)
 struct IntChunk {
     int32_t v[256];
@@ -233,6 +266,12 @@ struct RopeArgs {
 };
 hipError_t launch_rope_table(float2 *table, int table_len, int half, const double *inv_freq, hipStream_t s);
 hipError_t launch_rope_kv(int dtype, const RopeArgs &a, hipStream_t s);
+// RMSNorm of n_rows bf16 rows (d a multiple of 8) and, in the same launch, the cache append of a decode
+// step: for each of the a.T rows of a.qkv the key is rotated (qkv itself is left unrotated) and stored
+// with the value at a.tok_pos / a.tok_slot of the blocked bf16 or 8-bit cache.  The two halves are
+// independent; together they cost one launch.
+hipError_t launch_rmsnorm_append(const RopeArgs &a, const void *x, const void *g, void *y, int n_rows, int d,
+                                 float eps, hipStream_t s);
 
 struct AttnArgs {
     const void *qkv;         // rotated q (and, for prefill, k and v) rows
@@ -301,6 +340,7 @@ struct DecodeAttnArgs {
     const int32_t *slots;      // [B]
     const int32_t *pos;        // [B] position of the new token = keys - 1
     const int32_t *chunk_cu;   // [B+1] prefix sum of key chunks per sequence
+    const int32_t *chunk_seq;  // [total_chunks] sequence of every chunk, or nullptr (then found by bisection of chunk_cu)
     int32_t chunk_keys;        // keys per chunk (multiple of 64)
     int32_t total_chunks;
     const void *k_cache, *v_cache;
@@ -316,14 +356,30 @@ struct DecodeAttnArgs {
     // E4M3 cache (the 8-bit blocked layout): value = code * scale
     int32_t fp8;
     float k_scale, v_scale;
+    // Fused rotary embedding (one-token step only; rope_table null = off): the q and k rows of qkv arrive
+    // unrotated, every worker rotates its query rows at position pos[b], and the worker that owns the last
+    // chunk of a (sequence, kv head) adds the new token (position pos[b], not yet in the cache: the chunks
+    // cover positions below it) from registers, its key rotated and rounded as the cache will hold it
+    // (bf16, or the value of the E4M3 code of x / scale).  The caller appends it to the cache afterwards.
+    const float2 *rope_table;  // [rope_table_len][64] (cos, sin) of pos * inv_freq[i]
+    int32_t rope_table_len;
+    const double *inv_freq;    // [64], for positions beyond the table
+    double k_scale_d, v_scale_d;
 };
 hipError_t launch_decode_attn_mfma(const DecodeAttnArgs &a, hipStream_t s);
-// pos[b] = len[slot[b]]; len[slot[b]] += 1; chunk_cu = prefix sum of ceil((pos+1)/chunk_keys)
+// pos[b] = len[slot[b]]; len[slot[b]] += 1; chunk_cu = prefix sum of ceil((pos+1)/chunk_keys);
+// chunk_seq[c] = b for the chunks c of sequence b
 hipError_t launch_decode_meta_chunks(const int32_t *d_slots, int B, int32_t *d_len, int32_t *d_pos,
-                                     int32_t *chunk_cu, int chunk_keys, hipStream_t s);
+                                     int32_t *chunk_cu, int32_t *chunk_seq, int chunk_keys, hipStream_t s);
 // the same for B <= 256 with the slots taken from the host array (and stored to d_slots): one launch
 hipError_t launch_decode_meta_chunks_upload(const int32_t *host_slots, int32_t *d_slots, int B, int32_t *d_len,
-                                            int32_t *d_pos, int32_t *chunk_cu, int chunk_keys, hipStream_t s);
+                                            int32_t *d_pos, int32_t *chunk_cu, int32_t *chunk_seq, int chunk_keys,
+                                            hipStream_t s);
+// that and the RMSNorm of the step's B bf16 rows (d a multiple of 8) in one launch: blocks 0 .. B-1
+// normalise a row each, block B does the bookkeeping
+hipError_t launch_decode_meta_norm(const int32_t *host_slots, int32_t *d_slots, int B, int32_t *d_len, int32_t *d_pos,
+                                   int32_t *chunk_cu, int32_t *chunk_seq, int chunk_keys, const void *x, const void *g,
+                                   void *y, int d, float eps, hipStream_t s);
 
 // ---- MoE -----------------------------------------------------------------------------------------
 struct MoeRouteArgs {

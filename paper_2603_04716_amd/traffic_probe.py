@@ -16,6 +16,11 @@ The workload is the 8B-shaped bf16 layer: a 1 GiB pd_stream_copy (known traffic:
 1 GiB written), a prefill of 4 x 2048 tokens and a decode step of 256 sequences over 2048 cached
 tokens, each three times.  A counter reads KiB per dispatch; the copy kernel's reading against its
 known size gives the scale factor applied to every other kernel.
+
+`--decode-batches 64,128,256` replaces the prefill / batch-256 pair by decode steps at the listed
+batches (a kernel instance is told apart by its grid and workgroup size), and
+`--durations <kernel trace csv>` prints the mean duration, workgroup count and workgroup size of
+every (kernel, grid) of a `rocprofv3 --kernel-trace` run of the same workload.
 """
 import argparse
 import collections
@@ -30,7 +35,7 @@ COPY_BYTES = 1 << 30
 L_IN, N_SEQ, KV_LEN, BATCH = 2048, 4, 2048, 256
 
 
-def workload():
+def workload(decode_batches=None):
     import torch
     import pd_inputs as I
     import paper_2603_04716_amd as pd
@@ -43,20 +48,27 @@ def workload():
     out = torch.empty_like(x)
     cu = [L_IN * i for i in range(N_SEQ + 1)]
     pd.pd_layer_reserve(layer.h, T)
-    cache = layer.new_cache(BATCH, KV_LEN + 8)
+    bmax = max(decode_batches) if decode_batches else BATCH
+    cache = layer.new_cache(bmax, KV_LEN + 8)
     k, v = I.kv_fill(cfg["n_kv_heads"], KV_LEN, cfg["head_dim"], seed=11, dtype="bf16")
-    layer.fill_cache(cache, [KV_LEN] * BATCH, H._dev(k, "bf16"), H._dev(v, "bf16"))
-    xdec = H._dev(I.hidden(BATCH, cfg["d_model"], seed=12, dtype="bf16"), "bf16")
+    layer.fill_cache(cache, [KV_LEN] * bmax, H._dev(k, "bf16"), H._dev(v, "bf16"))
+    xdec = H._dev(I.hidden(bmax, cfg["d_model"], seed=12, dtype="bf16"), "bf16")
     odec = torch.empty_like(xdec)
     src = torch.ones(COPY_BYTES // 2, dtype=torch.bfloat16, device="cuda")
     dst = torch.empty_like(src)
-    slots = list(range(BATCH))
+    pd.pd_layer_reserve(layer.h, max(T, bmax))
     torch.cuda.synchronize()
     for _ in range(3):
         pd.pd_stream_copy(dst, src)
-        pd.pd_prefill(layer.h, x, cu, out)
-        pd.pd_kv_cache_set_lens(cache, slots, [KV_LEN] * BATCH)
-        pd.pd_decode_step(layer.h, xdec, slots, cache, odec)
+        if decode_batches:
+            for B in decode_batches:
+                for _rep in range(3):
+                    pd.pd_kv_cache_set_lens(cache, list(range(B)), [KV_LEN] * B)
+                    pd.pd_decode_step(layer.h, xdec[:B].contiguous(), list(range(B)), cache, odec[:B])
+        else:
+            pd.pd_prefill(layer.h, x, cu, out)
+            pd.pd_kv_cache_set_lens(cache, list(range(BATCH)), [KV_LEN] * BATCH)
+            pd.pd_decode_step(layer.h, xdec, list(range(BATCH)), cache, odec)
         torch.cuda.synchronize()
     layer.close()
 
@@ -76,6 +88,21 @@ def read_counter(path, counter):
                 continue
             agg[(short(r["Kernel_Name"]), int(r["Grid_Size"]))].append(float(r["Counter_Value"]))
     return agg
+
+
+def durations(trace_csv):
+    """Mean duration per (kernel, grid) of a kernel-trace csv (columns of rocprofv3's kernel_trace)."""
+    agg = collections.defaultdict(list)
+    with open(trace_csv) as f:
+        for r in csv.DictReader(f):
+            wg = int(r["Workgroup_Size_X"]) * int(r.get("Workgroup_Size_Y", 1) or 1) * int(r.get("Workgroup_Size_Z", 1) or 1)
+            grid = int(r["Grid_Size_X"]) * int(r.get("Grid_Size_Y", 1) or 1) * int(r.get("Grid_Size_Z", 1) or 1)
+            agg[(short(r["Kernel_Name"]), grid, wg)].append((int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3)
+    print("| kernel | workgroups | threads per workgroup | dispatches | mean us | min us |")
+    print("|---|---|---|---|---|---|")
+    for key in sorted(agg, key=lambda k: (k[0], k[1])):
+        v = agg[key]
+        print(f"| `{key[0]}` | {key[1] // key[2]} | {key[2]} | {len(v)} | {sum(v) / len(v):.1f} | {min(v):.1f} |")
 
 
 def summarise(fetch_csv, write_csv):
@@ -103,11 +130,15 @@ def summarise(fetch_csv, write_csv):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--summarise", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"))
+    ap.add_argument("--durations", metavar="KERNEL_TRACE_CSV")
+    ap.add_argument("--decode-batches", default="", help="comma-separated decode batches instead of prefill + batch 256")
     args = ap.parse_args()
     if args.summarise:
         summarise(*args.summarise)
+    elif args.durations:
+        durations(args.durations)
     else:
-        workload()
+        workload([int(b) for b in args.decode_batches.split(",")] if args.decode_batches else None)
 
 
 if __name__ == "__main__":

@@ -188,6 +188,38 @@ def test_bf16_decode_batch_sizes_ragged_cache(B):
     gl.close()
 
 
+@pytest.mark.parametrize("B", [17, 32, 33, 48, 64, 65, 100, 128])
+@pytest.mark.parametrize("hq,hkv,d,F", [(4, 2, 512, 1024), (6, 2, 1024, 1536)])
+def test_bf16_decode_mid_batches_wider_layers(B, hq, hkv, d, F):
+    """Decode batches of 17 .. 128 rows on layers with inner dimensions of 512 .. 1536 (the wide
+    register-operand kernel needs K in multiples of 512, the split-K tile kernels take the rest),
+    groups of 2 and 3 query heads per kv head, ragged cache lengths including an empty and a
+    block-aligned one; two steps, so the second attends over what the fused rotary embedding and
+    append of the first wrote."""
+    cfg = I.small_config(dtype="bf16", d_model=d, n_q_heads=hq, n_kv_heads=hkv, head_dim=128, d_ff=F)
+    ol, gl = both(cfg, std=0.04)
+    rng = np.random.default_rng(B + d)
+    lens = rng.integers(0, 130, B)
+    lens[0], lens[1] = 129, 63
+    cap = 136
+    oc, gc = O.KVCache(ol, B, cap), gl.cache(B, cap)
+    k, v = I.kv_fill(hkv, 129, 128, seed=77, dtype="bf16")
+    kd, vd = to_dev(k, "bf16"), to_dev(v, "bf16")
+    for i, n in enumerate(lens):
+        n = int(n)
+        oc.set(i, k[:, :n], v[:, :n])
+        if n > 0:
+            pd.pd_kv_cache_set(gc, i, kd[:, :n].contiguous(), vd[:, :n].contiguous())
+    slots = [int(s_) for s_ in rng.permutation(B)]
+    for step in range(2):
+        xn = I.hidden(B, d, seed=41 + step, dtype="bf16")
+        ref = O.decode_step(ol, xn, slots, oc)
+        got = gl.decode(xn, slots, gc)
+        assert relmax(got, ref) <= TOL["bf16"]
+        assert max(relmax(got[i], ref[i]) for i in range(B)) <= 2 * TOL["bf16"]
+    gl.close()
+
+
 def test_fp32_decode_beyond_rotary_table():
     """Positions past the precomputed rotary table (32768) take the on-the-fly double-precision
     path; fp32 bound 1e-5 must still hold there."""
