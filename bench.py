@@ -22,7 +22,9 @@ HBM_PEAK_GBPS = 8000.0
 N_LAYERS = 32
 L_IN, N_SEQ = 2048, 4              # prefill workload: 4 x 2048 = 8192 tokens
 KV_LEN = 2048
-BATCHES = [1, 2, 4, 8, 16, 32, 64, 128, 192, 224, 256]   # powers of two, refined below the largest
+# powers of two, refined around the batch where the 20 ms TPOT line is crossed, and past it, so that the
+# largest feasible batch is set by the TPOT target and not by the end of the sweep
+BATCHES = [1, 2, 4, 8, 16, 32, 64, 128, 192, 224, 256, 272, 288, 320]
 TTFT_SLO, TPOT_SLO, L_OUT = 2.0, 0.020, 512.0
 PREFILL_REPS = 12                  # back-to-back prefill calls per step (each the full 8192 tokens); median
 DECODE_REPS = 3                    # decode steps per batch size per step; median
@@ -73,7 +75,7 @@ def fp8_section(cfg, weights, x, cu, kd, vd):
     layer = H.Layer(cfg, weights, a8=True)
     T = x.shape[0]
     t_pre = layer.time_prefill(x, cu, iters=10, warmup=12)   # the clock settles over the first calls after a pause
-    batches = [b for b in BATCHES] + [320, 384, 448, 512, 576]
+    batches = sorted(set(BATCHES + [320, 384, 448, 512, 576]))
     bmax = max(batches)
     cache = layer.new_cache(bmax, KV_LEN + 8, fp8_scales=(0.5, 0.125))
     layer.fill_cache(cache, [KV_LEN] * bmax, kd, vd)
@@ -111,6 +113,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-fp8", action="store_true", help="skip the 8-bit section reported beside the bf16 figures")
+    ap.add_argument("--no-extra", action="store_true",
+                    help="skip the other configurations reported beside the headline (prefill at 8 x 1024 and 2 x 4096, "
+                         "long-context decode at KV 4096 / 8192 / 16384)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the path uses no second device and no collectives; "
@@ -196,7 +201,7 @@ def main():
     # per-kernel durations of a decode step (events between kernels; not part of the timed region)
     slots_all = list(range(bmax))
     pd.pd_profile_enable(layer.h, True)
-    for B in (BATCHES[0], BATCHES[-1]):
+    for B in (1, 8, 64, 256):
         for _ in range(3):
             pd.pd_kv_cache_set_lens(cache, slots_all[:B], [KV_LEN] * B)
             pd.pd_decode_step(layer.h, xdec[:B].contiguous(), slots_all[:B], cache, runs[B].out)
@@ -256,7 +261,7 @@ def main():
         "ms_per_step": round(wall / args.steps * 1e3, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "llama8b-shaped layer, bf16: prefill 4x2048 tokens; decode batch 1..256 at KV 2048; "
+        "config": {"workload": "llama8b-shaped layer, bf16: prefill 4x2048 tokens; decode batch 1..320 at KV 2048; "
                                "per-layer time x32", "n_layers_scaling": N_LAYERS, "l_in": L_IN, "kv_len": KV_LEN,
                    "ttft_slo_s": TTFT_SLO, "tpot_slo_s": TPOT_SLO, "l_out": L_OUT, "decode_graph": not args.no_graph,
                    "prefill_calls_per_step": PREFILL_REPS, "decode_calls_per_batch_per_step": DECODE_REPS,
@@ -274,6 +279,16 @@ def main():
                      "algorithmic_bytes": 2.0 * (T * d + 2 * f * d + T * f), "avg_launch_ms": round(gu_ms, 4)},
         "kernels": kernels,
     }
+    if not args.no_extra:
+        # the benchmark's other single-GPU configurations, measured by the same harness on the same layer
+        # (reported beside the headline, never as `value`)
+        from paper_2603_04716_amd import experiments as X
+        pd.pd_kv_cache_destroy(cache)
+        layer.caches.remove(cache)
+        del runs
+        torch.cuda.empty_cache()
+        line["prefill_vs_l_in"] = X.prefill_points(cfg, layer, x, iters=8, warmup=6)
+        line["long_context"] = X.longctx_cases(cfg, layer, modes=("uniform",), reps=5)
     layer.close()
     if not args.no_fp8:
         line["fp8"] = fp8_section(cfg, weights, x, cu, kd, vd)

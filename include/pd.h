@@ -298,6 +298,20 @@ pd_status pd_profile_read(pd_layer *layer, int32_t max_entries, const char **nam
 pd_status pd_stream_copy(void *dst, const void *src, int64_t bytes, void *stream);
 
 /*
+ * The other measurement aid: the matrix pipe alone on given operand values.  n_workgroups workgroups
+ * of 8 waves load their operands once - lane t of a workgroup takes a_vals[32 t .. 32 t + 31] (four
+ * A fragments) and b_vals[16 t .. 16 t + 15] (two B fragments), bf16 device arrays of 16384 and 8192
+ * elements, 16-byte aligned - and then issue iters x 8 v_mfma_f32_32x32x16_bf16 per wave with no
+ * memory traffic: 2 * 32 * 32 * 16 * 8 * iters * 8 * n_workgroups flops.  The time of this launch is
+ * the ceiling that operand values of that distribution allow the prefill GEMMs (Introduction:
+ * prefill is compute-bound), whatever feeds the matrix pipe.  sink: device fp32 [n_workgroups * 512],
+ * written once at the end.  Asynchronous on stream.
+ * Errors: PD_ERR_INVALID_ARG (NULL / misaligned pointer, n_workgroups outside 1 .. 65536, iters < 1).
+ */
+pd_status pd_mfma_probe(const void *a_vals, const void *b_vals, int32_t n_workgroups, int32_t iters,
+                        float *sink, void *stream);
+
+/*
  * The two ends of the decoder stack around the layers (the paper's measured throughputs are those
  * of whole served models; Section "Acquire ... throughput" times them end to end): the token
  * embedding in front and, behind the last layer, the final RMSNorm and the vocabulary projection.

@@ -23,7 +23,7 @@ PD_F32, PD_BF16 = 0, 1
 EXPORTS = [
     "pd_layer_create", "pd_layer_create_w8", "pd_layer_create_w8a8", "pd_quantize_rows_e4m3", "pd_gemm_e4m3", "pd_layer_destroy", "pd_layer_reserve", "pd_kv_cache_create", "pd_kv_cache_create_fp8",
     "pd_kv_cache_destroy", "pd_kv_cache_set", "pd_kv_cache_set_len", "pd_kv_cache_len",
-    "pd_kv_cache_set_lens", "pd_kv_cache_get", "pd_profile_enable", "pd_profile_read", "pd_stream_copy", "pd_head_create", "pd_head_create_w8", "pd_head_destroy", "pd_embed", "pd_lm_head", "pd_prefill", "pd_prefill_chunk", "pd_decode_step", "pd_decode_step_noalloc", "pd_last_expert_choice", "pd_allocate",
+    "pd_kv_cache_set_lens", "pd_kv_cache_get", "pd_profile_enable", "pd_profile_read", "pd_stream_copy", "pd_mfma_probe", "pd_head_create", "pd_head_create_w8", "pd_head_destroy", "pd_embed", "pd_lm_head", "pd_prefill", "pd_prefill_chunk", "pd_decode_step", "pd_decode_step_noalloc", "pd_last_expert_choice", "pd_allocate",
     "pd_fifo_replay", "pd_mm1_sojourn", "pd_fifo_replay_batched", "pd_prefill_throughput_dp", "pd_mg1_sojourn", "pd_kv_transfer_overhead", "pd_allocate_stages", "pd_status_string", "pd_last_error",
 ]
 
@@ -231,6 +231,13 @@ def pd_stream_copy(dst, src):
     if dst.numel() * dst.element_size() != nbytes:
         raise ValueError("pd_stream_copy: size mismatch")
     _check(lib.pd_stream_copy(_ptr(dst), _ptr(src), C.c_int64(nbytes), _stream()))
+
+
+def pd_mfma_probe(a_vals, b_vals, n_workgroups, iters, sink):
+    """Register-only matrix-instruction loop on the given operand values (bf16 tensors of 16384 and 8192 elements)."""
+    if a_vals.numel() != 16384 or b_vals.numel() != 8192 or sink.numel() < n_workgroups * 512:
+        raise ValueError("pd_mfma_probe: a_vals 16384, b_vals 8192 bf16 elements, sink n_workgroups * 512 floats")
+    _check(lib.pd_mfma_probe(_ptr(a_vals), _ptr(b_vals), C.c_int32(n_workgroups), C.c_int32(iters), _ptr(sink), _stream()))
 
 
 def pd_kv_cache_len(cache, slot):

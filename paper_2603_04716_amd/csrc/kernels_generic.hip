@@ -968,4 +968,48 @@ hipError_t launch_stream_copy(void *dst, const void *src, size_t n_vec16, hipStr
     return hipGetLastError();
 }
 
+// ---- matrix-core loop on register operands (ceiling of the matrix pipe for given operand values) -----
+typedef __bf16 probe_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float probe_f32x16 __attribute__((ext_vector_type(16)));
+
+// Each of the 512 lanes of a workgroup loads four A fragments and two B fragments (8 bf16 each) once and
+// then issues nothing but v_mfma_f32_32x32x16_bf16 on them: iters x 8 instructions per wave, 8 independent
+// accumulator blocks, no memory traffic inside the loop.
+__global__ __launch_bounds__(512) void mfma_probe_kernel(float *__restrict__ sink, const uint4 *__restrict__ a_vals,
+                                                         const uint4 *__restrict__ b_vals, int iters)
+{
+    probe_bf16x8 fa[4], fb[2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) fa[i] = __builtin_bit_cast(probe_bf16x8, a_vals[threadIdx.x * 4 + i]);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) fb[i] = __builtin_bit_cast(probe_bf16x8, b_vals[threadIdx.x * 2 + i]);
+    probe_f32x16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) t += acc[i][j][r];
+    sink[(size_t)blockIdx.x * 512 + threadIdx.x] = t;
+}
+
+hipError_t launch_mfma_probe(float *sink, const void *a_vals, const void *b_vals, int n_workgroups, int iters, hipStream_t s)
+{
+    mfma_probe_kernel<<<n_workgroups, 512, 0, s>>>(sink, (const uint4 *)a_vals, (const uint4 *)b_vals, iters);
+    return hipGetLastError();
+}
+
 }  // namespace pd

@@ -1405,6 +1405,18 @@ extern "C" pd_status pd_stream_copy(void *dst, const void *src, int64_t bytes, v
     return PD_OK;
 }
 
+extern "C" pd_status pd_mfma_probe(const void *a_vals, const void *b_vals, int32_t n_workgroups, int32_t iters,
+                                   float *sink, void *stream)
+{
+    if (!a_vals || !b_vals || !sink || n_workgroups < 1 || n_workgroups > 65536 || iters < 1 ||
+        ((uintptr_t)a_vals | (uintptr_t)b_vals) % 16 != 0) {
+        set_error("pd_mfma_probe: NULL or misaligned pointer, or a count outside 1 .. 65536 workgroups / iters >= 1");
+        return PD_ERR_INVALID_ARG;
+    }
+    HIP_TRY(launch_mfma_probe(sink, a_vals, b_vals, n_workgroups, iters, (hipStream_t)stream), PD_ERR_DEVICE);
+    return PD_OK;
+}
+
 // ---- stack ends: embedding, final norm + vocabulary projection -------------------------------------
 
 struct pd_head {

@@ -319,6 +319,7 @@ int attn_chunk_splits(const AttnArgs &a, int max_keys);
 size_t attn_chunk_split_bytes(const AttnArgs &a, int n_split);
 
 hipError_t launch_stream_copy(void *dst, const void *src, size_t n_vec16, hipStream_t s);
+hipError_t launch_mfma_probe(float *sink, const void *a_vals, const void *b_vals, int n_workgroups, int iters, hipStream_t s);
 // out[t, :] = table[ids[t], :] (rows of row_bytes bytes, a multiple of 4); ids outside 0 .. n_rows-1 give zeros
 hipError_t launch_embed_rows(void *out, const void *table, const int32_t *ids, int T, int n_rows,
                              size_t row_bytes, hipStream_t s);

@@ -9,6 +9,8 @@
     python -m paper_2603_04716_amd.experiments fp8kv        # decode curve over the KV cache held as 8-bit E4M3
                                                             # codes beside the bf16 cache, KV 2048 and 8192
     python -m paper_2603_04716_amd.experiments w8           # small-batch decode with 8-bit projection weights
+    python -m paper_2603_04716_amd.experiments operands     # the same prefill call on hidden states of different
+                                                            # values (what the operand values cost the clock)
     python -m paper_2603_04716_amd.experiments kvxfer       # KV hand-off: cache export / import per layer, the
                                                             # modelled link, Eq. (13) with that overhead
 
@@ -38,33 +40,40 @@ def _layer(name):
     return cfg, H.Layer(cfg, I.layer_weights(cfg))
 
 
+def prefill_points(cfg, layer, x, rl=None, iters=10, warmup=3):
+    """Maximum prefill throughput of x's tokens cut into sequences of 1024 / 2048 / 4096."""
+    T = x.shape[0]
+    pts = []
+    for l_in in (1024, 2048, 4096):
+        cu = I.uniform_cu_seqlens(T // l_in, l_in)
+        ms = layer.time_prefill(x, cu, iters=iters, warmup=warmup, router_logits=rl)
+        fl = H.prefill_flops(cfg, [l_in] * (T // l_in))
+        pts.append({"l_in": l_in, "ms_per_layer": round(ms, 4), "tok_s_model": round(T / (N_LAYERS * ms * 1e-3), 1),
+                    "tflops": round(fl / (ms * 1e-3) / 1e12, 1), "mfma_frac": round(fl / (ms * 1e-3) / MFMA_PEAK, 4)})
+    return pts
+
+
 def run_prefill(name="llama8b"):
     cfg, layer = _layer(name)
     T = 8192
     x = H._dev(I.hidden(T, cfg["d_model"], seed=10, dtype="bf16"), "bf16")
     rl = torch.from_numpy(I.router_logits(T, cfg["n_experts"], seed=13)).cuda() if cfg["n_experts"] else None
-    pts = []
-    for l_in in (1024, 2048, 4096):
-        cu = I.uniform_cu_seqlens(T // l_in, l_in)
-        ms = layer.time_prefill(x, cu, iters=10, warmup=3, router_logits=rl)
-        fl = H.prefill_flops(cfg, [l_in] * (T // l_in))
-        pts.append({"l_in": l_in, "ms_per_layer": round(ms, 4), "tok_s_model": round(T / (N_LAYERS * ms * 1e-3), 1),
-                    "tflops": round(fl / (ms * 1e-3) / 1e12, 1), "mfma_frac": round(fl / (ms * 1e-3) / MFMA_PEAK, 4)})
+    pts = prefill_points(cfg, layer, x, rl)
     layer.close()
     return {"experiment": "max prefill throughput vs input length", "layer": name, "tokens": T, "points": pts}
 
 
-def run_longctx():
-    cfg, layer = _layer("llama8b")
+def longctx_cases(cfg, layer, modes=("uniform", "ragged"), reps=7, kv_lengths=(4096, 8192, 16384), bmax=128):
+    """Decode TPOT against batch at long KV lengths and, per TPOT target, the largest batch that meets
+    it (powers of two, then bisection): section "Acquire decode throughput under TPOT constraints"."""
     hkv, hd, d = cfg["n_kv_heads"], cfg["head_dim"], cfg["d_model"]
-    bmax = 128
-    out = {"experiment": "long-context decode: TPOT vs batch, uniform and ragged KV", "cases": []}
+    cases = []
     xall = H._dev(I.hidden(bmax, d, seed=12, dtype="bf16"), "bf16")
-    for S in (4096, 8192, 16384):
+    for S in kv_lengths:
         cache = layer.new_cache(bmax, S + 8)
         k, v = I.kv_fill(hkv, S, hd, seed=11, dtype="bf16")
         kd, vd = H._dev(k, "bf16"), H._dev(v, "bf16")
-        for mode in ("uniform", "ragged"):
+        for mode in modes:
             lens_all = np.full(bmax, S, np.int32) if mode == "uniform" else I.ragged_kv_lengths(bmax, S, seed=S)
             layer.fill_cache(cache, lens_all, kd, vd)
             cache_pts = {}
@@ -72,12 +81,14 @@ def run_longctx():
             def tpot(B):
                 if B not in cache_pts:
                     run = layer.make_decode_step(cache, xall[:B].contiguous(), lens_all[:B])
-                    ms = H.median([run() for _ in range(7)])
+                    ms = H.median([run() for _ in range(reps)])
                     cache_pts[B] = ms
                 return N_LAYERS * cache_pts[B] * 1e-3
 
             curve = []
             for B in (1, 2, 4, 8, 16, 32, 64, 128):
+                if B > bmax:
+                    break
                 t = tpot(B)
                 by = H.decode_bytes(cfg, lens_all[:B])
                 curve.append({"batch": B, "tpot_ms": round(t * 1e3, 3), "tok_s": round(B / t, 1),
@@ -92,10 +103,16 @@ def run_longctx():
                              hbm_gbps=round(by / (t / N_LAYERS) / 1e9, 1),
                              hbm_frac=round(by / (t / N_LAYERS) / HBM_PEAK, 4), capped=(b == bmax))
                 targets.append(e)
-            out["cases"].append({"kv_capacity": S, "lengths": mode, "mean_kv": float(np.mean(lens_all)),
-                                 "curve": curve, "targets": targets})
+            cases.append({"kv_capacity": S, "lengths": mode, "mean_kv": float(np.mean(lens_all)),
+                          "curve": curve, "targets": targets})
         layer.free_cache(cache)
         del kd, vd
+    return cases
+
+
+def run_longctx():
+    cfg, layer = _layer("llama8b")
+    out = {"experiment": "long-context decode: TPOT vs batch, uniform and ragged KV", "cases": longctx_cases(cfg, layer)}
     layer.close()
     return out
 
@@ -133,8 +150,7 @@ def run_queue(n_req=2000):
         arr = I.poisson_arrivals(n_req, lam, seed=int(f * 100))
         soj = pd.pd_fifo_replay(arr, service)
         pred = pd.pd_mm1_sojourn(tp_hat, mean_l, lam)
-        rho = lam * service.mean()
-        pk = service.mean() + lam * float(np.mean(service ** 2)) / (2 * (1 - rho))
+        pk = pd.pd_mg1_sojourn(lam, float(service.mean()), float(np.mean(service ** 2)))   # Pollaczek-Khinchine
         res["rates"].append({"load": f, "lambda_req_s": round(lam, 4), "mean_ttft_s": round(float(np.mean(soj)), 5),
                              "mm1_pred_s": round(pred, 5), "ratio_measured_over_mm1": round(float(np.mean(soj)) / pred, 4),
                              "mg1_pk_s": round(pk, 5)})
@@ -625,11 +641,45 @@ def run_kvxfer():
     return out
 
 
+def run_operands():
+    """The same prefill call (4 x 2048 tokens, 8B shape) on hidden states of different values: the work
+    and the schedule are identical, only what the matrix pipe toggles differs.  Beside the register-only
+    loop of mfma_ceiling_probe this separates what the kernels' schedule costs from what the operand
+    values cost (the clock the chip sustains under its power limit)."""
+    cfg, layer = _layer("llama8b")
+    T, l_in = 8192, 2048
+    x = H._dev(I.hidden(T, cfg["d_model"], seed=10, dtype="bf16"), "bf16")
+    cu = I.uniform_cu_seqlens(T // l_in, l_in)
+    fl = H.prefill_flops(cfg, [l_in] * (T // l_in))
+    d, f = cfg["d_model"], cfg["d_ff"]
+    gemm_fl = {"qkv_proj": 2.0 * T * (cfg["n_q_heads"] + 2 * cfg["n_kv_heads"]) * cfg["head_dim"] * d,
+               "o_proj_residual": 2.0 * T * d * d, "gate_up_swiglu": 4.0 * T * f * d, "down_residual": 2.0 * T * d * f}
+    out = {"experiment": "prefill of 4 x 2048 tokens against the values of the hidden states", "cases": []}
+    for name, xx in (("N(0,1) (the benchmark's input)", x), ("all zeros", torch.zeros_like(x)),
+                     ("all ones", torch.ones_like(x)), ("N(0,1) again", x)):
+        ms = layer.time_prefill(xx, cu, iters=20, warmup=10)
+        pd.pd_profile_enable(layer.h, True)
+        o = torch.empty_like(xx)
+        acc = {}
+        for _ in range(4):
+            pd.pd_prefill(layer.h, xx, cu, o)
+            torch.cuda.synchronize()
+            for n, t in pd.pd_profile_read(layer.h):
+                acc.setdefault(n, []).append(t)
+        pd.pd_profile_enable(layer.h, False)
+        out["cases"].append({"hidden_states": name, "ms_per_layer": round(ms, 4),
+                             "pflops": round(fl / (ms * 1e-3) / 1e15, 3),
+                             "kernels_us": {n: round(H.median(v) * 1e3, 1) for n, v in acc.items()},
+                             "gemm_pflops": {n: round(gemm_fl[n] / (H.median(acc[n]) * 1e-3) / 1e15, 3) for n in gemm_fl}})
+    layer.close()
+    return out
+
+
 def main():
     which = sys.argv[1] if len(sys.argv) > 1 else "prefill"
     fn = {"prefill": run_prefill, "longctx": run_longctx, "queue": run_queue, "moe": run_moe,
           "chunk": run_chunk, "stack": run_stack, "queue_fixed": run_queue_fixed, "fp8kv": run_fp8kv, "kvxfer": run_kvxfer, "w8": run_w8, "a8": run_a8,
-          "stack_fp8": lambda: run_stack(batches=(1, 8, 64, 256, 448), fp8=True),
+          "operands": run_operands, "stack_fp8": lambda: run_stack(batches=(1, 8, 64, 256, 448), fp8=True),
           "chunk_fp8": lambda: run_chunk(fp8=True)}[which]
     print(json.dumps(fn()))
 

@@ -323,6 +323,32 @@ def test_stream_copy_is_bit_exact_and_checks_arguments():
         pd.pd_stream_copy(torch.zeros(9, dtype=torch.int32, device="cuda")[1:], src[:8])  # misaligned
 
 
+def test_mfma_probe_sums_and_checks_arguments():
+    """The register-only matrix-instruction loop (a measurement aid): what it leaves in its sink is a
+    closed form.  A lane's sink value is the sum over its 8 accumulator blocks x 16 registers; with all
+    operands 1 every accumulator element grows by the 16-deep contraction per instruction, so the value
+    is 8 * 16 * 16 * iters.  With one A fragment set to 2 for every lane the four blocks fed by it double."""
+    iters, n_wg = 37, 3
+    a = torch.ones(16384, dtype=torch.bfloat16, device="cuda")
+    b = torch.ones(8192, dtype=torch.bfloat16, device="cuda")
+    sink = torch.zeros(n_wg * 512 + 5, dtype=torch.float32, device="cuda")
+    pd.pd_mfma_probe(a, b, n_wg, iters, sink)
+    torch.cuda.synchronize()
+    assert torch.all(sink[:n_wg * 512] == 8 * 16 * 16 * iters) and torch.all(sink[n_wg * 512:] == 0)
+    a2 = a.clone().view(512, 4, 8)
+    a2[:, 1, :] = 2.0                                   # fragment 1 of every lane
+    pd.pd_mfma_probe(a2.reshape(-1).contiguous(), b, n_wg, iters, sink)
+    torch.cuda.synchronize()
+    assert torch.all(sink[:n_wg * 512] == (6 + 2 * 2) * 16 * 16 * iters)
+    import ctypes as C
+    st = pd.lib.pd_mfma_probe(C.c_void_p(a.data_ptr()), C.c_void_p(b.data_ptr()), C.c_int32(0), C.c_int32(5),
+                              C.c_void_p(sink.data_ptr()), None)
+    assert st == pd.PD_ERR_INVALID_ARG
+    st = pd.lib.pd_mfma_probe(C.c_void_p(a.data_ptr() + 2), C.c_void_p(b.data_ptr()), C.c_int32(1), C.c_int32(5),
+                              C.c_void_p(sink.data_ptr()), None)
+    assert st == pd.PD_ERR_INVALID_ARG
+
+
 @pytest.mark.parametrize("B", [1, 3, 8, 9, 40])
 def test_bf16_moe_decode_batch_sizes(B):
     """Mixture-of-experts decode on the matrix-core path: up to 16 (token, expert) pairs run the
