@@ -24,6 +24,8 @@
 // stream from HBM, so K is split over gridDim.y: each split writes an fp32 partial tile and a
 // second small kernel adds the splits in a fixed order and applies the epilogue (deterministic,
 // no atomics).
+#include <string.h>
+
 #include "pd_internal.h"
 
 namespace pd {
@@ -420,8 +422,83 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmArgs a, int spli
     *(uint2 *)((uint16_t *)a.C + (size_t)m * a.ldc + n) = o;
 }
 
+// The same sum for an EPI_RESIDUAL product whose rows are normalised next: one workgroup per row adds the
+// partials and the residual, stores the row (bf16) and its RMSNorm (statistics in fp32 on the stored,
+// rounded values, exactly what a separate norm launch would read); the workgroups behind the M rows do
+// the cache append of a decode step (rmsnorm_append_kernel's second half).
+__global__ __launch_bounds__(256) void splitk_reduce_norm_kernel(GemmArgs a, int splits, RopeArgs ap, int n_append)
+{
+    __shared__ float red[4];
+    __shared__ float cs[128], sn[128];
+    const int m = blockIdx.x;
+    if (m >= a.M) {
+        if (m - a.M < n_append) append_token_body(ap, m - a.M, cs, sn);
+        return;
+    }
+    const int n8 = a.N / 8;
+    const size_t plane = (size_t)a.M * a.N;
+    const uint16_t *R = (const uint16_t *)a.R + (size_t)m * a.ldr;
+    uint16_t *C = (uint16_t *)a.C + (size_t)m * a.ldc;
+    uint4 hrow[4];                                    // this thread's stored values: up to 4 chunks of 8 columns
+    float ss = 0.f;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int c8 = it * 256 + threadIdx.x;
+        if (c8 >= n8) break;
+        const int n = c8 * 8;
+        float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int z = 0; z < splits; ++z) {
+            const float *p = a.splitk_ws + z * plane + (size_t)m * a.N + n;
+            const float4 t0 = *(const float4 *)p, t1 = *(const float4 *)(p + 4);
+            v[0] += t0.x; v[1] += t0.y; v[2] += t0.z; v[3] += t0.w;
+            v[4] += t1.x; v[5] += t1.y; v[6] += t1.z; v[7] += t1.w;
+        }
+        const uint4 rr = *(const uint4 *)(R + n);
+        const uint32_t rw[4] = {rr.x, rr.y, rr.z, rr.w};
+        uint32_t o[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            o[j] = pack2bf(v[2 * j] + bfbits2f(rw[j] & 0xffffu), v[2 * j + 1] + bfbits2f(rw[j] >> 16));
+            const float x0 = bfbits2f(o[j] & 0xffffu), x1 = bfbits2f(o[j] >> 16);
+            ss += x0 * x0 + x1 * x1;
+        }
+        hrow[it] = make_uint4(o[0], o[1], o[2], o[3]);
+        *(uint4 *)(C + n) = hrow[it];
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    const float inv = rsqrtf((red[0] + red[1] + red[2] + red[3]) * (1.0f / (float)a.N) + a.fuse_eps);
+    uint16_t *Y = (uint16_t *)a.fuse_y + (size_t)m * a.N;
+    const uint16_t *G = (const uint16_t *)a.fuse_g;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int c8 = it * 256 + threadIdx.x;
+        if (c8 >= n8) break;
+        const int n = c8 * 8;
+        const uint4 gg = *(const uint4 *)(G + n);
+        const uint32_t w[4] = {hrow[it].x, hrow[it].y, hrow[it].z, hrow[it].w}, gw[4] = {gg.x, gg.y, gg.z, gg.w};
+        uint32_t o[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            o[j] = pack2bf(bfbits2f(w[j] & 0xffffu) * inv * bfbits2f(gw[j] & 0xffffu),
+                           bfbits2f(w[j] >> 16) * inv * bfbits2f(gw[j] >> 16));
+        *(uint4 *)(Y + n) = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+}
+
 hipError_t launch_splitk_reduce(const GemmArgs &a, int splits, hipStream_t s)
 {
+    if (a.fuse_y && a.fuse_g && a.fuse_done && a.epilogue == EPI_RESIDUAL && a.N % 8 == 0 && a.N <= 8192 &&
+        a.ldc % 8 == 0 && a.ldr % 8 == 0) {
+        RopeArgs none;
+        memset(&none, 0, sizeof(none));
+        const int n_append = a.fuse_append ? a.fuse_append->T : 0;
+        splitk_reduce_norm_kernel<<<a.M + n_append, 256, 0, s>>>(a, splits, a.fuse_append ? *a.fuse_append : none, n_append);
+        *a.fuse_done = 1;
+        return hipGetLastError();
+    }
     const size_t n_out = (size_t)a.M * (a.N / 4);
     splitk_reduce_kernel<<<(unsigned)((n_out + 255) / 256), 256, 0, s>>>(a, splits);
     return hipGetLastError();

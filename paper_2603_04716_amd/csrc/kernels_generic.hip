@@ -494,49 +494,7 @@ __global__ __launch_bounds__(256) void rmsnorm_append_kernel(RopeArgs a, const u
         rmsnorm_bf16_row(x + (size_t)blockIdx.x * d8, g, y + (size_t)blockIdx.x * d8, d8, d_inv, eps, red);
         return;
     }
-    const int t = blockIdx.x - n_rows;
-    const int half = a.hd >> 1;
-    const int pos = a.tok_pos[t], slot = a.tok_slot[t];
-    for (int i = threadIdx.x; i < half; i += 256) {
-        if (pos < a.table_len) {
-            float2 f = a.table[(size_t)pos * half + i];
-            cs[i] = f.x;
-            sn[i] = f.y;
-        } else {
-            double sv, cv;
-            sincos((double)pos * a.inv_freq[i], &sv, &cv);
-            cs[i] = (float)cv;
-            sn[i] = (float)sv;
-        }
-    }
-    __syncthreads();
-    const uint16_t *row = (const uint16_t *)a.qkv + (size_t)t * a.ld;
-    const size_t plane_elems = (size_t)a.max_len * a.hd;
-    for (int idx = threadIdx.x; idx < a.Hkv * half; idx += 256) {
-        const int gk = idx / half, i = idx - gk * half;
-        const uint16_t *kv = row + (size_t)(a.Hq + gk) * a.hd;
-        const float x0 = bfbits2f(kv[i]), x1 = bfbits2f(kv[i + half]);
-        const float y0 = x0 * cs[i] - x1 * sn[i], y1 = x1 * cs[i] + x0 * sn[i];
-        const size_t plane = ((size_t)slot * a.Hkv + gk) * plane_elems;
-        if (a.fp8) {
-            uint8_t *p8 = (uint8_t *)a.k_cache + plane;
-            p8[kblk8_off(pos, i)] = (uint8_t)e4m3_encode((double)y0 / a.k_scale);
-            p8[kblk8_off(pos, i + half)] = (uint8_t)e4m3_encode((double)y1 / a.k_scale);
-        } else {
-            uint16_t *pk = (uint16_t *)a.k_cache + plane;
-            pk[kblk_off(pos, i)] = f2bf(y0).x;
-            pk[kblk_off(pos, i + half)] = f2bf(y1).x;
-        }
-    }
-    const uint16_t *vsrc = row + (size_t)(a.Hq + a.Hkv) * a.hd;
-    for (int idx = threadIdx.x; idx < a.Hkv * a.hd; idx += 256) {
-        const int gv = idx / a.hd, i = idx - gv * a.hd;
-        const size_t plane = ((size_t)slot * a.Hkv + gv) * plane_elems;
-        if (a.fp8)
-            ((uint8_t *)a.v_cache)[plane + vblk8_off(pos, i)] = (uint8_t)e4m3_encode((double)bfbits2f(vsrc[idx]) / a.v_scale);
-        else
-            ((uint16_t *)a.v_cache)[plane + vblk_off(pos, i)] = vsrc[idx];
-    }
+    append_token_body(a, blockIdx.x - n_rows, cs, sn);
 }
 
 hipError_t launch_rmsnorm_append(const RopeArgs &a, const void *x, const void *g, void *y, int n_rows, int d,

@@ -849,12 +849,20 @@ static pd_status run_tail(pd_layer *L, const void *x, int T, const void *router_
     // h = x + o Wo^T
     g.A = L->o; g.lda = L->Nq; g.B = L->w_o; g.ldb = L->Nq; g.C = L->h; g.ldc = d; g.R = x; g.ldr = d;
     g.M = T; g.N = d; g.K = L->Nq; g.epilogue = EPI_RESIDUAL; g.n_groups = 1;
+    // where this product splits K over workgroups, the launch that adds the partials also normalises the
+    // rows it forms (and carries the decode step's cache append): one launch fewer
+    int norm_fused = 0;
+    if (c.dtype == PD_BF16 && !(L->a8 && T > kA8Rows)) {
+        g.fuse_g = L->g_ffn; g.fuse_y = L->y; g.fuse_eps = c.rms_eps; g.fuse_append = append; g.fuse_done = &norm_fused;
+    }
     STEP("o_proj_residual", run_gemm(L, g, s));
+    if (norm_fused) L->a8_src = nullptr;
     if (E == 0) {
         memset(&g, 0, sizeof(g));
         g.A = L->h; g.lda = d; g.B = L->w_gate; g.B1 = L->w_up; g.ldb = d; g.C = L->act; g.ldc = F;
         g.M = T; g.N = F; g.K = d; g.epilogue = EPI_SWIGLU; g.n_groups = 1;
-        if (append) {
+        if (norm_fused) {
+        } else if (append) {
             L->a8_src = nullptr;
             STEP("rmsnorm_ffn", launch_rmsnorm_append(*append, L->h, L->g_ffn, L->y, T, d, c.rms_eps, s));
         } else {
@@ -868,8 +876,12 @@ static pd_status run_tail(pd_layer *L, const void *x, int T, const void *router_
         STEP("down_residual", run_gemm(L, g, s));
         return PD_OK;
     }
-    if (append) STEP("rmsnorm_ffn", launch_rmsnorm_append(*append, L->h, L->g_ffn, L->y, T, d, c.rms_eps, s));
-    else STEP("rmsnorm_ffn", launch_rmsnorm(c.dtype, L->h, L->g_ffn, L->y, T, d, c.rms_eps, s));
+    if (norm_fused) {
+    } else if (append) {
+        STEP("rmsnorm_ffn", launch_rmsnorm_append(*append, L->h, L->g_ffn, L->y, T, d, c.rms_eps, s));
+    } else {
+        STEP("rmsnorm_ffn", launch_rmsnorm(c.dtype, L->h, L->g_ffn, L->y, T, d, c.rms_eps, s));
+    }
     const float *logits = (const float *)router_logits;
     if (!logits) {
         STEP("router_logits", launch_router_logits(c.dtype, L->y, L->w_router, L->logits, T, d, E, s));

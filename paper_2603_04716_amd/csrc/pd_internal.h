@@ -171,6 +171,8 @@ struct IntDst4 {
     int32_t start[5];   // array k is v[start[k] .. start[k + 1])
 };
 
+struct RopeArgs;
+
 enum Epilogue { EPI_NONE = 0, EPI_RESIDUAL = 1, EPI_SWIGLU = 2, EPI_PARTIAL = 3 /* internal: fp32 split-K partials */ };
 
 // C[M,N] = epilogue(A[M,K] * B[N,K]^T).  All matrices row-major with leading dimensions in
@@ -199,6 +201,16 @@ struct GemmArgs {
     const float *b_scale;
     // 8-bit activations (tiled kernel, F8 form): one scale per row of A; A and B then hold E4M3 codes
     const float *a_scale;
+    // Optional work for the launch that adds split-K partials of an EPI_RESIDUAL product (N a multiple of
+    // 8, at most 8192): the RMSNorm of the rows it has just formed, y = rmsnorm(C; fuse_g, fuse_eps) into
+    // fuse_y [M, N] (leading dimension N), and, if fuse_append is set, the cache append of a decode
+    // step (see launch_rmsnorm_append).  A launcher that does so sets *fuse_done = 1; otherwise (no split,
+    // another kernel) the caller runs the norm itself.
+    const void *fuse_g;
+    void *fuse_y;
+    float fuse_eps;
+    const RopeArgs *fuse_append;
+    int *fuse_done;
 };
 
 // ---- launchers (each returns hipGetLastError() after the launch) ------------------------------
@@ -264,6 +276,55 @@ struct RopeArgs {
     const float2 *table;     // optional [table_len][hd/2] (cos, sin) of pos * inv_freq, made in double
     int32_t table_len;
 };
+// The cache append of decode row t (bf16 layer, head_dim up to 256, blocked bf16 or 8-bit cache) by one
+// workgroup of 256 threads: the key of every kv head rotated at tok_pos[t] in fp32 and stored, the value
+// stored; the qkv buffer is only read.  cs, sn: 128 floats of LDS each.
+__device__ __forceinline__ void append_token_body(const RopeArgs &a, int t, float *cs, float *sn)
+{
+    const int half = a.hd >> 1;
+    const int pos = a.tok_pos[t], slot = a.tok_slot[t];
+    for (int i = threadIdx.x; i < half; i += 256) {
+        if (pos < a.table_len) {
+            float2 f = a.table[(size_t)pos * half + i];
+            cs[i] = f.x;
+            sn[i] = f.y;
+        } else {
+            double sv, cv;
+            sincos((double)pos * a.inv_freq[i], &sv, &cv);
+            cs[i] = (float)cv;
+            sn[i] = (float)sv;
+        }
+    }
+    __syncthreads();
+    const uint16_t *row = (const uint16_t *)a.qkv + (size_t)t * a.ld;
+    const size_t plane_elems = (size_t)a.max_len * a.hd;
+    for (int idx = threadIdx.x; idx < a.Hkv * half; idx += 256) {
+        const int gk = idx / half, i = idx - gk * half;
+        const uint16_t *kv = row + (size_t)(a.Hq + gk) * a.hd;
+        const float x0 = bfbits2f(kv[i]), x1 = bfbits2f(kv[i + half]);
+        const float y0 = x0 * cs[i] - x1 * sn[i], y1 = x1 * cs[i] + x0 * sn[i];
+        const size_t plane = ((size_t)slot * a.Hkv + gk) * plane_elems;
+        if (a.fp8) {
+            uint8_t *p8 = (uint8_t *)a.k_cache + plane;
+            p8[kblk8_off(pos, i)] = (uint8_t)e4m3_encode((double)y0 / a.k_scale);
+            p8[kblk8_off(pos, i + half)] = (uint8_t)e4m3_encode((double)y1 / a.k_scale);
+        } else {
+            uint16_t *pk = (uint16_t *)a.k_cache + plane;
+            pk[kblk_off(pos, i)] = f2bf(y0).x;
+            pk[kblk_off(pos, i + half)] = f2bf(y1).x;
+        }
+    }
+    const uint16_t *vsrc = row + (size_t)(a.Hq + a.Hkv) * a.hd;
+    for (int idx = threadIdx.x; idx < a.Hkv * a.hd; idx += 256) {
+        const int gv = idx / a.hd, i = idx - gv * a.hd;
+        const size_t plane = ((size_t)slot * a.Hkv + gv) * plane_elems;
+        if (a.fp8)
+            ((uint8_t *)a.v_cache)[plane + vblk8_off(pos, i)] = (uint8_t)e4m3_encode((double)bfbits2f(vsrc[idx]) / a.v_scale);
+        else
+            ((uint16_t *)a.v_cache)[plane + vblk_off(pos, i)] = vsrc[idx];
+    }
+}
+
 hipError_t launch_rope_table(float2 *table, int table_len, int half, const double *inv_freq, hipStream_t s);
 hipError_t launch_rope_kv(int dtype, const RopeArgs &a, hipStream_t s);
 // RMSNorm of n_rows bf16 rows (d a multiple of 8) and, in the same launch, the cache append of a decode
