@@ -426,16 +426,16 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(GemmArgs a, int spli
 // partials and the residual, stores the row (bf16) and its RMSNorm (statistics in fp32 on the stored,
 // rounded values, exactly what a separate norm launch would read); the workgroups behind the M rows do
 // the cache append of a decode step (rmsnorm_append_kernel's second half).
-__global__ __launch_bounds__(256) void splitk_reduce_norm_kernel(GemmArgs a, int splits, RopeArgs ap, int n_append)
+__global__ __launch_bounds__(512) void splitk_reduce_norm_kernel(GemmArgs a, int splits, RopeArgs ap, int n_append)
 {
-    __shared__ float red[4];
+    __shared__ float red[8];
     __shared__ float cs[128], sn[128];
     const int m = blockIdx.x;
     if (m >= a.M) {
         if (m - a.M < n_append) append_token_body(ap, m - a.M, cs, sn);
         return;
     }
-    const int n8 = a.N / 8;
+    const int n8 = a.N / 8, nt = blockDim.x;
     const size_t plane = (size_t)a.M * a.N;
     const uint16_t *R = (const uint16_t *)a.R + (size_t)m * a.ldr;
     uint16_t *C = (uint16_t *)a.C + (size_t)m * a.ldc;
@@ -443,17 +443,32 @@ __global__ __launch_bounds__(256) void splitk_reduce_norm_kernel(GemmArgs a, int
     float ss = 0.f;
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
-        const int c8 = it * 256 + threadIdx.x;
+        const int c8 = it * nt + threadIdx.x;
         if (c8 >= n8) break;
         const int n = c8 * 8;
         float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        for (int z = 0; z < splits; ++z) {
-            const float *p = a.splitk_ws + z * plane + (size_t)m * a.N + n;
-            const float4 t0 = *(const float4 *)p, t1 = *(const float4 *)(p + 4);
+        const float *p = a.splitk_ws + (size_t)m * a.N + n;
+        const uint4 rr = *(const uint4 *)(R + n);
+        int z = 0;
+        // four splits' loads in flight at a time: one round trip to the L2 per four splits
+        for (; z + 4 <= splits; z += 4) {
+            float4 t[8];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                t[2 * u] = *(const float4 *)(p + (z + u) * plane);
+                t[2 * u + 1] = *(const float4 *)(p + (z + u) * plane + 4);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {             // in split order: the sum does not depend on the grouping
+                v[0] += t[2 * u].x; v[1] += t[2 * u].y; v[2] += t[2 * u].z; v[3] += t[2 * u].w;
+                v[4] += t[2 * u + 1].x; v[5] += t[2 * u + 1].y; v[6] += t[2 * u + 1].z; v[7] += t[2 * u + 1].w;
+            }
+        }
+        for (; z < splits; ++z) {
+            const float4 t0 = *(const float4 *)(p + z * plane), t1 = *(const float4 *)(p + z * plane + 4);
             v[0] += t0.x; v[1] += t0.y; v[2] += t0.z; v[3] += t0.w;
             v[4] += t1.x; v[5] += t1.y; v[6] += t1.z; v[7] += t1.w;
         }
-        const uint4 rr = *(const uint4 *)(R + n);
         const uint32_t rw[4] = {rr.x, rr.y, rr.z, rr.w};
         uint32_t o[4];
 #pragma unroll
@@ -469,12 +484,14 @@ __global__ __launch_bounds__(256) void splitk_reduce_norm_kernel(GemmArgs a, int
     for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
     __syncthreads();
-    const float inv = rsqrtf((red[0] + red[1] + red[2] + red[3]) * (1.0f / (float)a.N) + a.fuse_eps);
+    float tot = 0.f;
+    for (int w = 0; w < nt / 64; ++w) tot += red[w];
+    const float inv = rsqrtf(tot * (1.0f / (float)a.N) + a.fuse_eps);
     uint16_t *Y = (uint16_t *)a.fuse_y + (size_t)m * a.N;
     const uint16_t *G = (const uint16_t *)a.fuse_g;
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
-        const int c8 = it * 256 + threadIdx.x;
+        const int c8 = it * nt + threadIdx.x;
         if (c8 >= n8) break;
         const int n = c8 * 8;
         const uint4 gg = *(const uint4 *)(G + n);
@@ -495,7 +512,7 @@ hipError_t launch_splitk_reduce(const GemmArgs &a, int splits, hipStream_t s)
         RopeArgs none;
         memset(&none, 0, sizeof(none));
         const int n_append = a.fuse_append ? a.fuse_append->T : 0;
-        splitk_reduce_norm_kernel<<<a.M + n_append, 256, 0, s>>>(a, splits, a.fuse_append ? *a.fuse_append : none, n_append);
+        splitk_reduce_norm_kernel<<<a.M + n_append, a.N > 2048 ? 512 : 256, 0, s>>>(a, splits, a.fuse_append ? *a.fuse_append : none, n_append);
         *a.fuse_done = 1;
         return hipGetLastError();
     }

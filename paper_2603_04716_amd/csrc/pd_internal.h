@@ -277,13 +277,13 @@ struct RopeArgs {
     int32_t table_len;
 };
 // The cache append of decode row t (bf16 layer, head_dim up to 256, blocked bf16 or 8-bit cache) by one
-// workgroup of 256 threads: the key of every kv head rotated at tok_pos[t] in fp32 and stored, the value
+// workgroup (all of its threads take part): the key of every kv head rotated at tok_pos[t] in fp32 and stored, the value
 // stored; the qkv buffer is only read.  cs, sn: 128 floats of LDS each.
 __device__ __forceinline__ void append_token_body(const RopeArgs &a, int t, float *cs, float *sn)
 {
-    const int half = a.hd >> 1;
+    const int half = a.hd >> 1, nt = blockDim.x;
     const int pos = a.tok_pos[t], slot = a.tok_slot[t];
-    for (int i = threadIdx.x; i < half; i += 256) {
+    for (int i = threadIdx.x; i < half; i += nt) {
         if (pos < a.table_len) {
             float2 f = a.table[(size_t)pos * half + i];
             cs[i] = f.x;
@@ -298,7 +298,7 @@ __device__ __forceinline__ void append_token_body(const RopeArgs &a, int t, floa
     __syncthreads();
     const uint16_t *row = (const uint16_t *)a.qkv + (size_t)t * a.ld;
     const size_t plane_elems = (size_t)a.max_len * a.hd;
-    for (int idx = threadIdx.x; idx < a.Hkv * half; idx += 256) {
+    for (int idx = threadIdx.x; idx < a.Hkv * half; idx += nt) {
         const int gk = idx / half, i = idx - gk * half;
         const uint16_t *kv = row + (size_t)(a.Hq + gk) * a.hd;
         const float x0 = bfbits2f(kv[i]), x1 = bfbits2f(kv[i + half]);
@@ -315,7 +315,7 @@ __device__ __forceinline__ void append_token_body(const RopeArgs &a, int t, floa
         }
     }
     const uint16_t *vsrc = row + (size_t)(a.Hq + a.Hkv) * a.hd;
-    for (int idx = threadIdx.x; idx < a.Hkv * a.hd; idx += 256) {
+    for (int idx = threadIdx.x; idx < a.Hkv * a.hd; idx += nt) {
         const int gv = idx / a.hd, i = idx - gv * a.hd;
         const size_t plane = ((size_t)slot * a.Hkv + gv) * plane_elems;
         if (a.fp8)

@@ -20,7 +20,10 @@ known size gives the scale factor applied to every other kernel.
 `--decode-batches 64,128,256` replaces the prefill / batch-256 pair by decode steps at the listed
 batches (a kernel instance is told apart by its grid and workgroup size), and
 `--durations <kernel trace csv>` prints the mean duration, workgroup count and workgroup size of
-every (kernel, grid) of a `rocprofv3 --kernel-trace` run of the same workload.
+every (kernel, grid) of a `rocprofv3 --kernel-trace` run of the same workload, and
+`--decode-steps <kernel trace csv> <fetch csv> <write csv>` lays the `--decode-batches` runs out step
+by step: one row per launch of a decode step, with its workgroups, K splits, mean duration and
+fetched / written bytes over the steps of that batch.
 """
 import argparse
 import collections
@@ -105,6 +108,66 @@ def durations(trace_csv):
         print(f"| `{key[0]}` | {key[1] // key[2]} | {key[2]} | {len(v)} | {sum(v) / len(v):.1f} | {min(v):.1f} |")
 
 
+def decode_steps(trace_csv, fetch_csv, write_csv):
+    """The launches of one decode step, batch by batch.  A step starts at decode_meta_norm_kernel
+    (its grid is batch + 1 workgroups) and ends at the last split-K sum or GEMM before the next
+    bookkeeping launch; the three runs dispatch the same sequence, so the counter files are matched to
+    the trace by position."""
+    def dispatches(path, counter=None):
+        rows = []
+        with open(path) as f:
+            for r in csv.DictReader(f):
+                if counter and r["Counter_Name"] != counter:
+                    continue
+                rows.append(r)
+        rows.sort(key=lambda r: int(r["Dispatch_Id"]))
+        return rows
+    trace = dispatches(trace_csv)
+    fetch, write = dispatches(fetch_csv, "FETCH_SIZE"), dispatches(write_csv, "WRITE_SIZE")
+    if not (len(trace) == len(fetch) == len(write)):
+        sys.exit(f"dispatch counts differ: trace {len(trace)}, fetch {len(fetch)}, write {len(write)}")
+    copy = [i for i, r in enumerate(trace) if short(r["Kernel_Name"]).startswith("stream_copy_kernel")]
+    f_scale = (COPY_BYTES / 1024.0) / (sum(float(fetch[i]["Counter_Value"]) for i in copy) / len(copy))
+    w_scale = (COPY_BYTES / 1024.0) / (sum(float(write[i]["Counter_Value"]) for i in copy) / len(copy))
+    step_kernels = ("decode_meta_norm_kernel", "gemm_mfma_kernel", "gemv_mfma_kernel", "wgemm_kernel",
+                    "splitk_reduce", "decode_attn", "rmsnorm")
+    steps = collections.defaultdict(list)             # batch -> list of steps (lists of dispatch indices)
+    cur = None
+    for i, r in enumerate(trace):
+        name = short(r["Kernel_Name"])
+        if name.startswith("decode_meta_norm_kernel"):
+            cur = [i]
+            steps[int(r["Grid_Size_X"]) // int(r["Workgroup_Size_X"]) - 1].append(cur)
+        elif cur is not None and name.startswith(step_kernels):
+            cur.append(i)
+        else:
+            cur = None
+    gemm_names = ["QKV projection", "O projection + residual", "gate/up + SwiGLU", "down projection + residual"]
+    print("| batch | launch | kernel | workgroups x K splits | threads | mean us | fetched MB | written MB |")
+    print("|---|---|---|---|---|---|---|---|")
+    for B in sorted(steps):
+        runs = [s for s in steps[B] if len(s) == len(steps[B][-1])]
+        total = 0.0
+        n_gemm = 0
+        for pos in range(len(runs[0])):
+            idx = [s[pos] for s in runs]
+            r = trace[idx[0]]
+            name = short(r["Kernel_Name"])
+            us = sum((int(trace[i]["End_Timestamp"]) - int(trace[i]["Start_Timestamp"])) / 1e3 for i in idx) / len(idx)
+            fm = sum(float(fetch[i]["Counter_Value"]) for i in idx) / len(idx) * f_scale * 1024 / 1e6
+            wm = sum(float(write[i]["Counter_Value"]) for i in idx) / len(idx) * w_scale * 1024 / 1e6
+            what = ""
+            if name.startswith(("gemm_mfma_kernel", "gemv_mfma_kernel", "wgemm_kernel")):
+                what = gemm_names[n_gemm] if n_gemm < 4 else ""
+                n_gemm += 1
+            elif name.startswith("splitk_reduce"):
+                what = "sum of the K splits"
+            wgx = int(r["Grid_Size_X"]) // int(r["Workgroup_Size_X"])
+            print(f"| {B} | {what} | `{name}` | {wgx} x {r['Grid_Size_Y']} | {r['Workgroup_Size_X']} | {us:.1f} | {fm:.1f} | {wm:.1f} |")
+            total += us
+        print(f"| {B} | all launches of the step | | | | {total:.1f} | | |")
+
+
 def summarise(fetch_csv, write_csv):
     fetch, write = read_counter(fetch_csv, "FETCH_SIZE"), read_counter(write_csv, "WRITE_SIZE")
     mean = lambda v: sum(v) / len(v)
@@ -131,12 +194,15 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--summarise", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"))
     ap.add_argument("--durations", metavar="KERNEL_TRACE_CSV")
+    ap.add_argument("--decode-steps", nargs=3, metavar=("KERNEL_TRACE_CSV", "FETCH_CSV", "WRITE_CSV"))
     ap.add_argument("--decode-batches", default="", help="comma-separated decode batches instead of prefill + batch 256")
     args = ap.parse_args()
     if args.summarise:
         summarise(*args.summarise)
     elif args.durations:
         durations(args.durations)
+    elif args.decode_steps:
+        decode_steps(*args.decode_steps)
     else:
         workload([int(b) for b in args.decode_batches.split(",")] if args.decode_batches else None)
 
