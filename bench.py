@@ -2,7 +2,7 @@
 """Benchmark of the P/D hot path on one MI355X.
 
 One "step" is one pass of the whole path on the Llama-8B-shaped bf16 layer: a prefill of 8192
-tokens (4 sequences of 2048; back-to-back calls, median per-call time), decode steps at every batch of the sweep 1..256 over a
+tokens (4 sequences of 2048; back-to-back calls, median per-call time), decode steps at every batch of the sweep 1..320 over a
 2048-token KV cache, and the allocation model on the curves just measured (per-layer times
 scaled by 32 layers).  Prints ONE JSON line.
 
