@@ -242,6 +242,44 @@ def test_fp32_decode_beyond_rotary_table():
     gl.close()
 
 
+@pytest.mark.parametrize("fp8", [False, True])
+def test_bf16_decode_beyond_rotary_table(fp8):
+    """The decode step of a bf16 layer on the matrix-core attention path rotates q and the new key inside
+    the attention kernel and appends the key in a later launch: both read the rotary table up to
+    position 32767 and compute the angle in double precision beyond it.  Three steps across that
+    boundary, two sequences (one short, inside the table), outputs and appended keys against the oracle."""
+    cfg = I.small_config(dtype="bf16", d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=128, d_ff=512)
+    ol, gl = both(cfg, std=0.05)
+    n = 32767
+    cap = n + 4
+    k, v = I.kv_fill(2, n, 128, seed=9, dtype="bf16")
+    oc = O.KVCache(ol, 2, cap, fp8_scales=(0.5, 0.125) if fp8 else None)
+    gc = gl.cache(2, cap, fp8_scales=(0.5, 0.125) if fp8 else None)
+    oc.set(0, k, v)
+    oc.set(1, k[:, :100], v[:, :100])
+    pd.pd_kv_cache_set(gc, 0, to_dev(k, "bf16"), to_dev(v, "bf16"))
+    pd.pd_kv_cache_set(gc, 1, to_dev(k[:, :100].copy(), "bf16"), to_dev(v[:, :100].copy(), "bf16"))
+    for step in range(3):                       # slot 0: positions 32767 (table), 32768, 32769 (computed)
+        xn = I.hidden(2, cfg["d_model"], seed=60 + step, dtype="bf16")
+        ref = O.decode_step(ol, xn, [0, 1], oc)
+        got = gl.decode(xn, [0, 1], gc)
+        assert relmax(got, ref) <= TOL["bf16"]
+        assert max(relmax(got[i], ref[i]) for i in range(2)) <= 2 * TOL["bf16"]
+    kk = torch.empty((2, n + 3, 128), dtype=torch.bfloat16, device="cuda")
+    vv = torch.empty_like(kk)
+    pd.pd_kv_cache_get(gc, 0, kk, vv)
+    torch.cuda.synchronize()
+    # appended keys and values: within the bf16 bound of the oracle's, plus, in the 8-bit cache, the one
+    # spacing of the representable values that rounding to a code can add
+    for got, ref, scale in ((to_np(kk)[:, n:], oc.k[0, :, n:n + 3], oc.k_scale), (to_np(vv)[:, n:], oc.v[0, :, n:n + 3], oc.v_scale)):
+        slack = TOL["bf16"] * np.max(np.abs(ref))
+        if fp8:
+            mag = np.maximum(np.maximum(np.abs(ref), np.abs(got)) / scale, 2.0 ** -6)
+            slack = slack + scale * 2.0 ** (np.floor(np.log2(mag)) - 3)
+        assert np.all(np.abs(got - ref) <= slack)
+    gl.close()
+
+
 def test_kv_cache_set_get_and_errors():
     cfg = I.small_config()
     ol, gl = both(cfg)
