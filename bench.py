@@ -280,6 +280,13 @@ def main():
         "kernels": kernels,
     }
     if not args.no_extra:
+        # what the matrix pipe alone sustains on operands distributed like this benchmark's (a loop of
+        # nothing but MFMAs on registers, same run): the launch runs at the chip's power limit, which
+        # depends on the operand values, so this is context for `frac`, which stays against the published peak
+        from paper_2603_04716_amd import mfma_ceiling_probe as MC
+        ceil_tf = MC.sustained_tflops(*MC.benchmark_operands(), iters=60000, reps=5, warmup=2)
+        line["roofline"]["mfma_only_loop_on_these_operand_values"] = {
+            "tflops": round(ceil_tf, 1), "achieved_over_it": round(line["roofline"]["achieved"] / ceil_tf, 4)}
         # the benchmark's other single-GPU configurations, measured by the same harness on the same layer
         # (reported beside the headline, never as `value`)
         from paper_2603_04716_amd import experiments as X

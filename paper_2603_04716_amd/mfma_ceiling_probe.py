@@ -19,17 +19,50 @@ sys.path.insert(0, ROOT)
 N_WG, ITERS, PEAK = 256, 200000, 2.5e15
 
 
+NA, NB = 16384, 8192                # bf16 elements of the A and B fragments of one workgroup
+
+
+def _dev(a):
+    import numpy as np
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a, np.float32)).cuda().to(torch.bfloat16).contiguous()
+
+
+def sustained_tflops(a_vals, b_vals, iters=ITERS, reps=7, warmup=2):
+    """TFLOP/s of the register-only loop on the given operand values (median of `reps` launches)."""
+    import numpy as np
+    import torch
+    import paper_2603_04716_amd as pd
+    ad, bd = _dev(a_vals), _dev(b_vals)
+    sink = torch.empty(N_WG * 512, dtype=torch.float32, device="cuda")
+    flops = 2.0 * 32 * 32 * 16 * 8 * iters * 8 * N_WG
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ts = []
+    for rep in range(warmup + reps):
+        e0.record()
+        pd.pd_mfma_probe(ad, bd, N_WG, iters, sink)
+        e1.record()
+        e1.synchronize()
+        if rep >= warmup:
+            ts.append(e0.elapsed_time(e1))
+    return flops / (float(np.median(ts)) * 1e-3) / 1e12
+
+
+def benchmark_operands(seed=0):
+    """A fragments drawn like the layer's weights, B fragments like its hidden states."""
+    import numpy as np
+    rng = np.random.default_rng(seed)
+    return 0.02 * rng.standard_normal(NA), rng.standard_normal(NB)
+
+
 def main():
     import numpy as np
     import torch
     import paper_2603_04716_amd as pd
 
     rng = np.random.default_rng(0)
-
-    def dev(a):
-        return torch.from_numpy(np.ascontiguousarray(a, np.float32)).cuda().to(torch.bfloat16).contiguous()
-
-    na, nb = 16384, 8192
+    dev = _dev
+    na, nb = NA, NB
     patterns = [
         ("all ones", np.ones(na), np.ones(nb)),
         ("zeros", np.zeros(na), np.zeros(nb)),
