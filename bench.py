@@ -32,8 +32,8 @@ DECODE_REPS = 3                    # decode steps per batch size per step; media
 # the FETCH_SIZE / WRITE_SIZE counters scaled by a plain copy (paper_2603_04716_amd/traffic_probe.py).
 # Valid only for the kernel source the counters were taken on.
 TRAFFIC = {"source": os.path.join("paper_2603_04716_amd", "csrc", "gemm_mfma.hip"),
-           "sha256": "e79f93f4e7cc419fe18254c59d05ee66bd4748cae39487d6a3a5fde62b072731",
-           "bytes_per_launch": 3053.6e6}
+           "sha256": "f1c3318cdf941103c39b45af982604ebc15103bbdc17a1d66b7331c2e1057cdc",
+           "bytes_per_launch": 3054.4e6}
 
 
 def counted_traffic():
