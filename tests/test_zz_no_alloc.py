@@ -15,9 +15,9 @@ from gpu_util import GpuLayer, TOL, relmax, to_dev, to_np
 pytestmark = pytest.mark.gpu
 
 
-def filled_pair(gl, n_slots, cap, lens, hkv, hd, dtype, seed):
+def filled_pair(gl, n_slots, cap, lens, hkv, hd, dtype, seed, fp8_scales=None):
     """Two caches with identical contents."""
-    ca, cb = gl.cache(n_slots, cap), gl.cache(n_slots, cap)
+    ca, cb = gl.cache(n_slots, cap, fp8_scales), gl.cache(n_slots, cap, fp8_scales)
     k, v = I.kv_fill(hkv, max(lens), hd, seed=seed, dtype=dtype)
     kd, vd = to_dev(k, dtype), to_dev(v, dtype)
     for s, n in enumerate(lens):
@@ -98,6 +98,31 @@ def test_two_calls_in_a_row_the_second_smaller(shape):
         pd.pd_decode_step_noalloc(gl.h, xd, rows, cb, out, None if rl is None else torch.from_numpy(rl).cuda())
         torch.cuda.synchronize()
         assert relmax(to_np(out), want) <= TOL[dt]
+    gl.close()
+
+
+def test_8bit_layer_and_cache_on_the_static_scratch():
+    """The 8-bit variants take the same route: E4M3 weights and cache, and, in the call of more than 256
+    rows, E4M3 activations (their codes and scales live in the scratch too).  300 rows, then 17."""
+    cfg = I.small_config(dtype="bf16", d_model=256, n_q_heads=4, n_kv_heads=2, head_dim=128, d_ff=512)
+    gl = GpuLayer(cfg, I.layer_weights(cfg, std=0.05), a8=True)
+    B1, B2, cap = 300, 17, 200
+    rng = np.random.default_rng(8)
+    lens = [int(n) for n in rng.integers(1, cap - 4, B1)]
+    ca, cb, k, v = filled_pair(gl, B1, cap, lens, 2, 128, "bf16", seed=9, fp8_scales=(0.5, 0.125))
+    for call, B in enumerate((B1, B2)):
+        slots = list(range(B)) if call == 0 else [int(s) for s in rng.permutation(B1)[:B]]
+        got, ref = step_both(gl, ca, cb, I.hidden(B, cfg["d_model"], seed=40 + call, dtype="bf16"), slots)
+        assert np.isfinite(got).all()
+        assert relmax(got, ref) <= TOL["bf16"], call
+        assert all(pd.pd_kv_cache_len(ca, s) == pd.pd_kv_cache_len(cb, s) for s in slots)
+    n = pd.pd_kv_cache_len(cb, 0)
+    ka = torch.empty((2, n, 128), dtype=torch.bfloat16, device="cuda")
+    va, kb, vb = torch.empty_like(ka), torch.empty_like(ka), torch.empty_like(ka)
+    pd.pd_kv_cache_get(ca, 0, ka, va)
+    pd.pd_kv_cache_get(cb, 0, kb, vb)
+    torch.cuda.synchronize()
+    assert torch.equal(ka, kb) and torch.equal(va, vb)
     gl.close()
 
 
