@@ -249,7 +249,12 @@ typedef struct {
 } pd_batch;
 
 /* Errors as pd_prefill; PD_ERR_KV_CAPACITY if any listed slot is full (checked before anything is
- * enqueued). */
+ * enqueued).
+ * Under graph capture: the launch grids (how the cached keys are divided over workers, whether a merge
+ * launch is needed) are chosen from the slot lengths at the time of the call, and the library's host
+ * record of those lengths advances at the call, not at a replay.  A captured step is therefore
+ * replayed only with the lengths it was captured at: set them back with pd_kv_cache_set_lens before
+ * each replay. */
 pd_status pd_decode_step(pd_layer *layer, const pd_batch *batch, pd_kv_cache *cache,
                          void *out_hidden, void *stream);
 

@@ -539,6 +539,9 @@ static hipError_t launch_decode_attn_t(const DecodeAttnArgs &a, int n_workers, h
     else decode_attn_kernel<false, FP8><<<(n_workers + 3) / 4, 256, 0, s>>>(a, n_workers);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    // every sequence has at least one chunk: with as many chunks as sequences each worker has normalised
+    // and stored its sequence itself and nothing is left to merge
+    if (a.total_chunks == a.B) return hipSuccess;
     decode_attn_merge_kernel<false><<<dim3(a.B, a.Hq), 128, 0, s>>>(a);
     return hipGetLastError();
 }
